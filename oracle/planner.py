@@ -1,0 +1,86 @@
+"""CPU oracle: which side-task work lands in which bubble.  Test infrastructure only.
+
+Follows the paper's bubble/side-task management loop for one worker serving one task (Section 4.4,
+Algorithm 2) and its program-directed time limit (Section 4.5):
+
+  * when a new bubble arrives and the current task is CREATED, the manager initialises it (-> PAUSED); that
+    bubble is spent on initialisation.  When the task is PAUSED, the manager starts it (-> RUNNING) and hands
+    it the bubble's end time;
+  * while RUNNING, before each step the task checks that the time left in the bubble is enough for the step
+    and runs the step only then; otherwise the rest of the bubble stays idle (the "insufficient time" share of
+    the paper's bubble-time breakdown, Section 6.5);
+  * when the bubble ends the task is paused.
+
+A "step" here is a chunk: a run of consecutive tiles of the task's current segment.  The task's work is a fixed
+sequence of segments (for PageRank: the phases of each iteration, in order); a chunk never spans two segments.
+Costs are modelled integer nanoseconds known up front, so the whole plan is a pure function of the declared
+bubble lengths and the cost table -- no clock is read.
+
+    remaining = L_i - guard
+    repeat:
+        n = the largest count of consecutive tiles from the cursor, inside the current segment, with
+            launch_cost + sum(cost) <= min(remaining, max_chunk)
+        n == 0  ->  idle for the rest of the bubble
+        else    ->  run the chunk; remaining -= launch_cost + sum(cost); advance the cursor
+
+When the last segment of a run completes the task starts over (run index + 1) unless `max_runs` is reached,
+after which it harvests nothing more.
+"""
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+
+@dataclass(frozen=True)
+class Record:
+    kind: str          # "INIT", "CHUNK", "IDLE"
+    bubble: int
+    run: int = 0
+    segment: int = 0   # index into the segment list of one run
+    tile0: int = 0
+    tile1: int = 0
+    modelled_ns: int = 0   # CHUNK: launch_cost + sum of tile costs; IDLE: modelled time left unused
+
+
+def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard: int, launch_cost: int,
+         max_chunk: int, max_runs: Optional[int] = None, start_created: bool = True) -> List[Record]:
+    """Plan over the given bubbles.  segments[g][t] is the modelled cost of tile t of segment g (ints >= 0).
+
+    start_created: the task begins in CREATED, so the first bubble is consumed by initialisation.
+    """
+    if launch_cost < 0 or guard < 0 or max_chunk <= 0:
+        raise ValueError("bad planner constants")
+    if any(len(seg) == 0 for seg in segments) or len(segments) == 0:
+        raise ValueError("every segment needs at least one tile")
+    if launch_cost == 0 and any(c <= 0 for seg in segments for c in seg):
+        raise ValueError("a chunk must have a positive modelled cost")
+    out: List[Record] = []
+    created = start_created
+    run, seg, tile = 0, 0, 0
+    for i, length in enumerate(bubble_lengths):
+        if created:
+            created = False
+            out.append(Record("INIT", i))
+            continue
+        remaining = length - guard
+        while True:
+            if max_runs is not None and run >= max_runs:
+                break                                   # task finished: nothing left to harvest
+            budget = min(remaining, max_chunk)
+            costs = segments[seg]
+            n, total = 0, launch_cost
+            while tile + n < len(costs) and total + costs[tile + n] <= budget:
+                total += costs[tile + n]
+                n += 1
+            if n == 0:
+                out.append(Record("IDLE", i, run, seg, tile, tile, max(remaining, 0)))
+                break
+            out.append(Record("CHUNK", i, run, seg, tile, tile + n, total))
+            remaining -= total
+            tile += n
+            if tile == len(costs):
+                tile = 0
+                seg += 1
+                if seg == len(segments):
+                    seg = 0
+                    run += 1
+    return out

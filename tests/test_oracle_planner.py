@@ -1,0 +1,99 @@
+"""Pins for the harvest planner: invariants, boundary cases and a hand-worked example."""
+import random
+
+import pytest
+
+from oracle.planner import plan, Record
+
+
+def test_first_bubble_is_spent_on_init_then_start():
+    # Algorithm 2: a CREATED task is initialised by the bubble that finds it; it runs from the next one
+    recs = plan([100, 100], [[10, 10]], guard=0, launch_cost=1, max_chunk=1000, max_runs=1)
+    assert recs[0] == Record("INIT", 0)
+    assert recs[1] == Record("CHUNK", 1, 0, 0, 0, 2, 21)
+    assert len(recs) == 2
+
+
+def test_hand_worked_example():
+    # two segments per run: [30, 30, 30] and [50]; guard 10, launch 5, max_chunk 70; bubbles 100, 60, 200
+    # bubble 0: budget 90 -> min(90, 70) = 70: 5 + 30 + 30 = 65 fits, + 30 = 95 no -> tiles 0..2, rem 25;
+    #           25: 5 + 30 > 25 -> idle 25
+    # bubble 1: rem 50: 5 + 30 = 35 -> tile 2..3, rem 15; segment 1: 5 + 50 > 15 -> idle 15
+    # bubble 2: rem 190: min(190, 70): 5 + 50 = 55 -> seg 1 done, run 1 starts; rem 135: 65 -> tiles 0..2, rem 70;
+    #           35 -> tile 2..3, rem 35; seg 1: 55 > 35 -> idle 35
+    recs = plan([100, 60, 200], [[30, 30, 30], [50]], guard=10, launch_cost=5, max_chunk=70, start_created=False)
+    assert recs == [
+        Record("CHUNK", 0, 0, 0, 0, 2, 65), Record("IDLE", 0, 0, 0, 2, 2, 25),
+        Record("CHUNK", 1, 0, 0, 2, 3, 35), Record("IDLE", 1, 0, 1, 0, 0, 15),
+        Record("CHUNK", 2, 0, 1, 0, 1, 55), Record("CHUNK", 2, 1, 0, 0, 2, 65),
+        Record("CHUNK", 2, 1, 0, 2, 3, 35), Record("IDLE", 2, 1, 1, 0, 0, 35),
+    ]
+
+
+def test_exact_fit_is_allowed_and_one_more_ns_is_not():
+    # "only if the remaining time is enough": cost == remaining runs, cost == remaining + 1 idles
+    assert plan([100], [[95]], guard=0, launch_cost=5, max_chunk=10**9, max_runs=1, start_created=False)[0].kind == "CHUNK"
+    assert plan([99], [[95]], guard=0, launch_cost=5, max_chunk=10**9, max_runs=1, start_created=False)[0].kind == "IDLE"
+    # one tile per bubble when the tile fills the bubble exactly
+    recs = plan([50, 50, 50], [[40], [40], [40]], guard=5, launch_cost=5, max_chunk=10**9, max_runs=1, start_created=False)
+    assert [r.kind for r in recs] == ["CHUNK", "IDLE", "CHUNK", "IDLE", "CHUNK"]
+    assert [r.bubble for r in recs if r.kind == "CHUNK"] == [0, 1, 2]
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_invariants_on_random_inputs(seed):
+    rng = random.Random(seed)
+    segments = [[rng.randint(1, 50) for _ in range(rng.randint(1, 12))] for _ in range(rng.randint(1, 6))]
+    bl = [rng.randint(0, 400) for _ in range(rng.randint(1, 40))]
+    guard, launch, max_chunk = rng.randint(0, 20), rng.randint(0, 10), rng.randint(60, 300)
+    max_runs = rng.choice([None, 1, 2])
+    recs = plan(bl, segments, guard, launch, max_chunk, max_runs)
+    assert recs[0] == Record("INIT", 0)
+    # chunks walk (run, segment, tile) in order without gaps or repeats, never crossing a segment
+    cur = (0, 0, 0)
+    used = {}
+    for r in recs[1:]:
+        assert r.bubble >= 1
+        if r.kind == "CHUNK":
+            assert (r.run, r.segment, r.tile0) == cur
+            assert r.tile0 < r.tile1 <= len(segments[r.segment])
+            assert r.modelled_ns == launch + sum(segments[r.segment][r.tile0:r.tile1])
+            assert r.modelled_ns <= max_chunk
+            used[r.bubble] = used.get(r.bubble, 0) + r.modelled_ns
+            assert used[r.bubble] <= bl[r.bubble] - guard      # never past the bubble's end minus the guard
+            if r.tile1 == len(segments[r.segment]):
+                cur = (r.run + (r.segment + 1 == len(segments)), (r.segment + 1) % len(segments), 0)
+            else:
+                cur = (r.run, r.segment, r.tile1)
+        elif r.kind == "IDLE":
+            # idle only when even the next tile alone does not fit
+            left = bl[r.bubble] - guard - used.get(r.bubble, 0)
+            assert launch + segments[r.segment][r.tile0] > min(left, max_chunk)
+    if max_runs is not None:
+        assert cur[0] <= max_runs
+    # greedy maximality: a chunk stops only at the segment end, at max_chunk/remaining, never earlier
+    used = {}
+    for r in recs[1:]:
+        if r.kind != "CHUNK":
+            continue
+        left = bl[r.bubble] - guard - used.get(r.bubble, 0)
+        if r.tile1 < len(segments[r.segment]):
+            assert r.modelled_ns + segments[r.segment][r.tile1] > min(left, max_chunk)
+        used[r.bubble] = used.get(r.bubble, 0) + r.modelled_ns
+
+
+def test_completed_run_covers_every_tile_exactly_once():
+    segments = [[7] * 9, [3], [11] * 30, [2] * 4]
+    recs = plan([10**6] * 3, segments, guard=0, launch_cost=1, max_chunk=50, max_runs=2)
+    seen = {}
+    for r in recs:
+        if r.kind == "CHUNK":
+            for t in range(r.tile0, r.tile1):
+                seen[(r.run, r.segment, t)] = seen.get((r.run, r.segment, t), 0) + 1
+    want = {(run, g, t) for run in range(2) for g, seg in enumerate(segments) for t in range(len(seg))}
+    assert set(seen) == want and set(seen.values()) == {1}
+
+
+def test_rejects_zero_cost_chunks():
+    with pytest.raises(ValueError):
+        plan([10], [[0, 0]], guard=0, launch_cost=0, max_chunk=10)
