@@ -1,0 +1,328 @@
+/*
+ * freeride.h -- C ABI of the bubble-harvesting runtime for one pipeline stage on one GPU.
+ *
+ * The library serves one GPU "side task" inside the idle windows (bubbles) of a pipeline-parallel training
+ * stage, after FreeRide (arXiv 2409.06941):
+ *   - the side task is a state machine with the states SUBMITTED, CREATED, PAUSED, RUNNING, STOPPED and the
+ *     transitions Create / Init / Start / Pause / RunNextStep / Stop (Section 4.1, Figure 3);
+ *   - the training system reports every bubble (start time, duration) to the manager (Section 3.2, Section 4.6),
+ *     which initialises or starts the current task when a bubble begins and pauses it when the bubble ends
+ *     (Section 4.4, Algorithm 2);
+ *   - before every step the task checks that the time left in the bubble is enough for that step
+ *     (program-directed time limit, Section 4.5);
+ *   - a task is accepted only when the stage's free memory exceeds what the task needs (Section 4.4,
+ *     Algorithm 1), and a task that allocates past its limit is stopped alone (memory limit, Section 4.5).
+ * The paper's manager, worker and task are separate processes joined by RPC; here they are one worker thread
+ * inside the calling process.
+ *
+ * Conventions
+ *   - Every function returns an int: FR_OK (0) or a negative FR_ERR_* code; results come back through
+ *     out-pointers.  No function throws, and a NULL required pointer gives FR_ERR_ARG.
+ *   - "device pointer" means memory of the context's GPU; "host pointer" means ordinary process memory.
+ *     The caller owns every buffer it passes in and keeps it alive until the object made from it is destroyed.
+ *   - Streams are hipStream_t handles passed as void* (for example torch.cuda.Stream.cuda_stream); NULL is
+ *     the default stream.
+ *   - Times are uint64_t nanoseconds of CLOCK_MONOTONIC (fr_now_ns).
+ *   - Task callbacks run on the library's worker thread only, never concurrently with each other.
+ *   - One context serves one GPU and one stage; contexts are independent.  Calls on one context may come
+ *     from any thread but fr_bubble_begin / fr_bubble_end must not race with each other.
+ */
+#ifndef FREERIDE_H
+#define FREERIDE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ------------------------------------------------------------------ status codes */
+#define FR_OK            0
+#define FR_ERR_ARG      (-1)   /* bad argument (NULL, out of range, shape the kernels do not support)       */
+#define FR_ERR_STATE    (-2)   /* call not legal in the current state                                        */
+#define FR_ERR_NOMEM    (-3)   /* task rejected at registration: not enough free memory (Algorithm 1)       */
+#define FR_ERR_OOM      (-4)   /* task exceeded its memory limit and was stopped (Section 4.5)              */
+#define FR_ERR_OVERRUN  (-5)   /* side work was still in flight when the bubble ended                        */
+#define FR_ERR_HIP      (-6)   /* a HIP runtime call failed; fr_last_hip_error gives the code               */
+
+/* Side-task states (Section 4.1). */
+#define FR_SUBMITTED 0
+#define FR_CREATED   1
+#define FR_PAUSED    2
+#define FR_RUNNING   3
+#define FR_STOPPED   4
+
+/* Event-log record kinds. */
+#define FR_EV_INIT  1   /* the bubble was spent on InitSideTask                                             */
+#define FR_EV_CHUNK 2   /* one step (a run of tiles) was enqueued in the bubble                             */
+#define FR_EV_IDLE  3   /* the next step did not fit: rest of the bubble left idle ("insufficient time")    */
+#define FR_EV_MISS  4   /* the step fitted the modelled budget but not the real clock; it was not launched  */
+
+typedef struct fr_ctx fr_ctx;
+typedef struct fr_alloc fr_alloc;
+typedef int32_t fr_task_id;
+
+/* ------------------------------------------------------------------ context */
+typedef struct fr_config {
+    int32_t  device_id;            /* HIP device ordinal.  -1 makes a host-only context: no HIP call is made,
+                                      the side stream is NULL and fr_alloc_device takes memory from the host
+                                      heap; meant for tasks that enqueue no GPU work (runtime tests).        */
+    uint32_t cu_count;             /* side stream may use this many compute units (first cu_count mask bits,
+                                      which the driver deals round-robin over the XCDs); 0 = use cu_mask.    */
+    uint32_t cu_mask[8];           /* 256-bit CU mask for the side stream when cu_count == 0; all-zero = no
+                                      mask (an ordinary stream on every CU).                                 */
+    uint64_t mem_available_bytes;  /* free device memory in this stage's bubbles (Section 2.2.1)             */
+    uint64_t guard_ns;             /* modelled work must end this long before the declared bubble end        */
+    uint64_t launch_cost_ns;       /* modelled fixed cost added to every step                                */
+    uint64_t max_chunk_ns;         /* upper bound on one step's modelled cost; 0 = unbounded                 */
+    uint32_t max_inflight;         /* steps enqueued but not yet finished on the GPU; 0 = default (8)        */
+    uint32_t event_log_capacity;   /* records kept (oldest dropped first); 0 = default (65536)               */
+    uint32_t time_steps;           /* nonzero: bracket every step with HIP events and report measured GPU ns */
+    uint32_t reserved;
+} fr_config;
+
+int fr_create(const fr_config* cfg, fr_ctx** out);
+/* Stops the task if any, joins the worker thread, destroys the side stream.  ctx is invalid afterwards. */
+int fr_destroy(fr_ctx* ctx);
+/* The side stream (hipStream_t) the library launches side-task work on; NULL for a host-only context. */
+int fr_side_stream(fr_ctx* ctx, void** hip_stream_out);
+/* Last failing HIP error code seen by this context (0 if none). */
+int fr_last_hip_error(fr_ctx* ctx);
+uint64_t fr_now_ns(void);
+
+/* ------------------------------------------------------------------ side task */
+typedef struct fr_step {
+    uint64_t modelled_ns;   /* modelled cost of the step without launch_cost; 0 = nothing fits / no work    */
+    uint64_t work_units;    /* task-defined amount of work in the step (PageRank: edges traversed)          */
+    uint32_t run;           /* task-defined cursor of the step: restart count,                              */
+    uint32_t segment;       /*   segment inside the run (a step never spans two segments),                  */
+    uint32_t tile0, tile1;  /*   tile range [tile0, tile1) inside the segment                               */
+    int32_t  finished;      /* plan_step sets 1 when the task has no work left at all                       */
+    int32_t  completes_run; /* plan_step sets 1 when this step ends a run (PageRank: the K-th iteration)    */
+} fr_step;
+
+/*
+ * The task's transition functions (Section 4.1).  `user` is the pointer given at registration.
+ * create   : SUBMITTED -> CREATED, host-side set-up only.
+ * init     : CREATED -> PAUSED, takes device memory through `a` (fr_alloc_device / fr_alloc_charge) and may
+ *            enqueue set-up work on `stream`.  Runs inside the first bubble that finds the task CREATED.
+ * plan_step: pure; describes the largest next step whose modelled cost + launch_cost_ns <= budget_ns.
+ *            Sets modelled_ns = 0 when not even the smallest step fits.
+ * run_step : RunNextStep(): enqueue exactly the planned step on `stream` and advance the cursor.
+ * stop     : -> STOPPED, release everything taken in init (the accounting allocator frees what it handed out).
+ * Each returns FR_OK or an FR_ERR_* code; a failure stops the task.
+ */
+typedef struct fr_task_ops {
+    int (*create)(void* user);
+    int (*init)(void* user, fr_alloc* a, void* stream);
+    int (*plan_step)(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* out);
+    int (*run_step)(void* user, void* stream, const fr_step* planned);
+    int (*stop)(void* user);
+} fr_task_ops;
+
+/* The side-task profile (Section 4.3): memory need and shortest step. */
+typedef struct fr_task_profile {
+    uint64_t mem_limit_bytes;   /* what the task may allocate; also what Algorithm 1 compares            */
+    uint64_t min_step_ns;       /* modelled cost of the task's smallest step (informational)             */
+} fr_task_profile;
+
+/*
+ * Algorithm 1 for one worker: the task is accepted only if ctx.mem_available_bytes > profile.mem_limit_bytes
+ * (strictly); otherwise FR_ERR_NOMEM.  On acceptance create() runs and the task is CREATED.  One task per
+ * context; a second registration while one is live gives FR_ERR_STATE.  `ops` is copied.
+ */
+int fr_task_register(fr_ctx* ctx, const fr_task_ops* ops, void* user, const fr_task_profile* profile,
+                     fr_task_id* id_out);
+/* StopSideTask(): legal from CREATED, PAUSED and RUNNING; waits for side work in flight, then calls stop(). */
+int fr_task_stop(fr_ctx* ctx, fr_task_id id);
+
+/*
+ * Accounting allocator handed to init().  fr_alloc_device returns device memory (256-byte aligned) or NULL;
+ * once the running total would pass the task's mem_limit_bytes it returns NULL and latches an out-of-memory
+ * condition, after which the runtime stops the task with FR_ERR_OOM and the stage is untouched.
+ * fr_alloc_charge only books `bytes` against the limit (for buffers the caller handed to the task); it
+ * returns FR_OK or FR_ERR_OOM.  Memory handed out is freed by the runtime after stop().
+ */
+void* fr_alloc_device(fr_alloc* a, size_t bytes);
+int   fr_alloc_charge(fr_alloc* a, size_t bytes);
+uint64_t fr_alloc_used(const fr_alloc* a);
+
+/*
+ * Bubble notifications from the stage's scheduler (Section 3.2: start timestamp and duration).
+ * fr_bubble_begin: a bubble of declared length `duration_ns` opened at `t_begin_ns`.  If the task is CREATED
+ *   it is initialised in this bubble; if PAUSED it is started and steps are planned against
+ *   duration_ns - guard_ns.  FR_ERR_STATE if a bubble is already open.
+ * fr_bubble_end: PauseSideTask().  Returns once the worker has stopped enqueuing.  FR_ERR_OVERRUN (also
+ *   counted) if side work is still in flight on the GPU at that moment; FR_ERR_STATE if no bubble is open.
+ */
+int fr_bubble_begin(fr_ctx* ctx, uint64_t t_begin_ns, uint64_t duration_ns);
+int fr_bubble_end(fr_ctx* ctx);
+
+typedef struct fr_progress {
+    int32_t  state;                 /* FR_SUBMITTED .. FR_STOPPED                                          */
+    int32_t  last_error;            /* FR_OK or the error that stopped the task                            */
+    uint64_t runs_completed;
+    uint64_t work_units_done;       /* summed over enqueued steps                                          */
+    uint64_t steps;                 /* steps enqueued                                                      */
+    uint64_t bubbles_seen;
+    uint64_t bubbles_used;          /* bubbles in which at least one step ran                              */
+    uint64_t ns_bubble_declared;    /* sum of declared bubble lengths                                      */
+    uint64_t ns_modelled;           /* sum of modelled step costs, launch_cost included                    */
+    uint64_t ns_measured;           /* sum of measured GPU time of steps (time_steps != 0), resolved so far */
+    uint64_t ns_idle_insufficient;  /* modelled time left idle because the next step did not fit           */
+    uint64_t overruns;
+    uint64_t deadline_misses;
+    uint64_t mem_used_bytes;
+} fr_progress;
+int fr_query_progress(fr_ctx* ctx, fr_task_id id, fr_progress* out);
+
+typedef struct fr_event {
+    uint32_t kind;          /* FR_EV_*                                                                      */
+    uint32_t bubble;        /* 0-based index of the bubble since fr_create                                  */
+    uint32_t run, segment, tile0, tile1;
+    uint64_t modelled_ns;   /* CHUNK/MISS: step cost + launch_cost; IDLE: modelled time left; INIT: 0       */
+    uint64_t work_units;
+    uint64_t t_host_ns;     /* host clock when the record was made                                          */
+    uint64_t measured_ns;   /* CHUNK: GPU time between the previous step's end (or the bubble's first
+                               launch) and this step's end; 0 if not timed or not finished yet              */
+} fr_event;
+/* Copies up to `cap` of the oldest retained records in order; *n_out = number copied.  Resolves finished
+   step timings first.  Does not consume the log; fr_event_log_clear does. */
+int fr_event_log(fr_ctx* ctx, fr_event* buf, size_t cap, size_t* n_out);
+int fr_event_log_clear(fr_ctx* ctx);
+
+/*
+ * The program-directed fit rule as a pure function (Section 4.5): given the cumulative costs
+ * prefix[0..n] (prefix[0] = 0, prefix[i] = cost of tiles 0..i-1) of one segment, the first tile `tile0`
+ * still to do and a budget, returns through *n_fit the largest n with
+ * launch_cost_ns + prefix[tile0 + n] - prefix[tile0] <= budget_ns (0 when not even one tile fits).
+ */
+int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint64_t budget_ns,
+                 uint64_t launch_cost_ns, uint32_t* n_fit);
+
+/* ------------------------------------------------------------------ the PageRank side task */
+/*
+ * Pull-based PageRank over an in-edge CSR, fp32 ranks, fixed iteration count, dangling mass spread uniformly,
+ * Jacobi iterations (the paper's graph-analytics side task, Section 6.1.4; one iteration = one pass over the
+ * graph, Section 6.2).  Work is cut into tiles fixed at init; results do not depend on how tiles are grouped
+ * into launches.  A run is the segment sequence  V_0, P_0, E_0, V_1, P_1, E_1, ..., V_K  where
+ *   V_k (vertex pass)  r_k = 1/V (k = 0) or base_{k-1} + d * acc_{k-1};  contrib_k = r_k / outdeg;
+ *                      per-tile partial sums of dangling r_k;  V_K writes r_K to ranks_out instead;
+ *   P_k (pull pass)    acc_k[v] = sum over v's in-edges of contrib_k[source];
+ *   E_k (epilogue)     sums of rows cut by pull-tile borders;  base_k = (1 - d)/V + d * D_k / V.
+ */
+#define FR_PR_SEG_VERTEX   0
+#define FR_PR_SEG_PULL     1
+#define FR_PR_SEG_EPILOGUE 2
+
+typedef struct fr_pagerank_desc {
+    int64_t  n_vertices;          /* V >= 1                                                                 */
+    int64_t  n_edges;             /* E >= 0, below 2^31                                                     */
+    const int32_t* row_ptr;       /* device, V + 1 entries: in-edge CSR row starts                          */
+    const int32_t* col;           /* device, E entries: source of each in-edge; 16-byte aligned             */
+    const int32_t* out_degree;    /* device, V entries: edges leaving each vertex, with multiplicity        */
+    float*   ranks_out;           /* device, V entries: r_K of the latest completed run                     */
+    float    damping;
+    int32_t  iterations;          /* K >= 0                                                                 */
+    int32_t  max_runs;            /* stop harvesting after this many completed runs; 0 = restart forever    */
+    int32_t  reserved;
+    uint64_t mem_limit_bytes;     /* the task's memory limit; caller buffers above are booked against it    */
+    /* cost model, integer picoseconds, fixed for the task's life (0 = library default) */
+    uint64_t ps_per_edge;         /* pull tile cost    = ceil(edges    * ps_per_edge   / 1000) ns           */
+    uint64_t ps_per_vertex;       /* vertex tile cost  = ceil(vertices * ps_per_vertex / 1000) ns           */
+    uint64_t epilogue_tile_ns;    /* epilogue tile cost                                                     */
+} fr_pagerank_desc;
+
+/* Builds the task object and fills in the callbacks and profile to register with.  No device work yet. */
+int fr_pagerank_make(const fr_pagerank_desc* d, fr_task_ops* ops_out, void** user_out, fr_task_profile* prof_out);
+/* Frees the task object; only after fr_task_stop (or if it was never registered). */
+int fr_pagerank_destroy(void* user);
+/* Bytes the task books against its limit: caller buffers plus what init allocates. */
+int fr_pagerank_footprint(void* user, uint64_t* bytes_out);
+/* Number of tiles of a segment kind (FR_PR_SEG_*), and its modelled tile costs in ns. */
+int fr_pagerank_tiles(void* user, int32_t seg_kind, uint32_t* n_tiles_out);
+int fr_pagerank_tile_costs(void* user, int32_t seg_kind, uint32_t* costs_host, size_t cap, size_t* n_out);
+/* Edges and vertices covered by one tile of the pull / vertex segments (constants of the build). */
+int fr_pagerank_tile_shape(uint32_t* pull_tile_edges_out, uint32_t* vertex_tile_vertices_out);
+/*
+ * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_tiles_per_launch` tiles per
+ * kernel launch (0 = a whole segment per launch), waits for it and leaves r_K in ranks_out.  Same kernels and
+ * tiles as the harvested path: the reference for the "any chunking gives the same bits" property.  The task
+ * must not be registered with a context (it initialises itself against its own mem_limit_bytes on `device_id`).
+ * phase_ns_out (host, 3 entries, may be NULL) receives the summed GPU time of the V, P and E segments.
+ */
+int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint32_t max_tiles_per_launch,
+                               uint64_t* phase_ns_out);
+
+/* ------------------------------------------------------------------ stage load and stage emulator */
+#define FR_LOAD_BUSYWAIT 0   /* one small kernel that spins on the GPU clock for fp_ns / bp_ns              */
+#define FR_LOAD_GPT      1   /* bf16 MFMA GEMM bursts shaped like `layers` transformer blocks               */
+
+typedef struct fr_load fr_load;
+typedef struct fr_load_desc {
+    int32_t  kind;
+    int32_t  layers, hidden, ffn, tokens;   /* FR_LOAD_GPT: all multiples of 256                            */
+    uint64_t fp_ns, bp_ns;                  /* FR_LOAD_BUSYWAIT                                             */
+    void*    workspace;                     /* device; FR_LOAD_GPT operands live here (bf16)                */
+    uint64_t workspace_bytes;
+    uint64_t seed;
+} fr_load_desc;
+int fr_load_workspace_bytes(const fr_load_desc* d, uint64_t* bytes_out);
+/* FR_LOAD_GPT fills the workspace with seeded values on `stream` (may be NULL) and waits for it. */
+int fr_load_make(const fr_load_desc* d, void* stream, fr_load** out);
+int fr_load_destroy(fr_load* l);
+/* Enqueue one forward / backward burst on `stream`: FP = 4 GEMMs per layer (QKV, projection, FFN up, FFN
+   down), BP = the 8 matching data- and weight-gradient GEMMs per layer. */
+int fr_load_fp(fr_load* l, void* stream);
+int fr_load_bp(fr_load* l, void* stream);
+/* Floating-point operations of one FP / BP burst (2 M N K per GEMM); 0 for busy-wait loads. */
+int fr_load_flops(fr_load* l, uint64_t* fp_flops_out, uint64_t* bp_flops_out);
+
+/*
+ * C[M, N] (bf16, row-major) = A[M, K] (bf16, row-major) x B[N, K]^T (bf16, row-major, i.e. both operands
+ * K-contiguous), fp32 accumulation on the MFMA units.  M, N multiples of 256 and K a multiple of 64, else
+ * FR_ERR_ARG.  All pointers device, 16-byte aligned.  Asynchronous on `stream`.
+ */
+int fr_gemm_bf16(const void* A, const void* B, void* C, int32_t M, int32_t N, int32_t K, void* stream);
+
+#define FR_SCHED_1F1B  0
+#define FR_SCHED_GPIPE 1
+typedef struct fr_stage fr_stage;
+typedef struct fr_stage_desc {
+    int32_t  schedule;      /* FR_SCHED_*                                                                   */
+    int32_t  p, m, stage;   /* pipeline depth, micro-batches per epoch, emulated stage (0-based)            */
+    uint64_t f_ns, b_ns;    /* declared FP / BP durations of every stage: fix the waits that stand for the
+                               other stages and the declared bubble lengths                                 */
+} fr_stage_desc;
+typedef struct fr_stage_op {
+    int32_t  kind;          /* 0 = FP, 1 = BP                                                               */
+    int32_t  microbatch;
+    uint64_t start_ns, end_ns;      /* in the ideal schedule, from the epoch start                          */
+    uint64_t bubble_before_ns;      /* idle time in front of this operation (0 = none)                      */
+} fr_stage_op;
+typedef struct fr_epoch_result {
+    uint64_t epoch_ns;          /* wall time of the epoch on this stage                                      */
+    uint64_t busy_ns;           /* sum of measured FP/BP burst times                                         */
+    uint64_t bubble_ns;         /* sum of declared bubble lengths                                            */
+    uint32_t n_ops, n_bubbles;
+    uint32_t overruns;          /* fr_bubble_end calls that reported FR_ERR_OVERRUN                          */
+    uint32_t reserved;
+} fr_epoch_result;
+/* Emulates one stage of a pipeline (Section 2.1): its operation order with the waits the other stages would
+   impose.  `load` supplies the FP/BP work; `stage_stream` is the stream it runs on. */
+int fr_stage_make(const fr_stage_desc* d, fr_load* load, void* stage_stream, fr_stage** out);
+int fr_stage_destroy(fr_stage* s);
+/* The stage's operations in order with ideal start/end times; *epoch_ns_out = ideal epoch length;
+   *tail_bubble_ns_out = idle time after the last operation. */
+int fr_stage_ops(fr_stage* s, fr_stage_op* buf, size_t cap, size_t* n_out, uint64_t* epoch_ns_out,
+                 uint64_t* tail_bubble_ns_out);
+/* Runs one epoch: each operation's burst is enqueued and waited for; each bubble is reported to `ctx`
+   (may be NULL: nothing is reported, the stage just waits) with fr_bubble_begin, waited out on the host
+   clock, and closed with fr_bubble_end. */
+int fr_stage_run_epoch(fr_stage* s, fr_ctx* ctx, fr_epoch_result* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREERIDE_H */

@@ -1,0 +1,287 @@
+// Stage load generator: what the emulated pipeline stage runs between bubbles.
+//
+// The paper harvests the bubbles of a transformer language model trained with pipeline parallelism
+// (Section 6.1.3); its forward and backward passes per micro-batch are the stage's busy periods (Section 2.1).
+// Here one busy period is a burst of bf16 GEMMs with the shapes of `layers` transformer blocks, run on the
+// MFMA units with fp32 accumulation, or (for the small timed configuration) a kernel that spins on the GPU
+// clock for a fixed time.
+
+#include <algorithm>
+#include <new>
+
+#include "common.h"
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+constexpr int BM = 128, BN = 128, BK = 32;     // workgroup tile
+constexpr int kThreads = 256;                  // 4 wavefronts as 2 x 2, each 64 x 64 of C
+constexpr int kLdsRow = BK + 8;                // bf16 elements per LDS row: 64 B of data + 16 B pad
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);           // round to nearest even (inputs here are finite)
+    return (uint16_t)(u >> 16);
+}
+
+// C[M, N] = A[M, K] * B[N, K]^T, bf16 in / bf16 out, fp32 accumulate.  M, N multiples of 128, K of 32.
+__global__ __launch_bounds__(kThreads) void k_gemm_bf16_nt(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                           uint16_t* __restrict__ C, int M, int N, int K)
+{
+    __shared__ __align__(16) uint16_t sA[BM * kLdsRow];
+    __shared__ __align__(16) uint16_t sB[BN * kLdsRow];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tiles_n = N / BN;
+    const int bm = (blockIdx.x / tiles_n) * BM, bn = (blockIdx.x % tiles_n) * BN;
+
+    // global -> register staging: the tile is 128 rows x 64 B; thread t moves 16 B pieces t and t + 256
+    const int ld_row0 = tid >> 2, ld_k = (tid & 3) * 8;
+    const uint16_t* gA = A + (size_t)(bm + ld_row0) * K + ld_k;
+    const uint16_t* gB = B + (size_t)(bn + ld_row0) * K + ld_k;
+    const size_t half = (size_t)64 * K;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    uint4 ra0 = *reinterpret_cast<const uint4*>(gA), ra1 = *reinterpret_cast<const uint4*>(gA + half);
+    uint4 rb0 = *reinterpret_cast<const uint4*>(gB), rb1 = *reinterpret_cast<const uint4*>(gB + half);
+
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        __syncthreads();                       // previous tile fully consumed
+        *reinterpret_cast<uint4*>(&sA[ld_row0 * kLdsRow + ld_k]) = ra0;
+        *reinterpret_cast<uint4*>(&sA[(ld_row0 + 64) * kLdsRow + ld_k]) = ra1;
+        *reinterpret_cast<uint4*>(&sB[ld_row0 * kLdsRow + ld_k]) = rb0;
+        *reinterpret_cast<uint4*>(&sB[(ld_row0 + 64) * kLdsRow + ld_k]) = rb1;
+        __syncthreads();
+        if (k0 + BK < K) {                     // fetch the next tile while this one is multiplied
+            ra0 = *reinterpret_cast<const uint4*>(gA + k0 + BK);
+            ra1 = *reinterpret_cast<const uint4*>(gA + half + k0 + BK);
+            rb0 = *reinterpret_cast<const uint4*>(gB + k0 + BK);
+            rb1 = *reinterpret_cast<const uint4*>(gB + half + k0 + BK);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                fa[i] = *reinterpret_cast<const bf16x8*>(&sA[(wm * 64 + i * 32 + frag_row) * kLdsRow + kk + frag_k]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fb[j] = *reinterpret_cast<const bf16x8*>(&sB[(wn * 64 + j * 32 + frag_row) * kLdsRow + kk + frag_k]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator layout of the 32 x 32 MFMA: lane l holds column l % 32, rows 8 * (r / 4) + 4 * (l / 32) + r % 4
+    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = bm + wm * 64 + i * 32 + 8 * (r >> 2) + row_in + (r & 3);
+                const int col = bn + wn * 64 + j * 32 + col_in;
+                C[(size_t)row * N + col] = f32_to_bf16_rne(acc[i][j][r]);
+            }
+}
+
+// Seeded fill: bf16 values uniform in [-1/8, 1/8) from a counter-based 64-bit mixer.
+__global__ __launch_bounds__(256) void k_fill_bf16(uint16_t* __restrict__ p, uint64_t n, uint64_t seed)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        uint64_t z = seed + i * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        const float u = (float)(z >> 40) * (1.0f / 16777216.0f);      // [0, 1)
+        p[i] = f32_to_bf16_rne((u - 0.5f) * 0.25f);
+    }
+}
+
+// Spins until the GPU's constant-rate clock has advanced by `ticks`, with a hard cap on loop trips so that the
+// kernel ends even if the clock did not advance.
+__global__ void k_busywait(uint64_t ticks, uint64_t max_trips)
+{
+    const uint64_t t0 = wall_clock64();
+    for (uint64_t i = 0; i < max_trips; ++i) {
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(16);
+    }
+}
+
+struct GemmShape { int M, N, K; size_t a_off, b_off, c_off; };   // offsets in bf16 elements into the workspace
+
+}  // namespace
+
+struct fr_load {
+    fr_load_desc d{};
+    int wall_clock_khz = 100000;
+    std::vector<GemmShape> fp, bp;
+    uint64_t fp_flops = 0, bp_flops = 0;
+    int hip_error = 0;
+};
+
+namespace {
+
+uint64_t r128(uint64_t elems) { return (elems + 127) & ~127ull; }
+
+// Lays out operands in the workspace and lists the GEMMs of one forward and one backward burst.
+// Per layer, with T tokens, hidden h, feed-forward width f:
+//   forward : QKV [T,h]x[h,3h], projection [T,h]x[h,h], up [T,h]x[h,f], down [T,f]x[f,h]
+//   backward: for each forward GEMM  Y[T,n] = X[T,k] W[n,k]^T  the data gradient  dX[T,k] = dY[T,n] W
+//             (M = T, N = k, K = n) and the weight gradient  dW[n,k] = dY^T X  (M = n, N = k, K = T).
+// Weights are distinct per layer; activations, gradients and the weight-gradient scratch are shared by layers.
+uint64_t plan_gpt(fr_load* l, bool fill_lists)
+{
+    const fr_load_desc& d = l->d;
+    const uint64_t T = d.tokens, h = d.hidden, f = d.ffn;
+    uint64_t off = 0;
+    auto take = [&](uint64_t elems) { uint64_t o = off; off += r128(elems); return o; };
+    const uint64_t n_out[4] = {3 * h, h, f, h}, k_in[4] = {h, h, h, f};
+    uint64_t maxn = 0, maxk = 0, maxw = 0;
+    for (int g = 0; g < 4; ++g) { maxn = std::max(maxn, n_out[g]); maxk = std::max(maxk, k_in[g]); maxw = std::max(maxw, n_out[g] * k_in[g]); }
+    const uint64_t x = take(T * maxk), y = take(T * maxn), dy = take(T * maxn), dx = take(T * maxk);
+    const uint64_t xt = take(T * maxk), dyt = take(T * maxn), dw = take(maxw), wt = take(maxw);
+    for (int layer = 0; layer < d.layers; ++layer) {
+        for (int g = 0; g < 4; ++g) {
+            const uint64_t w = take(n_out[g] * k_in[g]);
+            if (!fill_lists) continue;
+            l->fp.push_back({(int)T, (int)n_out[g], (int)k_in[g], x, w, y});
+            // dX = dY[T, n] x (W^T)[k, n]^T : the B operand is K-contiguous when read from the transposed copy
+            l->bp.push_back({(int)T, (int)k_in[g], (int)n_out[g], dy, wt, dx});
+            // dW = (dY^T)[n, T] x (X^T)[k, T]^T
+            l->bp.push_back({(int)n_out[g], (int)k_in[g], (int)T, dyt, xt, dw});
+        }
+    }
+    return off;
+}
+
+int gemm_launch(const void* A, const void* B, void* C, int M, int N, int K, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)((M / BM) * (N / BN));
+    hipLaunchKernelGGL(k_gemm_bf16_nt, dim3(grid), dim3(kThreads), 0, stream, (const uint16_t*)A, (const uint16_t*)B,
+                       (uint16_t*)C, M, N, K);
+    return hipGetLastError() == hipSuccess ? FR_OK : FR_ERR_HIP;
+}
+
+int burst(fr_load* l, const std::vector<GemmShape>& list, uint64_t ns, hipStream_t stream)
+{
+    if (l->d.kind == FR_LOAD_BUSYWAIT) return fr_busywait_launch(ns, l->wall_clock_khz, stream);
+    uint16_t* ws = static_cast<uint16_t*>(l->d.workspace);
+    for (const GemmShape& g : list) {
+        int rc = gemm_launch(ws + g.a_off, ws + g.b_off, ws + g.c_off, g.M, g.N, g.K, stream);
+        if (rc != FR_OK) return rc;
+    }
+    return FR_OK;
+}
+
+}  // namespace
+
+int fr_busywait_launch(uint64_t ns, int wall_clock_khz, hipStream_t stream)
+{
+    const uint64_t ticks = (uint64_t)((unsigned __int128)ns * (uint64_t)wall_clock_khz / 1000000ull);
+    const uint64_t max_trips = ns / 20 + 4096;        // one trip takes well over 20 ns
+    hipLaunchKernelGGL(k_busywait, dim3(1), dim3(64), 0, stream, ticks, max_trips);
+    return hipGetLastError() == hipSuccess ? FR_OK : FR_ERR_HIP;
+}
+
+extern "C" {
+
+int fr_gemm_bf16(const void* A, const void* B, void* C, int32_t M, int32_t N, int32_t K, void* stream)
+{
+    if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0) return FR_ERR_ARG;
+    if (M % 256 || N % 256 || K % 64) return FR_ERR_ARG;
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) return FR_ERR_ARG;
+    if ((uint64_t)(M / BM) * (uint64_t)(N / BN) > 0x7fffffffull) return FR_ERR_ARG;
+    return gemm_launch(A, B, C, M, N, K, (hipStream_t)stream);
+}
+
+int fr_load_workspace_bytes(const fr_load_desc* d, uint64_t* bytes_out)
+{
+    if (!d || !bytes_out) return FR_ERR_ARG;
+    if (d->kind == FR_LOAD_BUSYWAIT) { *bytes_out = 0; return FR_OK; }
+    if (d->kind != FR_LOAD_GPT) return FR_ERR_ARG;
+    if (d->layers < 1 || d->layers > 1024 || d->hidden < 256 || d->ffn < 256 || d->tokens < 256) return FR_ERR_ARG;
+    if (d->hidden % 256 || d->ffn % 256 || d->tokens % 256) return FR_ERR_ARG;
+    if (d->hidden > 65536 || d->ffn > 262144 || d->tokens > 1048576) return FR_ERR_ARG;
+    fr_load tmp;
+    tmp.d = *d;
+    *bytes_out = plan_gpt(&tmp, false) * 2;
+    return FR_OK;
+}
+
+int fr_load_make(const fr_load_desc* d, void* stream, fr_load** out)
+{
+    if (!d || !out) return FR_ERR_ARG;
+    uint64_t need = 0;
+    int rc = fr_load_workspace_bytes(d, &need);
+    if (rc != FR_OK) return rc;
+    fr_load* l = new (std::nothrow) fr_load();
+    if (!l) return FR_ERR_ARG;
+    l->d = *d;
+    if (d->kind == FR_LOAD_BUSYWAIT) {
+        if (d->fp_ns == 0 || d->bp_ns == 0 || d->fp_ns > 10000000000ull || d->bp_ns > 10000000000ull) { delete l; return FR_ERR_ARG; }
+        int dev = 0, khz = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+            delete l;
+            return FR_ERR_HIP;
+        }
+        l->wall_clock_khz = khz;
+        *out = l;
+        return FR_OK;
+    }
+    if (!d->workspace || d->workspace_bytes < need || ((uintptr_t)d->workspace & 255)) { delete l; return FR_ERR_ARG; }
+    plan_gpt(l, true);
+    for (const GemmShape& g : l->fp) l->fp_flops += 2ull * g.M * g.N * g.K;
+    for (const GemmShape& g : l->bp) l->bp_flops += 2ull * g.M * g.N * g.K;
+    hipLaunchKernelGGL(k_fill_bf16, dim3(4096), dim3(256), 0, (hipStream_t)stream, (uint16_t*)d->workspace, need / 2, d->seed);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize((hipStream_t)stream) != hipSuccess) { delete l; return FR_ERR_HIP; }
+    *out = l;
+    return FR_OK;
+}
+
+int fr_load_destroy(fr_load* l)
+{
+    if (!l) return FR_ERR_ARG;
+    delete l;
+    return FR_OK;
+}
+
+int fr_load_fp(fr_load* l, void* stream)
+{
+    if (!l) return FR_ERR_ARG;
+    return burst(l, l->fp, l->d.fp_ns, (hipStream_t)stream);
+}
+
+int fr_load_bp(fr_load* l, void* stream)
+{
+    if (!l) return FR_ERR_ARG;
+    return burst(l, l->bp, l->d.bp_ns, (hipStream_t)stream);
+}
+
+int fr_load_flops(fr_load* l, uint64_t* fp, uint64_t* bp)
+{
+    if (!l || !fp || !bp) return FR_ERR_ARG;
+    *fp = l->fp_flops;
+    *bp = l->bp_flops;
+    return FR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,575 @@
+// Bubble-harvesting runtime: side-task state machine, worker thread, step planning loop, memory accounting,
+// event log.  Follows FreeRide (arXiv 2409.06941): Section 4.1 (states and transitions), Section 4.4
+// (Algorithm 1: admission by memory; Algorithm 2: bubble -> Init / Start / Pause), Section 4.5 (program-directed
+// time limit, memory limit).  The paper's manager / worker / task processes are one worker thread here.
+
+#include <time.h>
+
+#include <atomic>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <thread>
+
+#include "common.h"
+
+namespace {
+
+inline void cpu_relax()
+{
+    __builtin_ia32_pause();
+}
+
+// A step's GPU time is measured between two events.  Inside a bubble the steps form a chain: the end event
+// of one step is the begin event of the next, so the measured times add up to the chain's span.
+struct PendingTiming {
+    uint64_t log_seq;        // sequence number of the CHUNK record this timing belongs to
+    hipEvent_t begin;
+    hipEvent_t end;
+};
+
+struct Task {
+    fr_task_ops ops{};
+    void* user = nullptr;
+    fr_task_profile prof{};
+    fr_task_id id = 0;
+    int state = FR_SUBMITTED;
+    int last_error = FR_OK;
+    fr_alloc alloc;
+    fr_progress prog{};
+};
+
+}  // namespace
+
+struct fr_ctx {
+    fr_config cfg{};
+    bool host_only = false;
+    hipStream_t side = nullptr;
+    int hip_error = 0;
+
+    std::mutex mu;                 // guards task, progress, log
+    std::mutex work_mu;            // held by the worker while it runs task callbacks for a bubble
+    std::thread worker;
+    std::atomic<bool> quit{false};
+    std::atomic<bool> abort_steps{false};   // fr_task_stop / fr_destroy ask the step loop to leave
+
+    // bubble hand-off (stage thread -> worker)
+    std::atomic<uint64_t> bubble_seq{0};    // bumped by fr_bubble_begin after the fields below are written
+    std::atomic<uint64_t> ack_seq{0};       // worker: "I will enqueue nothing more for bubble ack_seq"
+    std::atomic<bool> end_requested{false};
+    bool bubble_open = false;               // stage thread only
+    uint64_t cur_begin = 0, cur_len = 0;
+    uint32_t cur_index = 0;                 // 0-based bubble index
+    uint64_t bubbles_total = 0;
+
+    Task* task = nullptr;
+    fr_task_id next_id = 1;
+
+    // event log ring
+    std::vector<fr_event> log;
+    uint64_t log_first_seq = 0;             // sequence number of log[log_head]
+    size_t log_head = 0, log_count = 0;
+
+    // step timing
+    std::vector<hipEvent_t> free_events;
+    std::deque<PendingTiming> pending;
+    hipEvent_t chain_tail = nullptr;        // end event of the newest step of the bubble being served
+};
+
+namespace {
+
+uint64_t now_ns()
+{
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (uint64_t)ts.tv_sec * 1000000000ull + (uint64_t)ts.tv_nsec;
+}
+
+// ---- log (ctx->mu held) ----
+uint64_t log_push(fr_ctx* c, const fr_event& ev)
+{
+    const size_t cap = c->log.size();
+    uint64_t seq = c->log_first_seq + c->log_count;
+    if (c->log_count == cap) {            // drop the oldest
+        c->log_head = (c->log_head + 1) % cap;
+        c->log_first_seq++;
+        c->log_count--;
+    }
+    c->log[(c->log_head + c->log_count) % cap] = ev;
+    c->log_count++;
+    return seq;
+}
+
+fr_event* log_at(fr_ctx* c, uint64_t seq)
+{
+    if (seq < c->log_first_seq || seq >= c->log_first_seq + c->log_count) return nullptr;
+    return &c->log[(c->log_head + (seq - c->log_first_seq)) % c->log.size()];
+}
+
+hipEvent_t event_get(fr_ctx* c)
+{
+    if (!c->free_events.empty()) {
+        hipEvent_t e = c->free_events.back();
+        c->free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Resolve finished step timings (ctx->mu held).  wait = true blocks until every pending step has finished.
+void resolve_timings(fr_ctx* c, bool wait)
+{
+    while (!c->pending.empty()) {
+        PendingTiming& p = c->pending.front();
+        hipError_t q = wait ? hipEventSynchronize(p.end) : hipEventQuery(p.end);
+        if (q == hipErrorNotReady) break;
+        float ms = 0.f;
+        if (q == hipSuccess && hipEventElapsedTime(&ms, p.begin, p.end) == hipSuccess) {
+            const uint64_t ns = (uint64_t)((double)ms * 1.0e6 + 0.5);
+            if (fr_event* ev = log_at(c, p.log_seq)) ev->measured_ns = ns;
+            if (c->task) c->task->prog.ns_measured += ns;
+        }
+        // Steps resolve in order, so nothing older still needs this begin event.  The end event lives on if a
+        // later step uses (or may still come to use) it as its begin; that step releases it.
+        c->free_events.push_back(p.begin);
+        const bool next_begins_here = c->pending.size() > 1 && c->pending[1].begin == p.end;
+        if (p.end != c->chain_tail && !next_begins_here) c->free_events.push_back(p.end);
+        c->pending.pop_front();
+    }
+}
+
+void stop_task_locked(fr_ctx* c, Task* t, int error)
+{
+    // ctx->mu held, work_mu held by the caller or caller is the worker itself
+    if (t->state == FR_STOPPED) return;
+    if (!c->host_only && c->side) (void)hipStreamSynchronize(c->side);
+    resolve_timings(c, true);
+    if (t->ops.stop) t->ops.stop(t->user);
+    t->prog.mem_used_bytes = t->alloc.used;
+    fr_alloc_release(&t->alloc);
+    t->state = FR_STOPPED;
+    if (error != FR_OK) t->last_error = error;
+}
+
+// One bubble, on the worker thread, work_mu held.
+void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint32_t index)
+{
+    Task* t;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        t = c->task;
+        if (!t) return;
+        t->prog.bubbles_seen++;
+        t->prog.ns_bubble_declared += len;
+    }
+    auto stop_now = [&]() { return c->end_requested.load(std::memory_order_acquire) || c->abort_steps.load() || c->quit.load(); };
+
+    if (t->state == FR_CREATED) {
+        // Algorithm 2: a CREATED current task is initialised by the new bubble.
+        int rc = t->ops.init ? t->ops.init(t->user, &t->alloc, (void*)c->side) : FR_OK;
+        std::lock_guard<std::mutex> lk(c->mu);
+        fr_event ev{};
+        ev.kind = FR_EV_INIT; ev.bubble = index; ev.t_host_ns = now_ns();
+        log_push(c, ev);
+        t->prog.mem_used_bytes = t->alloc.used;
+        if (t->alloc.oom) stop_task_locked(c, t, FR_ERR_OOM);
+        else if (rc != FR_OK) {
+            if (rc == FR_ERR_HIP) c->hip_error = t->alloc.hip_error ? t->alloc.hip_error : c->hip_error;
+            stop_task_locked(c, t, rc);
+        } else t->state = FR_PAUSED;
+        return;
+    }
+    if (t->state != FR_PAUSED) return;
+
+    {   // StartSideTask(): the task learns the bubble's end time
+        std::lock_guard<std::mutex> lk(c->mu);
+        t->state = FR_RUNNING;
+    }
+    const uint64_t guard = c->cfg.guard_ns, launch = c->cfg.launch_cost_ns;
+    const uint64_t max_chunk = c->cfg.max_chunk_ns ? c->cfg.max_chunk_ns : ~0ull;
+    const uint32_t max_inflight = c->cfg.max_inflight ? c->cfg.max_inflight : 8;
+    const bool timed = c->cfg.time_steps && !c->host_only;
+    int64_t remaining = (int64_t)len - (int64_t)guard;
+    const int64_t total = remaining;
+    bool used = false;
+    int fail = FR_OK;
+
+    while (!stop_now()) {
+        const uint64_t budget = remaining > 0 ? ((uint64_t)remaining < max_chunk ? (uint64_t)remaining : max_chunk) : 0;
+        fr_step st{};
+        int rc = t->ops.plan_step(t->user, budget, launch, &st);
+        if (rc != FR_OK) { fail = rc; break; }
+        if (st.finished) break;
+        if (st.modelled_ns == 0) {
+            // the remaining time is not enough for the next step: leave the rest of the bubble idle
+            std::lock_guard<std::mutex> lk(c->mu);
+            fr_event ev{};
+            ev.kind = FR_EV_IDLE; ev.bubble = index; ev.run = st.run; ev.segment = st.segment;
+            ev.tile0 = st.tile0; ev.tile1 = st.tile0;
+            ev.modelled_ns = remaining > 0 ? (uint64_t)remaining : 0; ev.t_host_ns = now_ns();
+            log_push(c, ev);
+            t->prog.ns_idle_insufficient += ev.modelled_ns;
+            break;
+        }
+        const uint64_t cost = st.modelled_ns + launch;
+        // real-clock check: the model says the step ends `consumed + cost` after the bubble began; if the
+        // host is later than that, the step must still end before the declared end of the bubble
+        const uint64_t consumed = (uint64_t)(total - remaining);
+        const uint64_t now = now_ns();
+        const uint64_t start_est = now > t_begin + consumed ? now : t_begin + consumed;
+        if (start_est + cost > t_begin + len) {
+            std::lock_guard<std::mutex> lk(c->mu);
+            fr_event ev{};
+            ev.kind = FR_EV_MISS; ev.bubble = index; ev.run = st.run; ev.segment = st.segment;
+            ev.tile0 = st.tile0; ev.tile1 = st.tile1; ev.modelled_ns = cost; ev.work_units = st.work_units;
+            ev.t_host_ns = now;
+            log_push(c, ev);
+            t->prog.deadline_misses++;
+            break;
+        }
+        if (timed) {
+            // bound the number of steps enqueued ahead of the GPU
+            bool left = false;
+            for (;;) {
+                size_t inflight;
+                {
+                    std::lock_guard<std::mutex> lk(c->mu);
+                    resolve_timings(c, false);
+                    inflight = c->pending.size();
+                }
+                if (inflight < max_inflight) break;
+                if (stop_now()) { left = true; break; }
+                cpu_relax();
+            }
+            if (left) break;
+        }
+        hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+        bool chain_head = false;
+        if (timed) {
+            std::lock_guard<std::mutex> lk(c->mu);
+            if (c->chain_tail) ev_begin = c->chain_tail;
+            else { ev_begin = event_get(c); chain_head = true; }
+            ev_end = event_get(c);
+        }
+        if (timed && chain_head && ev_begin) (void)hipEventRecord(ev_begin, c->side);
+        rc = t->ops.run_step(t->user, (void*)c->side, &st);
+        if (timed && ev_end) (void)hipEventRecord(ev_end, c->side);
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            fr_event ev{};
+            ev.kind = FR_EV_CHUNK; ev.bubble = index; ev.run = st.run; ev.segment = st.segment;
+            ev.tile0 = st.tile0; ev.tile1 = st.tile1; ev.modelled_ns = cost; ev.work_units = st.work_units;
+            ev.t_host_ns = now;
+            const uint64_t lseq = log_push(c, ev);
+            if (timed && ev_begin && ev_end) {
+                c->pending.push_back(PendingTiming{lseq, ev_begin, ev_end});
+                c->chain_tail = ev_end;
+            }
+            t->prog.steps++;
+            t->prog.work_units_done += st.work_units;
+            t->prog.ns_modelled += cost;
+            if (st.completes_run) t->prog.runs_completed++;
+            if (!used) { used = true; t->prog.bubbles_used++; }
+        }
+        if (rc != FR_OK) { fail = rc; break; }
+        remaining -= (int64_t)cost;
+    }
+    (void)seq;
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->chain_tail) {
+        // close the chain: nobody will begin at its tail any more
+        bool unresolved = false;
+        for (const PendingTiming& p : c->pending) unresolved |= (p.end == c->chain_tail);
+        if (!unresolved) c->free_events.push_back(c->chain_tail);
+        c->chain_tail = nullptr;
+    }
+    if (fail != FR_OK) stop_task_locked(c, t, fail);
+    else if (t->state == FR_RUNNING) t->state = FR_PAUSED;   // PauseSideTask()
+}
+
+void worker_main(fr_ctx* c)
+{
+    if (!c->host_only) (void)hipSetDevice(c->cfg.device_id);
+    uint64_t seen = 0;
+    uint32_t idle_spins = 0;
+    while (!c->quit.load(std::memory_order_acquire)) {
+        const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
+        if (seq == seen) {
+            // Spin while a live task may be handed a bubble at any moment; back off otherwise.
+            if (++idle_spins > 20000) {
+                bool live;
+                {
+                    std::lock_guard<std::mutex> lk(c->mu);
+                    live = c->task && c->task->state != FR_STOPPED;
+                    if (live && !c->pending.empty()) resolve_timings(c, false);
+                }
+                if (!live) std::this_thread::sleep_for(std::chrono::microseconds(200));
+                idle_spins = 0;
+            } else cpu_relax();
+            continue;
+        }
+        idle_spins = 0;
+        seen = seq;
+        const uint64_t t_begin = c->cur_begin, len = c->cur_len;
+        const uint32_t index = c->cur_index;
+        {
+            std::lock_guard<std::mutex> wl(c->work_mu);
+            serve_bubble(c, seq, t_begin, len, index);
+        }
+        c->ack_seq.store(seq, std::memory_order_release);
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ allocator
+void fr_alloc_reset(fr_alloc* a, uint64_t limit, bool host_only, int device)
+{
+    a->limit = limit; a->used = 0; a->oom = false; a->host_only = host_only; a->device = device;
+    a->hip_error = 0; a->blocks.clear();
+}
+
+void fr_alloc_release(fr_alloc* a)
+{
+    for (void* p : a->blocks) {
+        if (a->host_only) std::free(p);
+        else (void)hipFree(p);
+    }
+    a->blocks.clear();
+    a->used = 0;
+}
+
+extern "C" {
+
+uint64_t fr_now_ns(void) { return now_ns(); }
+
+void* fr_alloc_device(fr_alloc* a, size_t bytes)
+{
+    if (!a || a->oom) return nullptr;
+    const uint64_t rounded = ((uint64_t)bytes + 255) & ~255ull;
+    if (rounded > a->limit || a->used > a->limit - rounded) { a->oom = true; return nullptr; }
+    void* p = nullptr;
+    if (a->host_only) {
+        p = std::aligned_alloc(256, rounded ? rounded : 256);
+        if (!p) { a->oom = true; return nullptr; }
+    } else {
+        hipError_t e = hipMalloc(&p, rounded ? rounded : 256);
+        if (e != hipSuccess) { a->hip_error = (int)e; a->oom = true; return nullptr; }
+    }
+    a->blocks.push_back(p);
+    a->used += rounded;
+    return p;
+}
+
+int fr_alloc_charge(fr_alloc* a, size_t bytes)
+{
+    if (!a) return FR_ERR_ARG;
+    if (a->oom) return FR_ERR_OOM;
+    if ((uint64_t)bytes > a->limit || a->used > a->limit - (uint64_t)bytes) { a->oom = true; return FR_ERR_OOM; }
+    a->used += bytes;
+    return FR_OK;
+}
+
+uint64_t fr_alloc_used(const fr_alloc* a) { return a ? a->used : 0; }
+
+// ------------------------------------------------------------------ context
+int fr_create(const fr_config* cfg, fr_ctx** out)
+{
+    if (!cfg || !out) return FR_ERR_ARG;
+    if (cfg->cu_count > 256) return FR_ERR_ARG;
+    fr_ctx* c = new (std::nothrow) fr_ctx();
+    if (!c) return FR_ERR_ARG;
+    c->cfg = *cfg;
+    c->host_only = cfg->device_id < 0;
+    c->log.resize(cfg->event_log_capacity ? cfg->event_log_capacity : 65536);
+    if (!c->host_only) {
+        int n = 0;
+        hipError_t e = hipGetDeviceCount(&n);
+        if (e != hipSuccess || cfg->device_id >= n) { c->hip_error = (int)e; delete c; return e != hipSuccess ? FR_ERR_HIP : FR_ERR_ARG; }
+        e = hipSetDevice(cfg->device_id);
+        if (e != hipSuccess) { delete c; return FR_ERR_HIP; }
+        uint32_t mask[8] = {0};
+        bool masked = false;
+        if (cfg->cu_count > 0 && cfg->cu_count < 256) {
+            for (uint32_t i = 0; i < cfg->cu_count; ++i) mask[i / 32] |= 1u << (i % 32);
+            masked = true;
+        } else if (cfg->cu_count == 0) {
+            for (int i = 0; i < 8; ++i) { mask[i] = cfg->cu_mask[i]; masked |= mask[i] != 0; }
+        }
+        // Both stream kinds keep the default priority.
+        if (masked) e = hipExtStreamCreateWithCUMask(&c->side, 8, mask);
+        else e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+        if (e != hipSuccess) { delete c; return FR_ERR_HIP; }
+    }
+    c->worker = std::thread(worker_main, c);
+    *out = c;
+    return FR_OK;
+}
+
+int fr_destroy(fr_ctx* c)
+{
+    if (!c) return FR_ERR_ARG;
+    c->abort_steps.store(true);
+    c->end_requested.store(true);
+    c->quit.store(true, std::memory_order_release);
+    if (c->worker.joinable()) c->worker.join();
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (c->task) {
+            stop_task_locked(c, c->task, FR_OK);
+            delete c->task;
+            c->task = nullptr;
+        }
+        resolve_timings(c, true);
+        for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
+        c->free_events.clear();
+    }
+    if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+    delete c;
+    return FR_OK;
+}
+
+int fr_side_stream(fr_ctx* c, void** out)
+{
+    if (!c || !out) return FR_ERR_ARG;
+    *out = (void*)c->side;
+    return FR_OK;
+}
+
+int fr_last_hip_error(fr_ctx* c) { return c ? c->hip_error : 0; }
+
+// ------------------------------------------------------------------ task
+int fr_task_register(fr_ctx* c, const fr_task_ops* ops, void* user, const fr_task_profile* prof, fr_task_id* id_out)
+{
+    if (!c || !ops || !prof || !id_out || !ops->plan_step || !ops->run_step) return FR_ERR_ARG;
+    std::lock_guard<std::mutex> wl(c->work_mu);
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->task && c->task->state != FR_STOPPED) return FR_ERR_STATE;
+    // Algorithm 1 with a single worker: the worker qualifies only if its free memory exceeds the task's need.
+    if (!(c->cfg.mem_available_bytes > prof->mem_limit_bytes)) return FR_ERR_NOMEM;   // RejectSideTask()
+    delete c->task;
+    Task* t = new (std::nothrow) Task();
+    if (!t) return FR_ERR_ARG;
+    t->ops = *ops; t->user = user; t->prof = *prof; t->id = c->next_id++;
+    fr_alloc_reset(&t->alloc, prof->mem_limit_bytes, c->host_only, c->cfg.device_id);
+    t->state = FR_SUBMITTED;
+    int rc = ops->create ? ops->create(user) : FR_OK;      // CreateSideTask()
+    if (rc != FR_OK) { delete t; c->task = nullptr; return rc; }
+    t->state = FR_CREATED;
+    c->task = t;
+    *id_out = t->id;
+    return FR_OK;
+}
+
+int fr_task_stop(fr_ctx* c, fr_task_id id)
+{
+    if (!c) return FR_ERR_ARG;
+    c->abort_steps.store(true);
+    std::lock_guard<std::mutex> wl(c->work_mu);     // the worker is outside every callback now
+    c->abort_steps.store(false);
+    std::lock_guard<std::mutex> lk(c->mu);
+    Task* t = c->task;
+    if (!t || t->id != id) return FR_ERR_ARG;
+    if (t->state == FR_STOPPED || t->state == FR_SUBMITTED) return FR_ERR_STATE;
+    stop_task_locked(c, t, FR_OK);
+    return FR_OK;
+}
+
+int fr_bubble_begin(fr_ctx* c, uint64_t t_begin_ns, uint64_t duration_ns)
+{
+    if (!c) return FR_ERR_ARG;
+    if (c->bubble_open) return FR_ERR_STATE;
+    c->bubble_open = true;
+    c->cur_begin = t_begin_ns;
+    c->cur_len = duration_ns;
+    c->cur_index = (uint32_t)c->bubbles_total++;
+    c->end_requested.store(false, std::memory_order_release);
+    c->bubble_seq.fetch_add(1, std::memory_order_release);
+    return FR_OK;
+}
+
+int fr_bubble_end(fr_ctx* c)
+{
+    if (!c) return FR_ERR_ARG;
+    if (!c->bubble_open) return FR_ERR_STATE;
+    c->end_requested.store(true, std::memory_order_release);
+    const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
+    while (c->ack_seq.load(std::memory_order_acquire) != seq) cpu_relax();   // worker enqueues nothing more
+    c->bubble_open = false;
+    if (c->host_only || !c->side) return FR_OK;
+    bool has_task;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        has_task = c->task && c->task->state != FR_STOPPED && c->task->state != FR_CREATED;
+    }
+    if (!has_task) return FR_OK;
+    hipError_t q = hipStreamQuery(c->side);
+    if (q == hipErrorNotReady) {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (c->task) c->task->prog.overruns++;
+        return FR_ERR_OVERRUN;
+    }
+    if (q != hipSuccess) { c->hip_error = (int)q; return FR_ERR_HIP; }
+    return FR_OK;
+}
+
+int fr_query_progress(fr_ctx* c, fr_task_id id, fr_progress* out)
+{
+    if (!c || !out) return FR_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    Task* t = c->task;
+    if (!t || t->id != id) return FR_ERR_ARG;
+    if (!c->host_only) resolve_timings(c, false);
+    *out = t->prog;
+    out->state = t->state;
+    out->last_error = t->last_error;
+    if (t->state != FR_STOPPED) out->mem_used_bytes = t->alloc.used;
+    return FR_OK;
+}
+
+int fr_event_log(fr_ctx* c, fr_event* buf, size_t cap, size_t* n_out)
+{
+    if (!c || !n_out || (!buf && cap)) return FR_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->host_only) resolve_timings(c, false);
+    const size_t n = c->log_count < cap ? c->log_count : cap;
+    for (size_t i = 0; i < n; ++i) buf[i] = c->log[(c->log_head + i) % c->log.size()];
+    *n_out = n;
+    return FR_OK;
+}
+
+int fr_event_log_clear(fr_ctx* c)
+{
+    if (!c) return FR_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->host_only) resolve_timings(c, true);
+    c->log_first_seq += c->log_count;
+    c->log_head = 0;
+    c->log_count = 0;
+    return FR_OK;
+}
+
+int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint64_t budget_ns,
+                 uint64_t launch_cost_ns, uint32_t* n_fit)
+{
+    if (!prefix || !n_fit || tile0 > n_tiles) return FR_ERR_ARG;
+    *n_fit = 0;
+    if (budget_ns < launch_cost_ns) return FR_OK;
+    const uint64_t room = budget_ns - launch_cost_ns;
+    const uint64_t base = prefix[tile0];
+    // largest index hi in [tile0, n_tiles] with prefix[hi] - base <= room
+    uint32_t lo = tile0, hi = n_tiles;
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo + 1) / 2;
+        if (prefix[mid] - base <= room) lo = mid;
+        else hi = mid - 1;
+    }
+    *n_fit = lo - tile0;
+    return FR_OK;
+}
+
+}  // extern "C"

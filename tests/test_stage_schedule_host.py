@@ -1,0 +1,37 @@
+"""The library's ideal stage schedule equals the oracle simulator's, window for window (host only)."""
+import pytest
+
+import paper_2409_06941_amd as fr
+from oracle import schedule
+
+KIND = {"1f1b": fr.FR_SCHED_1F1B, "gpipe": fr.FR_SCHED_GPIPE}
+
+
+@pytest.mark.parametrize("sched", ["1f1b", "gpipe"])
+@pytest.mark.parametrize("p,m", [(1, 1), (4, 8), (8, 16), (8, 32), (16, 16), (5, 3), (3, 7)])
+@pytest.mark.parametrize("f,b", [(2_000_000, 4_000_000), (3_000_001, 2_999_999), (7, 11)])
+def test_ops_and_bubbles_match_oracle(sched, p, m, f, b):
+    timed, T = schedule.simulate(sched, p, m, f, b)
+    for s in range(p):
+        st = fr.Stage(KIND[sched], p, m, s, f, b)
+        ops, epoch, tail = st.fr_stage_ops()
+        st.fr_stage_destroy()
+        assert epoch == T
+        assert [("F" if o.kind == 0 else "B", o.microbatch, o.start_ns, o.end_ns) for o in ops] == \
+            [(o.kind, o.mb, o.start, o.end) for o in timed[s]]
+        windows, _ = schedule.bubbles(sched, p, m, f, b, s)
+        got, t = [], 0
+        for o in ops:
+            if o.bubble_before_ns:
+                got.append((o.start_ns - o.bubble_before_ns, o.start_ns))
+            t = o.end_ns
+        if tail:
+            got.append((t, t + tail))
+        assert got == windows
+
+
+def test_bad_stage_arguments_are_rejected():
+    for args in [(0, 0, 4, 0, 1, 1), (0, 4, 0, 0, 1, 1), (0, 4, 4, 4, 1, 1), (0, 4, 4, 0, 0, 1), (7, 4, 4, 0, 1, 1)]:
+        with pytest.raises(fr.FreeRideError) as e:
+            fr.Stage(*args)
+        assert e.value.code == fr.FR_ERR_ARG
