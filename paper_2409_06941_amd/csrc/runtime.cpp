@@ -76,6 +76,12 @@ struct fr_ctx {
     std::vector<hipEvent_t> free_events;
     std::deque<PendingTiming> pending;
     hipEvent_t chain_tail = nullptr;        // end event of the newest step of the bubble being served
+
+    // Overrun detection: the worker records this event behind the last work it enqueued for a bubble;
+    // fr_bubble_end asks whether it has completed.  (A stream query is not used: it may report "not ready"
+    // for a stream whose last command carries no completion signal, although all work has finished.)
+    hipEvent_t tail_event = nullptr;
+    bool tail_armed = false;                // written by the worker before ack_seq, read after it
 };
 
 namespace {
@@ -181,6 +187,8 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             if (rc == FR_ERR_HIP) c->hip_error = t->alloc.hip_error ? t->alloc.hip_error : c->hip_error;
             stop_task_locked(c, t, rc);
         } else t->state = FR_PAUSED;
+        if (!c->host_only && c->tail_event && t->state == FR_PAUSED)
+            c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
         return;
     }
     if (t->state != FR_PAUSED) return;
@@ -279,6 +287,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         remaining -= (int64_t)cost;
     }
     (void)seq;
+    if (used && !c->host_only && c->tail_event) c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->chain_tail) {
         // close the chain: nobody will begin at its tail any more
@@ -316,6 +325,7 @@ void worker_main(fr_ctx* c)
         seen = seq;
         const uint64_t t_begin = c->cur_begin, len = c->cur_len;
         const uint32_t index = c->cur_index;
+        c->tail_armed = false;
         {
             std::lock_guard<std::mutex> wl(c->work_mu);
             serve_bubble(c, seq, t_begin, len, index);
@@ -404,6 +414,8 @@ int fr_create(const fr_config* cfg, fr_ctx** out)
         if (masked) e = hipExtStreamCreateWithCUMask(&c->side, 8, mask);
         else e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
         if (e != hipSuccess) { delete c; return FR_ERR_HIP; }
+        e = hipEventCreateWithFlags(&c->tail_event, hipEventDisableTiming);
+        if (e != hipSuccess) { (void)hipStreamDestroy(c->side); delete c; return FR_ERR_HIP; }
     }
     c->worker = std::thread(worker_main, c);
     *out = c;
@@ -429,6 +441,7 @@ int fr_destroy(fr_ctx* c)
         c->free_events.clear();
     }
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+    if (c->tail_event) (void)hipEventDestroy(c->tail_event);
     delete c;
     return FR_OK;
 }
@@ -500,14 +513,8 @@ int fr_bubble_end(fr_ctx* c)
     const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
     while (c->ack_seq.load(std::memory_order_acquire) != seq) cpu_relax();   // worker enqueues nothing more
     c->bubble_open = false;
-    if (c->host_only || !c->side) return FR_OK;
-    bool has_task;
-    {
-        std::lock_guard<std::mutex> lk(c->mu);
-        has_task = c->task && c->task->state != FR_STOPPED && c->task->state != FR_CREATED;
-    }
-    if (!has_task) return FR_OK;
-    hipError_t q = hipStreamQuery(c->side);
+    if (c->host_only || !c->tail_armed) return FR_OK;     // nothing was enqueued for this bubble
+    hipError_t q = hipEventQuery(c->tail_event);
     if (q == hipErrorNotReady) {
         std::lock_guard<std::mutex> lk(c->mu);
         if (c->task) c->task->prog.overruns++;
