@@ -87,17 +87,25 @@ def main():
     side_probe = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0)
     cal_iters = 5
     cal = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=cal_iters)
-    cal.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 0, want_phase_ns=False)      # warm
+    t_init = time.time()
+    cal.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 0, want_phase_ns=False)      # init + warm
+    t_init = time.time() - t_init
     ph = cal.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 0, want_phase_ns=True)
-    n_epi = cal.fr_pagerank_tiles(fr.FR_PR_SEG_EPILOGUE)
+    info = cal.fr_pagerank_info()
+    n_hub_tiles = cal.fr_pagerank_tiles(fr.FR_PR_SEG_HUBFIN)
     cal.fr_pagerank_destroy()
     side_probe.fr_destroy()
-    ps_per_vertex = max(1, int(ph[0] * 1000 * args.derate / ((cal_iters + 1) * V)))
-    ps_per_edge = max(1, int(ph[1] * 1000 * args.derate / (cal_iters * E)))
-    epi_tile_ns = max(1, int(ph[2] * args.derate / (cal_iters * n_epi)))
-    log("standalone phases over %d iterations: V %.1f us, P %.1f us, E %.1f us per iteration" %
-        (cal_iters, ph[0] / 1e3 / (cal_iters + 1), ph[1] / 1e3 / cal_iters, ph[2] / 1e3 / cal_iters))
-    standalone_iter_ns = ph[0] / (cal_iters + 1) + (ph[1] + ph[2]) / cal_iters
+    M = max(1, info.messages)
+    v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3] / cal_iters
+    ps_per_vertex = max(1, int(v_ns * 1000 * args.derate / V))
+    ps_per_message = max(1, int((s_ns * 1000 * args.derate - V * ps_per_vertex) / M))
+    ps_per_edge = max(1, int((g_ns * 1000 * args.derate - (V + 64 * info.hub_partitions) * ps_per_vertex) / max(1, E)))
+    hubfin_tile_ns = max(1, int(h_ns * args.derate / n_hub_tiles))
+    log("layout: M/E=%.3f, %d+%d destination partitions, %d source partitions, %d hubs, init+first run %.2fs" %
+        (info.messages / max(1, E), info.regular_partitions, info.hub_partitions, info.source_partitions, info.hubs, t_init))
+    log("standalone per iteration: scatter %.1f us, gather %.1f us, hub finish %.1f us (first vertex pass %.1f us)" %
+        (s_ns / 1e3, g_ns / 1e3, h_ns / 1e3, v_ns / 1e3))
+    standalone_iter_ns = s_ns + g_ns + h_ns
 
     # ---- runtime, task, stage
     mem_cap = cfg.mem_cap_bytes if cfg.mem_cap_bytes else (64 << 30)
@@ -105,9 +113,14 @@ def main():
                      mem_available_bytes=mem_cap + 1, guard_ns=100_000, launch_cost_ns=8_000, max_chunk_ns=0,
                      max_inflight=32, time_steps=1, event_log_capacity=1 << 18)
     task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
-                           mem_limit_bytes=mem_cap, ps_per_edge=ps_per_edge, ps_per_vertex=ps_per_vertex,
-                           epilogue_tile_ns=epi_tile_ns)
+                           mem_limit_bytes=mem_cap, ps_per_edge=ps_per_edge, ps_per_message=ps_per_message,
+                           ps_per_vertex=ps_per_vertex, hubfin_tile_ns=hubfin_tile_ns)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
+    t_end = time.time() + 60
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+        time.sleep(0.001)
+    ctx.fr_bubble_end()
     kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
     stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
 
@@ -139,13 +152,16 @@ def main():
     bubble_ns = sum(r.bubble_ns for r in with_task)
     chunk_ns = sum(e.measured_ns for e in events if e.kind == fr.FR_EV_CHUNK)
     idle_ns = sum(e.modelled_ns for e in events if e.kind == fr.FR_EV_IDLE)
-    seg_kind = lambda s: fr.FR_PR_SEG_VERTEX if s == 3 * K else s % 3
-    pull = [e for e in events if e.kind == fr.FR_EV_CHUNK and seg_kind(e.segment) == fr.FR_PR_SEG_PULL and e.measured_ns > 0]
-    pull_ns = sum(e.measured_ns for e in pull)
-    pull_edges = sum(e.work_units for e in pull)
-    # algorithmic bytes of the pull kernel: 4 B per CSR entry + row_ptr, compulsory contrib read and acc write
-    # per vertex (4E + 12V + 4 for a whole pass), charged in proportion to the edges a launch covers
-    pull_bytes = pull_edges * (4.0 + (12.0 * V + 4.0) / E)
+    seg_kind = lambda g: fr.FR_PR_SEG_VERTEX if g == 0 else 1 + (g - 1) % 3
+    timed = [e for e in events if e.kind == fr.FR_EV_CHUNK and e.measured_ns > 0]
+    per_kind_ns = [sum(e.measured_ns for e in timed if seg_kind(e.segment) == k) for k in range(4)]
+    per_kind_n = [sum(1 for e in timed if seg_kind(e.segment) == k) for k in range(4)]
+    timed_edges = sum(e.work_units for e in timed)
+    # One iteration = S + G + H launches and moves 4E + 24V + 4 algorithmic bytes (col entries, row starts, one
+    # compulsory read of every contribution, the rank write, and the vertex pass); iterations done = edges / E.
+    iters_done = timed_edges / E
+    pull_ns = sum(per_kind_ns)
+    pull_bytes = iters_done * (4.0 * E + 24.0 * V + 4.0)
     pull_gbs = pull_bytes / pull_ns if pull_ns else 0.0
     iter_bytes = 4.0 * E + 24.0 * V + 4.0
     e_with = statistics.mean(r.epoch_ns for r in with_task)
@@ -182,10 +198,18 @@ def main():
         "standalone_iteration_us": standalone_iter_ns / 1e3,
         "standalone_gbs": iter_bytes / standalone_iter_ns,
         "stage_tflops": ((fp_flops + bp_flops) * cfg.m / (busy_with / 1e9) / 1e12) if fp_flops else None,
-        "roofline": {"kernel": "k_pull", "bound": "hbm", "achieved": pull_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": pull_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "launches": len(pull), "avg_launch_us": (pull_ns / len(pull) / 1e3) if pull else None,
-                     "bytes_per_launch": (pull_bytes / len(pull)) if pull else None},
+        "roofline": {"kernel": "k_scatter + k_gather + k_hubfin (one PageRank iteration)", "bound": "hbm",
+                     "achieved": pull_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pull_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "iterations": iters_done,
+                     "avg_iteration_us": (pull_ns / iters_done / 1e3) if iters_done else None,
+                     "avg_launch_us": {"k_scatter": per_kind_ns[1] / max(1, per_kind_n[1]) / 1e3,
+                                       "k_gather": per_kind_ns[2] / max(1, per_kind_n[2]) / 1e3,
+                                       "k_hubfin": per_kind_ns[3] / max(1, per_kind_n[3]) / 1e3},
+                     "launches": {"k_scatter": per_kind_n[1], "k_gather": per_kind_n[2], "k_hubfin": per_kind_n[3]},
+                     "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0},
+        "layout": {"messages_per_edge": info.messages / max(1, E), "hubs": info.hubs,
+                   "destination_partitions": info.regular_partitions + info.hub_partitions,
+                   "bytes_resident": info.bytes_resident, "bytes_peak_init": info.bytes_peak},
         "paper_context": {"bubble_rate_pct": 42.4, "cost_savings_pct": 7.8, "overhead_pct": 1.1,
                           "pagerank_iterations_per_s": 333.9, "hardware": "4x RTX 6000 Ada (paper, Section 6)"},
     }

@@ -146,7 +146,10 @@ int fr_task_stop(fr_ctx* ctx, fr_task_id id);
  */
 void* fr_alloc_device(fr_alloc* a, size_t bytes);
 int   fr_alloc_charge(fr_alloc* a, size_t bytes);
+/* Returns a block taken with fr_alloc_device before the task stops (set-up scratch); FR_ERR_ARG if unknown. */
+int   fr_alloc_free(fr_alloc* a, void* p);
 uint64_t fr_alloc_used(const fr_alloc* a);
+uint64_t fr_alloc_peak(const fr_alloc* a);   /* highest value fr_alloc_used has reached */
 
 /*
  * Bubble notifications from the stage's scheduler (Section 3.2: start timestamp and duration).
@@ -154,7 +157,9 @@ uint64_t fr_alloc_used(const fr_alloc* a);
  *   it is initialised in this bubble; if PAUSED it is started and steps are planned against
  *   duration_ns - guard_ns.  FR_ERR_STATE if a bubble is already open.
  * fr_bubble_end: PauseSideTask().  Returns once the worker has stopped enqueuing.  FR_ERR_OVERRUN (also
- *   counted) if side work is still in flight on the GPU at that moment; FR_ERR_STATE if no bubble is open.
+ *   counted) if side work is still in flight on the GPU at that moment, or if InitSideTask is still running
+ *   (the call does not wait for it; bubbles that open before it finishes are seen but not used);
+ *   FR_ERR_STATE if no bubble is open.
  */
 int fr_bubble_begin(fr_ctx* ctx, uint64_t t_begin_ns, uint64_t duration_ns);
 int fr_bubble_end(fr_ctx* ctx);
@@ -205,22 +210,27 @@ int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint6
 /*
  * Pull-based PageRank over an in-edge CSR, fp32 ranks, fixed iteration count, dangling mass spread uniformly,
  * Jacobi iterations (the paper's graph-analytics side task, Section 6.1.4; one iteration = one pass over the
- * graph, Section 6.2).  Work is cut into tiles fixed at init; results do not depend on how tiles are grouped
- * into launches.  A run is the segment sequence  V_0, P_0, E_0, V_1, P_1, E_1, ..., V_K  where
- *   V_k (vertex pass)  r_k = 1/V (k = 0) or base_{k-1} + d * acc_{k-1};  contrib_k = r_k / outdeg;
- *                      per-tile partial sums of dangling r_k;  V_K writes r_K to ranks_out instead;
- *   P_k (pull pass)    acc_k[v] = sum over v's in-edges of contrib_k[source];
- *   E_k (epilogue)     sums of rows cut by pull-tile borders;  base_k = (1 - d)/V + d * D_k / V.
+ * graph, Section 6.2).  InitSideTask rebuilds the CSR into a partition-centric layout on the GPU; work is cut
+ * into tiles fixed at that point and results do not depend on how tiles are grouped into launches.
+ * A run is the segment sequence  V0, S_0, G_0, H_0, S_1, G_1, H_1, ..., S_{K-1}, G_{K-1}, H_{K-1}  where
+ *   V0  (vertex pass)  r_0 = 1/V, contrib_0 = r_0 / outdeg, per-tile partial sums of dangling r_0;
+ *   S_k (scatter)      one message contrib_k[u] per (destination partition, source u) pair;
+ *   G_k (gather)       acc_k[v] = sum over v's in-edges of the source's message, then for the partition's rows
+ *                      r_{k+1} = base_k + d * acc_k, contrib_{k+1}, dangling partials;
+ *                      base_k = (1 - d)/V + d * D_k / V, D_k = sum of the dangling partials of r_k;
+ *   H_k (hub finish)   the same for rows whose in-edges were dealt out to virtual rows.
+ * The last iteration writes r_K to ranks_out.  With K = 0, V0 writes r_0 there.
  */
-#define FR_PR_SEG_VERTEX   0
-#define FR_PR_SEG_PULL     1
-#define FR_PR_SEG_EPILOGUE 2
+#define FR_PR_SEG_VERTEX  0
+#define FR_PR_SEG_SCATTER 1
+#define FR_PR_SEG_GATHER  2
+#define FR_PR_SEG_HUBFIN  3
 
 typedef struct fr_pagerank_desc {
     int64_t  n_vertices;          /* V >= 1                                                                 */
     int64_t  n_edges;             /* E >= 0, below 2^31                                                     */
     const int32_t* row_ptr;       /* device, V + 1 entries: in-edge CSR row starts                          */
-    const int32_t* col;           /* device, E entries: source of each in-edge; 16-byte aligned             */
+    const int32_t* col;           /* device, E entries: source of each in-edge                              */
     const int32_t* out_degree;    /* device, V entries: edges leaving each vertex, with multiplicity        */
     float*   ranks_out;           /* device, V entries: r_K of the latest completed run                     */
     float    damping;
@@ -228,29 +238,45 @@ typedef struct fr_pagerank_desc {
     int32_t  max_runs;            /* stop harvesting after this many completed runs; 0 = restart forever    */
     int32_t  reserved;
     uint64_t mem_limit_bytes;     /* the task's memory limit; caller buffers above are booked against it    */
-    /* cost model, integer picoseconds, fixed for the task's life (0 = library default) */
-    uint64_t ps_per_edge;         /* pull tile cost    = ceil(edges    * ps_per_edge   / 1000) ns           */
-    uint64_t ps_per_vertex;       /* vertex tile cost  = ceil(vertices * ps_per_vertex / 1000) ns           */
-    uint64_t epilogue_tile_ns;    /* epilogue tile cost                                                     */
+    /* cost model, integer picoseconds, fixed for the task's life (0 = library default); tile cost in ns =
+       ceil(sum / 1000), at least 1:
+         vertex tile  : rows * ps_per_vertex
+         scatter tile : messages * ps_per_message + sources * ps_per_vertex
+         gather tile  : edges * ps_per_edge + rows * ps_per_vertex
+         hub tile     : hubfin_tile_ns (already ns)                                                         */
+    uint64_t ps_per_edge;
+    uint64_t ps_per_message;
+    uint64_t ps_per_vertex;
+    uint64_t hubfin_tile_ns;
 } fr_pagerank_desc;
+
+/* Facts about the layout built by InitSideTask. */
+typedef struct fr_pagerank_info_t {
+    uint64_t messages;            /* distinct (destination partition, source) pairs                         */
+    uint32_t regular_partitions, hub_partitions, source_partitions;
+    uint32_t hubs, virtual_rows;
+    uint32_t reserved;
+    uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
+    uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */
+} fr_pagerank_info_t;
 
 /* Builds the task object and fills in the callbacks and profile to register with.  No device work yet. */
 int fr_pagerank_make(const fr_pagerank_desc* d, fr_task_ops* ops_out, void** user_out, fr_task_profile* prof_out);
 /* Frees the task object; only after fr_task_stop (or if it was never registered). */
 int fr_pagerank_destroy(void* user);
-/* Bytes the task books against its limit: caller buffers plus what init allocates. */
-int fr_pagerank_footprint(void* user, uint64_t* bytes_out);
-/* Number of tiles of a segment kind (FR_PR_SEG_*), and its modelled tile costs in ns. */
+/* The four calls below need the layout, so they return FR_ERR_STATE until InitSideTask has run. */
+int fr_pagerank_info(void* user, fr_pagerank_info_t* out);
+/* Number of tiles of a segment kind (FR_PR_SEG_*), their modelled costs in ns, and the work they hold
+   (vertex: rows, scatter: messages, gather: edges, hub: 0). */
 int fr_pagerank_tiles(void* user, int32_t seg_kind, uint32_t* n_tiles_out);
 int fr_pagerank_tile_costs(void* user, int32_t seg_kind, uint32_t* costs_host, size_t cap, size_t* n_out);
-/* Edges and vertices covered by one tile of the pull / vertex segments (constants of the build). */
-int fr_pagerank_tile_shape(uint32_t* pull_tile_edges_out, uint32_t* vertex_tile_vertices_out);
+int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work_host, size_t cap, size_t* n_out);
 /*
  * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_tiles_per_launch` tiles per
  * kernel launch (0 = a whole segment per launch), waits for it and leaves r_K in ranks_out.  Same kernels and
  * tiles as the harvested path: the reference for the "any chunking gives the same bits" property.  The task
  * must not be registered with a context (it initialises itself against its own mem_limit_bytes on `device_id`).
- * phase_ns_out (host, 3 entries, may be NULL) receives the summed GPU time of the V, P and E segments.
+ * phase_ns_out (host, 4 entries indexed by FR_PR_SEG_*, may be NULL) receives the summed GPU time per segment kind.
  */
 int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint32_t max_tiles_per_launch,
                                uint64_t* phase_ns_out);

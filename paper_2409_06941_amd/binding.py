@@ -9,7 +9,7 @@ LIB_PATH = _build.LIB
 FR_OK, FR_ERR_ARG, FR_ERR_STATE, FR_ERR_NOMEM, FR_ERR_OOM, FR_ERR_OVERRUN, FR_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 FR_SUBMITTED, FR_CREATED, FR_PAUSED, FR_RUNNING, FR_STOPPED = range(5)
 FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS = 1, 2, 3, 4
-FR_PR_SEG_VERTEX, FR_PR_SEG_PULL, FR_PR_SEG_EPILOGUE = 0, 1, 2
+FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_HUBFIN = 0, 1, 2, 3
 FR_LOAD_BUSYWAIT, FR_LOAD_GPT = 0, 1
 FR_SCHED_1F1B, FR_SCHED_GPIPE = 0, 1
 
@@ -68,7 +68,14 @@ class fr_pagerank_desc(C.Structure):
     _fields_ = [("n_vertices", C.c_int64), ("n_edges", C.c_int64), ("row_ptr", C.c_void_p), ("col", C.c_void_p),
                 ("out_degree", C.c_void_p), ("ranks_out", C.c_void_p), ("damping", C.c_float), ("iterations", C.c_int32),
                 ("max_runs", C.c_int32), ("reserved", C.c_int32), ("mem_limit_bytes", C.c_uint64),
-                ("ps_per_edge", C.c_uint64), ("ps_per_vertex", C.c_uint64), ("epilogue_tile_ns", C.c_uint64)]
+                ("ps_per_edge", C.c_uint64), ("ps_per_message", C.c_uint64), ("ps_per_vertex", C.c_uint64),
+                ("hubfin_tile_ns", C.c_uint64)]
+
+
+class fr_pagerank_info_t(C.Structure):
+    _fields_ = [("messages", C.c_uint64), ("regular_partitions", C.c_uint32), ("hub_partitions", C.c_uint32),
+                ("source_partitions", C.c_uint32), ("hubs", C.c_uint32), ("virtual_rows", C.c_uint32),
+                ("reserved", C.c_uint32), ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
 
 
 class fr_load_desc(C.Structure):
@@ -103,7 +110,9 @@ SIGNATURES = {
     "fr_task_stop": (C.c_int, [C.c_void_p, C.c_int32]),
     "fr_alloc_device": (C.c_void_p, [C.c_void_p, C.c_size_t]),
     "fr_alloc_charge": (C.c_int, [C.c_void_p, C.c_size_t]),
+    "fr_alloc_free": (C.c_int, [C.c_void_p, C.c_void_p]),
     "fr_alloc_used": (C.c_uint64, [C.c_void_p]),
+    "fr_alloc_peak": (C.c_uint64, [C.c_void_p]),
     "fr_bubble_begin": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64]),
     "fr_bubble_end": (C.c_int, [C.c_void_p]),
     "fr_query_progress": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(fr_progress)]),
@@ -112,10 +121,10 @@ SIGNATURES = {
     "fr_chunk_fit": (C.c_int, [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint32)]),
     "fr_pagerank_make": (C.c_int, [C.POINTER(fr_pagerank_desc), C.POINTER(fr_task_ops), C.POINTER(C.c_void_p), C.POINTER(fr_task_profile)]),
     "fr_pagerank_destroy": (C.c_int, [C.c_void_p]),
-    "fr_pagerank_footprint": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64)]),
+    "fr_pagerank_info": (C.c_int, [C.c_void_p, C.POINTER(fr_pagerank_info_t)]),
     "fr_pagerank_tiles": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32)]),
     "fr_pagerank_tile_costs": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
-    "fr_pagerank_tile_shape": (C.c_int, [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
+    "fr_pagerank_tile_work": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_pagerank_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
     "fr_load_workspace_bytes": (C.c_int, [C.POINTER(fr_load_desc), C.POINTER(C.c_uint64)]),
     "fr_load_make": (C.c_int, [C.POINTER(fr_load_desc), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -252,13 +261,15 @@ class PageRankTask:
     """fr_pagerank_make and friends.  Tensors (torch, on the GPU) are only read for their data_ptr."""
 
     def __init__(self, n_vertices, n_edges, row_ptr, col, out_degree, ranks_out, damping=0.85, iterations=30,
-                 max_runs=0, mem_limit_bytes=1 << 40, ps_per_edge=0, ps_per_vertex=0, epilogue_tile_ns=0):
+                 max_runs=0, mem_limit_bytes=1 << 40, ps_per_edge=0, ps_per_message=0, ps_per_vertex=0,
+                 hubfin_tile_ns=0):
         d = fr_pagerank_desc()
         d.n_vertices, d.n_edges = n_vertices, n_edges
         d.row_ptr, d.col, d.out_degree, d.ranks_out = _ptr(row_ptr), _ptr(col), _ptr(out_degree), _ptr(ranks_out)
         d.damping, d.iterations, d.max_runs = damping, iterations, max_runs
         d.mem_limit_bytes = mem_limit_bytes
-        d.ps_per_edge, d.ps_per_vertex, d.epilogue_tile_ns = ps_per_edge, ps_per_vertex, epilogue_tile_ns
+        d.ps_per_edge, d.ps_per_message, d.ps_per_vertex = ps_per_edge, ps_per_message, ps_per_vertex
+        d.hubfin_tile_ns = hubfin_tile_ns
         self.desc = d
         self._keep = (row_ptr, col, out_degree, ranks_out)
         self.ops = fr_task_ops()
@@ -272,10 +283,17 @@ class PageRankTask:
             _check(lib().fr_pagerank_destroy(self.user), "fr_pagerank_destroy")
             self.user = C.c_void_p()
 
-    def fr_pagerank_footprint(self):
-        out = C.c_uint64()
-        _check(lib().fr_pagerank_footprint(self.user, C.byref(out)), "fr_pagerank_footprint")
-        return out.value
+    def fr_pagerank_info(self):
+        out = fr_pagerank_info_t()
+        _check(lib().fr_pagerank_info(self.user, C.byref(out)), "fr_pagerank_info")
+        return out
+
+    def fr_pagerank_tile_work(self, seg_kind):
+        n = self.fr_pagerank_tiles(seg_kind)
+        buf = (C.c_uint64 * n)()
+        got = C.c_size_t()
+        _check(lib().fr_pagerank_tile_work(self.user, seg_kind, buf, n, C.byref(got)), "fr_pagerank_tile_work")
+        return list(buf)
 
     def fr_pagerank_tiles(self, seg_kind):
         out = C.c_uint32()
@@ -290,16 +308,10 @@ class PageRankTask:
         return list(buf)
 
     def fr_pagerank_run_standalone(self, device_id=0, stream=None, max_tiles_per_launch=0, want_phase_ns=False):
-        ph = (C.c_uint64 * 3)()
+        ph = (C.c_uint64 * 4)()
         _check(lib().fr_pagerank_run_standalone(self.user, device_id, _stream(stream), max_tiles_per_launch,
                                                 ph if want_phase_ns else None), "fr_pagerank_run_standalone")
         return list(ph) if want_phase_ns else None
-
-
-def fr_pagerank_tile_shape():
-    a, b = C.c_uint32(), C.c_uint32()
-    _check(lib().fr_pagerank_tile_shape(C.byref(a), C.byref(b)), "fr_pagerank_tile_shape")
-    return a.value, b.value
 
 
 class Load:

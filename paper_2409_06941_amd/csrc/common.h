@@ -16,7 +16,9 @@ struct fr_alloc {
     bool host_only = false;
     int device = 0;
     int hip_error = 0;
-    std::vector<void*> blocks;
+    uint64_t peak = 0;
+    struct Block { void* ptr; uint64_t bytes; };
+    std::vector<Block> blocks;
 };
 
 void fr_alloc_reset(fr_alloc* a, uint64_t limit, bool host_only, int device);

@@ -1,0 +1,341 @@
+// Builds the partition-centric layout (pr_layout.h) of the PageRank side task on the GPU, once, in InitSideTask
+// (Section 4.1 of the paper: the transition that loads the task's context into GPU memory).
+//
+// Pipeline: check the CSR -> mark hubs and number their virtual rows (scan) -> one 64-bit key per edge
+// (partition, source, local row) -> radix sort -> message starts (flags, scan) -> id stream, message sources,
+// per-partition offsets, per-bin message ranges.  rocPRIM supplies the device-wide sort and scans; they run
+// once per task and are not part of any iteration.
+
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+#include <algorithm>
+
+#include "pr_layout.h"
+
+namespace {
+
+constexpr int kBlk = 256;
+
+inline unsigned blocks_for(uint64_t n) { return (unsigned)((n + kBlk - 1) / kBlk); }
+
+// Row that holds edge e: the v with row_ptr[v] <= e < row_ptr[v + 1].
+__device__ __forceinline__ int32_t row_of_edge(const int32_t* __restrict__ row_ptr, int64_t V, int64_t e)
+{
+    int64_t lo = 0, hi = V;            // first index in [0, V] whose row_ptr exceeds e
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)row_ptr[mid] > e) hi = mid;
+        else lo = mid + 1;
+    }
+    return (int32_t)(lo - 1);
+}
+
+__global__ void k_set_i32(int32_t* p, int32_t value) { *p = value; }
+
+// Structure check of the caller's CSR so that no later kernel can index out of bounds.
+__global__ __launch_bounds__(kBlk) void k_validate(int64_t V, int64_t E, const int32_t* __restrict__ row_ptr,
+                                                   const int32_t* __restrict__ col, int32_t* __restrict__ bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kBlk;
+    int err = 0;
+    if (i == 0 && (row_ptr[0] != 0 || (int64_t)row_ptr[V] != E)) err = 1;
+    for (int64_t v = i; v < V; v += stride) {
+        const int32_t a = row_ptr[v], b = row_ptr[v + 1];
+        if (a > b || a < 0 || (int64_t)b > E) err = 1;
+    }
+    for (int64_t e = i; e < E; e += stride) {
+        const int32_t c = col[e];
+        if (c < 0 || (int64_t)c >= V) err = 1;
+    }
+    if (err) *bad = 1;
+}
+
+// packed[v] = (virtual rows of v) << 32 | (1 if v is a hub)
+__global__ __launch_bounds__(kBlk) void k_hub_mark(int64_t V, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ packed)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (v >= V) return;
+    const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
+    const bool hub = indeg > kHubSplit;
+    const uint64_t nsplit = hub ? (indeg + kHubSplit - 1) / kHubSplit : 0;
+    packed[v] = (nsplit << 32) | (hub ? 1u : 0u);
+}
+
+__global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, const int32_t* __restrict__ row_ptr,
+                                                     const uint64_t* __restrict__ scanned, uint32_t n_hubs,
+                                                     uint32_t n_vrows, int32_t* __restrict__ hub_row,
+                                                     uint32_t* __restrict__ hub_vbase)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (v == 0) hub_vbase[n_hubs] = n_vrows;
+    if (v >= V) return;
+    const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
+    if (indeg <= kHubSplit) return;
+    const uint32_t h = (uint32_t)(scanned[v] & 0xffffffffu);
+    if (h < n_hubs) {
+        hub_row[h] = (int32_t)v;
+        hub_vbase[h] = (uint32_t)(scanned[v] >> 32);
+    }
+}
+
+// 1/outdeg (0 for dangling vertices) with the sign bit marking hub rows.
+__global__ __launch_bounds__(kBlk) void k_inv_tag(int64_t V, const int32_t* __restrict__ row_ptr,
+                                                  const int32_t* __restrict__ outdeg, float* __restrict__ inv_tag)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (v >= V) return;
+    const int32_t d = outdeg[v];
+    float inv = d > 0 ? 1.0f / (float)d : 0.0f;
+    if ((uint32_t)(row_ptr[v + 1] - row_ptr[v]) > kHubSplit) inv = __uint_as_float(__float_as_uint(inv) | 0x80000000u);
+    inv_tag[v] = inv;
+}
+
+__global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, const int32_t* __restrict__ row_ptr,
+                                               const int32_t* __restrict__ col, const uint64_t* __restrict__ scanned,
+                                               uint32_t q_reg, uint64_t* __restrict__ keys)
+{
+    const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (e >= E) return;
+    const int32_t v = row_of_edge(row_ptr, V, e);
+    const int64_t begin = row_ptr[v];
+    const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - begin);
+    uint64_t q, local;
+    if (indeg > kHubSplit) {
+        const uint64_t hv = (scanned[v] >> 32) + (uint64_t)(e - begin) / kHubSplit;
+        q = q_reg + hv / kVrowsPerHubPart;
+        local = hv % kVrowsPerHubPart;
+    } else {
+        q = (uint64_t)v / kRowsPerPart;
+        local = (uint64_t)v % kRowsPerPart;
+    }
+    keys[e] = (q << (kKeyLocalBits + kKeySrcBits)) | ((uint64_t)(uint32_t)col[e] << kKeyLocalBits) | local;
+}
+
+__global__ __launch_bounds__(kBlk) void k_flags(int64_t E, const uint64_t* __restrict__ keys, uint32_t* __restrict__ flag)
+{
+    const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (e >= E) return;
+    flag[e] = (e == 0 || (keys[e] >> kKeyLocalBits) != (keys[e - 1] >> kKeyLocalBits)) ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
+                                               const uint32_t* __restrict__ flag, const uint32_t* __restrict__ incl,
+                                               uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
+{
+    const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (e >= padded) return;
+    if (e >= E) { ids16[e] = 0; return; }
+    const uint64_t k = keys[e];
+    const uint32_t f = flag[e];
+    ids16[e] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) | (f << 15));
+    if (f) {
+        const uint64_t m = (uint64_t)incl[e] - 1;
+        const uint32_t u = (uint32_t)((k >> kKeyLocalBits) & 0x7fffffffu);
+        if (m < M) src16[m] = (uint16_t)(u % kSrcPerPart);
+    }
+}
+
+__global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint32_t* __restrict__ flag,
+                                                const uint32_t* __restrict__ incl, uint32_t* __restrict__ mbase)
+{
+    const uint32_t c = blockIdx.x * kBlk + threadIdx.x;
+    if (c > n_chunks) return;
+    const int64_t e = (int64_t)c * kIdChunk;
+    mbase[c] = e < E ? incl[e] - flag[e] : M;
+}
+
+__device__ __forceinline__ int64_t lower_bound_key(const uint64_t* __restrict__ keys, int64_t E, uint64_t target)
+{
+    int64_t lo = 0, hi = E;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (keys[mid] < target) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kBlk) void k_eoff(uint32_t Q, int64_t E, const uint64_t* __restrict__ keys, uint32_t* __restrict__ eoff)
+{
+    const uint32_t q = blockIdx.x * kBlk + threadIdx.x;
+    if (q > Q) return;
+    eoff[q] = (uint32_t)lower_bound_key(keys, E, (uint64_t)q << (kKeyLocalBits + kKeySrcBits));
+}
+
+// bins[p * Q + q] = message range of the edges of partition q whose source lies in source partition p.
+// The first edge of a bin always starts a message, so "messages before it" = incl - 1 there.
+__global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E, uint32_t M, const uint64_t* __restrict__ keys,
+                                               const uint32_t* __restrict__ incl, uint2* __restrict__ bins)
+{
+    const uint64_t idx = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (idx >= (uint64_t)P * Q) return;
+    const uint64_t p = idx / Q, q = idx % Q;
+    const uint64_t base = q << (kKeyLocalBits + kKeySrcBits);
+    const int64_t lo = lower_bound_key(keys, E, base + ((p * kSrcPerPart) << kKeyLocalBits));
+    const int64_t hi = lower_bound_key(keys, E, base + (((p + 1) * kSrcPerPart) << kKeyLocalBits));
+    uint2 r;
+    r.x = lo < E ? incl[lo] - 1 : M;
+    r.y = hi < E ? incl[hi] - 1 : M;
+    if (r.y < r.x) r.y = r.x;
+    bins[idx] = r;
+}
+
+__global__ __launch_bounds__(kBlk) void k_msgs_of_p(uint32_t P, uint32_t Q, const uint2* __restrict__ bins, uint64_t* __restrict__ out)
+{
+    const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
+    if (p >= P) return;
+    uint64_t s = 0;
+    for (uint32_t q = 0; q < Q; ++q) s += bins[(uint64_t)p * Q + q].y - bins[(uint64_t)p * Q + q].x;
+    out[p] = s;
+}
+
+struct Scratch {
+    fr_alloc* a;
+    std::vector<void*> held;
+    template <typename T>
+    T* take(uint64_t count)
+    {
+        void* p = fr_alloc_device(a, (size_t)(count ? count : 1) * sizeof(T));
+        if (p) held.push_back(p);
+        return static_cast<T*>(p);
+    }
+    ~Scratch()
+    {
+        for (void* p : held) (void)fr_alloc_free(a, p);
+    }
+};
+
+template <typename T>
+bool keep(fr_alloc* a, T** out, uint64_t count)
+{
+    *out = static_cast<T*>(fr_alloc_device(a, (size_t)(count ? count : 1) * sizeof(T)));
+    return *out != nullptr;
+}
+
+}  // namespace
+
+#define PREP_HIP(expr)                                             \
+    do {                                                           \
+        hipError_t e__ = (expr);                                   \
+        if (e__ != hipSuccess) { *hip_error = (int)e__; return FR_ERR_HIP; } \
+    } while (0)
+#define PREP_NEED(ptr)                                             \
+    do {                                                           \
+        if (!(ptr)) { if (a->hip_error) *hip_error = a->hip_error; return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM; } \
+    } while (0)
+
+int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
+                    const int32_t* out_degree, fr_alloc* a, hipStream_t stream, int* hip_error)
+{
+    L->V = V; L->E = E;
+    L->q_reg = (uint32_t)((V + kRowsPerPart - 1) / kRowsPerPart);
+    L->P = (uint32_t)((V + kSrcPerPart - 1) / kSrcPerPart);
+    L->n_chunks = (uint32_t)((E + kIdChunk - 1) / kIdChunk);
+    const int64_t padded = (int64_t)std::max<uint32_t>(L->n_chunks, 1) * kIdChunk;
+
+    Scratch tmp{a, {}};
+
+    // ---- refuse a malformed CSR before anything indexes with it
+    int32_t* bad = tmp.take<int32_t>(1);
+    PREP_NEED(bad);
+    hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, stream, bad, 0);
+    const unsigned vgrid = std::min<unsigned>(blocks_for((uint64_t)std::max<int64_t>(V, E)), 65536u);
+    hipLaunchKernelGGL(k_validate, dim3(vgrid), dim3(kBlk), 0, stream, V, E, row_ptr, col, bad);
+    int32_t bad_host = 0;
+    PREP_HIP(hipMemcpyAsync(&bad_host, bad, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipStreamSynchronize(stream));
+    if (bad_host) return FR_ERR_ARG;
+
+    // ---- hubs and their virtual rows
+    uint64_t* packed = tmp.take<uint64_t>((uint64_t)V);
+    uint64_t* scanned = tmp.take<uint64_t>((uint64_t)V);
+    PREP_NEED(packed); PREP_NEED(scanned);
+    hipLaunchKernelGGL(k_hub_mark, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, packed);
+    {
+        size_t bytes = 0;
+        PREP_HIP(rocprim::exclusive_scan(nullptr, bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
+        void* t = tmp.take<uint8_t>(bytes);
+        PREP_NEED(t);
+        PREP_HIP(rocprim::exclusive_scan(t, bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
+    }
+    uint64_t last_packed = 0, last_scanned = 0;
+    PREP_HIP(hipMemcpyAsync(&last_packed, packed + (V - 1), 8, hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipMemcpyAsync(&last_scanned, scanned + (V - 1), 8, hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipStreamSynchronize(stream));
+    const uint64_t totals = last_packed + last_scanned;
+    L->n_hubs = (uint32_t)(totals & 0xffffffffu);
+    L->n_vrows = (uint32_t)(totals >> 32);
+    L->q_hub = (L->n_vrows + kVrowsPerHubPart - 1) / kVrowsPerHubPart;
+    L->n_hub_tiles = std::max<uint32_t>(1, (L->n_hubs + kHubsPerTile - 1) / kHubsPerTile);
+    const uint32_t Q = L->Q();
+    if ((uint64_t)Q >= (1ull << (63 - kKeyLocalBits - kKeySrcBits))) return FR_ERR_ARG;
+
+    if (!keep(a, &L->hub_row, L->n_hubs) || !keep(a, &L->hub_vbase, (uint64_t)L->n_hubs + 1) || !keep(a, &L->inv_tag, (uint64_t)V))
+        PREP_NEED((void*)nullptr);
+    hipLaunchKernelGGL(k_hub_tables, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, scanned, L->n_hubs,
+                       L->n_vrows, L->hub_row, L->hub_vbase);
+    hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, out_degree, L->inv_tag);
+
+    // ---- persistent arrays whose size does not depend on the message count
+    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->eoff, (uint64_t)Q + 1) ||
+        !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->bins, (uint64_t)L->P * Q))
+        PREP_NEED((void*)nullptr);
+
+    uint64_t* keys = nullptr;
+    uint32_t *flag = nullptr, *incl = nullptr;
+    uint32_t M = 0;
+    if (E > 0) {
+        uint64_t* keys_in = tmp.take<uint64_t>((uint64_t)E);
+        keys = tmp.take<uint64_t>((uint64_t)E);
+        PREP_NEED(keys_in); PREP_NEED(keys);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, row_ptr, col, scanned, L->q_reg, keys_in);
+        unsigned end_bit = kKeyLocalBits + kKeySrcBits;
+        while (end_bit < 63 && (1ull << (end_bit - kKeyLocalBits - kKeySrcBits)) < (uint64_t)Q) ++end_bit;
+        {
+            size_t bytes = 0;
+            PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, keys_in, keys, (size_t)E, 0u, end_bit, stream));
+            void* t = tmp.take<uint8_t>(bytes);
+            PREP_NEED(t);
+            PREP_HIP(rocprim::radix_sort_keys(t, bytes, keys_in, keys, (size_t)E, 0u, end_bit, stream));
+        }
+        flag = tmp.take<uint32_t>((uint64_t)E);
+        incl = tmp.take<uint32_t>((uint64_t)E);
+        PREP_NEED(flag); PREP_NEED(incl);
+        hipLaunchKernelGGL(k_flags, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, E, keys, flag);
+        {
+            size_t bytes = 0;
+            PREP_HIP(rocprim::inclusive_scan(nullptr, bytes, flag, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
+            void* t = tmp.take<uint8_t>(bytes);
+            PREP_NEED(t);
+            PREP_HIP(rocprim::inclusive_scan(t, bytes, flag, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
+        }
+        PREP_HIP(hipMemcpyAsync(&M, incl + (E - 1), 4, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipStreamSynchronize(stream));
+    }
+    L->M = M;
+    if (!keep(a, &L->src16, (uint64_t)M)) PREP_NEED((void*)nullptr);
+
+    hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, flag, incl,
+                       L->ids16, L->src16);
+    hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, flag, incl, L->mbase);
+    hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, L->eoff);
+    hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->P * Q)), dim3(kBlk), 0, stream, L->P, Q, E, M, keys, incl, L->bins);
+    uint64_t* mp = tmp.take<uint64_t>(L->P);
+    PREP_NEED(mp);
+    hipLaunchKernelGGL(k_msgs_of_p, dim3(blocks_for(L->P)), dim3(kBlk), 0, stream, L->P, Q, L->bins, mp);
+    PREP_HIP(hipGetLastError());
+
+    // ---- host copies for the cost model
+    std::vector<uint32_t> eoff_host((size_t)Q + 1);
+    L->msgs_of_p.assign(L->P, 0);
+    PREP_HIP(hipMemcpyAsync(eoff_host.data(), L->eoff, ((size_t)Q + 1) * 4, hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipMemcpyAsync(L->msgs_of_p.data(), mp, (size_t)L->P * 8, hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipStreamSynchronize(stream));
+    L->edges_of_q.resize(Q);
+    for (uint32_t q = 0; q < Q; ++q) L->edges_of_q[q] = eoff_host[q + 1] - eoff_host[q];
+    if (eoff_host[Q] != (uint32_t)E) return FR_ERR_ARG;
+    return FR_OK;     // `tmp` returns the scratch blocks to the allocator
+}

@@ -1,0 +1,67 @@
+// Partition-centric layout of the PageRank side task's graph (internal to the library).
+//
+// The pull pass "acc[v] = sum over in-edges (u -> v) of contrib[u]" is a random 4-byte gather per edge when run
+// straight off the CSR, and gathers, not bytes, are what a GPU runs out of.  The layout below turns the pass into
+// two streaming sweeps whose random accesses all land in LDS (the two-phase partition-centric idea of Beamer et
+// al., "propagation blocking", 2017, and Lakhotia et al., "PCPM", 2018, rebuilt around CDNA's 160 KB LDS):
+//
+//   * destination rows are cut into partitions of kRowsPerPart rows; sources into partitions of kSrcPerPart;
+//   * all in-edges of one destination partition q are stored together, ordered by source u and then by row;
+//     one MESSAGE is made per distinct (q, u) pair, however many rows of q the source u points to;
+//   * scatter sweep, one workgroup per source partition p: the p-slice of contrib sits in LDS; for every q the
+//     messages of bin (p, q) are written, msg[m] = contrib[src of m] -- sequential writes;
+//   * gather sweep, one workgroup per destination partition q: 64-bit fixed-point accumulators for q's rows
+//     sit in LDS; the id stream of q (one 16-bit local row id per edge, top bit set where a new message starts)
+//     and q's messages are read sequentially and added into LDS with integer atomics.  Integer addition is
+//     associative, so the sums do not depend on the order the hardware performs them in.
+//
+// Rows with more than kHubSplit in-edges ("hubs") would both unbalance their partition and serialise the LDS
+// atomics, so each hub's in-edges are dealt out to virtual rows of at most kHubSplit edges, kept in hub
+// partitions of kVrowsPerHubPart virtual rows; a small finishing step adds a hub's virtual rows up.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "common.h"
+
+constexpr uint32_t kRowsPerPart = 8192;      // destination rows per regular partition (64 KB of u64 in LDS)
+constexpr uint32_t kSrcPerPart = 16384;      // source vertices per scatter partition (64 KB of fp32 in LDS)
+constexpr uint32_t kHubSplit = 2048;         // rows with more in-edges than this are split into virtual rows
+constexpr uint32_t kVrowsPerHubPart = 64;    // virtual rows per hub partition
+constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane)
+constexpr uint32_t kHubsPerTile = 256;       // hubs finished per workgroup
+constexpr int kKeyLocalBits = 14;            // sort key = partition << 45 | source << 14 | local row
+constexpr int kKeySrcBits = 31;
+
+struct PrLayout {
+    int64_t V = 0, E = 0;
+    uint64_t M = 0;                  // messages = distinct (destination partition, source) pairs
+    uint32_t q_reg = 0, q_hub = 0;   // regular and hub destination partitions
+    uint32_t P = 0;                  // source partitions
+    uint32_t n_hubs = 0, n_vrows = 0;
+    uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
+    uint32_t n_hub_tiles = 1;
+
+    // device arrays (allocated through the task's accounting allocator)
+    uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id, bit 15 = first edge of a message
+    uint16_t* src16 = nullptr;       // [M] source id relative to its source partition
+    uint32_t* eoff = nullptr;        // [Q + 1] first edge (in sorted order) of every destination partition
+    uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
+    uint2* bins = nullptr;           // [P * Q] message range [x, y) of bin (p, q), p-major
+    int32_t* hub_row = nullptr;      // [n_hubs] row id of hub h
+    uint32_t* hub_vbase = nullptr;   // [n_hubs + 1] first virtual row of hub h
+    float* inv_tag = nullptr;        // [V] 1/outdeg (0 if dangling), sign bit set for hub rows
+
+    // host copies used by the cost model
+    std::vector<uint32_t> edges_of_q;    // [Q]
+    std::vector<uint64_t> msgs_of_p;     // [P]
+
+    uint32_t Q() const { return q_reg + q_hub; }
+};
+
+// Builds the layout on `stream` from the caller's in-edge CSR (device pointers) and waits for it.
+// Temporary memory is taken from and returned to `a`.  Returns FR_OK, FR_ERR_OOM, FR_ERR_HIP or FR_ERR_ARG
+// (malformed CSR).  `hip_error` receives the failing HIP code, if any.
+int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
+                    const int32_t* out_degree, fr_alloc* a, hipStream_t stream, int* hip_error);

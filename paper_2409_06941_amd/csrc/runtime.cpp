@@ -59,6 +59,7 @@ struct fr_ctx {
     std::atomic<uint64_t> bubble_seq{0};    // bumped by fr_bubble_begin after the fields below are written
     std::atomic<uint64_t> ack_seq{0};       // worker: "I will enqueue nothing more for bubble ack_seq"
     std::atomic<bool> end_requested{false};
+    std::atomic<bool> in_init{false};       // the worker is inside the task's init()
     bool bubble_open = false;               // stage thread only
     uint64_t cur_begin = 0, cur_len = 0;
     uint32_t cur_index = 0;                 // 0-based bubble index
@@ -176,7 +177,9 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
 
     if (t->state == FR_CREATED) {
         // Algorithm 2: a CREATED current task is initialised by the new bubble.
+        c->in_init.store(true, std::memory_order_release);
         int rc = t->ops.init ? t->ops.init(t->user, &t->alloc, (void*)c->side) : FR_OK;
+        c->in_init.store(false, std::memory_order_release);
         std::lock_guard<std::mutex> lk(c->mu);
         fr_event ev{};
         ev.kind = FR_EV_INIT; ev.bubble = index; ev.t_host_ns = now_ns();
@@ -340,14 +343,14 @@ void worker_main(fr_ctx* c)
 void fr_alloc_reset(fr_alloc* a, uint64_t limit, bool host_only, int device)
 {
     a->limit = limit; a->used = 0; a->oom = false; a->host_only = host_only; a->device = device;
-    a->hip_error = 0; a->blocks.clear();
+    a->hip_error = 0; a->peak = 0; a->blocks.clear();
 }
 
 void fr_alloc_release(fr_alloc* a)
 {
-    for (void* p : a->blocks) {
-        if (a->host_only) std::free(p);
-        else (void)hipFree(p);
+    for (const fr_alloc::Block& b : a->blocks) {
+        if (a->host_only) std::free(b.ptr);
+        else (void)hipFree(b.ptr);
     }
     a->blocks.clear();
     a->used = 0;
@@ -370,9 +373,24 @@ void* fr_alloc_device(fr_alloc* a, size_t bytes)
         hipError_t e = hipMalloc(&p, rounded ? rounded : 256);
         if (e != hipSuccess) { a->hip_error = (int)e; a->oom = true; return nullptr; }
     }
-    a->blocks.push_back(p);
+    a->blocks.push_back({p, rounded});
     a->used += rounded;
+    if (a->used > a->peak) a->peak = a->used;
     return p;
+}
+
+int fr_alloc_free(fr_alloc* a, void* p)
+{
+    if (!a || !p) return FR_ERR_ARG;
+    for (size_t i = 0; i < a->blocks.size(); ++i) {
+        if (a->blocks[i].ptr != p) continue;
+        if (a->host_only) std::free(p);
+        else (void)hipFree(p);
+        a->used -= a->blocks[i].bytes;
+        a->blocks.erase(a->blocks.begin() + (long)i);
+        return FR_OK;
+    }
+    return FR_ERR_ARG;
 }
 
 int fr_alloc_charge(fr_alloc* a, size_t bytes)
@@ -381,10 +399,12 @@ int fr_alloc_charge(fr_alloc* a, size_t bytes)
     if (a->oom) return FR_ERR_OOM;
     if ((uint64_t)bytes > a->limit || a->used > a->limit - (uint64_t)bytes) { a->oom = true; return FR_ERR_OOM; }
     a->used += bytes;
+    if (a->used > a->peak) a->peak = a->used;
     return FR_OK;
 }
 
 uint64_t fr_alloc_used(const fr_alloc* a) { return a ? a->used : 0; }
+uint64_t fr_alloc_peak(const fr_alloc* a) { return a ? a->peak : 0; }
 
 // ------------------------------------------------------------------ context
 int fr_create(const fr_config* cfg, fr_ctx** out)
@@ -511,7 +531,17 @@ int fr_bubble_end(fr_ctx* c)
     if (!c->bubble_open) return FR_ERR_STATE;
     c->end_requested.store(true, std::memory_order_release);
     const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
-    while (c->ack_seq.load(std::memory_order_acquire) != seq) cpu_relax();   // worker enqueues nothing more
+    while (c->ack_seq.load(std::memory_order_acquire) != seq) {              // worker enqueues nothing more
+        if (c->in_init.load(std::memory_order_acquire)) {
+            // InitSideTask has outlived the bubble.  The stage is not held up for it: the call returns at once
+            // and the initialisation goes on beside the stage's next operation.
+            c->bubble_open = false;
+            std::lock_guard<std::mutex> lk(c->mu);
+            if (c->task) c->task->prog.overruns++;
+            return FR_ERR_OVERRUN;
+        }
+        cpu_relax();
+    }
     c->bubble_open = false;
     if (c->host_only || !c->tail_armed) return FR_OK;     // nothing was enqueued for this bubble
     hipError_t q = hipEventQuery(c->tail_event);

@@ -18,14 +18,36 @@ def _dev(a, dtype):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).cuda()
 
 
+def _init_bubble(ctx, tid, length_ns=2_000_000_000):
+    """One long bubble for InitSideTask (Algorithm 2: the first bubble that finds the task CREATED initialises it)."""
+    import time
+    ctx.fr_bubble_begin(fr.fr_now_ns(), length_ns)
+    deadline = time.time() + 30
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < deadline:
+        time.sleep(0.001)
+    return ctx.fr_bubble_end()
+
+
 def _segments(task, iterations):
     v = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX)
-    p = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_PULL)
-    e = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_EPILOGUE)
-    segs = []
+    s = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_SCATTER)
+    g = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER)
+    h = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN)
+    segs = [v]
     for _ in range(iterations):
-        segs += [v, p, e]
-    return segs + [v]
+        segs += [s, g, h]
+    return segs
+
+
+def _check_cost_rule(task, pe, pm, pv, hub_ns):
+    """Tile costs follow the documented integer formula."""
+    rows = task.fr_pagerank_tile_work(fr.FR_PR_SEG_VERTEX)
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX) == [max(1, -(-r * pv // 1000)) for r in rows]
+    info = task.fr_pagerank_info()
+    edges = task.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
+    grow = rows + [64] * info.hub_partitions
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 1000)) for e, r in zip(edges, grow)]
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN) == [hub_ns] * max(1, -(-info.hubs // 256))
 
 
 def test_config1_harvest_matches_plan_and_oracle_bits():
@@ -44,9 +66,11 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     ctx = fr.Context(device_id=0, guard_ns=guard, launch_cost_ns=launch, max_chunk_ns=max_chunk, time_steps=1,
                      mem_available_bytes=1 << 40)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=cfg.iterations, max_runs=3,
-                           mem_limit_bytes=1 << 30, ps_per_edge=40, ps_per_vertex=100, epilogue_tile_ns=5000)
-    segs = _segments(task, cfg.iterations)
+                           mem_limit_bytes=1 << 30, ps_per_edge=400, ps_per_message=2500, ps_per_vertex=300,
+                           hubfin_tile_ns=15000)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    assert ctx.fr_query_progress(tid).state == fr.FR_PAUSED
     stream = torch.cuda.Stream()
     load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=cfg.busy_fp_ns, bp_ns=cfg.busy_bp_ns)
     stage = fr.Stage(fr.FR_SCHED_1F1B, cfg.p, cfg.m, cfg.stage, cfg.busy_fp_ns, cfg.busy_bp_ns, load, stream)
@@ -57,6 +81,8 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
         results.append(stage.fr_stage_run_epoch(ctx))
     pr = ctx.fr_query_progress(tid)
     log = ctx.fr_event_log()
+    segs = _segments(task, cfg.iterations)          # the cost tables exist once InitSideTask has run
+    _check_cost_rule(task, 400, 2500, 300, 15000)
     ctx.fr_task_stop(tid)
     got = ranks.cpu().numpy()
     want_bits = ref.cpu().numpy()
@@ -66,7 +92,7 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     ctx.fr_destroy()
 
     windows, T = schedule.bubbles("1f1b", cfg.p, cfg.m, cfg.busy_fp_ns, cfg.busy_bp_ns, cfg.stage)
-    lengths = [e - a for a, e in windows] * n_epochs
+    lengths = [2_000_000_000] + [e - a for a, e in windows] * n_epochs
     assert [r.n_bubbles for r in results] == [len(windows)] * n_epochs
     assert pr.overruns == 0 and pr.deadline_misses == 0 and sum(r.overruns for r in results) == 0
     assert pr.bubbles_seen == len(lengths)
@@ -94,7 +120,6 @@ def test_pagerank_task_is_stopped_alone_when_it_exceeds_its_memory_limit():
     ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
     ctx = fr.Context(device_id=0, mem_available_bytes=1 << 40)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=200_000)
-    assert task.fr_pagerank_footprint() > 200_000
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     ctx.fr_bubble_begin(fr.fr_now_ns(), 50_000_000)
     import time

@@ -94,17 +94,51 @@ def test_memory_limit_refuses_the_task():
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
     ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
     t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=1 << 40)
-    need = t.fr_pagerank_footprint()
+    with pytest.raises(fr.FreeRideError) as e:          # layout facts exist only after InitSideTask
+        t.fr_pagerank_info()
+    assert e.value.code == fr.FR_ERR_STATE
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    info = t.fr_pagerank_info()
     t.fr_pagerank_destroy()
-    assert need >= 4 * g.n_edges + 24 * g.n_vertices
-    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=need - 1)
+    caller = 4 * g.n_edges + 4 * (g.n_vertices + 1) + 8 * g.n_vertices
+    assert info.bytes_peak >= info.bytes_resident > caller
+    assert 0 < info.messages <= g.n_edges
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=info.bytes_peak - 1)
     with pytest.raises(fr.FreeRideError) as e:
         t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     assert e.value.code == fr.FR_ERR_OOM
     t.fr_pagerank_destroy()
-    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=need)
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, mem_limit_bytes=info.bytes_peak)
     t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     t.fr_pagerank_destroy()
+
+
+def test_layout_facts_match_the_graph():
+    # messages = distinct (destination partition, source) pairs; hubs = rows with more than 2048 in-edges
+    g = graphs.rmat_csr(15, 1 << 19, seed=6)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=1)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    info = t.fr_pagerank_info()
+    edges = t.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
+    msgs = t.fr_pagerank_tile_work(fr.FR_PR_SEG_SCATTER)
+    t.fr_pagerank_destroy()
+    indeg = np.diff(g.row_ptr)
+    hub = indeg > 2048
+    assert info.hubs == int(hub.sum())
+    assert info.virtual_rows == int(np.ceil(indeg[hub] / 2048).sum())
+    assert info.regular_partitions == -(-g.n_vertices // 8192) and info.source_partitions == -(-g.n_vertices // 16384)
+    assert info.hub_partitions == -(-info.virtual_rows // 64)
+    assert sum(edges) == g.n_edges and sum(msgs) == info.messages
+    # recount the messages on the host: regular rows by row // 8192, hub rows by their virtual-row partition
+    row = np.repeat(np.arange(g.n_vertices), indeg)
+    pos = np.arange(g.n_edges) - np.repeat(g.row_ptr[:-1], indeg)
+    vbase = np.zeros(g.n_vertices, dtype=np.int64)
+    vbase[hub] = np.cumsum(np.ceil(indeg[hub] / 2048).astype(np.int64)) - np.ceil(indeg[hub] / 2048).astype(np.int64)
+    part = np.where(hub[row], info.regular_partitions + (vbase[row] + pos // 2048) // 64, row // 8192)
+    want = np.unique(part.astype(np.int64) * g.n_vertices + g.col).size
+    assert info.messages == want
 
 
 def test_malformed_csr_is_refused_before_any_kernel_uses_it():

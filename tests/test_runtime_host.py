@@ -258,3 +258,32 @@ def test_late_notification_is_a_deadline_miss_not_an_overrun():
     c.fr_destroy()
     assert pr.deadline_misses == 1 and pr.steps == 0
     assert log[-1][0] == "MISS"
+
+
+def test_init_that_outlives_its_bubble_does_not_hold_the_stage():
+    # InitSideTask is protected like any step (Section 4.5): when it is still running at the bubble's end the
+    # stage is not made to wait; the call reports an overrun and the task starts running in a later bubble.
+    ms = 1_000_000
+
+    class SlowInit(FakeTask):
+        def _init(self, user, alloc, stream):
+            time.sleep(0.08)
+            return super()._init(user, alloc, stream)
+
+    c = fr.Context(device_id=-1, guard_ns=0, launch_cost_ns=0)
+    t = SlowInit([[1 * ms]], max_runs=1)
+    t.ops = fr.fr_task_ops(fr.binding.CREATE_FN(t._create), fr.binding.INIT_FN(t._init), fr.binding.PLAN_FN(t._plan),
+                           fr.binding.RUN_FN(t._run), fr.binding.STOP_FN(t._stop))
+    tid = c.fr_task_register(t.ops, None, fr.fr_task_profile(10, 1))
+    c.fr_bubble_begin(fr.fr_now_ns(), 5 * ms)
+    time.sleep(0.005)
+    t0 = time.time()
+    assert c.fr_bubble_end() == fr.FR_ERR_OVERRUN
+    assert time.time() - t0 < 0.02                                  # returned at once
+    assert c.fr_query_progress(tid).state == fr.FR_CREATED
+    time.sleep(0.12)                                                # init finishes between bubbles
+    assert c.fr_query_progress(tid).state == fr.FR_PAUSED
+    assert _bubble(c, 50 * ms, hold_s=0.01) == fr.FR_OK
+    pr = c.fr_query_progress(tid)
+    c.fr_destroy()
+    assert pr.overruns == 1 and pr.runs_completed == 1
