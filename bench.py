@@ -99,10 +99,10 @@ def main():
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3] / cal_iters
     ps_per_vertex = max(1, int(v_ns * 1000 * args.derate / V))
     ps_per_message = max(1, int((s_ns * 1000 * args.derate - V * ps_per_vertex) / M))
-    ps_per_edge = max(1, int((g_ns * 1000 * args.derate - (V + 64 * info.hub_partitions) * ps_per_vertex) / max(1, E)))
+    ps_per_edge = max(1, int((g_ns * 1000 * args.derate - V * ps_per_vertex) / max(1, E)))
     hubfin_tile_ns = max(1, int(h_ns * args.derate / n_hub_tiles))
-    log("layout: M/E=%.3f, %d+%d destination partitions, %d source partitions, %d hubs, init+first run %.2fs" %
-        (info.messages / max(1, E), info.regular_partitions, info.hub_partitions, info.source_partitions, info.hubs, t_init))
+    log("layout: M/E=%.3f, %d destination partitions, %d source partitions, %d hubs in %d virtual rows, init+first run %.2fs" %
+        (info.messages / max(1, E), info.partitions, info.source_partitions, info.hubs, info.virtual_rows, t_init))
     log("standalone per iteration: scatter %.1f us, gather %.1f us, hub finish %.1f us (first vertex pass %.1f us)" %
         (s_ns / 1e3, g_ns / 1e3, h_ns / 1e3, v_ns / 1e3))
     standalone_iter_ns = s_ns + g_ns + h_ns
@@ -208,7 +208,7 @@ def main():
                      "launches": {"k_scatter": per_kind_n[1], "k_gather": per_kind_n[2], "k_hubfin": per_kind_n[3]},
                      "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0},
         "layout": {"messages_per_edge": info.messages / max(1, E), "hubs": info.hubs,
-                   "destination_partitions": info.regular_partitions + info.hub_partitions,
+                   "destination_partitions": info.partitions, "source_partitions": info.source_partitions,
                    "bytes_resident": info.bytes_resident, "bytes_peak_init": info.bytes_peak},
         "paper_context": {"bubble_rate_pct": 42.4, "cost_savings_pct": 7.8, "overhead_pct": 1.1,
                           "pagerank_iterations_per_s": 333.9, "hardware": "4x RTX 6000 Ada (paper, Section 6)"},

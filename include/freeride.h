@@ -253,8 +253,11 @@ typedef struct fr_pagerank_desc {
 /* Facts about the layout built by InitSideTask. */
 typedef struct fr_pagerank_info_t {
     uint64_t messages;            /* distinct (destination partition, source) pairs                         */
-    uint32_t regular_partitions, hub_partitions, source_partitions;
-    uint32_t hubs, virtual_rows;
+    uint32_t partitions;          /* destination partitions (gather tiles)                                  */
+    uint32_t source_partitions;   /* scatter tiles                                                          */
+    uint32_t hubs;                /* rows with more than hub_split in-edges                                 */
+    uint32_t virtual_rows;        /* pieces the hubs' in-edges were dealt out to                            */
+    uint32_t hub_split;
     uint32_t reserved;
     uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
     uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */

@@ -73,8 +73,8 @@ class fr_pagerank_desc(C.Structure):
 
 
 class fr_pagerank_info_t(C.Structure):
-    _fields_ = [("messages", C.c_uint64), ("regular_partitions", C.c_uint32), ("hub_partitions", C.c_uint32),
-                ("source_partitions", C.c_uint32), ("hubs", C.c_uint32), ("virtual_rows", C.c_uint32),
+    _fields_ = [("messages", C.c_uint64), ("partitions", C.c_uint32), ("source_partitions", C.c_uint32),
+                ("hubs", C.c_uint32), ("virtual_rows", C.c_uint32), ("hub_split", C.c_uint32),
                 ("reserved", C.c_uint32), ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
 
 

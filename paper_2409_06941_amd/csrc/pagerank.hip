@@ -12,8 +12,8 @@
 //   G_k  gather      (tile = destination partition): id stream + messages -> 64-bit fixed-point sums in LDS;
 //                    then, fused, the next vertex pass for the partition's rows:
 //                    r_{k+1} = base_k + d * sum, contrib_{k+1} = r_{k+1} / outdeg, dangling partials
-//                    (hub partitions only store their virtual rows' sums)
-//   H_k  hub finish  (tile = 256 hubs): add a hub's virtual rows, same vertex-pass arithmetic
+//                    (sums of hubs' virtual rows are only stored)
+//   H_k  hub finish  (tile = 16 hubs): add a hub's virtual rows, same vertex-pass arithmetic
 // base_k = (1 - d)/V + d * D_k / V, D_k = fixed-order sum of the dangling partials of r_k.
 // In the last iteration G and H write r_K to ranks_out instead of contrib.
 // No floating-point atomics anywhere: float sums have a fixed order, the LDS atomics add integers.
@@ -27,8 +27,17 @@
 
 namespace {
 
-constexpr int kBlock = 512;                     // threads per workgroup of the sweeps (8 wavefronts)
-constexpr int kWaves = kBlock / 64;
+#ifndef FR_GATHER_BLOCK
+#define FR_GATHER_BLOCK 1024
+#endif
+#ifndef FR_SCATTER_BLOCK
+#define FR_SCATTER_BLOCK 1024
+#endif
+constexpr int kBlock = 512;                     // threads per workgroup of the first vertex pass
+constexpr int kGatherBlock = FR_GATHER_BLOCK;   // threads per workgroup of the gather sweep
+constexpr int kGatherWaves = kGatherBlock / 64;
+constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the scatter sweep
+constexpr int kScatterWaves = kScatterBlock / 64;
 constexpr float kFixScale = 4611686018427387904.0f;        // 2^62: contrib sums are <= 1, so they fit u64
 constexpr float kFixInv = 1.0f / 4611686018427387904.0f;
 
@@ -54,13 +63,26 @@ __device__ __forceinline__ float block_sum(float x, float* lds /* >= 8 floats */
     return s;
 }
 
-// D = sum of dpart[0 .. n): strided over the first 256 threads, then a fixed tree, so every kernel that calls
-// this gets the same bits whatever its workgroup size (>= 256).  All threads call; all get the result.
-__device__ __forceinline__ float dangling_total(const float* __restrict__ dpart, uint32_t n, float* lds /* >= 8 */)
+// D = sum of dpart[0 .. n), in two halves so that the loads can be issued long before the sum is needed:
+// dangling_partial (threads 0..255 each add up a strided share) and dangling_finish (fixed tree over those 256
+// partial sums).  Every kernel that uses the pair gets the same bits whatever its workgroup size (>= 256).
+__device__ __forceinline__ float dangling_partial(const float* __restrict__ dpart, uint32_t n)
 {
     float s = 0.0f;
-    if (threadIdx.x < 256)
-        for (uint32_t i = threadIdx.x; i < n; i += 256) s += dpart[i];
+    if (threadIdx.x < 256) {
+        uint32_t i = threadIdx.x;
+        for (; i + 768 < n; i += 1024) {
+            const float a = dpart[i], b = dpart[i + 256], c = dpart[i + 512], d = dpart[i + 768];
+            s += a; s += b; s += c; s += d;
+        }
+        for (; i < n; i += 256) s += dpart[i];
+    }
+    return s;
+}
+
+// All threads call; all get the result.
+__device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 floats */)
+{
     s = wave_sum(s);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     __syncthreads();
@@ -74,7 +96,7 @@ __device__ __forceinline__ float inv_of_tag(float tag) { return __uint_as_float(
 
 struct DevArgs {
     int64_t V, E;
-    uint32_t M, q_reg, q_hub, P, n_hubs, n_dpart;
+    uint32_t M, Q, P, n_hubs, n_vrows, n_dpart;
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
@@ -87,7 +109,7 @@ struct DevArgs {
     float* msg;
     float* contrib;
     float* dpart;                 // [2][n_dpart]
-    unsigned long long* vacc;     // [q_hub * kVrowsPerHubPart]
+    unsigned long long* vacc;     // [n_vrows]
     float* ranks_out;
 };
 
@@ -113,38 +135,71 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
         const float total = block_sum(dangling, red);
         if (threadIdx.x == 0) A.dpart[q] = total;
         if (q == 0)
-            for (uint32_t i = A.q_reg + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;   // hub slots
+            for (uint32_t i = A.Q + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;   // hub slots
     }
 }
 
 // ---- S_k ----
-__global__ __launch_bounds__(kBlock) void k_scatter(DevArgs A, uint32_t tile0)
+// One workgroup per source partition: its slice of contrib sits in LDS, and for every destination partition q
+// the messages of bin (p, q) are written in order.  Bin descriptors are staged in LDS a batch at a time; each
+// wavefront works on two bins at once, eight messages per lane per step, so that sixteen independent loads are
+// in flight before the first one is needed.
+constexpr uint32_t kDescBatch = 1024;
+
+__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
-    __shared__ uint32_t next_bin;
+    __shared__ uint2 desc[kDescBatch];
     const uint32_t p = tile0 + blockIdx.x;
     const int64_t v0 = (int64_t)p * kSrcPerPart;
     const uint32_t n = (uint32_t)((A.V - v0) < (int64_t)kSrcPerPart ? (A.V - v0) : (int64_t)kSrcPerPart);
-    for (uint32_t i = threadIdx.x * 4; i < n; i += kBlock * 4) {
+    for (uint32_t i = threadIdx.x * 4; i < n; i += kScatterBlock * 4) {
         if (i + 3 < n) *reinterpret_cast<float4*>(&slice[i]) = *reinterpret_cast<const float4*>(A.contrib + v0 + i);
         else
             for (uint32_t c = i; c < n; ++c) slice[c] = A.contrib[v0 + c];
     }
-    if (threadIdx.x == 0) next_bin = kWaves;
-    __syncthreads();
-    const uint32_t Q = A.q_reg + A.q_hub;
-    const int lane = threadIdx.x & 63;
-    uint32_t q = threadIdx.x >> 6;                  // every wavefront starts on its own bin, then takes the next free one
-    while (q < Q) {
-        const uint2 b = A.bins[(uint64_t)p * Q + q];
-        const uint32_t end = b.y < A.M ? b.y : A.M;
-        for (uint32_t m = b.x + lane; m < end; m += 64) {
-            const uint32_t s = A.src16[m];
-            A.msg[m] = s < n ? slice[s] : 0.0f;
+    const uint32_t Q = A.Q;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (uint32_t qb = 0; qb < Q; qb += kDescBatch) {
+        const uint32_t nb = Q - qb < kDescBatch ? Q - qb : kDescBatch;
+        __syncthreads();                                   // slice loaded / previous batch consumed
+        for (uint32_t i = threadIdx.x; i < nb; i += kScatterBlock) {
+            uint2 b = A.bins[(uint64_t)p * Q + qb + i];
+            if (b.y > A.M) b.y = A.M;
+            if (b.x > b.y) b.x = b.y;
+            desc[i] = b;
         }
-        uint32_t nq = 0;
-        if (lane == 0) nq = atomicAdd(&next_bin, 1u);
-        q = __shfl(nq, 0, 64);
+        __syncthreads();
+        for (uint32_t i = 2 * wave; i < nb; i += 2 * kScatterWaves) {
+            uint32_t pos[2], end[2];
+            pos[0] = desc[i].x; end[0] = desc[i].y;
+            if (i + 1 < nb) { pos[1] = desc[i + 1].x; end[1] = desc[i + 1].y; }
+            else { pos[1] = 0; end[1] = 0; }
+            while (pos[0] < end[0] || pos[1] < end[1]) {
+                uint32_t src[2][8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const uint32_t m = pos[h] + lane + 64 * t;
+                        src[h][t] = m < end[h] ? A.src16[m] : 0u;
+                    }
+                float val[2][8];
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) val[h][t] = src[h][t] < n ? slice[src[h][t]] : 0.0f;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const uint32_t m = pos[h] + lane + 64 * t;
+                        if (m < end[h]) A.msg[m] = val[h][t];
+                    }
+                pos[0] = pos[0] + 512 < end[0] ? pos[0] + 512 : end[0];
+                pos[1] = pos[1] + 512 < end[1] ? pos[1] + 512 : end[1];
+            }
+        }
     }
 }
 
@@ -160,92 +215,146 @@ __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t x, int lane)
     return incl - x;
 }
 
-__global__ __launch_bounds__(kBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
+constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
+
+// One workgroup per destination partition; its accumulators (one u64 per row, plus the spare slots for hubs'
+// virtual rows) sit in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
+// three-stage software pipeline over the wavefront's chunks, so that no step waits on a load it has just issued:
+//   A  ids and message base of chunk i + 2 are requested;
+//   B  chunk i + 1 (ids now here): flags are prefix-summed over the wavefront, which tells every id which
+//      message it belongs to; the messages are requested;
+//   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
+//      accumulator with an LDS atomic.
+__global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
 {
-    __shared__ unsigned long long acc[kRowsPerPart];
-    __shared__ float red[8];
+    __shared__ unsigned long long acc[kAccSlots];
+    __shared__ float red[32];
     const uint32_t q = tile0 + blockIdx.x;
-    const bool hub_part = q >= A.q_reg;
-    uint32_t nrows;
-    if (!hub_part) {
-        const int64_t left = A.V - (int64_t)q * kRowsPerPart;
-        nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
-    } else nrows = kVrowsPerHubPart;
-    for (uint32_t i = threadIdx.x; i < nrows; i += kBlock) acc[i] = 0ull;
+    const int64_t left = A.V - (int64_t)q * kRowsPerPart;
+    const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
+    for (uint32_t i = threadIdx.x; i < kAccSlots; i += kGatherBlock) acc[i] = 0ull;
+    const float d_part = dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     __syncthreads();
 
     const uint32_t e0 = A.eoff[q], e1 = A.eoff[q + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (e1 > e0) {
         const uint32_t c0 = e0 / kIdChunk, c1 = (e1 - 1) / kIdChunk;
-        for (uint32_t c = c0 + wave; c <= c1; c += kWaves) {
-            const uint4 raw = reinterpret_cast<const uint4*>(A.ids16)[(uint64_t)c * (kIdChunk / 8) + lane];
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-            uint32_t id[8];
+        const uint4* ids4 = reinterpret_cast<const uint4*>(A.ids16);
+        uint32_t cA = c0 + wave;                 // chunk whose ids are in rawA
+        uint4 rawA = make_uint4(0, 0, 0, 0);
+        uint32_t mbA = 0;
+        if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
+        uint4 rawP = make_uint4(0, 0, 0, 0);     // chunk waiting for stage C
+        float valP[8];
+        uint32_t okP = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { id[2 * j] = w[j] & 0xffffu; id[2 * j + 1] = w[j] >> 16; }
+        for (int j = 0; j < 8; ++j) valP[j] = 0.0f;
+        while (cA <= c1) {
+            // ---- stage B on chunk cA
+            const uint32_t w[4] = {rawA.x, rawA.y, rawA.z, rawA.w};
             uint32_t nf = 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) nf += id[j] >> 15;
-            uint32_t ord = A.mbase[c] + wave_exclusive_scan(nf, lane);     // messages begun before this lane's ids
-            const uint32_t ebase = c * kIdChunk + lane * 8;
-            float val = 0.0f;
+            for (int j = 0; j < 4; ++j) nf += ((w[j] >> 15) & 1u) + (w[j] >> 31);
+            uint32_t ord = mbA + wave_exclusive_scan(nf, (int)lane);      // messages begun before this lane's ids
+            const uint32_t ebase = cA * kIdChunk + lane * 8;
+            float valN[8];
+            uint32_t okN = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t f = id[j] >> 15;
-                ord += f;
-                if (f | (j == 0)) {
-                    const uint32_t mi = ord - 1;
-                    val = mi < A.M ? A.msg[mi] : 0.0f;
-                }
+                const uint32_t id = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+                ord += id >> 15;
                 const uint32_t e = ebase + j;
-                const uint32_t loc = id[j] & 0x3fffu;
-                if (e >= e0 && e < e1 && loc < nrows)
-                    atomicAdd(&acc[loc], (unsigned long long)(val * kFixScale));
+                const uint32_t mi = ord - 1;                               // this id's message
+                const bool ok = e >= e0 && e < e1 && (id & 0x3fffu) < kAccSlots && mi < A.M;
+                okN |= (ok ? 1u : 0u) << j;
+                valN[j] = A.msg[ok ? mi : 0u];
+            }
+            const uint4 rawN = rawA;
+            // ---- stage A on the next chunk of this wavefront
+            const uint32_t cN = cA + kGatherWaves;
+            if (cN <= c1) { rawA = ids4[(uint64_t)cN * (kIdChunk / 8) + lane]; mbA = A.mbase[cN]; }
+            // ---- stage C on the previous chunk
+            {
+                const uint32_t wp[4] = {rawP.x, rawP.y, rawP.z, rawP.w};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
+                    if ((okP >> j) & 1u) atomicAdd(&acc[id & 0x3fffu], (unsigned long long)(valP[j] * kFixScale));
+                }
+            }
+            rawP = rawN;
+            okP = okN;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) valP[j] = valN[j];
+            cA = cN;
+        }
+        {   // drain: stage C on the last chunk
+            const uint32_t wp[4] = {rawP.x, rawP.y, rawP.z, rawP.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
+                if ((okP >> j) & 1u) atomicAdd(&acc[id & 0x3fffu], (unsigned long long)(valP[j] * kFixScale));
             }
         }
     }
     __syncthreads();
 
-    if (hub_part) {
-        const uint32_t vb = (q - A.q_reg) * kVrowsPerHubPart;
-        for (uint32_t i = threadIdx.x; i < nrows; i += kBlock) A.vacc[vb + i] = acc[i];
-        return;
+    // virtual rows dealt to this partition: hv = q + slot * Q
+    for (uint32_t slot = threadIdx.x; slot < kMaxVrowsPerPart; slot += kGatherBlock) {
+        const uint64_t hv = (uint64_t)q + (uint64_t)slot * A.Q;
+        if (hv < A.n_vrows) A.vacc[hv] = acc[kRowsPerPart + slot];
     }
-    const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart, red);
+    // fused vertex pass for the partition's own rows
+    const float D = dangling_finish(d_part, red);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     const int64_t v0 = (int64_t)q * kRowsPerPart;
     float dangling = 0.0f;
-    for (uint32_t i = threadIdx.x; i < nrows; i += kBlock) {
-        const float tag = A.inv_tag[v0 + i];
-        if (is_hub_tag(tag)) continue;                 // finished by H_k
+    constexpr int kRowsPerThread = (kRowsPerPart + kGatherBlock - 1) / kGatherBlock;
+    float tag[kRowsPerThread];
+#pragma unroll
+    for (int t = 0; t < kRowsPerThread; ++t) {
+        const uint32_t i = threadIdx.x + kGatherBlock * t;
+        tag[t] = i < nrows ? A.inv_tag[v0 + i] : -0.0f;           // rows past the end behave like hubs: skipped
+    }
+#pragma unroll
+    for (int t = 0; t < kRowsPerThread; ++t) {
+        const uint32_t i = threadIdx.x + kGatherBlock * t;
+        if (i >= nrows || is_hub_tag(tag[t])) continue;            // hubs are finished by H_k
         const float s = (float)acc[i] * kFixInv;
         const float r = fmaf(A.damping, s, base);
         if (final_pass) A.ranks_out[v0 + i] = r;
         else {
-            A.contrib[v0 + i] = r * tag;
-            dangling += (tag == 0.0f ? r : 0.0f);
+            A.contrib[v0 + i] = r * tag[t];
+            dangling += (tag[t] == 0.0f ? r : 0.0f);
         }
     }
     if (!final_pass) {
-        const float total = block_sum(dangling, red);
+        const float total = block_sum(dangling, red + 8);
         if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + q] = total;
     }
 }
 
 // ---- H_k ----
-__global__ __launch_bounds__(kHubsPerTile) void k_hubfin(DevArgs A, uint32_t tile0, int parity, int final_pass)
+// 16 hubs per workgroup, 16 lanes per hub: the lanes add up the hub's virtual rows (integers, any order), the
+// group's first lane applies the vertex-pass arithmetic.
+__global__ __launch_bounds__(256) void k_hubfin(DevArgs A, uint32_t tile0, int parity, int final_pass)
 {
-    __shared__ float red[8];
+    __shared__ float red[24];
     const uint32_t t = tile0 + blockIdx.x;
-    const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart, red);
+    const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
-    const uint32_t h = t * kHubsPerTile + threadIdx.x;
+    const uint32_t h = t * kHubsPerTile + (threadIdx.x >> 4);
+    const uint32_t sub = threadIdx.x & 15;
     float dangling = 0.0f;
+    unsigned long long s = 0ull;
     if (h < A.n_hubs) {
-        unsigned long long s = 0ull;
         const uint32_t a = A.hub_vbase[h], b = A.hub_vbase[h + 1];
-        for (uint32_t i = a; i < b && i < A.q_hub * kVrowsPerHubPart; ++i) s += A.vacc[i];
+        for (uint32_t i = a + sub; i < b && i < A.n_vrows; i += 16) s += A.vacc[i];
+    }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) s += (unsigned long long)__shfl_xor((long long)s, off, 64);
+    if (h < A.n_hubs && sub == 0) {
         const int32_t v = A.hub_row[h];
         const float inv = inv_of_tag(A.inv_tag[v]);
         const float r = fmaf(A.damping, (float)s * kFixInv, base);
@@ -256,8 +365,8 @@ __global__ __launch_bounds__(kHubsPerTile) void k_hubfin(DevArgs A, uint32_t til
         }
     }
     if (!final_pass) {
-        const float total = block_sum(dangling, red);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.q_reg + t] = total;
+        const float total = block_sum(dangling, red + 8);
+        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.Q + t] = total;
     }
 }
 
@@ -289,15 +398,14 @@ struct PrTask {
     uint32_t tiles_of(int kind) const
     {
         switch (kind) {
-        case FR_PR_SEG_VERTEX: return L.q_reg;
+        case FR_PR_SEG_VERTEX: return L.Q;
         case FR_PR_SEG_SCATTER: return L.P;
-        case FR_PR_SEG_GATHER: return L.Q();
+        case FR_PR_SEG_GATHER: return L.Q;
         default: return L.n_hub_tiles;
         }
     }
     uint64_t rows_of_q(uint32_t q) const
     {
-        if (q >= L.q_reg) return kVrowsPerHubPart;
         return std::min<uint64_t>(kRowsPerPart, (uint64_t)L.V - (uint64_t)q * kRowsPerPart);
     }
 };
@@ -307,8 +415,8 @@ void build_cost_tables(PrTask* p)
     const PrLayout& L = p->L;
     const uint64_t pe = p->d.ps_per_edge, pm = p->d.ps_per_message, pv = p->d.ps_per_vertex;
     auto& v = p->prefix[FR_PR_SEG_VERTEX];
-    v.assign(L.q_reg + 1, 0);
-    for (uint32_t q = 0; q < L.q_reg; ++q) v[q + 1] = v[q] + ceil_ps_to_ns((unsigned __int128)p->rows_of_q(q) * pv);
+    v.assign(L.Q + 1, 0);
+    for (uint32_t q = 0; q < L.Q; ++q) v[q + 1] = v[q] + ceil_ps_to_ns((unsigned __int128)p->rows_of_q(q) * pv);
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
     s.assign(L.P + 1, 0);
     for (uint32_t i = 0; i < L.P; ++i) {
@@ -316,8 +424,8 @@ void build_cost_tables(PrTask* p)
         s[i + 1] = s[i] + ceil_ps_to_ns((unsigned __int128)L.msgs_of_p[i] * pm + (unsigned __int128)srcs * pv);
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
-    g.assign(L.Q() + 1, 0);
-    for (uint32_t q = 0; q < L.Q(); ++q)
+    g.assign(L.Q + 1, 0);
+    for (uint32_t q = 0; q < L.Q; ++q)
         g[q + 1] = g[q] + ceil_ps_to_ns((unsigned __int128)L.edges_of_q[q] * pe + (unsigned __int128)p->rows_of_q(q) * pv);
     auto& h = p->prefix[FR_PR_SEG_HUBFIN];
     h.assign(L.n_hub_tiles + 1, 0);
@@ -335,9 +443,9 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
     } else {
         const uint32_t k = (g - 1) / 3;
         const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
-        if (kind == FR_PR_SEG_SCATTER) hipLaunchKernelGGL(k_scatter, dim3(n), dim3(kBlock), 0, stream, p->args, tile0);
-        else if (kind == FR_PR_SEG_GATHER) hipLaunchKernelGGL(k_gather, dim3(n), dim3(kBlock), 0, stream, p->args, tile0, parity, final_pass);
-        else hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(kHubsPerTile), 0, stream, p->args, tile0, parity, final_pass);
+        if (kind == FR_PR_SEG_SCATTER) hipLaunchKernelGGL(k_scatter, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0);
+        else if (kind == FR_PR_SEG_GATHER) hipLaunchKernelGGL(k_gather, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
+        else hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, tile0, parity, final_pass);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
@@ -363,12 +471,12 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     int rc = pr_build_layout(&p->L, V, E, p->d.row_ptr, p->d.col, p->d.out_degree, a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
-    p->n_dpart = L.q_reg + L.n_hub_tiles;
+    p->n_dpart = L.Q + L.n_hub_tiles;
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
-        !take(a, &p->vacc, (uint64_t)std::max<uint32_t>(L.q_hub, 1) * kVrowsPerHubPart))
+        !take(a, &p->vacc, (uint64_t)L.n_vrows))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
     DevArgs& A = p->args;
-    A.V = V; A.E = E; A.M = (uint32_t)L.M; A.q_reg = L.q_reg; A.q_hub = L.q_hub; A.P = L.P; A.n_hubs = L.n_hubs;
+    A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.P = L.P; A.n_hubs = L.n_hubs; A.n_vrows = L.n_vrows;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.ids16 = L.ids16; A.src16 = L.src16; A.eoff = L.eoff; A.mbase = L.mbase; A.bins = L.bins;
     A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.inv_tag = L.inv_tag;
@@ -482,8 +590,8 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out)
     if (p->prefix[0].empty()) return FR_ERR_STATE;       // known once InitSideTask has run
     std::memset(out, 0, sizeof(*out));
     out->messages = p->L.M;
-    out->regular_partitions = p->L.q_reg;
-    out->hub_partitions = p->L.q_hub;
+    out->partitions = p->L.Q;
+    out->hub_split = p->L.hub_split;
     out->source_partitions = p->L.P;
     out->hubs = p->L.n_hubs;
     out->virtual_rows = p->L.n_vrows;

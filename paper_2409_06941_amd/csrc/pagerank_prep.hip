@@ -54,17 +54,17 @@ __global__ __launch_bounds__(kBlk) void k_validate(int64_t V, int64_t E, const i
 }
 
 // packed[v] = (virtual rows of v) << 32 | (1 if v is a hub)
-__global__ __launch_bounds__(kBlk) void k_hub_mark(int64_t V, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ packed)
+__global__ __launch_bounds__(kBlk) void k_hub_mark(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ packed)
 {
     const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (v >= V) return;
     const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
-    const bool hub = indeg > kHubSplit;
-    const uint64_t nsplit = hub ? (indeg + kHubSplit - 1) / kHubSplit : 0;
+    const bool hub = indeg > split;
+    const uint64_t nsplit = hub ? ((uint64_t)indeg + split - 1) / split : 0;
     packed[v] = (nsplit << 32) | (hub ? 1u : 0u);
 }
 
-__global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, const int32_t* __restrict__ row_ptr,
+__global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr,
                                                      const uint64_t* __restrict__ scanned, uint32_t n_hubs,
                                                      uint32_t n_vrows, int32_t* __restrict__ hub_row,
                                                      uint32_t* __restrict__ hub_vbase)
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, const int32_t* _
     if (v == 0) hub_vbase[n_hubs] = n_vrows;
     if (v >= V) return;
     const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
-    if (indeg <= kHubSplit) return;
+    if (indeg <= split) return;
     const uint32_t h = (uint32_t)(scanned[v] & 0xffffffffu);
     if (h < n_hubs) {
         hub_row[h] = (int32_t)v;
@@ -82,20 +82,21 @@ __global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, const int32_t* _
 }
 
 // 1/outdeg (0 for dangling vertices) with the sign bit marking hub rows.
-__global__ __launch_bounds__(kBlk) void k_inv_tag(int64_t V, const int32_t* __restrict__ row_ptr,
+__global__ __launch_bounds__(kBlk) void k_inv_tag(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr,
                                                   const int32_t* __restrict__ outdeg, float* __restrict__ inv_tag)
 {
     const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (v >= V) return;
     const int32_t d = outdeg[v];
     float inv = d > 0 ? 1.0f / (float)d : 0.0f;
-    if ((uint32_t)(row_ptr[v + 1] - row_ptr[v]) > kHubSplit) inv = __uint_as_float(__float_as_uint(inv) | 0x80000000u);
+    if ((uint32_t)(row_ptr[v + 1] - row_ptr[v]) > split) inv = __uint_as_float(__float_as_uint(inv) | 0x80000000u);
     inv_tag[v] = inv;
 }
 
-__global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, const int32_t* __restrict__ row_ptr,
+// Virtual row hv of a hub goes to partition hv % Q, accumulator slot kRowsPerPart + hv / Q.
+__global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, uint32_t split, const int32_t* __restrict__ row_ptr,
                                                const int32_t* __restrict__ col, const uint64_t* __restrict__ scanned,
-                                               uint32_t q_reg, uint64_t* __restrict__ keys)
+                                               uint32_t Q, uint64_t* __restrict__ keys)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= E) return;
@@ -103,10 +104,10 @@ __global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, const int32
     const int64_t begin = row_ptr[v];
     const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - begin);
     uint64_t q, local;
-    if (indeg > kHubSplit) {
-        const uint64_t hv = (scanned[v] >> 32) + (uint64_t)(e - begin) / kHubSplit;
-        q = q_reg + hv / kVrowsPerHubPart;
-        local = hv % kVrowsPerHubPart;
+    if (indeg > split) {
+        const uint64_t hv = (scanned[v] >> 32) + (uint64_t)(e - begin) / split;
+        q = hv % Q;
+        local = kRowsPerPart + hv / Q;
     } else {
         q = (uint64_t)v / kRowsPerPart;
         local = (uint64_t)v % kRowsPerPart;
@@ -231,10 +232,12 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                     const int32_t* out_degree, fr_alloc* a, hipStream_t stream, int* hip_error)
 {
     L->V = V; L->E = E;
-    L->q_reg = (uint32_t)((V + kRowsPerPart - 1) / kRowsPerPart);
+    L->Q = (uint32_t)((V + kRowsPerPart - 1) / kRowsPerPart);
     L->P = (uint32_t)((V + kSrcPerPart - 1) / kSrcPerPart);
     L->n_chunks = (uint32_t)((E + kIdChunk - 1) / kIdChunk);
     const int64_t padded = (int64_t)std::max<uint32_t>(L->n_chunks, 1) * kIdChunk;
+    const uint32_t Q = L->Q;
+    if ((uint64_t)Q >= (1ull << (63 - kKeyLocalBits - kKeySrcBits))) return FR_ERR_ARG;
 
     Scratch tmp{a, {}};
 
@@ -249,35 +252,38 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_HIP(hipStreamSynchronize(stream));
     if (bad_host) return FR_ERR_ARG;
 
-    // ---- hubs and their virtual rows
+    // ---- hubs and their virtual rows; the split length doubles until the spare slots hold all virtual rows
     uint64_t* packed = tmp.take<uint64_t>((uint64_t)V);
     uint64_t* scanned = tmp.take<uint64_t>((uint64_t)V);
     PREP_NEED(packed); PREP_NEED(scanned);
-    hipLaunchKernelGGL(k_hub_mark, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, packed);
-    {
-        size_t bytes = 0;
-        PREP_HIP(rocprim::exclusive_scan(nullptr, bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
-        void* t = tmp.take<uint8_t>(bytes);
-        PREP_NEED(t);
-        PREP_HIP(rocprim::exclusive_scan(t, bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
+    void* scan_tmp = nullptr;
+    size_t scan_bytes = 0;
+    PREP_HIP(rocprim::exclusive_scan(nullptr, scan_bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
+    scan_tmp = tmp.take<uint8_t>(scan_bytes);
+    PREP_NEED(scan_tmp);
+    uint32_t split = kHubSplitMin;
+    for (;;) {
+        hipLaunchKernelGGL(k_hub_mark, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, packed);
+        PREP_HIP(rocprim::exclusive_scan(scan_tmp, scan_bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
+        uint64_t last_packed = 0, last_scanned = 0;
+        PREP_HIP(hipMemcpyAsync(&last_packed, packed + (V - 1), 8, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipMemcpyAsync(&last_scanned, scanned + (V - 1), 8, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipStreamSynchronize(stream));
+        const uint64_t totals = last_packed + last_scanned;
+        L->n_hubs = (uint32_t)(totals & 0xffffffffu);
+        L->n_vrows = (uint32_t)(totals >> 32);
+        if ((uint64_t)L->n_vrows <= (uint64_t)kMaxVrowsPerPart * Q) break;
+        if (split >= 0x40000000u) return FR_ERR_ARG;       // cannot happen for E < 2^31
+        split *= 2;
     }
-    uint64_t last_packed = 0, last_scanned = 0;
-    PREP_HIP(hipMemcpyAsync(&last_packed, packed + (V - 1), 8, hipMemcpyDeviceToHost, stream));
-    PREP_HIP(hipMemcpyAsync(&last_scanned, scanned + (V - 1), 8, hipMemcpyDeviceToHost, stream));
-    PREP_HIP(hipStreamSynchronize(stream));
-    const uint64_t totals = last_packed + last_scanned;
-    L->n_hubs = (uint32_t)(totals & 0xffffffffu);
-    L->n_vrows = (uint32_t)(totals >> 32);
-    L->q_hub = (L->n_vrows + kVrowsPerHubPart - 1) / kVrowsPerHubPart;
+    L->hub_split = split;
     L->n_hub_tiles = std::max<uint32_t>(1, (L->n_hubs + kHubsPerTile - 1) / kHubsPerTile);
-    const uint32_t Q = L->Q();
-    if ((uint64_t)Q >= (1ull << (63 - kKeyLocalBits - kKeySrcBits))) return FR_ERR_ARG;
 
     if (!keep(a, &L->hub_row, L->n_hubs) || !keep(a, &L->hub_vbase, (uint64_t)L->n_hubs + 1) || !keep(a, &L->inv_tag, (uint64_t)V))
         PREP_NEED((void*)nullptr);
-    hipLaunchKernelGGL(k_hub_tables, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, scanned, L->n_hubs,
+    hipLaunchKernelGGL(k_hub_tables, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, scanned, L->n_hubs,
                        L->n_vrows, L->hub_row, L->hub_vbase);
-    hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, out_degree, L->inv_tag);
+    hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, out_degree, L->inv_tag);
 
     // ---- persistent arrays whose size does not depend on the message count
     if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->eoff, (uint64_t)Q + 1) ||
@@ -291,7 +297,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         uint64_t* keys_in = tmp.take<uint64_t>((uint64_t)E);
         keys = tmp.take<uint64_t>((uint64_t)E);
         PREP_NEED(keys_in); PREP_NEED(keys);
-        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, row_ptr, col, scanned, L->q_reg, keys_in);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, keys_in);
         unsigned end_bit = kKeyLocalBits + kKeySrcBits;
         while (end_bit < 63 && (1ull << (end_bit - kKeyLocalBits - kKeySrcBits)) < (uint64_t)Q) ++end_bit;
         {

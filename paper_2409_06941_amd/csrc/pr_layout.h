@@ -15,9 +15,11 @@
 //     and q's messages are read sequentially and added into LDS with integer atomics.  Integer addition is
 //     associative, so the sums do not depend on the order the hardware performs them in.
 //
-// Rows with more than kHubSplit in-edges ("hubs") would both unbalance their partition and serialise the LDS
-// atomics, so each hub's in-edges are dealt out to virtual rows of at most kHubSplit edges, kept in hub
-// partitions of kVrowsPerHubPart virtual rows; a small finishing step adds a hub's virtual rows up.
+// Rows with more than hub_split in-edges ("hubs") would both unbalance their partition and serialise the LDS
+// atomics, so each hub's in-edges are dealt out to virtual rows of at most hub_split edges, and the virtual rows
+// are dealt round-robin over all partitions (each partition has kMaxVrowsPerPart spare accumulator slots behind
+// its own rows); a small finishing step adds a hub's virtual rows up.  hub_split is kHubSplitMin unless the
+// graph has so many hub edges that the spare slots would not hold them, in which case it is doubled until they do.
 #pragma once
 
 #include <cstdint>
@@ -25,21 +27,29 @@
 
 #include "common.h"
 
-constexpr uint32_t kRowsPerPart = 8192;      // destination rows per regular partition (64 KB of u64 in LDS)
-constexpr uint32_t kSrcPerPart = 16384;      // source vertices per scatter partition (64 KB of fp32 in LDS)
-constexpr uint32_t kHubSplit = 2048;         // rows with more in-edges than this are split into virtual rows
-constexpr uint32_t kVrowsPerHubPart = 64;    // virtual rows per hub partition
+#ifndef FR_ROWS_PER_PART
+#define FR_ROWS_PER_PART 8192
+#endif
+#ifndef FR_SRC_PER_PART
+#define FR_SRC_PER_PART 16384
+#endif
+constexpr uint32_t kRowsPerPart = FR_ROWS_PER_PART;   // destination rows per regular partition (8 B each in LDS)
+constexpr uint32_t kSrcPerPart = FR_SRC_PER_PART;     // source vertices per scatter partition (4 B each in LDS)
+constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub_split are split into virtual rows
+constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane)
-constexpr uint32_t kHubsPerTile = 256;       // hubs finished per workgroup
+constexpr uint32_t kHubsPerTile = 16;        // hubs finished per workgroup (16 lanes each)
+static_assert(kRowsPerPart + kMaxVrowsPerPart <= 16384 && kSrcPerPart <= 65536, "id fields");
 constexpr int kKeyLocalBits = 14;            // sort key = partition << 45 | source << 14 | local row
 constexpr int kKeySrcBits = 31;
 
 struct PrLayout {
     int64_t V = 0, E = 0;
     uint64_t M = 0;                  // messages = distinct (destination partition, source) pairs
-    uint32_t q_reg = 0, q_hub = 0;   // regular and hub destination partitions
+    uint32_t Q = 0;                  // destination partitions
     uint32_t P = 0;                  // source partitions
     uint32_t n_hubs = 0, n_vrows = 0;
+    uint32_t hub_split = kHubSplitMin;
     uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
     uint32_t n_hub_tiles = 1;
 
@@ -57,7 +67,8 @@ struct PrLayout {
     std::vector<uint32_t> edges_of_q;    // [Q]
     std::vector<uint64_t> msgs_of_p;     // [P]
 
-    uint32_t Q() const { return q_reg + q_hub; }
+    // virtual rows dealt to partition q: those hv < n_vrows with hv % Q == q; hv sits in slot hv / Q
+    uint32_t vrows_of_q(uint32_t q) const { return n_vrows > q ? (n_vrows - q + Q - 1) / Q : 0; }
 };
 
 // Builds the layout on `stream` from the caller's in-edge CSR (device pointers) and waits for it.

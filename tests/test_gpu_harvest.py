@@ -45,9 +45,8 @@ def _check_cost_rule(task, pe, pm, pv, hub_ns):
     assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX) == [max(1, -(-r * pv // 1000)) for r in rows]
     info = task.fr_pagerank_info()
     edges = task.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
-    grow = rows + [64] * info.hub_partitions
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 1000)) for e, r in zip(edges, grow)]
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN) == [hub_ns] * max(1, -(-info.hubs // 256))
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 1000)) for e, r in zip(edges, rows)]
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN) == [hub_ns] * max(1, -(-info.hubs // 16))
 
 
 def test_config1_harvest_matches_plan_and_oracle_bits():

@@ -126,19 +126,39 @@ def test_layout_facts_match_the_graph():
     t.fr_pagerank_destroy()
     indeg = np.diff(g.row_ptr)
     hub = indeg > 2048
-    assert info.hubs == int(hub.sum())
-    assert info.virtual_rows == int(np.ceil(indeg[hub] / 2048).sum())
-    assert info.regular_partitions == -(-g.n_vertices // 8192) and info.source_partitions == -(-g.n_vertices // 16384)
-    assert info.hub_partitions == -(-info.virtual_rows // 64)
-    assert sum(edges) == g.n_edges and sum(msgs) == info.messages
-    # recount the messages on the host: regular rows by row // 8192, hub rows by their virtual-row partition
+    Q = -(-g.n_vertices // 8192)
+    assert info.hub_split == 2048 and info.hubs == int(hub.sum()) and info.hubs > 0
+    nsplit = np.ceil(indeg[hub] / 2048).astype(np.int64)
+    assert info.virtual_rows == int(nsplit.sum())
+    assert info.partitions == Q and info.source_partitions == -(-g.n_vertices // 16384)
+    assert sum(edges) == g.n_edges and sum(msgs) == info.messages and len(edges) == Q
+    # recount the messages on the host: a regular row lives in partition row // 8192, virtual row hv in hv % Q
     row = np.repeat(np.arange(g.n_vertices), indeg)
     pos = np.arange(g.n_edges) - np.repeat(g.row_ptr[:-1], indeg)
     vbase = np.zeros(g.n_vertices, dtype=np.int64)
-    vbase[hub] = np.cumsum(np.ceil(indeg[hub] / 2048).astype(np.int64)) - np.ceil(indeg[hub] / 2048).astype(np.int64)
-    part = np.where(hub[row], info.regular_partitions + (vbase[row] + pos // 2048) // 64, row // 8192)
+    vbase[hub] = np.cumsum(nsplit) - nsplit
+    part = np.where(hub[row], (vbase[row] + pos // 2048) % Q, row // 8192)
+    assert np.array_equal(np.bincount(part, minlength=Q), np.array(edges))
     want = np.unique(part.astype(np.int64) * g.n_vertices + g.col).size
     assert info.messages == want
+
+
+def test_hub_split_grows_when_spare_slots_would_overflow():
+    # 3 vertices, one row with 1.2 million in-edges (multi-edges): at the default split of 2048 that row alone
+    # would need 586 virtual rows but one partition has only 128 spare slots, so the split doubles to 16384
+    n = 1_200_000
+    src = np.concatenate([np.full(n, 1, np.int32), np.array([0, 2], np.int32)])
+    dst = np.concatenate([np.zeros(n, np.int32), np.array([1, 1], np.int32)])
+    g = graphs.csr_from_edges(3, src, dst)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(3, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(3, g.n_edges, rp, col, od, ranks, iterations=6)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    info = t.fr_pagerank_info()
+    t.fr_pagerank_destroy()
+    assert info.hub_split == 16384 and info.hubs == 1 and info.virtual_rows == -(-n // 16384)
+    want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 6)
+    assert np.abs(ranks.cpu().numpy().astype(np.float64) - want).max() <= TOL
 
 
 def test_malformed_csr_is_refused_before_any_kernel_uses_it():
