@@ -204,25 +204,14 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
 }
 
 // ---- G_k ----
-__device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t x, int lane)
-{
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t y = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += y;
-    }
-    return incl - x;
-}
-
 constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
 
 // One workgroup per destination partition; its accumulators (one u64 per row, plus the spare slots for hubs'
 // virtual rows) sit in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
 // three-stage software pipeline over the wavefront's chunks, so that no step waits on a load it has just issued:
 //   A  ids and message base of chunk i + 2 are requested;
-//   B  chunk i + 1 (ids now here): flags are prefix-summed over the wavefront, which tells every id which
-//      message it belongs to; the messages are requested;
+//   B  chunk i + 1 (ids now here): ballots of the message-start flags tell every id which message it belongs
+//      to; the messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
 //   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
 //      accumulator with an LDS atomic.
 __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
@@ -251,21 +240,23 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t til
 #pragma unroll
         for (int j = 0; j < 8; ++j) valP[j] = 0.0f;
         while (cA <= c1) {
-            // ---- stage B on chunk cA
+            // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a
+            // fixed j the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set
+            // bits below the lane tells every id how many messages have begun up to it.
             const uint32_t w[4] = {rawA.x, rawA.y, rawA.z, rawA.w};
-            uint32_t nf = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) nf += ((w[j] >> 15) & 1u) + (w[j] >> 31);
-            uint32_t ord = mbA + wave_exclusive_scan(nf, (int)lane);      // messages begun before this lane's ids
-            const uint32_t ebase = cA * kIdChunk + lane * 8;
+            const uint32_t ebase = cA * kIdChunk + lane;
+            uint32_t begun = mbA;                                          // messages begun before row j of the chunk
             float valN[8];
             uint32_t okN = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const uint32_t id = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
-                ord += id >> 15;
-                const uint32_t e = ebase + j;
-                const uint32_t mi = ord - 1;                               // this id's message
+                const uint32_t f = id >> 15;
+                const unsigned long long ballot = __ballot(f != 0);
+                const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+                const uint32_t mi = begun + below + f - 1;                 // this id's message
+                begun += (uint32_t)__popcll(ballot);
+                const uint32_t e = ebase + 64 * j;
                 const bool ok = e >= e0 && e < e1 && (id & 0x3fffu) < kAccSlots && mi < A.M;
                 okN |= (ok ? 1u : 0u) << j;
                 valN[j] = A.msg[ok ? mi : 0u];

@@ -122,16 +122,25 @@ __global__ __launch_bounds__(kBlk) void k_flags(int64_t E, const uint64_t* __res
     flag[e] = (e == 0 || (keys[e] >> kKeyLocalBits) != (keys[e - 1] >> kKeyLocalBits)) ? 1u : 0u;
 }
 
+// Id stream and message sources.  Inside every chunk of kIdChunk ids the stream is stored transposed: stream
+// position r = 64 * j + lane of the chunk sits at slot 8 * lane + j, so that one 16-byte load hands a lane the
+// ids 64 apart and, for a fixed j, the 64 lanes of a wavefront hold 64 consecutive ids of the stream.
+__device__ __forceinline__ int64_t id_slot(int64_t e)
+{
+    const int64_t r = e % kIdChunk;
+    return e - r + (r % 64) * (kIdChunk / 64) + r / 64;
+}
+
 __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
                                                const uint32_t* __restrict__ flag, const uint32_t* __restrict__ incl,
                                                uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= padded) return;
-    if (e >= E) { ids16[e] = 0; return; }
+    if (e >= E) { ids16[id_slot(e)] = 0; return; }
     const uint64_t k = keys[e];
     const uint32_t f = flag[e];
-    ids16[e] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) | (f << 15));
+    ids16[id_slot(e)] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) | (f << 15));
     if (f) {
         const uint64_t m = (uint64_t)incl[e] - 1;
         const uint32_t u = (uint32_t)((k >> kKeyLocalBits) & 0x7fffffffu);

@@ -37,7 +37,7 @@ constexpr uint32_t kRowsPerPart = FR_ROWS_PER_PART;   // destination rows per re
 constexpr uint32_t kSrcPerPart = FR_SRC_PER_PART;     // source vertices per scatter partition (4 B each in LDS)
 constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub_split are split into virtual rows
 constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
-constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane)
+constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
 constexpr uint32_t kHubsPerTile = 16;        // hubs finished per workgroup (16 lanes each)
 static_assert(kRowsPerPart + kMaxVrowsPerPart <= 16384 && kSrcPerPart <= 65536, "id fields");
 constexpr int kKeyLocalBits = 14;            // sort key = partition << 45 | source << 14 | local row
@@ -54,7 +54,8 @@ struct PrLayout {
     uint32_t n_hub_tiles = 1;
 
     // device arrays (allocated through the task's accounting allocator)
-    uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id, bit 15 = first edge of a message
+    uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id, bit 15 = first edge of a message;
+                                     // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
     uint16_t* src16 = nullptr;       // [M] source id relative to its source partition
     uint32_t* eoff = nullptr;        // [Q + 1] first edge (in sorted order) of every destination partition
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
