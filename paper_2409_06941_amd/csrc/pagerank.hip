@@ -36,6 +36,10 @@ namespace {
 constexpr int kBlock = 512;                     // threads per workgroup of the first vertex pass
 constexpr int kGatherBlock = FR_GATHER_BLOCK;   // threads per workgroup of the gather sweep
 constexpr int kGatherWaves = kGatherBlock / 64;
+#ifndef FR_GATHER_UNROLL
+#define FR_GATHER_UNROLL 1
+#endif
+constexpr int kGatherUnroll = FR_GATHER_UNROLL;  // chunks per wavefront per pipeline stage
 constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the scatter sweep
 constexpr int kScatterWaves = kScatterBlock / 64;
 constexpr float kFixScale = 4611686018427387904.0f;        // 2^62: contrib sums are <= 1, so they fit u64
@@ -228,64 +232,85 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t til
     const uint32_t e0 = A.eoff[q], e1 = A.eoff[q + 1];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (e1 > e0) {
+        constexpr int U = kGatherUnroll;         // chunks a wavefront has in each pipeline stage
         const uint32_t c0 = e0 / kIdChunk, c1 = (e1 - 1) / kIdChunk;
         const uint4* ids4 = reinterpret_cast<const uint4*>(A.ids16);
-        uint32_t cA = c0 + wave;                 // chunk whose ids are in rawA
-        uint4 rawA = make_uint4(0, 0, 0, 0);
-        uint32_t mbA = 0;
-        if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
-        uint4 rawP = make_uint4(0, 0, 0, 0);     // chunk waiting for stage C
-        float valP[8];
-        uint32_t okP = 0;
+        uint32_t cA[U];                          // chunks whose ids are in rawA
+        uint4 rawA[U];
+        uint32_t mbA[U];
+        uint4 rawP[U];                           // chunks waiting for stage C
+        float valP[U][8];
+        uint32_t okP[U];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) valP[j] = 0.0f;
-        while (cA <= c1) {
-            // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a
+        for (int u = 0; u < U; ++u) {
+            cA[u] = c0 + wave + kGatherWaves * u;
+            rawA[u] = make_uint4(0, 0, 0, 0);
+            mbA[u] = 0;
+            if (cA[u] <= c1) { rawA[u] = ids4[(uint64_t)cA[u] * (kIdChunk / 8) + lane]; mbA[u] = A.mbase[cA[u]]; }
+            rawP[u] = make_uint4(0, 0, 0, 0);
+            okP[u] = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) valP[u][j] = 0.0f;
+        }
+        while (cA[0] <= c1) {
+            // ---- stage B on chunks cA[]: lane l holds the ids at stream positions 64 j + l of a chunk, so for a
             // fixed j the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set
             // bits below the lane tells every id how many messages have begun up to it.
-            const uint32_t w[4] = {rawA.x, rawA.y, rawA.z, rawA.w};
-            const uint32_t ebase = cA * kIdChunk + lane;
-            uint32_t begun = mbA;                                          // messages begun before row j of the chunk
-            float valN[8];
-            uint32_t okN = 0;
+            float valN[U][8];
+            uint32_t okN[U];
+            uint4 rawN[U];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t id = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
-                const uint32_t f = id >> 15;
-                const unsigned long long ballot = __ballot(f != 0);
-                const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
-                const uint32_t mi = begun + below + f - 1;                 // this id's message
-                begun += (uint32_t)__popcll(ballot);
-                const uint32_t e = ebase + 64 * j;
-                const bool ok = e >= e0 && e < e1 && (id & 0x3fffu) < kAccSlots && mi < A.M;
-                okN |= (ok ? 1u : 0u) << j;
-                valN[j] = A.msg[ok ? mi : 0u];
+            for (int u = 0; u < U; ++u) {
+                const uint32_t w[4] = {rawA[u].x, rawA[u].y, rawA[u].z, rawA[u].w};
+                const uint32_t ebase = cA[u] * kIdChunk + lane;
+                const bool live = cA[u] <= c1;
+                uint32_t begun = mbA[u];                                   // messages begun before row j of the chunk
+                okN[u] = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t id = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+                    const uint32_t f = id >> 15;
+                    const unsigned long long ballot = __ballot(f != 0);
+                    const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+                    const uint32_t mi = begun + below + f - 1;             // this id's message
+                    begun += (uint32_t)__popcll(ballot);
+                    const uint32_t e = ebase + 64 * j;
+                    const bool ok = live && e >= e0 && e < e1 && (id & kLocalMask) < kAccSlots && mi < A.M;
+                    okN[u] |= (ok ? 1u : 0u) << j;
+                    valN[u][j] = A.msg[ok ? mi : 0u];
+                }
+                rawN[u] = rawA[u];
             }
-            const uint4 rawN = rawA;
-            // ---- stage A on the next chunk of this wavefront
-            const uint32_t cN = cA + kGatherWaves;
-            if (cN <= c1) { rawA = ids4[(uint64_t)cN * (kIdChunk / 8) + lane]; mbA = A.mbase[cN]; }
-            // ---- stage C on the previous chunk
-            {
-                const uint32_t wp[4] = {rawP.x, rawP.y, rawP.z, rawP.w};
+            // ---- stage A on this wavefront's next chunks
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                cA[u] += kGatherWaves * U;
+                if (cA[u] <= c1) { rawA[u] = ids4[(uint64_t)cA[u] * (kIdChunk / 8) + lane]; mbA[u] = A.mbase[cA[u]]; }
+                else rawA[u] = make_uint4(0, 0, 0, 0);
+            }
+            // ---- stage C on the previous chunks
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t wp[4] = {rawP[u].x, rawP[u].y, rawP[u].z, rawP[u].w};
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
-                    if ((okP >> j) & 1u) atomicAdd(&acc[id & 0x3fffu], (unsigned long long)(valP[j] * kFixScale));
+                    if ((okP[u] >> j) & 1u) atomicAdd(&acc[id & kLocalMask], (unsigned long long)(valP[u][j] * kFixScale));
                 }
-            }
-            rawP = rawN;
-            okP = okN;
+                rawP[u] = rawN[u];
+                okP[u] = okN[u];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) valP[j] = valN[j];
-            cA = cN;
+                for (int j = 0; j < 8; ++j) valP[u][j] = valN[u][j];
+            }
         }
-        {   // drain: stage C on the last chunk
-            const uint32_t wp[4] = {rawP.x, rawP.y, rawP.z, rawP.w};
+        // drain: stage C on the last chunks
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t wp[4] = {rawP[u].x, rawP[u].y, rawP[u].z, rawP[u].w};
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
-                if ((okP >> j) & 1u) atomicAdd(&acc[id & 0x3fffu], (unsigned long long)(valP[j] * kFixScale));
+                if ((okP[u] >> j) & 1u) atomicAdd(&acc[id & kLocalMask], (unsigned long long)(valP[u][j] * kFixScale));
             }
         }
     }

@@ -39,8 +39,9 @@ constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub
 constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
 constexpr uint32_t kHubsPerTile = 16;        // hubs finished per workgroup (16 lanes each)
-static_assert(kRowsPerPart + kMaxVrowsPerPart <= 16384 && kSrcPerPart <= 65536, "id fields");
-constexpr int kKeyLocalBits = 14;            // sort key = partition << 45 | source << 14 | local row
+constexpr int kKeyLocalBits = 15;            // sort key = partition << 46 | source << 15 | local row
+constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
+static_assert(kRowsPerPart + kMaxVrowsPerPart <= (1u << kKeyLocalBits) && kSrcPerPart <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
 
 struct PrLayout {
