@@ -115,12 +115,16 @@ __global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, uint32_t sp
     keys[e] = (q << (kKeyLocalBits + kKeySrcBits)) | ((uint64_t)(uint32_t)col[e] << kKeyLocalBits) | local;
 }
 
-__global__ __launch_bounds__(kBlk) void k_flags(int64_t E, const uint64_t* __restrict__ keys, uint32_t* __restrict__ flag)
+// 1 where edge e (in sorted order) is the first of its (partition, source) group, i.e. starts a message.
+__host__ __device__ __forceinline__ uint32_t flag_of(const uint64_t* __restrict__ keys, int64_t e)
 {
-    const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
-    if (e >= E) return;
-    flag[e] = (e == 0 || (keys[e] >> kKeyLocalBits) != (keys[e - 1] >> kKeyLocalBits)) ? 1u : 0u;
+    return (e == 0 || (keys[e] >> kKeyLocalBits) != (keys[e - 1] >> kKeyLocalBits)) ? 1u : 0u;
 }
+
+struct FlagOf {
+    const uint64_t* keys;
+    __host__ __device__ uint32_t operator()(size_t e) const { return flag_of(keys, (int64_t)e); }
+};
 
 // Id stream and message sources.  Inside every chunk of kIdChunk ids the stream is stored transposed: stream
 // position r = 64 * j + lane of the chunk sits at slot 8 * lane + j, so that one 16-byte load hands a lane the
@@ -132,14 +136,14 @@ __device__ __forceinline__ int64_t id_slot(int64_t e)
 }
 
 __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
-                                               const uint32_t* __restrict__ flag, const uint32_t* __restrict__ incl,
+                                               const uint32_t* __restrict__ incl,
                                                uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= padded) return;
     if (e >= E) { ids16[id_slot(e)] = 0; return; }
     const uint64_t k = keys[e];
-    const uint32_t f = flag[e];
+    const uint32_t f = flag_of(keys, e);
     ids16[id_slot(e)] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) | (f << 15));
     if (f) {
         const uint64_t m = (uint64_t)incl[e] - 1;
@@ -148,13 +152,13 @@ __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64
     }
 }
 
-__global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint32_t* __restrict__ flag,
+__global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint64_t* __restrict__ keys,
                                                 const uint32_t* __restrict__ incl, uint32_t* __restrict__ mbase)
 {
     const uint32_t c = blockIdx.x * kBlk + threadIdx.x;
     if (c > n_chunks) return;
     const int64_t e = (int64_t)c * kIdChunk;
-    mbase[c] = e < E ? incl[e] - flag[e] : M;
+    mbase[c] = e < E ? incl[e] - flag_of(keys, e) : M;
 }
 
 __device__ __forceinline__ int64_t lower_bound_key(const uint64_t* __restrict__ keys, int64_t E, uint64_t target)
@@ -211,6 +215,11 @@ struct Scratch {
         void* p = fr_alloc_device(a, (size_t)(count ? count : 1) * sizeof(T));
         if (p) held.push_back(p);
         return static_cast<T*>(p);
+    }
+    void drop(void* p)
+    {
+        for (size_t i = 0; i < held.size(); ++i)
+            if (held[i] == p) { (void)fr_alloc_free(a, p); held.erase(held.begin() + (long)i); return; }
     }
     ~Scratch()
     {
@@ -294,48 +303,59 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                        L->n_vrows, L->hub_row, L->hub_vbase);
     hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, out_degree, L->inv_tag);
 
-    // ---- persistent arrays whose size does not depend on the message count
-    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->eoff, (uint64_t)Q + 1) ||
-        !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->bins, (uint64_t)L->P * Q))
-        PREP_NEED((void*)nullptr);
+    tmp.drop(packed);
+    tmp.drop(scan_tmp);
 
+    // ---- sort the edges by (partition, source, local row); set-up scratch is returned as soon as it is done with
     uint64_t* keys = nullptr;
-    uint32_t *flag = nullptr, *incl = nullptr;
+    uint32_t* incl = nullptr;
     uint32_t M = 0;
     if (E > 0) {
-        uint64_t* keys_in = tmp.take<uint64_t>((uint64_t)E);
-        keys = tmp.take<uint64_t>((uint64_t)E);
-        PREP_NEED(keys_in); PREP_NEED(keys);
-        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, keys_in);
+        uint64_t* keys_a = tmp.take<uint64_t>((uint64_t)E);
+        uint64_t* keys_b = tmp.take<uint64_t>((uint64_t)E);
+        PREP_NEED(keys_a); PREP_NEED(keys_b);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, keys_a);
         unsigned end_bit = kKeyLocalBits + kKeySrcBits;
         while (end_bit < 63 && (1ull << (end_bit - kKeyLocalBits - kKeySrcBits)) < (uint64_t)Q) ++end_bit;
         {
+            rocprim::double_buffer<uint64_t> db(keys_a, keys_b);
             size_t bytes = 0;
-            PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, keys_in, keys, (size_t)E, 0u, end_bit, stream));
+            PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, db, (size_t)E, 0u, end_bit, stream));
             void* t = tmp.take<uint8_t>(bytes);
             PREP_NEED(t);
-            PREP_HIP(rocprim::radix_sort_keys(t, bytes, keys_in, keys, (size_t)E, 0u, end_bit, stream));
+            PREP_HIP(rocprim::radix_sort_keys(t, bytes, db, (size_t)E, 0u, end_bit, stream));
+            PREP_HIP(hipStreamSynchronize(stream));
+            keys = db.current();
+            tmp.drop(t);
+            tmp.drop(keys == keys_a ? keys_b : keys_a);
         }
-        flag = tmp.take<uint32_t>((uint64_t)E);
+        tmp.drop(scanned);
         incl = tmp.take<uint32_t>((uint64_t)E);
-        PREP_NEED(flag); PREP_NEED(incl);
-        hipLaunchKernelGGL(k_flags, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, E, keys, flag);
+        PREP_NEED(incl);
         {
+            auto flags = rocprim::make_transform_iterator(rocprim::make_counting_iterator<size_t>(0), FlagOf{keys});
             size_t bytes = 0;
-            PREP_HIP(rocprim::inclusive_scan(nullptr, bytes, flag, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
+            PREP_HIP(rocprim::inclusive_scan(nullptr, bytes, flags, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
             void* t = tmp.take<uint8_t>(bytes);
             PREP_NEED(t);
-            PREP_HIP(rocprim::inclusive_scan(t, bytes, flag, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
+            PREP_HIP(rocprim::inclusive_scan(t, bytes, flags, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
         }
         PREP_HIP(hipMemcpyAsync(&M, incl + (E - 1), 4, hipMemcpyDeviceToHost, stream));
         PREP_HIP(hipStreamSynchronize(stream));
+    } else {
+        tmp.drop(scanned);
     }
+
+    // ---- the arrays that stay
+    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->eoff, (uint64_t)Q + 1) ||
+        !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->bins, (uint64_t)L->P * Q))
+        PREP_NEED((void*)nullptr);
     L->M = M;
     if (!keep(a, &L->src16, (uint64_t)M)) PREP_NEED((void*)nullptr);
 
-    hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, flag, incl,
+    hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
                        L->ids16, L->src16);
-    hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, flag, incl, L->mbase);
+    hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, L->eoff);
     hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->P * Q)), dim3(kBlk), 0, stream, L->P, Q, E, M, keys, incl, L->bins);
     uint64_t* mp = tmp.take<uint64_t>(L->P);

@@ -1,0 +1,71 @@
+"""GPU parity at the benchmark's full size (cfg2), in the launch configuration bench.py times: the side task is
+harvested inside the bubbles of the GEMM-loaded stage, then compared with the fp64 oracle element by element and,
+bit for bit, with a standalone run of the same kernels."""
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2409_06941_amd as fr          # noqa: E402
+from oracle.pagerank import pagerank       # noqa: E402
+from workloads import configs              # noqa: E402
+
+
+def test_cfg2_full_size_harvested_run_matches_oracle_and_standalone_bits():
+    cfg = configs.by_name("cfg2")
+    print("building cfg2 graph", flush=True)
+    g = cfg.build_graph()
+    V, E, K = g.n_vertices, g.n_edges, cfg.iterations
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    rp, col, od = dev(g.row_ptr), dev(g.col), dev(g.out_degree)
+    ref = torch.zeros(V, dtype=torch.float32, device="cuda")
+    ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+
+    print("standalone run, 37 tiles per launch", flush=True)
+    t = fr.PageRankTask(V, E, rp, col, od, ref, damping=cfg.damping, iterations=K)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), 37)
+    t.fr_pagerank_destroy()
+
+    print("harvested run beside the GEMM stage load", flush=True)
+    L = cfg.load
+    stream = torch.cuda.Stream()
+    ws = torch.empty(fr.Load.fr_load_workspace_bytes(fr.FR_LOAD_GPT, L.layers, L.hidden, L.ffn, L.tokens), dtype=torch.uint8, device="cuda")
+    load = fr.Load(fr.FR_LOAD_GPT, L.layers, L.hidden, L.ffn, L.tokens, workspace=ws, seed=cfg.seed, stream=stream)
+    ctx = fr.Context(device_id=0, guard_ns=200_000, launch_cost_ns=10_000, time_steps=1, mem_available_bytes=1 << 40)
+    # generous modelled costs (about 2x what the kernels need) so that no step overruns its bubble
+    task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=1, mem_limit_bytes=8 << 30,
+                           ps_per_edge=2, ps_per_message=3, ps_per_vertex=2, hubfin_tile_ns=200)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)
+    t_end = time.time() + 60
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+        time.sleep(0.001)
+    assert ctx.fr_bubble_end() == fr.FR_OK
+    stage = fr.Stage(fr.FR_SCHED_1F1B, cfg.p, cfg.m, cfg.stage, 4_500_000, 9_000_000, load, stream)
+    for ep in range(3):
+        print("epoch", ep, flush=True)
+        stage.fr_stage_run_epoch(ctx)
+        if ctx.fr_query_progress(tid).runs_completed >= 1:
+            break
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    ctx.fr_task_stop(tid)
+    got = ranks.cpu().numpy()
+    ref_bits = ref.cpu().numpy()
+    task.fr_pagerank_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+
+    assert pr.runs_completed == 1 and pr.overruns == 0
+    assert sum(e.work_units for e in log if e.kind == fr.FR_EV_CHUNK) == K * E
+    assert np.array_equal(got.view(np.uint32), ref_bits.view(np.uint32))
+
+    print("oracle", flush=True)
+    want = pagerank(g.row_ptr, g.col, g.out_degree, cfg.damping, K)
+    err = np.abs(got.astype(np.float64) - want)
+    assert err.max() <= 1e-5
+    big = want > 1.0 / V
+    assert (err[big] / want[big]).max() <= 1e-4
+    assert abs(float(got.astype(np.float64).sum()) - 1.0) <= 1e-4
