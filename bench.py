@@ -30,7 +30,9 @@ def main():
     ap.add_argument("--steps", type=int, default=12)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2")
-    ap.add_argument("--derate", type=float, default=1.25, help="modelled cost = measured standalone cost x derate")
+    ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
+    ap.add_argument("--margin", type=float, default=1.05, help="final model = measured in-bubble step cost x margin")
+    ap.add_argument("--guard-ns", type=int, default=100_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -97,10 +99,13 @@ def main():
     side_probe.fr_destroy()
     M = max(1, info.messages)
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3] / cal_iters
-    ps_per_vertex = max(1, int(v_ns * 1000 * args.derate / V))
-    ps_per_message = max(1, int((s_ns * 1000 * args.derate - V * ps_per_vertex) / M))
-    ps_per_edge = max(1, int((g_ns * 1000 * args.derate - V * ps_per_vertex) / max(1, E)))
-    hubfin_tile_ns = max(1, int(h_ns * args.derate / n_hub_tiles))
+    def rates(v_ns, s_ns, g_ns, h_ns, derate):
+        """Picosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
+        pv = max(1, int(v_ns * 1000 * derate / V))
+        pm = max(1, int((s_ns * 1000 * derate - V * pv) / M))
+        pe = max(1, int((g_ns * 1000 * derate - V * pv) / max(1, E)))
+        return dict(ps_per_vertex=pv, ps_per_message=pm, ps_per_edge=pe,
+                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)))
     log("layout: M/E=%.3f, %d destination partitions, %d source partitions, %d hubs in %d virtual rows, init+first run %.2fs" %
         (info.messages / max(1, E), info.partitions, info.source_partitions, info.hubs, info.virtual_rows, t_init))
     log("standalone per iteration: scatter %.1f us, gather %.1f us, hub finish %.1f us (first vertex pass %.1f us)" %
@@ -109,21 +114,39 @@ def main():
 
     # ---- runtime, task, stage
     mem_cap = cfg.mem_cap_bytes if cfg.mem_cap_bytes else (64 << 30)
-    ctx = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0,
-                     mem_available_bytes=mem_cap + 1, guard_ns=100_000, launch_cost_ns=8_000, max_chunk_ns=0,
-                     max_inflight=32, time_steps=1, event_log_capacity=1 << 18)
-    task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
-                           mem_limit_bytes=mem_cap, ps_per_edge=ps_per_edge, ps_per_message=ps_per_message,
-                           ps_per_vertex=ps_per_vertex, hubfin_tile_ns=hubfin_tile_ns)
-    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
-    ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
-    t_end = time.time() + 60
-    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
-        time.sleep(0.001)
-    ctx.fr_bubble_end()
     kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
     stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
+    seg_kind = lambda g: fr.FR_PR_SEG_VERTEX if g == 0 else 1 + (g - 1) % 3
 
+    def start_task(launch_cost_ns, model):
+        ctx = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0,
+                         mem_available_bytes=mem_cap + 1, guard_ns=args.guard_ns, launch_cost_ns=launch_cost_ns,
+                         max_chunk_ns=0, max_inflight=32, time_steps=1, event_log_capacity=1 << 18)
+        task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
+                               mem_limit_bytes=mem_cap, **model)
+        tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+        ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
+        t_end = time.time() + 60
+        while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+            time.sleep(0.001)
+        ctx.fr_bubble_end()
+        return ctx, task, tid
+
+    # Second profiling pass, in place: one epoch with the standalone model (generously derated) shows what a
+    # step costs inside real bubbles, launch gaps included; the final model is that cost plus a small margin.
+    ctx, task, tid = start_task(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate))
+    stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.02)
+    n_tiles = [task.fr_pagerank_tiles(k) for k in range(4)]
+    prof = [[], [], [], []]
+    for e in ctx.fr_event_log(1 << 18):
+        if e.kind == fr.FR_EV_CHUNK and e.measured_ns > 0 and e.tile0 == 0 and e.tile1 == n_tiles[seg_kind(e.segment)]:
+            prof[seg_kind(e.segment)].append(e.measured_ns)
+    ctx.fr_task_stop(tid); task.fr_pagerank_destroy(); ctx.fr_destroy()
+    insitu = [statistics.median(p) if p else x for p, x in zip(prof, (v_ns, s_ns, g_ns, h_ns))]
+    log("in-bubble step times: vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
+        tuple(x / 1e3 for x in insitu))
+    ctx, task, tid = start_task(1_000, rates(*insitu, args.margin))
     def epochs(n, with_task):
         out = []
         for _ in range(n):
@@ -152,7 +175,6 @@ def main():
     bubble_ns = sum(r.bubble_ns for r in with_task)
     chunk_ns = sum(e.measured_ns for e in events if e.kind == fr.FR_EV_CHUNK)
     idle_ns = sum(e.modelled_ns for e in events if e.kind == fr.FR_EV_IDLE)
-    seg_kind = lambda g: fr.FR_PR_SEG_VERTEX if g == 0 else 1 + (g - 1) % 3
     timed = [e for e in events if e.kind == fr.FR_EV_CHUNK and e.measured_ns > 0]
     per_kind_ns = [sum(e.measured_ns for e in timed if seg_kind(e.segment) == k) for k in range(4)]
     per_kind_n = [sum(1 for e in timed if seg_kind(e.segment) == k) for k in range(4)]
