@@ -212,14 +212,15 @@ int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint6
  * Jacobi iterations (the paper's graph-analytics side task, Section 6.1.4; one iteration = one pass over the
  * graph, Section 6.2).  InitSideTask rebuilds the CSR into a partition-centric layout on the GPU; work is cut
  * into tiles fixed at that point and results do not depend on how tiles are grouped into launches.
- * A run is the segment sequence  V0, S_0, G_0, H_0, S_1, G_1, H_1, ..., S_{K-1}, G_{K-1}, H_{K-1}  where
+ * A run is the segment sequence  V0, S_0, G_0, S_1, G_1, ..., S_{K-1}, G_{K-1}, H  where
  *   V0  (vertex pass)  r_0 = 1/V, contrib_0 = r_0 / outdeg, per-tile partial sums of dangling r_0;
- *   S_k (scatter)      one message contrib_k[u] per (destination partition, source u) pair;
+ *   S_k (scatter)      one message contrib_k[u] per (destination partition, source u) pair; for k > 0 it first
+ *                      finishes the rows whose in-edges were dealt out to virtual rows (hubs);
  *   G_k (gather)       acc_k[v] = sum over v's in-edges of the source's message, then for the partition's rows
  *                      r_{k+1} = base_k + d * acc_k, contrib_{k+1}, dangling partials;
  *                      base_k = (1 - d)/V + d * D_k / V, D_k = sum of the dangling partials of r_k;
- *   H_k (hub finish)   the same for rows whose in-edges were dealt out to virtual rows.
- * The last iteration writes r_K to ranks_out.  With K = 0, V0 writes r_0 there.
+ *   H   (hub finish)   r_K of the hubs, once, after the last iteration.
+ * The last iteration writes r_K to ranks_out.  With K = 0 the run is V0 alone, which writes r_0 there.
  */
 #define FR_PR_SEG_VERTEX  0
 #define FR_PR_SEG_SCATTER 1

@@ -6,16 +6,18 @@
 // bits whichever launch carries it, so pausing and resuming at any tile boundary cannot change the result.
 //
 // The pull pass runs on the partition-centric layout of pr_layout.h.  One run = segments
-//     V0, S_0 G_0 H_0, S_1 G_1 H_1, ..., S_{K-1} G_{K-1} H_{K-1}
+//     V0, S_0 G_0, S_1 G_1, ..., S_{K-1} G_{K-1}, H
 //   V0   vertex pass (tile = destination partition): r_0 = 1/V, contrib_0 = r_0 / outdeg, dangling partials
-//   S_k  scatter     (tile = source partition): contrib_k slice in LDS -> one message per (partition, source)
+//   S_k  scatter     (tile = source partition): contrib_k slice in LDS -> one message per (partition, source);
+//                    for k > 0 the hubs that live in the slice are finished first (their virtual rows, summed by
+//                    G_{k-1}, are added up and run through the vertex-pass arithmetic)
 //   G_k  gather      (tile = destination partition): id stream + messages -> 64-bit fixed-point sums in LDS;
 //                    then, fused, the next vertex pass for the partition's rows:
 //                    r_{k+1} = base_k + d * sum, contrib_{k+1} = r_{k+1} / outdeg, dangling partials
 //                    (sums of hubs' virtual rows are only stored)
-//   H_k  hub finish  (tile = 16 hubs): add a hub's virtual rows, same vertex-pass arithmetic
+//   H    hub finish  (tile = 16 hubs): after the last iteration, the hubs' r_K
 // base_k = (1 - d)/V + d * D_k / V, D_k = fixed-order sum of the dangling partials of r_k.
-// In the last iteration G and H write r_K to ranks_out instead of contrib.
+// In the last iteration G writes r_K to ranks_out instead of contrib; H does the same for the hubs.
 // No floating-point atomics anywhere: float sums have a fixed order, the LDS atomics add integers.
 
 #include <algorithm>
@@ -109,6 +111,7 @@ struct DevArgs {
     const uint2* bins;
     const int32_t* hub_row;
     const uint32_t* hub_vbase;
+    const uint32_t* hub_of_p;
     const float* inv_tag;
     float* msg;
     float* contrib;
@@ -150,17 +153,48 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
 // in flight before the first one is needed.
 constexpr uint32_t kDescBatch = 1024;
 
-__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0)
+// `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
+__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
     __shared__ uint2 desc[kDescBatch];
+    __shared__ float red[32];
     const uint32_t p = tile0 + blockIdx.x;
     const int64_t v0 = (int64_t)p * kSrcPerPart;
     const uint32_t n = (uint32_t)((A.V - v0) < (int64_t)kSrcPerPart ? (A.V - v0) : (int64_t)kSrcPerPart);
+    const float d_part = first ? 0.0f : dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     for (uint32_t i = threadIdx.x * 4; i < n; i += kScatterBlock * 4) {
         if (i + 3 < n) *reinterpret_cast<float4*>(&slice[i]) = *reinterpret_cast<const float4*>(A.contrib + v0 + i);
         else
             for (uint32_t c = i; c < n; ++c) slice[c] = A.contrib[v0 + c];
+    }
+    if (!first) {
+        // finish the hubs of this slice: 16 lanes add up a hub's virtual rows, the first of them applies
+        // r = base + d * sum and puts contrib = r / outdeg into the slice
+        const float D = dangling_finish(d_part, red);              // (its barriers also order the slice loads)
+        const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
+        const uint32_t h0 = A.hub_of_p[p], h1 = A.hub_of_p[p + 1];
+        const uint32_t sub = threadIdx.x & 15;
+        float dangling = 0.0f;
+        for (uint32_t hb = h0; hb < h1; hb += kScatterBlock / 16) {      // uniform trip count for the whole workgroup
+            const uint32_t h = hb + (threadIdx.x >> 4);
+            unsigned long long s = 0ull;
+            if (h < h1 && h < A.n_hubs) {
+                const uint32_t a = A.hub_vbase[h], b = A.hub_vbase[h + 1];
+                for (uint32_t i = a + sub; i < b && i < A.n_vrows; i += 16) s += A.vacc[i];
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) s += (unsigned long long)__shfl_xor((long long)s, off, 64);
+            if (h < h1 && h < A.n_hubs && sub == 0) {
+                const int64_t v = A.hub_row[h];
+                const float inv = inv_of_tag(A.inv_tag[v]);
+                const float r = fmaf(A.damping, (float)s * kFixInv, base);
+                if (v >= v0 && v < v0 + (int64_t)n) slice[v - v0] = r * inv;
+                dangling += (inv == 0.0f ? r : 0.0f);
+            }
+        }
+        const float total = block_sum(dangling, red + 8);
+        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.Q + p] = total;
     }
     const uint32_t Q = A.Q;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -380,10 +414,7 @@ __global__ __launch_bounds__(256) void k_hubfin(DevArgs A, uint32_t tile0, int p
             dangling = (inv == 0.0f ? r : 0.0f);
         }
     }
-    if (!final_pass) {
-        const float total = block_sum(dangling, red + 8);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.Q + t] = total;
-    }
+    (void)dangling;          // H only runs after the last iteration: nothing reads its dangling sum
 }
 
 uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
@@ -409,8 +440,14 @@ struct PrTask {
     int hip_error = 0;
     uint32_t run = 0, seg = 0, tile = 0;  // cursor
 
-    uint32_t n_segments() const { return 1u + 3u * (uint32_t)d.iterations; }
-    int kind_of(uint32_t g) const { return g == 0 ? FR_PR_SEG_VERTEX : 1 + (int)((g - 1) % 3u); }
+    // V0, then S_k G_k for k < K, then H (no S, G, H at all when K = 0)
+    uint32_t n_segments() const { return d.iterations == 0 ? 1u : 2u + 2u * (uint32_t)d.iterations; }
+    int kind_of(uint32_t g) const
+    {
+        if (g == 0) return FR_PR_SEG_VERTEX;
+        if (g + 1 == n_segments()) return FR_PR_SEG_HUBFIN;
+        return ((g - 1) & 1u) ? FR_PR_SEG_GATHER : FR_PR_SEG_SCATTER;
+    }
     uint32_t tiles_of(int kind) const
     {
         switch (kind) {
@@ -456,12 +493,15 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
     const uint32_t K = (uint32_t)p->d.iterations;
     if (kind == FR_PR_SEG_VERTEX) {
         hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, p->args, tile0, K == 0 ? 1 : 0);
+    } else if (kind == FR_PR_SEG_HUBFIN) {
+        // after G_{K-1}: the dangling partials of r_{K-1} sit in set (K-1) & 1
+        hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, tile0, (int)((K - 1) & 1u), 1);
     } else {
-        const uint32_t k = (g - 1) / 3;
-        const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
-        if (kind == FR_PR_SEG_SCATTER) hipLaunchKernelGGL(k_scatter, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0);
-        else if (kind == FR_PR_SEG_GATHER) hipLaunchKernelGGL(k_gather, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
-        else hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, tile0, parity, final_pass);
+        const uint32_t k = (g - 1) / 2;
+        if (kind == FR_PR_SEG_SCATTER)      // S_k finishes the hubs of r_k with D_{k-1}: set (k-1) & 1
+            hipLaunchKernelGGL(k_scatter, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, (int)((k + 1) & 1u), k == 0 ? 1 : 0);
+        else
+            hipLaunchKernelGGL(k_gather, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, (int)(k & 1u), (k + 1 == K) ? 1 : 0);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
@@ -487,7 +527,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     int rc = pr_build_layout(&p->L, V, E, p->d.row_ptr, p->d.col, p->d.out_degree, a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
-    p->n_dpart = L.Q + L.n_hub_tiles;
+    p->n_dpart = L.Q + L.P;                  // one slot per gather tile, one per scatter tile (its hubs)
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
         !take(a, &p->vacc, (uint64_t)L.n_vrows))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
@@ -495,7 +535,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.P = L.P; A.n_hubs = L.n_hubs; A.n_vrows = L.n_vrows;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.ids16 = L.ids16; A.src16 = L.src16; A.eoff = L.eoff; A.mbase = L.mbase; A.bins = L.bins;
-    A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.inv_tag = L.inv_tag;
+    A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.hub_of_p = L.hub_of_p; A.inv_tag = L.inv_tag;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.vacc = p->vacc; A.ranks_out = p->d.ranks_out;
     build_cost_tables(p);
     p->footprint_after = fr_alloc_used(a);

@@ -197,6 +197,21 @@ __global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E
     bins[idx] = r;
 }
 
+// hub_of_p[p] = first hub whose row id is >= p * kSrcPerPart (hub_row is ascending).
+__global__ __launch_bounds__(kBlk) void k_hub_of_p(uint32_t P, uint32_t n_hubs, const int32_t* __restrict__ hub_row, uint32_t* __restrict__ hub_of_p)
+{
+    const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
+    if (p > P) return;
+    const int64_t target = (int64_t)p * kSrcPerPart;
+    uint32_t lo = 0, hi = n_hubs;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if ((int64_t)hub_row[mid] < target) lo = mid + 1;
+        else hi = mid;
+    }
+    hub_of_p[p] = lo;
+}
+
 __global__ __launch_bounds__(kBlk) void k_msgs_of_p(uint32_t P, uint32_t Q, const uint2* __restrict__ bins, uint64_t* __restrict__ out)
 {
     const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
@@ -302,6 +317,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     hipLaunchKernelGGL(k_hub_tables, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, scanned, L->n_hubs,
                        L->n_vrows, L->hub_row, L->hub_vbase);
     hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, out_degree, L->inv_tag);
+    if (!keep(a, &L->hub_of_p, (uint64_t)L->P + 1)) PREP_NEED((void*)nullptr);
+    hipLaunchKernelGGL(k_hub_of_p, dim3(blocks_for((uint64_t)L->P + 1)), dim3(kBlk), 0, stream, L->P, L->n_hubs, L->hub_row, L->hub_of_p);
 
     tmp.drop(packed);
     tmp.drop(scan_tmp);

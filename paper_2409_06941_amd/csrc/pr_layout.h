@@ -63,6 +63,7 @@ struct PrLayout {
     uint2* bins = nullptr;           // [P * Q] message range [x, y) of bin (p, q), p-major
     int32_t* hub_row = nullptr;      // [n_hubs] row id of hub h
     uint32_t* hub_vbase = nullptr;   // [n_hubs + 1] first virtual row of hub h
+    uint32_t* hub_of_p = nullptr;    // [P + 1] first hub (hubs are numbered in row order) of every source partition
     float* inv_tag = nullptr;        // [V] 1/outdeg (0 if dangling), sign bit set for hub rows
 
     // host copies used by the cost model

@@ -35,8 +35,8 @@ def _segments(task, iterations):
     h = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN)
     segs = [v]
     for _ in range(iterations):
-        segs += [s, g, h]
-    return segs
+        segs += [s, g]
+    return segs + [h]
 
 
 def _check_cost_rule(task, pe, pm, pv, hub_ns):
