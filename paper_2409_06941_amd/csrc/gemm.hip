@@ -16,9 +16,11 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BM = 128, BN = 128, BK = 32;     // workgroup tile
-constexpr int kThreads = 256;                  // 4 wavefronts as 2 x 2, each 64 x 64 of C
-constexpr int kLdsRow = BK + 8;                // bf16 elements per LDS row: 64 B of data + 16 B pad
+constexpr int BM = 256, BN = 128, BK = 64;     // workgroup tile
+constexpr int kThreads = 512;                  // 8 wavefronts as 4 x 2, each 64 x 64 of C
+constexpr int kLdsRow = BK + 8;                // bf16 elements per LDS row: 128 B of data + 16 B pad, which spreads
+                                               // the rows one 16-byte-per-lane LDS access touches over the banks
+constexpr int kXcds = 8;
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
 {
@@ -27,78 +29,89 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
     return (uint16_t)(u >> 16);
 }
 
-// C[M, N] = A[M, K] * B[N, K]^T, bf16 in / bf16 out, fp32 accumulate.  M, N multiples of 128, K of 32.
-__global__ __launch_bounds__(kThreads) void k_gemm_bf16_nt(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
-                                                           uint16_t* __restrict__ C, int M, int N, int K)
+// C[M, N] = A[M, K] * B[N, K]^T, bf16 in / bf16 out, fp32 accumulate.  M multiple of 256, N of 128, K of 64.
+// Per k-tile: the registers holding the tile go to LDS, the next tile's global loads are issued into the same
+// registers, and the tile is multiplied out of LDS (4 k-steps of v_mfma_f32_32x32x16_bf16, 2 x 2 MFMA tiles per
+// wavefront).  Two workgroups share a CU (54 KB of LDS and 128 registers per lane each), so one multiplies while
+// the other sits at its barrier.  The staging registers are named scalars on purpose: as small private arrays
+// they are moved to LDS or scratch by the compiler and the kernel runs three times slower.
+// Workgroups are dealt round-robin over the 8 XCDs by the hardware; the tile map undoes that so that each XCD
+// walks a contiguous run of tiles (same A rows, consecutive B columns) and reuses its own L2.
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void k_gemm_bf16_nt(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C, int M, int N, int K)
 {
+    constexpr int kPiecesPerRow = BK / 8, kRowsPerPass = kThreads / kPiecesPerRow;     // 8 pieces of 16 B, 64 rows
     __shared__ __align__(16) uint16_t sA[BM * kLdsRow];
     __shared__ __align__(16) uint16_t sB[BN * kLdsRow];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int tiles_n = N / BN;
-    const int bm = (blockIdx.x / tiles_n) * BM, bn = (blockIdx.x % tiles_n) * BN;
+    const int tiles_n = N / BN, n_tiles = (int)gridDim.x;
+    int tile = (int)blockIdx.x;
+    if (n_tiles % kXcds == 0) tile = (tile % kXcds) * (n_tiles / kXcds) + tile / kXcds;
+    const int bm = (tile / tiles_n) * BM, bn = (tile % tiles_n) * BN;
 
-    // global -> register staging: the tile is 128 rows x 64 B; thread t moves 16 B pieces t and t + 256
-    const int ld_row0 = tid >> 2, ld_k = (tid & 3) * 8;
-    const uint16_t* gA = A + (size_t)(bm + ld_row0) * K + ld_k;
-    const uint16_t* gB = B + (size_t)(bn + ld_row0) * K + ld_k;
-    const size_t half = (size_t)64 * K;
+    const int ld_row = tid / kPiecesPerRow, ld_k = (tid % kPiecesPerRow) * 8;
+    const uint16_t* gA = A + (size_t)(bm + ld_row) * K + ld_k;
+    const uint16_t* gB = B + (size_t)(bn + ld_row) * K + ld_k;
+    const size_t step = (size_t)kRowsPerPass * K;
 
-    f32x16 acc[2][2];
+    f32x16 acc00, acc01, acc10, acc11;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    for (int r = 0; r < 16; ++r) { acc00[r] = 0.0f; acc01[r] = 0.0f; acc10[r] = 0.0f; acc11[r] = 0.0f; }
 
-    uint4 ra0 = *reinterpret_cast<const uint4*>(gA), ra1 = *reinterpret_cast<const uint4*>(gA + half);
-    uint4 rb0 = *reinterpret_cast<const uint4*>(gB), rb1 = *reinterpret_cast<const uint4*>(gB + half);
+    uint4 a0 = *reinterpret_cast<const uint4*>(gA), a1 = *reinterpret_cast<const uint4*>(gA + step);
+    uint4 a2 = *reinterpret_cast<const uint4*>(gA + 2 * step), a3 = *reinterpret_cast<const uint4*>(gA + 3 * step);
+    uint4 b0 = *reinterpret_cast<const uint4*>(gB), b1 = *reinterpret_cast<const uint4*>(gB + step);
 
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    uint16_t* wA = &sA[ld_row * kLdsRow + ld_k];
+    uint16_t* wB = &sB[ld_row * kLdsRow + ld_k];
+    const uint16_t* rA = &sA[(wm * 64 + frag_row) * kLdsRow + frag_k];
+    const uint16_t* rB = &sB[(wn * 64 + frag_row) * kLdsRow + frag_k];
+    constexpr int kPass = kRowsPerPass * kLdsRow;
     for (int k0 = 0; k0 < K; k0 += BK) {
         __syncthreads();                       // previous tile fully consumed
-        *reinterpret_cast<uint4*>(&sA[ld_row0 * kLdsRow + ld_k]) = ra0;
-        *reinterpret_cast<uint4*>(&sA[(ld_row0 + 64) * kLdsRow + ld_k]) = ra1;
-        *reinterpret_cast<uint4*>(&sB[ld_row0 * kLdsRow + ld_k]) = rb0;
-        *reinterpret_cast<uint4*>(&sB[(ld_row0 + 64) * kLdsRow + ld_k]) = rb1;
+        *reinterpret_cast<uint4*>(wA) = a0;
+        *reinterpret_cast<uint4*>(wA + kPass) = a1;
+        *reinterpret_cast<uint4*>(wA + 2 * kPass) = a2;
+        *reinterpret_cast<uint4*>(wA + 3 * kPass) = a3;
+        *reinterpret_cast<uint4*>(wB) = b0;
+        *reinterpret_cast<uint4*>(wB + kPass) = b1;
         __syncthreads();
         if (k0 + BK < K) {                     // fetch the next tile while this one is multiplied
-            ra0 = *reinterpret_cast<const uint4*>(gA + k0 + BK);
-            ra1 = *reinterpret_cast<const uint4*>(gA + half + k0 + BK);
-            rb0 = *reinterpret_cast<const uint4*>(gB + k0 + BK);
-            rb1 = *reinterpret_cast<const uint4*>(gB + half + k0 + BK);
+            const uint16_t* pA = gA + k0 + BK;
+            const uint16_t* pB = gB + k0 + BK;
+            a0 = *reinterpret_cast<const uint4*>(pA);
+            a1 = *reinterpret_cast<const uint4*>(pA + step);
+            a2 = *reinterpret_cast<const uint4*>(pA + 2 * step);
+            a3 = *reinterpret_cast<const uint4*>(pA + 3 * step);
+            b0 = *reinterpret_cast<const uint4*>(pB);
+            b1 = *reinterpret_cast<const uint4*>(pB + step);
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(&sA[(wm * 64 + i * 32 + frag_row) * kLdsRow + kk + frag_k]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(&sB[(wn * 64 + j * 32 + frag_row) * kLdsRow + kk + frag_k]);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            const bf16x8 fa0 = *reinterpret_cast<const bf16x8*>(rA + kk);
+            const bf16x8 fa1 = *reinterpret_cast<const bf16x8*>(rA + 32 * kLdsRow + kk);
+            const bf16x8 fb0 = *reinterpret_cast<const bf16x8*>(rB + kk);
+            const bf16x8 fb1 = *reinterpret_cast<const bf16x8*>(rB + 32 * kLdsRow + kk);
+            acc00 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0, acc00, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb1, acc01, 0, 0, 0);
+            acc10 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb0, acc10, 0, 0, 0);
+            acc11 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1, acc11, 0, 0, 0);
         }
     }
 
     // accumulator layout of the 32 x 32 MFMA: lane l holds column l % 32, rows 8 * (r / 4) + 4 * (l / 32) + r % 4
-    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    const int col = bn + wn * 64 + (lane & 31), row_in = (lane >> 5) * 4;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = bm + wm * 64 + i * 32 + 8 * (r >> 2) + row_in + (r & 3);
-                const int col = bn + wn * 64 + j * 32 + col_in;
-                C[(size_t)row * N + col] = f32_to_bf16_rne(acc[i][j][r]);
-            }
+    for (int r = 0; r < 16; ++r) {
+        const int row = bm + wm * 64 + 8 * (r >> 2) + row_in + (r & 3);
+        C[(size_t)row * N + col] = f32_to_bf16_rne(acc00[r]);
+        C[(size_t)row * N + col + 32] = f32_to_bf16_rne(acc01[r]);
+        C[(size_t)(row + 32) * N + col] = f32_to_bf16_rne(acc10[r]);
+        C[(size_t)(row + 32) * N + col + 32] = f32_to_bf16_rne(acc11[r]);
+    }
 }
 
 // Seeded fill: bf16 values uniform in [-1/8, 1/8) from a counter-based 64-bit mixer.
