@@ -18,6 +18,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+# HBM-side bytes one PageRank iteration (k_scatter + k_gather) moves on cfg2, from the FETCH_SIZE / WRITE_SIZE
+# counter runs summarised under profiles/ (FETCH_SIZE scaled by 1.985, the factor a plain streaming kernel of known
+# size shows).  Only valid for the kernels those counters were taken on: set to None when the kernels change.
+CFG2_TRAFFIC_BYTES = 608.3e6
 
 
 def log(*a):
@@ -224,7 +228,7 @@ def main():
         "stage_tflops": ((fp_flops + bp_flops) * cfg.m / (busy_with / 1e9) / 1e12) if fp_flops else None,
         "roofline": {"kernel": "k_scatter + k_gather (one PageRank iteration)", "bound": "hbm",
                      "achieved": pull_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pull_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "iterations": iters_done,
+                     "traffic": CFG2_TRAFFIC_BYTES if cfg.name == "cfg2" else None, "iterations": iters_done,
                      "avg_iteration_us": (pull_ns / iters_done / 1e3) if iters_done else None,
                      "avg_launch_us": {"k_scatter": per_kind_ns[1] / max(1, per_kind_n[1]) / 1e3,
                                        "k_gather": per_kind_ns[2] / max(1, per_kind_n[2]) / 1e3,
