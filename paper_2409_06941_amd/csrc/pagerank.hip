@@ -100,9 +100,12 @@ __device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 flo
 __device__ __forceinline__ bool is_hub_tag(float tag) { return (__float_as_uint(tag) >> 31) != 0; }
 __device__ __forceinline__ float inv_of_tag(float tag) { return __uint_as_float(__float_as_uint(tag) & 0x7fffffffu); }
 
+enum : uint32_t { kShape_64x8 = 0, kShape_64x4, kShape_32x4, kShape_32x2 };
+
 struct DevArgs {
     int64_t V, E;
     uint32_t M, Q, P, n_hubs, n_vrows, n_dpart;
+    uint32_t scatter_shape;       // lanes per bin x messages per lane in the scatter sweep (kShape_*)
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
@@ -146,6 +149,17 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
     }
 }
 
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), and every XCD has an L2 of its
+// own.  This map gives XCD x the x-th contiguous eighth of a launch's n tiles, in order, so that tiles which touch
+// neighbouring memory at about the same time do so through the same L2.  It is a bijection on [0, n) for any n.
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t n)
+{
+    constexpr uint32_t kXcds = 8;
+    const uint32_t x = b % kXcds, i = b / kXcds;
+    const uint32_t rem = n % kXcds;
+    return x * (n / kXcds) + (x < rem ? x : rem) + i;
+}
+
 // ---- S_k ----
 // One workgroup per source partition: its slice of contrib sits in LDS, and for every destination partition q
 // the messages of bin (p, q) are written in order.  Bin descriptors are staged in LDS a batch at a time; each
@@ -153,13 +167,64 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
 // in flight before the first one is needed.
 constexpr uint32_t kDescBatch = 1024;
 
+// The messages of `nb` bins (ranges [x, y) of message numbers, staged in LDS) are produced from the slice.
+// L lanes share a bin and move up to T messages each per step, for 16 / T bins at a time: a wavefront keeps
+// sixteen loads per lane in flight over (16 / T) * (64 / L) bins.  Short bins (large graphs) want small L * T,
+// so that lanes and issue slots are not spent on messages that are not there; long bins want L = 64, T = 8.
+// The values written do not depend on L and T.
+template <uint32_t L, uint32_t T>
+__device__ __forceinline__ void scatter_bins(const uint16_t* __restrict__ src16, float* __restrict__ msg, const uint2* desc,
+                                             uint32_t nb, const float* slice, uint32_t n)
+{
+    constexpr uint32_t H = 16 / T, kGroups = 64 / L;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t grp = lane / L, sub = lane % L;
+    for (uint32_t i = H * kGroups * wave; i < nb; i += H * kGroups * kScatterWaves) {
+        uint32_t pos[H], end[H];
+        bool more = false;
+#pragma unroll
+        for (uint32_t h = 0; h < H; ++h) {
+            const uint32_t b = i + h * kGroups + grp;
+            pos[h] = 0; end[h] = 0;
+            if (b < nb) { pos[h] = desc[b].x; end[h] = desc[b].y; }
+            more = more || pos[h] < end[h];
+        }
+        while (more) {
+            uint32_t src[H][T];
+#pragma unroll
+            for (uint32_t h = 0; h < H; ++h)
+#pragma unroll
+                for (uint32_t t = 0; t < T; ++t) {
+                    const uint32_t m = pos[h] + sub + L * t;
+                    src[h][t] = m < end[h] ? src16[m] : 0u;
+                }
+            float val[H][T];
+#pragma unroll
+            for (uint32_t h = 0; h < H; ++h)
+#pragma unroll
+                for (uint32_t t = 0; t < T; ++t) val[h][t] = src[h][t] < n ? slice[src[h][t]] : 0.0f;
+            more = false;
+#pragma unroll
+            for (uint32_t h = 0; h < H; ++h) {
+#pragma unroll
+                for (uint32_t t = 0; t < T; ++t) {
+                    const uint32_t m = pos[h] + sub + L * t;
+                    if (m < end[h]) msg[m] = val[h][t];
+                }
+                pos[h] = pos[h] + T * L < end[h] ? pos[h] + T * L : end[h];
+                more = more || pos[h] < end[h];
+            }
+        }
+    }
+}
+
 // `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
 __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
     __shared__ uint2 desc[kDescBatch];
     __shared__ float red[32];
-    const uint32_t p = tile0 + blockIdx.x;
+    const uint32_t p = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
     const int64_t v0 = (int64_t)p * kSrcPerPart;
     const uint32_t n = (uint32_t)((A.V - v0) < (int64_t)kSrcPerPart ? (A.V - v0) : (int64_t)kSrcPerPart);
     const float d_part = first ? 0.0f : dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
@@ -197,7 +262,6 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
         if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.Q + p] = total;
     }
     const uint32_t Q = A.Q;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (uint32_t qb = 0; qb < Q; qb += kDescBatch) {
         const uint32_t nb = Q - qb < kDescBatch ? Q - qb : kDescBatch;
         __syncthreads();                                   // slice loaded / previous batch consumed
@@ -208,35 +272,11 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
             desc[i] = b;
         }
         __syncthreads();
-        for (uint32_t i = 2 * wave; i < nb; i += 2 * kScatterWaves) {
-            uint32_t pos[2], end[2];
-            pos[0] = desc[i].x; end[0] = desc[i].y;
-            if (i + 1 < nb) { pos[1] = desc[i + 1].x; end[1] = desc[i + 1].y; }
-            else { pos[1] = 0; end[1] = 0; }
-            while (pos[0] < end[0] || pos[1] < end[1]) {
-                uint32_t src[2][8];
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const uint32_t m = pos[h] + lane + 64 * t;
-                        src[h][t] = m < end[h] ? A.src16[m] : 0u;
-                    }
-                float val[2][8];
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) val[h][t] = src[h][t] < n ? slice[src[h][t]] : 0.0f;
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const uint32_t m = pos[h] + lane + 64 * t;
-                        if (m < end[h]) A.msg[m] = val[h][t];
-                    }
-                pos[0] = pos[0] + 512 < end[0] ? pos[0] + 512 : end[0];
-                pos[1] = pos[1] + 512 < end[1] ? pos[1] + 512 : end[1];
-            }
+        switch (A.scatter_shape) {
+        case kShape_64x4: scatter_bins<64, 4>(A.src16, A.msg, desc, nb, slice, n); break;
+        case kShape_32x4: scatter_bins<32, 4>(A.src16, A.msg, desc, nb, slice, n); break;
+        case kShape_32x2: scatter_bins<32, 2>(A.src16, A.msg, desc, nb, slice, n); break;
+        default: scatter_bins<64, 8>(A.src16, A.msg, desc, nb, slice, n); break;
         }
     }
 }
@@ -508,6 +548,18 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
     return FR_OK;
 }
 
+// Shape of the scatter sweep's inner loop (lanes per bin x messages per lane): the smallest step, L * T
+// messages, that covers an average bin with a third to spare (measured: 27-message bins run fastest as 32 x 2,
+// 94-message bins as 32 x 4, 305-message bins as 64 x 8).
+uint32_t scatter_shape_for(uint64_t messages, uint64_t bins)
+{
+    const uint64_t want = bins ? 4 * (messages / bins) / 3 : 0;
+    if (want <= 64) return kShape_32x2;
+    if (want <= 128) return kShape_32x4;
+    if (want <= 256) return kShape_64x4;
+    return kShape_64x8;
+}
+
 template <typename T>
 bool take(fr_alloc* a, T** out, uint64_t count)
 {
@@ -534,6 +586,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     DevArgs& A = p->args;
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.P = L.P; A.n_hubs = L.n_hubs; A.n_vrows = L.n_vrows;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
+    A.scatter_shape = scatter_shape_for(L.M, (uint64_t)L.P * L.Q);
     A.ids16 = L.ids16; A.src16 = L.src16; A.eoff = L.eoff; A.mbase = L.mbase; A.bins = L.bins;
     A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.hub_of_p = L.hub_of_p; A.inv_tag = L.inv_tag;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.vacc = p->vacc; A.ranks_out = p->d.ranks_out;

@@ -53,6 +53,23 @@ def test_ragged_sizes_span_tiles_and_tails(scale, edges, seed):
     _check(graphs.rmat_csr(scale, edges, seed=seed), iterations=12)
 
 
+@pytest.mark.parametrize("edges,lo,hi", [(1200, 1, 48), (2400, 49, 96), (5000, 97, 192), (40_000, 193, 1 << 20)])
+def test_every_scatter_shape(edges, lo, hi):
+    # the scatter sweep picks its inner-loop shape from the average bin length (messages per source partition x
+    # destination partition): one case per shape, on 2^16 vertices = 4 x 8 bins
+    src, dst = graphs.rmat_edges(16, edges, seed=12)
+    g = graphs.csr_from_edges(1 << 16, src, dst)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=1)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    info = t.fr_pagerank_info()
+    t.fr_pagerank_destroy()
+    avg = info.messages // (info.partitions * info.source_partitions)
+    assert lo <= avg <= hi, avg
+    _check(g, iterations=7)
+
+
 def test_non_power_of_two_vertices_fixed_outdeg():
     _check(graphs.fixed_outdeg_csr(10_007, 32, seed=3), iterations=20)
 
