@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--margin", type=float, default=1.05, help="final model = measured in-bubble step cost x margin")
     ap.add_argument("--guard-ns", type=int, default=100_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it.", file=sys.stderr)
@@ -100,20 +101,29 @@ def main():
     info = cal.fr_pagerank_info()
     n_hub_tiles = cal.fr_pagerank_tiles(fr.FR_PR_SEG_HUBFIN)
     cal.fr_pagerank_destroy()
+    # shortest steps: one iteration launched one tile at a time; a launch of a few tiles takes about as long as
+    # one tile alone, which the additive tile costs cannot express (min_step_ns of the task's cost model)
+    one = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=1)
+    ph1 = one.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 1, want_phase_ns=True)
+    n_tiles_kind = [one.fr_pagerank_tiles(k) for k in range(4)]
+    one.fr_pagerank_destroy()
+    floors = [int(args.derate * ph1[k] / max(1, n_tiles_kind[k])) for k in range(4)]
     side_probe.fr_destroy()
     M = max(1, info.messages)
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3]      # V0 and H run once per run
     def rates(v_ns, s_ns, g_ns, h_ns, derate):
-        """Picosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
-        pv = max(1, int(v_ns * 1000 * derate / V))
-        pm = max(1, int((s_ns * 1000 * derate - V * pv) / M))
-        pe = max(1, int((g_ns * 1000 * derate - V * pv) / max(1, E)))
-        return dict(ps_per_vertex=pv, ps_per_message=pm, ps_per_edge=pe,
-                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)))
+        """Femtosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
+        pv = max(1, int(v_ns * 1e6 * derate / V))
+        pm = max(1, int((s_ns * 1e6 * derate - V * pv) / M))
+        pe = max(1, int((g_ns * 1e6 * derate - V * pv) / max(1, E)))
+        return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe,
+                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)), min_step_ns=floors)
     log("layout: M/E=%.3f, %d destination partitions, %d source partitions, %d hubs in %d virtual rows, init+first run %.2fs" %
         (info.messages / max(1, E), info.partitions, info.source_partitions, info.hubs, info.virtual_rows, t_init))
     log("standalone per iteration: scatter %.1f us, gather %.1f us (once per run: first vertex pass %.1f us, hub finish %.1f us)" %
         (s_ns / 1e3, g_ns / 1e3, v_ns / 1e3, h_ns / 1e3))
+    log("shortest steps (one tile per launch, x %.2f): vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
+        ((args.derate,) + tuple(x / 1e3 for x in floors)))
     standalone_iter_ns = s_ns + g_ns
 
     # ---- runtime, task, stage
@@ -176,6 +186,15 @@ def main():
     p1 = ctx.fr_query_progress(tid)
     ctx.fr_task_stop(tid)
 
+    if args.dump_events:
+        with open(args.dump_events, "w") as fh:
+            for r in with_task:
+                fh.write(json.dumps({"epoch_ns": r.epoch_ns, "busy_ns": r.busy_ns, "bubble_ns": r.bubble_ns,
+                                     "n_bubbles": r.n_bubbles, "overruns": r.overruns}) + "\n")
+            for e in events:
+                fh.write(json.dumps({"kind": e.kind, "bubble": e.bubble, "run": e.run, "segment": e.segment,
+                                     "tile0": e.tile0, "tile1": e.tile1, "modelled_ns": e.modelled_ns,
+                                     "measured_ns": e.measured_ns, "t_host_ns": e.t_host_ns}) + "\n")
     wall_s = t1 - t0
     edges = p1.work_units_done - p0.work_units_done
     bubble_ns = sum(r.bubble_ns for r in with_task)

@@ -239,16 +239,20 @@ typedef struct fr_pagerank_desc {
     int32_t  max_runs;            /* stop harvesting after this many completed runs; 0 = restart forever    */
     int32_t  reserved;
     uint64_t mem_limit_bytes;     /* the task's memory limit; caller buffers above are booked against it    */
-    /* cost model, integer picoseconds, fixed for the task's life (0 = library default); tile cost in ns =
-       ceil(sum / 1000), at least 1:
-         vertex tile  : rows * ps_per_vertex
-         scatter tile : messages * ps_per_message + sources * ps_per_vertex
-         gather tile  : edges * ps_per_edge + rows * ps_per_vertex
+    /* cost model, integer femtoseconds (a streaming kernel spends about 1000 fs on an edge, so picoseconds would
+       be too coarse), fixed for the task's life (0 = library default); tile cost in ns = ceil(sum / 10^6), at least 1:
+         vertex tile  : rows * fs_per_vertex
+         scatter tile : messages * fs_per_message + sources * fs_per_vertex
+         gather tile  : edges * fs_per_edge + rows * fs_per_vertex
          hub tile     : hubfin_tile_ns (already ns)                                                         */
-    uint64_t ps_per_edge;
-    uint64_t ps_per_message;
-    uint64_t ps_per_vertex;
+    uint64_t fs_per_edge;
+    uint64_t fs_per_message;
+    uint64_t fs_per_vertex;
     uint64_t hubfin_tile_ns;
+    /* Shortest step per segment kind (indexed by FR_PR_SEG_*), ns; 0 = none.  A launch of a few tiles takes about
+       as long as one tile alone (the tiles run side by side), so the modelled cost of a step is
+       max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.                   */
+    uint64_t min_step_ns[4];
 } fr_pagerank_desc;
 
 /* Facts about the layout built by InitSideTask. */

@@ -18,10 +18,14 @@ bubble lengths and the cost table -- no clock is read.
 
     remaining = L_i - guard
     repeat:
+        step(n) = launch_cost + max(sum of the next n tile costs, floor of the segment)
         n = the largest count of consecutive tiles from the cursor, inside the current segment, with
-            launch_cost + sum(cost) <= min(remaining, max_chunk)
+            step(n) <= min(remaining, max_chunk)
         n == 0  ->  idle for the rest of the bubble
-        else    ->  run the chunk; remaining -= launch_cost + sum(cost); advance the cursor
+        else    ->  run the chunk; remaining -= step(n); advance the cursor
+
+The floor is the profiled duration of the segment's shortest step (Section 4.3 profiles the per-step duration):
+tiles of one step run side by side on the GPU, so a step of a few tiles is not shorter than a step of one.
 
 When the last segment of a run completes the task starts over (run index + 1) unless `max_runs` is reached,
 after which it harvests nothing more.
@@ -38,15 +42,21 @@ class Record:
     segment: int = 0   # index into the segment list of one run
     tile0: int = 0
     tile1: int = 0
-    modelled_ns: int = 0   # CHUNK: launch_cost + sum of tile costs; IDLE: modelled time left unused
+    modelled_ns: int = 0   # CHUNK: launch_cost + max(sum of tile costs, floor); IDLE: modelled time left unused
 
 
 def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard: int, launch_cost: int,
-         max_chunk: int, max_runs: Optional[int] = None, start_created: bool = True) -> List[Record]:
-    """Plan over the given bubbles.  segments[g][t] is the modelled cost of tile t of segment g (ints >= 0).
+         max_chunk: int, max_runs: Optional[int] = None, start_created: bool = True,
+         floors: Optional[Sequence[int]] = None) -> List[Record]:
+    """Plan over the given bubbles.  segments[g][t] is the modelled cost of tile t of segment g (ints >= 0);
+    floors[g] (default 0) is the least modelled cost of any step of segment g.
 
     start_created: the task begins in CREATED, so the first bubble is consumed by initialisation.
     """
+    if floors is None:
+        floors = [0] * len(segments)
+    if len(floors) != len(segments) or any(f < 0 for f in floors):
+        raise ValueError("one non-negative floor per segment")
     if launch_cost < 0 or guard < 0 or max_chunk <= 0:
         raise ValueError("bad planner constants")
     if any(len(seg) == 0 for seg in segments) or len(segments) == 0:
@@ -67,10 +77,11 @@ def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard
                 break                                   # task finished: nothing left to harvest
             budget = min(remaining, max_chunk)
             costs = segments[seg]
-            n, total = 0, launch_cost
-            while tile + n < len(costs) and total + costs[tile + n] <= budget:
-                total += costs[tile + n]
+            n, tiles_cost = 0, 0
+            while tile + n < len(costs) and launch_cost + max(tiles_cost + costs[tile + n], floors[seg]) <= budget:
+                tiles_cost += costs[tile + n]
                 n += 1
+            total = launch_cost + max(tiles_cost, floors[seg])
             if n == 0:
                 out.append(Record("IDLE", i, run, seg, tile, tile, max(remaining, 0)))
                 break

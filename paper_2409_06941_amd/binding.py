@@ -68,8 +68,8 @@ class fr_pagerank_desc(C.Structure):
     _fields_ = [("n_vertices", C.c_int64), ("n_edges", C.c_int64), ("row_ptr", C.c_void_p), ("col", C.c_void_p),
                 ("out_degree", C.c_void_p), ("ranks_out", C.c_void_p), ("damping", C.c_float), ("iterations", C.c_int32),
                 ("max_runs", C.c_int32), ("reserved", C.c_int32), ("mem_limit_bytes", C.c_uint64),
-                ("ps_per_edge", C.c_uint64), ("ps_per_message", C.c_uint64), ("ps_per_vertex", C.c_uint64),
-                ("hubfin_tile_ns", C.c_uint64)]
+                ("fs_per_edge", C.c_uint64), ("fs_per_message", C.c_uint64), ("fs_per_vertex", C.c_uint64),
+                ("hubfin_tile_ns", C.c_uint64), ("min_step_ns", C.c_uint64 * 4)]
 
 
 class fr_pagerank_info_t(C.Structure):
@@ -261,15 +261,17 @@ class PageRankTask:
     """fr_pagerank_make and friends.  Tensors (torch, on the GPU) are only read for their data_ptr."""
 
     def __init__(self, n_vertices, n_edges, row_ptr, col, out_degree, ranks_out, damping=0.85, iterations=30,
-                 max_runs=0, mem_limit_bytes=1 << 40, ps_per_edge=0, ps_per_message=0, ps_per_vertex=0,
-                 hubfin_tile_ns=0):
+                 max_runs=0, mem_limit_bytes=1 << 40, fs_per_edge=0, fs_per_message=0, fs_per_vertex=0,
+                 hubfin_tile_ns=0, min_step_ns=(0, 0, 0, 0)):
         d = fr_pagerank_desc()
         d.n_vertices, d.n_edges = n_vertices, n_edges
         d.row_ptr, d.col, d.out_degree, d.ranks_out = _ptr(row_ptr), _ptr(col), _ptr(out_degree), _ptr(ranks_out)
         d.damping, d.iterations, d.max_runs = damping, iterations, max_runs
         d.mem_limit_bytes = mem_limit_bytes
-        d.ps_per_edge, d.ps_per_message, d.ps_per_vertex = ps_per_edge, ps_per_message, ps_per_vertex
+        d.fs_per_edge, d.fs_per_message, d.fs_per_vertex = fs_per_edge, fs_per_message, fs_per_vertex
         d.hubfin_tile_ns = hubfin_tile_ns
+        for k in range(4):
+            d.min_step_ns[k] = int(min_step_ns[k])
         self.desc = d
         self._keep = (row_ptr, col, out_degree, ranks_out)
         self.ops = fr_task_ops()

@@ -459,9 +459,9 @@ __global__ __launch_bounds__(256) void k_hubfin(DevArgs A, uint32_t tile0, int p
 
 uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
-uint64_t ceil_ps_to_ns(unsigned __int128 ps)
+uint64_t ceil_fs_to_ns(unsigned __int128 fs)
 {
-    const uint64_t ns = (uint64_t)((ps + 999) / 1000);
+    const uint64_t ns = (uint64_t)((fs + 999999) / 1000000);
     return ns ? ns : 1;
 }
 
@@ -506,20 +506,20 @@ struct PrTask {
 void build_cost_tables(PrTask* p)
 {
     const PrLayout& L = p->L;
-    const uint64_t pe = p->d.ps_per_edge, pm = p->d.ps_per_message, pv = p->d.ps_per_vertex;
+    const uint64_t pe = p->d.fs_per_edge, pm = p->d.fs_per_message, pv = p->d.fs_per_vertex;
     auto& v = p->prefix[FR_PR_SEG_VERTEX];
     v.assign(L.Q + 1, 0);
-    for (uint32_t q = 0; q < L.Q; ++q) v[q + 1] = v[q] + ceil_ps_to_ns((unsigned __int128)p->rows_of_q(q) * pv);
+    for (uint32_t q = 0; q < L.Q; ++q) v[q + 1] = v[q] + ceil_fs_to_ns((unsigned __int128)p->rows_of_q(q) * pv);
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
     s.assign(L.P + 1, 0);
     for (uint32_t i = 0; i < L.P; ++i) {
         const uint64_t srcs = std::min<uint64_t>(kSrcPerPart, (uint64_t)L.V - (uint64_t)i * kSrcPerPart);
-        s[i + 1] = s[i] + ceil_ps_to_ns((unsigned __int128)L.msgs_of_p[i] * pm + (unsigned __int128)srcs * pv);
+        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.msgs_of_p[i] * pm + (unsigned __int128)srcs * pv);
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
     g.assign(L.Q + 1, 0);
     for (uint32_t q = 0; q < L.Q; ++q)
-        g[q + 1] = g[q] + ceil_ps_to_ns((unsigned __int128)L.edges_of_q[q] * pe + (unsigned __int128)p->rows_of_q(q) * pv);
+        g[q + 1] = g[q] + ceil_fs_to_ns((unsigned __int128)L.edges_of_q[q] * pe + (unsigned __int128)p->rows_of_q(q) * pv);
     auto& h = p->prefix[FR_PR_SEG_HUBFIN];
     h.assign(L.n_hub_tiles + 1, 0);
     for (uint32_t t = 0; t < L.n_hub_tiles; ++t) h[t + 1] = h[t] + std::max<uint64_t>(1, p->d.hubfin_tile_ns);
@@ -613,12 +613,14 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     if (p->d.max_runs > 0 && p->run >= (uint32_t)p->d.max_runs) { out->finished = 1; return FR_OK; }
     const int kind = p->kind_of(p->seg);
     const std::vector<uint64_t>& pre = p->prefix[kind];
+    const uint64_t floor_ns = p->d.min_step_ns[kind];
+    if (floor_ns > budget_ns || launch_cost_ns > budget_ns - floor_ns) return FR_OK;     // even the shortest step is too long
     uint32_t n = 0;
     int rc = fr_chunk_fit(pre.data(), p->tiles_of(kind), p->tile, budget_ns, launch_cost_ns, &n);
     if (rc != FR_OK) return rc;
     if (n == 0) return FR_OK;
     out->tile1 = p->tile + n;
-    out->modelled_ns = pre[p->tile + n] - pre[p->tile];
+    out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     if (kind == FR_PR_SEG_GATHER) {
         uint64_t edges = 0;
         for (uint32_t q = p->tile; q < p->tile + n; ++q) edges += p->L.edges_of_q[q];
@@ -664,9 +666,9 @@ int fr_pagerank_make(const fr_pagerank_desc* d, fr_task_ops* ops_out, void** use
     PrTask* p = new (std::nothrow) PrTask();
     if (!p) return FR_ERR_ARG;
     p->d = *d;
-    if (!p->d.ps_per_edge) p->d.ps_per_edge = 2;
-    if (!p->d.ps_per_message) p->d.ps_per_message = 2;
-    if (!p->d.ps_per_vertex) p->d.ps_per_vertex = 4;
+    if (!p->d.fs_per_edge) p->d.fs_per_edge = 2000;
+    if (!p->d.fs_per_message) p->d.fs_per_message = 2000;
+    if (!p->d.fs_per_vertex) p->d.fs_per_vertex = 4000;
     if (!p->d.hubfin_tile_ns) p->d.hubfin_tile_ns = 2000;
     ops_out->create = pr_create;
     ops_out->init = pr_init;

@@ -38,7 +38,7 @@ def test_cfg2_full_size_harvested_run_matches_oracle_and_standalone_bits():
     ctx = fr.Context(device_id=0, guard_ns=200_000, launch_cost_ns=10_000, time_steps=1, mem_available_bytes=1 << 40)
     # generous modelled costs (about 2x what the kernels need) so that no step overruns its bubble
     task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=1, mem_limit_bytes=8 << 30,
-                           ps_per_edge=2, ps_per_message=3, ps_per_vertex=2, hubfin_tile_ns=200)
+                           fs_per_edge=2000, fs_per_message=3000, fs_per_vertex=2000, hubfin_tile_ns=200)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)
     t_end = time.time() + 60

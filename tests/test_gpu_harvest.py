@@ -39,13 +39,18 @@ def _segments(task, iterations):
     return segs + [h]
 
 
+def _floors(min_step_ns, iterations):
+    fv, fs, fg, fh = min_step_ns
+    return [fv] + [fs, fg] * iterations + [fh]
+
+
 def _check_cost_rule(task, pe, pm, pv, hub_ns):
     """Tile costs follow the documented integer formula."""
     rows = task.fr_pagerank_tile_work(fr.FR_PR_SEG_VERTEX)
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX) == [max(1, -(-r * pv // 1000)) for r in rows]
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX) == [max(1, -(-r * pv // 10**6)) for r in rows]
     info = task.fr_pagerank_info()
     edges = task.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 1000)) for e, r in zip(edges, rows)]
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 10**6)) for e, r in zip(edges, rows)]
     assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN) == [hub_ns] * max(1, -(-info.hubs // 16))
 
 
@@ -62,11 +67,14 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     t_ref.fr_pagerank_destroy()
 
     guard, launch, max_chunk = 300_000, 25_000, 500_000
+    # shortest-step floors (vertex, scatter, gather, hub finish): above one tile's cost for scatter and gather, so
+    # that single-tile steps are charged the floor and two-tile steps the sum
+    floors = (9_000, 60_000, 80_000, 20_000)
     ctx = fr.Context(device_id=0, guard_ns=guard, launch_cost_ns=launch, max_chunk_ns=max_chunk, time_steps=1,
                      mem_available_bytes=1 << 40)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=cfg.iterations, max_runs=3,
-                           mem_limit_bytes=1 << 30, ps_per_edge=400, ps_per_message=2500, ps_per_vertex=300,
-                           hubfin_tile_ns=15000)
+                           mem_limit_bytes=1 << 30, fs_per_edge=400_000, fs_per_message=2_500_000, fs_per_vertex=300_000,
+                           hubfin_tile_ns=15000, min_step_ns=floors)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     assert _init_bubble(ctx, tid) == fr.FR_OK
     assert ctx.fr_query_progress(tid).state == fr.FR_PAUSED
@@ -81,7 +89,7 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     pr = ctx.fr_query_progress(tid)
     log = ctx.fr_event_log()
     segs = _segments(task, cfg.iterations)          # the cost tables exist once InitSideTask has run
-    _check_cost_rule(task, 400, 2500, 300, 15000)
+    _check_cost_rule(task, 400_000, 2_500_000, 300_000, 15000)
     ctx.fr_task_stop(tid)
     got = ranks.cpu().numpy()
     want_bits = ref.cpu().numpy()
@@ -96,7 +104,10 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     assert pr.overruns == 0 and pr.deadline_misses == 0 and sum(r.overruns for r in results) == 0
     assert pr.bubbles_seen == len(lengths)
 
-    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=3)
+    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=3, floors=_floors(floors, cfg.iterations))
+    # the one scatter tile costs less than its floor, so scatter steps are charged the floor; two gather tiles cost more
+    assert all(r.modelled_ns == launch + 60_000 for r in want if r.kind == "CHUNK" and r.segment == 1)
+    assert any(r.modelled_ns > launch + 80_000 for r in want if r.kind == "CHUNK" and r.segment == 2)
     got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
     want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
     assert got_log == want_log

@@ -97,3 +97,52 @@ def test_completed_run_covers_every_tile_exactly_once():
 def test_rejects_zero_cost_chunks():
     with pytest.raises(ValueError):
         plan([10], [[0, 0]], guard=0, launch_cost=0, max_chunk=10)
+
+
+def test_floor_hand_worked_example():
+    # one segment [10, 10, 10, 10, 10, 10] with floor 25, second segment [40] with floor 0; launch 5, guard 0
+    # bubble 0 (58): step(n) = 5 + max(10 n, 25): n = 5 -> 55 fits, n = 6 -> 65 no -> tiles 0..5 cost 55, rem 3 -> idle
+    # bubble 1 (29): step(1) = 5 + max(10, 25) = 30 > 29 -> idle 29: one tile alone is charged the floor
+    # bubble 2 (30): step(1) = 30 fits exactly -> tile 5..6 cost 30, rem 0; next segment 45 > 0 -> idle 0
+    # bubble 3 (100): segment 1: 45, rem 55; run 1 segment 0: n = 5 -> 55 fits -> rem 0 -> idle 0
+    recs = plan([58, 29, 30, 100], [[10] * 6, [40]], guard=0, launch_cost=5, max_chunk=10**9, start_created=False,
+                floors=[25, 0])
+    assert recs == [
+        Record("CHUNK", 0, 0, 0, 0, 5, 55), Record("IDLE", 0, 0, 0, 5, 5, 3),
+        Record("IDLE", 1, 0, 0, 5, 5, 29),
+        Record("CHUNK", 2, 0, 0, 5, 6, 30), Record("IDLE", 2, 0, 1, 0, 0, 0),
+        Record("CHUNK", 3, 0, 1, 0, 1, 45), Record("CHUNK", 3, 1, 0, 0, 5, 55), Record("IDLE", 3, 1, 0, 5, 5, 0),
+    ]
+
+
+def test_zero_floors_change_nothing_and_bad_floors_are_rejected():
+    segs, bl = [[30, 30, 30], [50]], [100, 60, 200]
+    assert plan(bl, segs, 10, 5, 70, start_created=False) == plan(bl, segs, 10, 5, 70, start_created=False, floors=[0, 0])
+    with pytest.raises(ValueError):
+        plan(bl, segs, 10, 5, 70, floors=[0])
+    with pytest.raises(ValueError):
+        plan(bl, segs, 10, 5, 70, floors=[0, -1])
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_floor_invariants_on_random_inputs(seed):
+    # every chunk is charged launch + max(sum, floor), fits its budget, and is maximal: one more tile would not fit
+    rng = random.Random(1000 + seed)
+    segments = [[rng.randint(1, 50) for _ in range(rng.randint(1, 12))] for _ in range(rng.randint(1, 6))]
+    floors = [rng.choice([0, rng.randint(1, 120)]) for _ in segments]
+    bl = [rng.randint(0, 400) for _ in range(rng.randint(1, 40))]
+    guard, launch, max_chunk = rng.randint(0, 20), rng.randint(0, 10), rng.randint(60, 300)
+    recs = plan(bl, segments, guard, launch, max_chunk, None, start_created=False, floors=floors)
+    left = {}
+    for r in recs:
+        rem = left.get(r.bubble, bl[r.bubble] - guard)
+        costs = segments[r.segment]
+        step = lambda a, b: launch + max(sum(costs[a:b]), floors[r.segment])
+        if r.kind == "CHUNK":
+            assert r.modelled_ns == step(r.tile0, r.tile1) <= min(rem, max_chunk)
+            if r.tile1 < len(costs):
+                assert step(r.tile0, r.tile1 + 1) > min(rem, max_chunk)
+            left[r.bubble] = rem - r.modelled_ns
+        else:
+            assert r.kind == "IDLE" and step(r.tile0, r.tile0 + 1) > min(rem, max_chunk)
+            assert r.modelled_ns == max(rem, 0)
