@@ -80,6 +80,11 @@ typedef struct fr_config {
     uint32_t event_log_capacity;   /* records kept (oldest dropped first); 0 = default (65536)               */
     uint32_t time_steps;           /* nonzero: bracket every step with HIP events and report measured GPU ns */
     uint32_t reserved;
+    uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
+                                      callback or InitSideTask -- is still going on this long after the end of the
+                                      bubble it belongs to is stopped (FR_STOPPED, last_error FR_ERR_OVERRUN, memory
+                                      released), as the paper's worker kills the task's process.  Checked at the next
+                                      bubble notifications; 0 = never.                                           */
 } fr_config;
 
 int fr_create(const fr_config* cfg, fr_ctx** out);
@@ -129,12 +134,17 @@ typedef struct fr_task_profile {
 
 /*
  * Algorithm 1 for one worker: the task is accepted only if ctx.mem_available_bytes > profile.mem_limit_bytes
- * (strictly); otherwise FR_ERR_NOMEM.  On acceptance create() runs and the task is CREATED.  One task per
- * context; a second registration while one is live gives FR_ERR_STATE.  `ops` is copied.
+ * (strictly); otherwise FR_ERR_NOMEM.  An accepted task joins the worker's queue (SUBMITTED).  Algorithm 2: when
+ * the worker has no live current task the head of the queue becomes current, create() runs (on the thread that
+ * makes it current: the caller of this function or of fr_task_stop, or the worker thread) and the task is
+ * CREATED; if create() fails the task is dropped (from this call: its error is returned).  The current task
+ * gives way to the next one when it stops, or when its plan_step reports `finished` while others are waiting.
+ * `ops` is copied.  fr_query_progress works for every id this context has handed out.
  */
 int fr_task_register(fr_ctx* ctx, const fr_task_ops* ops, void* user, const fr_task_profile* profile,
                      fr_task_id* id_out);
-/* StopSideTask(): legal from CREATED, PAUSED and RUNNING; waits for side work in flight, then calls stop(). */
+/* StopSideTask(): legal from CREATED, PAUSED and RUNNING; waits for side work in flight, then calls stop().
+   A task still waiting in the queue (SUBMITTED) just leaves it.  FR_ERR_STATE if already stopped. */
 int fr_task_stop(fr_ctx* ctx, fr_task_id id);
 
 /*
@@ -157,9 +167,10 @@ uint64_t fr_alloc_peak(const fr_alloc* a);   /* highest value fr_alloc_used has 
  *   it is initialised in this bubble; if PAUSED it is started and steps are planned against
  *   duration_ns - guard_ns.  FR_ERR_STATE if a bubble is already open.
  * fr_bubble_end: PauseSideTask().  Returns once the worker has stopped enqueuing.  FR_ERR_OVERRUN (also
- *   counted) if side work is still in flight on the GPU at that moment, or if InitSideTask is still running
- *   (the call does not wait for it; bubbles that open before it finishes are seen but not used);
- *   FR_ERR_STATE if no bubble is open.
+ *   counted) if side work is still in flight on the GPU at that moment, or if InitSideTask or a step callback is
+ *   still running (the call does not wait for InitSideTask at all and for a step callback only 0.2 ms past the
+ *   bubble's declared end; bubbles that open before it returns are seen but not used).  With grace_ns set, work
+ *   that is still going on grace_ns later gets the task stopped.  FR_ERR_STATE if no bubble is open.
  */
 int fr_bubble_begin(fr_ctx* ctx, uint64_t t_begin_ns, uint64_t duration_ns);
 int fr_bubble_end(fr_ctx* ctx);
@@ -179,6 +190,7 @@ typedef struct fr_progress {
     uint64_t overruns;
     uint64_t deadline_misses;
     uint64_t mem_used_bytes;
+    uint64_t killed;                /* 1 if the framework-enforced limit stopped the task                  */
 } fr_progress;
 int fr_query_progress(fr_ctx* ctx, fr_task_id id, fr_progress* out);
 

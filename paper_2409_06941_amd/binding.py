@@ -27,7 +27,7 @@ class fr_config(C.Structure):
     _fields_ = [("device_id", C.c_int32), ("cu_count", C.c_uint32), ("cu_mask", C.c_uint32 * 8),
                 ("mem_available_bytes", C.c_uint64), ("guard_ns", C.c_uint64), ("launch_cost_ns", C.c_uint64),
                 ("max_chunk_ns", C.c_uint64), ("max_inflight", C.c_uint32), ("event_log_capacity", C.c_uint32),
-                ("time_steps", C.c_uint32), ("reserved", C.c_uint32)]
+                ("time_steps", C.c_uint32), ("reserved", C.c_uint32), ("grace_ns", C.c_uint64)]
 
 
 class fr_step(C.Structure):
@@ -55,7 +55,7 @@ class fr_progress(C.Structure):
                 ("work_units_done", C.c_uint64), ("steps", C.c_uint64), ("bubbles_seen", C.c_uint64),
                 ("bubbles_used", C.c_uint64), ("ns_bubble_declared", C.c_uint64), ("ns_modelled", C.c_uint64),
                 ("ns_measured", C.c_uint64), ("ns_idle_insufficient", C.c_uint64), ("overruns", C.c_uint64),
-                ("deadline_misses", C.c_uint64), ("mem_used_bytes", C.c_uint64)]
+                ("deadline_misses", C.c_uint64), ("mem_used_bytes", C.c_uint64), ("killed", C.c_uint64)]
 
 
 class fr_event(C.Structure):
@@ -200,7 +200,7 @@ class Context:
     """fr_ctx: one GPU, one stage."""
 
     def __init__(self, device_id=0, cu_count=0, cu_mask=None, mem_available_bytes=1 << 62, guard_ns=0,
-                 launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0):
+                 launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0, grace_ns=0):
         cfg = fr_config()
         cfg.device_id = device_id
         cfg.cu_count = cu_count
@@ -209,6 +209,7 @@ class Context:
         cfg.mem_available_bytes = mem_available_bytes
         cfg.guard_ns, cfg.launch_cost_ns, cfg.max_chunk_ns = guard_ns, launch_cost_ns, max_chunk_ns
         cfg.max_inflight, cfg.event_log_capacity, cfg.time_steps = max_inflight, event_log_capacity, time_steps
+        cfg.grace_ns = grace_ns
         self.handle = C.c_void_p()
         _check(lib().fr_create(C.byref(cfg), C.byref(self.handle)), "fr_create")
         self._keep = []

@@ -1,7 +1,8 @@
 // Bubble-harvesting runtime: side-task state machine, worker thread, step planning loop, memory accounting,
 // event log.  Follows FreeRide (arXiv 2409.06941): Section 4.1 (states and transitions), Section 4.4
 // (Algorithm 1: admission by memory; Algorithm 2: bubble -> Init / Start / Pause), Section 4.5 (program-directed
-// time limit, memory limit).  The paper's manager / worker / task processes are one worker thread here.
+// time limit and the framework-enforced limit with its grace period, memory limit).  The paper's manager / worker /
+// task processes are one worker thread here; a task that the paper would kill is stopped and its memory released.
 
 #include <time.h>
 
@@ -60,12 +61,22 @@ struct fr_ctx {
     std::atomic<uint64_t> ack_seq{0};       // worker: "I will enqueue nothing more for bubble ack_seq"
     std::atomic<bool> end_requested{false};
     std::atomic<bool> in_init{false};       // the worker is inside the task's init()
+    std::atomic<uint64_t> in_callback{0};   // nonzero: the worker is inside plan_step / run_step since that time
+    // Framework-enforced limit (Section 4.5): armed when a bubble ends with side work still going on (on the GPU,
+    // or a callback that has not returned); if the work is still going on `grace_ns` later the task is killed.
+    std::atomic<bool> kill_current{false};  // the worker stops the current task the next time it is between callbacks
+    bool enforce_armed = false;             // stage thread only
+    bool enforce_gpu = false;               //   what is late: GPU work behind tail_event, or a host callback
+    uint64_t enforce_callback = 0;          //   the late callback's start time (identifies it)
+    uint64_t enforce_deadline = 0;
     bool bubble_open = false;               // stage thread only
     uint64_t cur_begin = 0, cur_len = 0;
     uint32_t cur_index = 0;                 // 0-based bubble index
     uint64_t bubbles_total = 0;
 
-    Task* task = nullptr;
+    Task* task = nullptr;                   // the worker's current task (Algorithm 2)
+    std::deque<Task*> queue;                // accepted tasks waiting their turn (Algorithm 1 appends, Algorithm 2 pops)
+    std::vector<Task*> tasks;               // every task registered with this context, owned
     fr_task_id next_id = 1;
 
     // event log ring
@@ -162,6 +173,42 @@ void stop_task_locked(fr_ctx* c, Task* t, int error)
     if (error != FR_OK) t->last_error = error;
 }
 
+// Algorithm 2: when the worker has no live current task, the next one in its queue becomes current and is
+// created.  ctx->mu and work_mu held.
+void promote_locked(fr_ctx* c)
+{
+    while ((!c->task || c->task->state == FR_STOPPED) && !c->queue.empty()) {
+        Task* t = c->queue.front();
+        c->queue.pop_front();
+        const int rc = t->ops.create ? t->ops.create(t->user) : FR_OK;      // CreateSideTask()
+        if (rc != FR_OK) { t->state = FR_STOPPED; t->last_error = rc; continue; }
+        t->state = FR_CREATED;
+        c->task = t;
+    }
+}
+
+Task* find_task(fr_ctx* c, fr_task_id id)
+{
+    for (Task* t : c->tasks)
+        if (t->id == id) return t;
+    return nullptr;
+}
+
+// The framework-enforced limit has expired for the current task: stop it, as the paper's worker kills the
+// task's process, and let the next queued task take its place.  Worker thread, work_mu held.
+bool killed_if_asked(fr_ctx* c, Task* t)
+{
+    if (!c->kill_current.load(std::memory_order_acquire)) return false;
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->kill_current.store(false, std::memory_order_release);
+    if (t->state != FR_STOPPED) {
+        t->prog.killed = 1;
+        stop_task_locked(c, t, FR_ERR_OVERRUN);
+        promote_locked(c);
+    }
+    return true;
+}
+
 // One bubble, on the worker thread, work_mu held.
 void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint32_t index)
 {
@@ -174,6 +221,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         t->prog.ns_bubble_declared += len;
     }
     auto stop_now = [&]() { return c->end_requested.load(std::memory_order_acquire) || c->abort_steps.load() || c->quit.load(); };
+    if (killed_if_asked(c, t)) return;
 
     if (t->state == FR_CREATED) {
         // Algorithm 2: a CREATED current task is initialised by the new bubble.
@@ -189,7 +237,11 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         else if (rc != FR_OK) {
             if (rc == FR_ERR_HIP) c->hip_error = t->alloc.hip_error ? t->alloc.hip_error : c->hip_error;
             stop_task_locked(c, t, rc);
+        } else if (c->kill_current.exchange(false)) {
+            t->prog.killed = 1;                          // the initialisation outlived its bubble and the grace period
+            stop_task_locked(c, t, FR_ERR_OVERRUN);
         } else t->state = FR_PAUSED;
+        if (t->state == FR_STOPPED) promote_locked(c);
         if (!c->host_only && c->tail_event && t->state == FR_PAUSED)
             c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
         return;
@@ -206,15 +258,18 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     const bool timed = c->cfg.time_steps && !c->host_only;
     int64_t remaining = (int64_t)len - (int64_t)guard;
     const int64_t total = remaining;
-    bool used = false;
+    bool used = false, finished = false;
     int fail = FR_OK;
 
     while (!stop_now()) {
         const uint64_t budget = remaining > 0 ? ((uint64_t)remaining < max_chunk ? (uint64_t)remaining : max_chunk) : 0;
         fr_step st{};
+        c->in_callback.store(now_ns(), std::memory_order_release);
         int rc = t->ops.plan_step(t->user, budget, launch, &st);
+        c->in_callback.store(0, std::memory_order_release);
         if (rc != FR_OK) { fail = rc; break; }
-        if (st.finished) break;
+        if (c->kill_current.load(std::memory_order_acquire)) break;
+        if (st.finished) { finished = true; break; }
         if (st.modelled_ns == 0) {
             // the remaining time is not enough for the next step: leave the rest of the bubble idle
             std::lock_guard<std::mutex> lk(c->mu);
@@ -267,7 +322,9 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             ev_end = event_get(c);
         }
         if (timed && chain_head && ev_begin) (void)hipEventRecord(ev_begin, c->side);
+        c->in_callback.store(now_ns(), std::memory_order_release);
         rc = t->ops.run_step(t->user, (void*)c->side, &st);
+        c->in_callback.store(0, std::memory_order_release);
         if (timed && ev_end) (void)hipEventRecord(ev_end, c->side);
         {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -287,6 +344,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             if (!used) { used = true; t->prog.bubbles_used++; }
         }
         if (rc != FR_OK) { fail = rc; break; }
+        if (c->kill_current.load(std::memory_order_acquire)) break;
         remaining -= (int64_t)cost;
     }
     (void)seq;
@@ -300,7 +358,12 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         c->chain_tail = nullptr;
     }
     if (fail != FR_OK) stop_task_locked(c, t, fail);
+    else if (c->kill_current.exchange(false)) {
+        t->prog.killed = 1;
+        stop_task_locked(c, t, FR_ERR_OVERRUN);
+    } else if (finished && !c->queue.empty()) stop_task_locked(c, t, FR_OK);   // done: the worker moves on to the next task
     else if (t->state == FR_RUNNING) t->state = FR_PAUSED;   // PauseSideTask()
+    if (t->state == FR_STOPPED) promote_locked(c);
 }
 
 void worker_main(fr_ctx* c)
@@ -335,6 +398,24 @@ void worker_main(fr_ctx* c)
         }
         c->ack_seq.store(seq, std::memory_order_release);
     }
+}
+
+// How long fr_bubble_end waits for a step callback that is still running after the bubble's end.
+constexpr uint64_t kCallbackPatienceNs = 200000;
+
+// Stage thread, between bubbles or at a bubble's edge: has the work that was late at an earlier bubble end
+// finished meanwhile?  If not and the grace period is over, ask the worker to stop the task.
+void enforce_check(fr_ctx* c)
+{
+    if (!c->enforce_armed) return;
+    bool still_late;
+    if (c->enforce_gpu) still_late = c->tail_event && hipEventQuery(c->tail_event) == hipErrorNotReady;
+    else if (c->enforce_callback == 1) still_late = c->in_init.load(std::memory_order_acquire);
+    else still_late = c->in_callback.load(std::memory_order_acquire) == c->enforce_callback;
+    if (!still_late) { c->enforce_armed = false; return; }
+    if (now_ns() < c->enforce_deadline) return;
+    c->kill_current.store(true, std::memory_order_release);
+    c->enforce_armed = false;
 }
 
 }  // namespace
@@ -451,11 +532,11 @@ int fr_destroy(fr_ctx* c)
     if (c->worker.joinable()) c->worker.join();
     {
         std::lock_guard<std::mutex> lk(c->mu);
-        if (c->task) {
-            stop_task_locked(c, c->task, FR_OK);
-            delete c->task;
-            c->task = nullptr;
-        }
+        if (c->task) stop_task_locked(c, c->task, FR_OK);
+        c->task = nullptr;
+        c->queue.clear();
+        for (Task* t : c->tasks) delete t;
+        c->tasks.clear();
         resolve_timings(c, true);
         for (hipEvent_t e : c->free_events) (void)hipEventDestroy(e);
         c->free_events.clear();
@@ -479,21 +560,24 @@ int fr_last_hip_error(fr_ctx* c) { return c ? c->hip_error : 0; }
 int fr_task_register(fr_ctx* c, const fr_task_ops* ops, void* user, const fr_task_profile* prof, fr_task_id* id_out)
 {
     if (!c || !ops || !prof || !id_out || !ops->plan_step || !ops->run_step) return FR_ERR_ARG;
-    std::lock_guard<std::mutex> wl(c->work_mu);
-    std::lock_guard<std::mutex> lk(c->mu);
-    if (c->task && c->task->state != FR_STOPPED) return FR_ERR_STATE;
     // Algorithm 1 with a single worker: the worker qualifies only if its free memory exceeds the task's need.
     if (!(c->cfg.mem_available_bytes > prof->mem_limit_bytes)) return FR_ERR_NOMEM;   // RejectSideTask()
-    delete c->task;
+    std::lock_guard<std::mutex> wl(c->work_mu);
+    std::lock_guard<std::mutex> lk(c->mu);
     Task* t = new (std::nothrow) Task();
     if (!t) return FR_ERR_ARG;
     t->ops = *ops; t->user = user; t->prof = *prof; t->id = c->next_id++;
     fr_alloc_reset(&t->alloc, prof->mem_limit_bytes, c->host_only, c->cfg.device_id);
     t->state = FR_SUBMITTED;
-    int rc = ops->create ? ops->create(user) : FR_OK;      // CreateSideTask()
-    if (rc != FR_OK) { delete t; c->task = nullptr; return rc; }
-    t->state = FR_CREATED;
-    c->task = t;
+    c->tasks.push_back(t);
+    c->queue.push_back(t);                   // Algorithm 1: AddToQueue
+    promote_locked(c);                       // Algorithm 2: becomes current at once if the worker has no live task
+    if (t->state == FR_STOPPED) {            // its create() failed
+        const int rc = t->last_error;
+        c->tasks.pop_back();
+        delete t;
+        return rc;
+    }
     *id_out = t->id;
     return FR_OK;
 }
@@ -505,10 +589,17 @@ int fr_task_stop(fr_ctx* c, fr_task_id id)
     std::lock_guard<std::mutex> wl(c->work_mu);     // the worker is outside every callback now
     c->abort_steps.store(false);
     std::lock_guard<std::mutex> lk(c->mu);
-    Task* t = c->task;
-    if (!t || t->id != id) return FR_ERR_ARG;
-    if (t->state == FR_STOPPED || t->state == FR_SUBMITTED) return FR_ERR_STATE;
+    Task* t = find_task(c, id);
+    if (!t) return FR_ERR_ARG;
+    if (t->state == FR_STOPPED) return FR_ERR_STATE;
+    if (t->state == FR_SUBMITTED) {          // still waiting in the queue: it just leaves it
+        for (size_t i = 0; i < c->queue.size(); ++i)
+            if (c->queue[i] == t) { c->queue.erase(c->queue.begin() + (long)i); break; }
+        t->state = FR_STOPPED;
+        return FR_OK;
+    }
     stop_task_locked(c, t, FR_OK);
+    promote_locked(c);
     return FR_OK;
 }
 
@@ -516,6 +607,7 @@ int fr_bubble_begin(fr_ctx* c, uint64_t t_begin_ns, uint64_t duration_ns)
 {
     if (!c) return FR_ERR_ARG;
     if (c->bubble_open) return FR_ERR_STATE;
+    enforce_check(c);
     c->bubble_open = true;
     c->cur_begin = t_begin_ns;
     c->cur_len = duration_ns;
@@ -529,13 +621,23 @@ int fr_bubble_end(fr_ctx* c)
 {
     if (!c) return FR_ERR_ARG;
     if (!c->bubble_open) return FR_ERR_STATE;
+    enforce_check(c);
     c->end_requested.store(true, std::memory_order_release);
     const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
     while (c->ack_seq.load(std::memory_order_acquire) != seq) {              // worker enqueues nothing more
-        if (c->in_init.load(std::memory_order_acquire)) {
-            // InitSideTask has outlived the bubble.  The stage is not held up for it: the call returns at once
-            // and the initialisation goes on beside the stage's next operation.
+        // A callback that outlives the bubble does not hold the stage up: the call returns at once for
+        // InitSideTask (known to be long) and after kCallbackPatience for a step callback, and the work goes on
+        // beside the stage's next operation until it returns or the grace period runs out.
+        const bool init_late = c->in_init.load(std::memory_order_acquire);
+        const uint64_t cb = c->in_callback.load(std::memory_order_acquire);
+        const uint64_t now = now_ns();
+        if (init_late || (cb && now > cb + kCallbackPatienceNs && now > c->cur_begin + c->cur_len)) {
             c->bubble_open = false;
+            if (c->cfg.grace_ns && !c->enforce_armed) {
+                c->enforce_armed = true; c->enforce_gpu = false;
+                c->enforce_callback = init_late ? 1 : cb;
+                c->enforce_deadline = now + c->cfg.grace_ns;
+            }
             std::lock_guard<std::mutex> lk(c->mu);
             if (c->task) c->task->prog.overruns++;
             return FR_ERR_OVERRUN;
@@ -546,6 +648,10 @@ int fr_bubble_end(fr_ctx* c)
     if (c->host_only || !c->tail_armed) return FR_OK;     // nothing was enqueued for this bubble
     hipError_t q = hipEventQuery(c->tail_event);
     if (q == hipErrorNotReady) {
+        if (c->cfg.grace_ns && !c->enforce_armed) {
+            c->enforce_armed = true; c->enforce_gpu = true;
+            c->enforce_deadline = now_ns() + c->cfg.grace_ns;
+        }
         std::lock_guard<std::mutex> lk(c->mu);
         if (c->task) c->task->prog.overruns++;
         return FR_ERR_OVERRUN;
@@ -558,8 +664,8 @@ int fr_query_progress(fr_ctx* c, fr_task_id id, fr_progress* out)
 {
     if (!c || !out) return FR_ERR_ARG;
     std::lock_guard<std::mutex> lk(c->mu);
-    Task* t = c->task;
-    if (!t || t->id != id) return FR_ERR_ARG;
+    Task* t = find_task(c, id);
+    if (!t) return FR_ERR_ARG;
     if (!c->host_only) resolve_timings(c, false);
     *out = t->prog;
     out->state = t->state;

@@ -2,6 +2,7 @@
 import ctypes
 import os
 import re
+import subprocess
 
 import paper_2409_06941_amd as fr
 
@@ -24,10 +25,21 @@ def test_every_declared_function_is_exported_and_bound():
     assert declared == set(fr.binding.SIGNATURES), declared ^ set(fr.binding.SIGNATURES)
 
 
-def test_struct_sizes_match_the_header_layout():
-    # natural alignment, as a C compiler lays the header's structs out
-    assert ctypes.sizeof(fr.fr_config) == 4 + 4 + 32 + 8 * 4 + 4 * 4
-    assert ctypes.sizeof(fr.fr_step) == 8 + 8 + 4 * 4 + 4 + 4
-    assert ctypes.sizeof(fr.fr_event) == 6 * 4 + 4 * 8
-    assert ctypes.sizeof(fr.fr_progress) == 8 + 12 * 8
-    assert ctypes.sizeof(fr.fr_stage_op) == 8 + 3 * 8
+STRUCTS = ["fr_config", "fr_step", "fr_task_profile", "fr_progress", "fr_event", "fr_pagerank_desc", "fr_pagerank_info_t",
+           "fr_load_desc", "fr_stage_desc", "fr_stage_op", "fr_epoch_result"]
+
+
+def test_struct_sizes_match_the_header_layout(tmp_path):
+    # the C compiler's view of the header against the ctypes structures of the binding
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include "freeride.h"\nint main(void) {\n' +
+                   "".join('  printf("%s %%zu\\n", sizeof(%s));\n' % (n, n) for n in STRUCTS) + "  return 0;\n}\n")
+    exe = tmp_path / "sizes"
+    include = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c11", "-I", include, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    sizes = dict((line.split()[0], int(line.split()[1])) for line in out.splitlines())
+    for n in STRUCTS:
+        assert ctypes.sizeof(getattr(fr.binding, n)) == sizes[n], n
+    assert sizes["fr_config"] == 4 + 4 + 32 + 8 * 4 + 4 * 4 + 8
+    assert sizes["fr_progress"] == 8 + 13 * 8

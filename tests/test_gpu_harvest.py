@@ -167,3 +167,34 @@ def test_cu_masked_side_stream_runs_the_same_bits():
         ctx.fr_destroy()
         outs.append(ranks.cpu().numpy())
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
+@pytest.mark.parametrize("grace_ns,killed", [(200_000, True), (0, False)])
+def test_framework_enforced_limit_stops_a_task_whose_gpu_work_outlives_the_grace_period(grace_ns, killed):
+    # a cost model that claims every step is free makes the worker enqueue up to max_inflight whole sweeps at the
+    # very end of the bubble: about 2 ms of GPU work behind a 0.5 ms bubble (Section 4.5, framework-enforced limit)
+    import time
+    g = graphs.rmat_csr(22, 1 << 26, seed=1)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    ctx = fr.Context(device_id=0, guard_ns=0, launch_cost_ns=0, time_steps=1, max_inflight=32, grace_ns=grace_ns)
+    task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=50, max_runs=0,
+                           fs_per_edge=1, fs_per_message=1, fs_per_vertex=1, hubfin_tile_ns=1)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 500_000)
+    time.sleep(0.0005)
+    assert ctx.fr_bubble_end() == fr.FR_ERR_OVERRUN
+    time.sleep(0.0004)                                   # past the grace period, the sweeps are still running
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 1_000)           # the verdict falls at the next bubble notification
+    ctx.fr_bubble_end()
+    time.sleep(0.05)
+    pr = ctx.fr_query_progress(tid)
+    if killed:
+        assert pr.state == fr.FR_STOPPED and pr.last_error == fr.FR_ERR_OVERRUN and pr.killed == 1
+        assert pr.mem_used_bytes > 0                     # what it held when it was stopped; released since
+    else:
+        assert pr.state == fr.FR_PAUSED and pr.killed == 0 and pr.overruns >= 1
+        ctx.fr_task_stop(tid)
+    task.fr_pagerank_destroy()
+    ctx.fr_destroy()

@@ -114,9 +114,13 @@ def test_admission_needs_strictly_more_free_memory_than_the_task_asks(ctx):
     tid = ctx.fr_task_register(t.ops, None, fr.fr_task_profile(999, 1))
     assert t.calls == ["create"]
     assert ctx.fr_query_progress(tid).state == fr.FR_CREATED
-    with pytest.raises(fr.FreeRideError) as e:                    # one live task per context
-        ctx.fr_task_register(t.ops, None, fr.fr_task_profile(10, 1))
-    assert e.value.code == fr.FR_ERR_STATE
+    # Algorithm 1 looks at the worker's free memory only: a second accepted task waits in the worker's queue
+    t2 = FakeTask([[1]])
+    tid2 = ctx.fr_task_register(t2.ops, None, fr.fr_task_profile(10, 1))
+    assert ctx.fr_query_progress(tid2).state == fr.FR_SUBMITTED and t2.calls == []
+    with pytest.raises(fr.FreeRideError) as e:
+        ctx.fr_task_register(t2.ops, None, fr.fr_task_profile(1000, 1))
+    assert e.value.code == fr.FR_ERR_NOMEM
 
 
 def test_state_walk_created_paused_running_paused_stopped(ctx):
@@ -287,3 +291,118 @@ def test_init_that_outlives_its_bubble_does_not_hold_the_stage():
     pr = c.fr_query_progress(tid)
     c.fr_destroy()
     assert pr.overruns == 1 and pr.runs_completed == 1
+
+
+def test_queued_tasks_take_over_in_order_when_the_current_one_finishes_or_stops():
+    # Algorithms 1 and 2: accepted tasks queue up on the worker; the head becomes current (created) when the worker
+    # has no live task, is initialised by the next bubble and runs from the one after
+    ms = 1_000_000
+    c = fr.Context(device_id=-1, guard_ns=0, launch_cost_ns=0)
+    a, b, d = FakeTask([[1 * ms, 1 * ms]], max_runs=1), FakeTask([[1 * ms]], max_runs=0), FakeTask([[1 * ms]], max_runs=1)
+    ia = c.fr_task_register(a.ops, None, fr.fr_task_profile(10, 1))
+    ib = c.fr_task_register(b.ops, None, fr.fr_task_profile(10, 1))
+    idd = c.fr_task_register(d.ops, None, fr.fr_task_profile(10, 1))
+    assert [c.fr_query_progress(i).state for i in (ia, ib, idd)] == [fr.FR_CREATED, fr.FR_SUBMITTED, fr.FR_SUBMITTED]
+    assert _bubble(c, 10 * ms) == fr.FR_OK                      # a: init
+    assert _bubble(c, 10 * ms) == fr.FR_OK                      # a: both tiles, then finished -> b becomes current
+    pa = c.fr_query_progress(ia)
+    assert pa.state == fr.FR_STOPPED and pa.runs_completed == 1 and pa.last_error == fr.FR_OK and a.calls[-1] == "stop"
+    assert c.fr_query_progress(ib).state == fr.FR_CREATED and b.calls == ["create"]
+    assert _bubble(c, 10 * ms) == fr.FR_OK                      # b: init
+    assert _bubble(c, 3 * ms + 1) == fr.FR_OK                   # b: three one-tile runs
+    assert c.fr_query_progress(ib).runs_completed == 3 and c.fr_query_progress(idd).state == fr.FR_SUBMITTED
+    c.fr_task_stop(ib)                                          # b never finishes by itself; stopping it promotes d
+    assert c.fr_query_progress(ib).state == fr.FR_STOPPED and c.fr_query_progress(idd).state == fr.FR_CREATED
+    assert _bubble(c, 10 * ms) == fr.FR_OK and _bubble(c, 10 * ms) == fr.FR_OK
+    pd = c.fr_query_progress(idd)
+    assert pd.runs_completed == 1 and pd.state == fr.FR_PAUSED   # finished with nobody waiting: stays paused
+    c.fr_destroy()
+    assert d.calls[-1] == "stop"
+
+
+def test_a_queued_task_can_be_withdrawn():
+    c = fr.Context(device_id=-1)
+    a, b = FakeTask([[1]]), FakeTask([[1]])
+    ia = c.fr_task_register(a.ops, None, fr.fr_task_profile(10, 1))
+    ib = c.fr_task_register(b.ops, None, fr.fr_task_profile(10, 1))
+    c.fr_task_stop(ib)
+    assert c.fr_query_progress(ib).state == fr.FR_STOPPED and b.calls == []          # never created, never stopped
+    with pytest.raises(fr.FreeRideError) as e:
+        c.fr_task_stop(ib)
+    assert e.value.code == fr.FR_ERR_STATE
+    c.fr_task_stop(ia)
+    assert c.fr_query_progress(ia).state == fr.FR_STOPPED
+    c.fr_destroy()
+
+
+class _SlowRun(FakeTask):
+    """A task whose run_step does not return for `sleep_s` (a misbehaving side task, Section 4.5)."""
+    sleep_s = 0.08
+
+    def _run(self, user, stream, planned):
+        time.sleep(self.sleep_s)
+        return super()._run(user, stream, planned)
+
+
+def _slow(cls, *args, **kw):
+    t = cls(*args, **kw)
+    t.ops = fr.fr_task_ops(fr.binding.CREATE_FN(t._create), fr.binding.INIT_FN(t._init), fr.binding.PLAN_FN(t._plan),
+                           fr.binding.RUN_FN(t._run), fr.binding.STOP_FN(t._stop))
+    return t
+
+
+@pytest.mark.parametrize("grace_ms,killed", [(10, True), (0, False), (500, False)])
+def test_framework_enforced_limit_stops_a_task_whose_step_does_not_return(grace_ms, killed):
+    # the stage is never held up by the late callback; once the grace period is over the task is stopped (the
+    # paper's worker kills the process) and the next task in the queue takes over
+    ms = 1_000_000
+    c = fr.Context(device_id=-1, guard_ns=0, launch_cost_ns=0, grace_ns=grace_ms * ms)
+    bad, good = _slow(_SlowRun, [[1 * ms]]), FakeTask([[1 * ms]], max_runs=1)
+    ib = c.fr_task_register(bad.ops, None, fr.fr_task_profile(10, 1))
+    ig = c.fr_task_register(good.ops, None, fr.fr_task_profile(10, 1))
+    assert _bubble(c, 10 * ms) == fr.FR_OK                      # init
+    c.fr_bubble_begin(fr.fr_now_ns(), 5 * ms)
+    time.sleep(0.005)
+    t0 = time.time()
+    assert c.fr_bubble_end() == fr.FR_ERR_OVERRUN               # run_step is still asleep
+    assert time.time() - t0 < 0.02
+    assert c.fr_query_progress(ib).state == fr.FR_RUNNING
+    time.sleep(0.03)                                            # past a 10 ms grace period, callback still asleep
+    c.fr_bubble_begin(fr.fr_now_ns(), 1 * ms)                   # the check happens at bubble notifications
+    time.sleep(0.001)
+    c.fr_bubble_end()
+    time.sleep(0.1)                                             # the callback returns; the worker acts on the verdict
+    pb = c.fr_query_progress(ib)
+    if killed:
+        assert pb.state == fr.FR_STOPPED and pb.last_error == fr.FR_ERR_OVERRUN and pb.killed == 1
+        assert bad.calls[-1] == "stop"
+        # the queue moves on (the worker may already have served the short bubble late and initialised the next task)
+        assert c.fr_query_progress(ig).state in (fr.FR_CREATED, fr.FR_PAUSED) and good.calls[0] == "create"
+    else:
+        assert pb.state == fr.FR_PAUSED and pb.killed == 0 and pb.overruns >= 1
+        assert c.fr_query_progress(ig).state == fr.FR_SUBMITTED
+    c.fr_destroy()
+
+
+def test_framework_enforced_limit_covers_initialisation():
+    ms = 1_000_000
+
+    class SlowInit(FakeTask):
+        def _init(self, user, alloc, stream):
+            time.sleep(0.08)
+            return super()._init(user, alloc, stream)
+
+    c = fr.Context(device_id=-1, guard_ns=0, launch_cost_ns=0, grace_ns=10 * ms)
+    t = _slow(SlowInit, [[1 * ms]])
+    tid = c.fr_task_register(t.ops, None, fr.fr_task_profile(10, 1))
+    c.fr_bubble_begin(fr.fr_now_ns(), 5 * ms)
+    time.sleep(0.005)
+    assert c.fr_bubble_end() == fr.FR_ERR_OVERRUN
+    time.sleep(0.03)
+    c.fr_bubble_begin(fr.fr_now_ns(), 1 * ms)
+    time.sleep(0.001)
+    c.fr_bubble_end()
+    time.sleep(0.1)
+    pr = c.fr_query_progress(tid)
+    c.fr_destroy()
+    assert pr.state == fr.FR_STOPPED and pr.last_error == fr.FR_ERR_OVERRUN and pr.killed == 1
