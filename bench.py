@@ -214,6 +214,7 @@ def main():
     e_with = statistics.mean(r.epoch_ns for r in with_task)
     base = base_a + base_b
     e_without = statistics.mean(r.epoch_ns for r in base)
+    ew, eo = [r.epoch_ns for r in with_task], [r.epoch_ns for r in base]
     busy_with = statistics.mean(r.busy_ns for r in with_task)
     busy_without = statistics.mean(r.busy_ns for r in base)
 
@@ -239,6 +240,11 @@ def main():
         "stage_slowdown_pct": 100.0 * (e_with - e_without) / e_without,
         "stage_busy_slowdown_pct": 100.0 * (busy_with - busy_without) / busy_without,
         "epoch_ms_with": e_with / 1e6, "epoch_ms_without": e_without / 1e6,
+        "epoch_ms_with_min_med_max": [min(ew) / 1e6, statistics.median(ew) / 1e6, max(ew) / 1e6],
+        "epoch_ms_without_min_med_max": [min(eo) / 1e6, statistics.median(eo) / 1e6, max(eo) / 1e6],
+        "stage_slowdown_pct_of_medians": 100.0 * (statistics.median(ew) - statistics.median(eo)) / statistics.median(eo),
+        "steps_per_bubble": len(timed) / max(1, sum(r.n_bubbles for r in with_task)),
+        "mean_step_us": (chunk_ns / len(timed) / 1e3) if timed else None,
         "overruns": int(p1.overruns - p0.overruns), "deadline_misses": int(p1.deadline_misses - p0.deadline_misses),
         "runs_completed": int(p1.runs_completed - p0.runs_completed),
         "iterations_per_s_wall": (edges / E) / wall_s,

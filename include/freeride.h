@@ -79,7 +79,11 @@ typedef struct fr_config {
     uint32_t max_inflight;         /* steps enqueued but not yet finished on the GPU; 0 = default (8)        */
     uint32_t event_log_capacity;   /* records kept (oldest dropped first); 0 = default (65536)               */
     uint32_t time_steps;           /* nonzero: bracket every step with HIP events and report measured GPU ns */
-    uint32_t reserved;
+    uint32_t adapt_costs;          /* nonzero: the profiler keeps running (Section 4.3): every measured step updates a
+                                      cost scale for its cost class (measured / modelled, taken at once when it
+                                      rises, eased by 1/8 per step when it falls) and steps are planned against the
+                                      scaled costs.  The plan then depends on measurements and no longer matches a
+                                      plan computed ahead of time.  Needs time_steps.                          */
     uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
                                       callback or InitSideTask -- is still going on this long after the end of the
                                       bubble it belongs to is stopped (FR_STOPPED, last_error FR_ERR_OVERRUN, memory
@@ -105,6 +109,9 @@ typedef struct fr_step {
     uint32_t tile0, tile1;  /*   tile range [tile0, tile1) inside the segment                               */
     int32_t  finished;      /* plan_step sets 1 when the task has no work left at all                       */
     int32_t  completes_run; /* plan_step sets 1 when this step ends a run (PageRank: the K-th iteration)    */
+    uint32_t cost_class;    /* 0..7: steps of one class share a cost scale when costs adapt (PageRank: the
+                               segment kind)                                                                */
+    uint32_t reserved;
 } fr_step;
 
 /*
@@ -217,6 +224,17 @@ int fr_event_log_clear(fr_ctx* ctx);
  */
 int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint64_t budget_ns,
                  uint64_t launch_cost_ns, uint32_t* n_fit);
+
+/*
+ * Cost adaptation (fr_config.adapt_costs).  Scales are parts per million of the task's own modelled cost,
+ * 1000000 at the start, kept within [250000, 16000000].
+ * fr_cost_scale_next: the update rule as a pure function: with r = measured_ns / modelled_ns (in ppm, clamped to
+ *   the range above; the old scale if modelled_ns is 0) the new scale is r if r >= scale_ppm, else
+ *   scale_ppm - (scale_ppm - r) / 8.
+ * fr_cost_scales: the context's eight current scales (host array of 8).
+ */
+uint32_t fr_cost_scale_next(uint32_t scale_ppm, uint64_t modelled_ns, uint64_t measured_ns);
+int fr_cost_scales(fr_ctx* ctx, uint32_t* scales_ppm_out);
 
 /* ------------------------------------------------------------------ the PageRank side task */
 /*

@@ -27,12 +27,13 @@ class fr_config(C.Structure):
     _fields_ = [("device_id", C.c_int32), ("cu_count", C.c_uint32), ("cu_mask", C.c_uint32 * 8),
                 ("mem_available_bytes", C.c_uint64), ("guard_ns", C.c_uint64), ("launch_cost_ns", C.c_uint64),
                 ("max_chunk_ns", C.c_uint64), ("max_inflight", C.c_uint32), ("event_log_capacity", C.c_uint32),
-                ("time_steps", C.c_uint32), ("reserved", C.c_uint32), ("grace_ns", C.c_uint64)]
+                ("time_steps", C.c_uint32), ("adapt_costs", C.c_uint32), ("grace_ns", C.c_uint64)]
 
 
 class fr_step(C.Structure):
     _fields_ = [("modelled_ns", C.c_uint64), ("work_units", C.c_uint64), ("run", C.c_uint32), ("segment", C.c_uint32),
-                ("tile0", C.c_uint32), ("tile1", C.c_uint32), ("finished", C.c_int32), ("completes_run", C.c_int32)]
+                ("tile0", C.c_uint32), ("tile1", C.c_uint32), ("finished", C.c_int32), ("completes_run", C.c_int32),
+                ("cost_class", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 CREATE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p)
@@ -119,6 +120,8 @@ SIGNATURES = {
     "fr_event_log": (C.c_int, [C.c_void_p, C.POINTER(fr_event), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_event_log_clear": (C.c_int, [C.c_void_p]),
     "fr_chunk_fit": (C.c_int, [C.POINTER(C.c_uint64), C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint32)]),
+    "fr_cost_scale_next": (C.c_uint32, [C.c_uint32, C.c_uint64, C.c_uint64]),
+    "fr_cost_scales": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "fr_pagerank_make": (C.c_int, [C.POINTER(fr_pagerank_desc), C.POINTER(fr_task_ops), C.POINTER(C.c_void_p), C.POINTER(fr_task_profile)]),
     "fr_pagerank_destroy": (C.c_int, [C.c_void_p]),
     "fr_pagerank_info": (C.c_int, [C.c_void_p, C.POINTER(fr_pagerank_info_t)]),
@@ -196,11 +199,16 @@ def fr_chunk_fit(prefix, tile0, budget_ns, launch_cost_ns):
     return out.value
 
 
+def fr_cost_scale_next(scale_ppm, modelled_ns, measured_ns):
+    return lib().fr_cost_scale_next(scale_ppm, modelled_ns, measured_ns)
+
+
 class Context:
     """fr_ctx: one GPU, one stage."""
 
     def __init__(self, device_id=0, cu_count=0, cu_mask=None, mem_available_bytes=1 << 62, guard_ns=0,
-                 launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0, grace_ns=0):
+                 launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0, grace_ns=0,
+                 adapt_costs=0):
         cfg = fr_config()
         cfg.device_id = device_id
         cfg.cu_count = cu_count
@@ -209,7 +217,7 @@ class Context:
         cfg.mem_available_bytes = mem_available_bytes
         cfg.guard_ns, cfg.launch_cost_ns, cfg.max_chunk_ns = guard_ns, launch_cost_ns, max_chunk_ns
         cfg.max_inflight, cfg.event_log_capacity, cfg.time_steps = max_inflight, event_log_capacity, time_steps
-        cfg.grace_ns = grace_ns
+        cfg.grace_ns, cfg.adapt_costs = grace_ns, adapt_costs
         self.handle = C.c_void_p()
         _check(lib().fr_create(C.byref(cfg), C.byref(self.handle)), "fr_create")
         self._keep = []
@@ -256,6 +264,11 @@ class Context:
 
     def fr_event_log_clear(self):
         return _check(lib().fr_event_log_clear(self.handle), "fr_event_log_clear")
+
+    def fr_cost_scales(self):
+        out = (C.c_uint32 * 8)()
+        _check(lib().fr_cost_scales(self.handle, out), "fr_cost_scales")
+        return list(out)
 
 
 class PageRankTask:

@@ -610,6 +610,7 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     std::memset(out, 0, sizeof(*out));
     out->run = p->run; out->segment = p->seg; out->tile0 = p->tile; out->tile1 = p->tile;
     if (!p->inited) return FR_ERR_STATE;
+    out->cost_class = (uint32_t)p->kind_of(p->seg);
     if (p->d.max_runs > 0 && p->run >= (uint32_t)p->d.max_runs) { out->finished = 1; return FR_OK; }
     const int kind = p->kind_of(p->seg);
     const std::vector<uint64_t>& pre = p->prefix[kind];

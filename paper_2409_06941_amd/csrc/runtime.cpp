@@ -29,7 +29,11 @@ struct PendingTiming {
     uint64_t log_seq;        // sequence number of the CHUNK record this timing belongs to
     hipEvent_t begin;
     hipEvent_t end;
+    uint32_t cost_class;     // for cost adaptation: the step's class and the task's own (unscaled) modelled cost
+    uint64_t task_modelled_ns;
 };
+
+constexpr uint32_t kScaleOne = 1000000, kScaleMin = 250000, kScaleMax = 16000000;
 
 struct Task {
     fr_task_ops ops{};
@@ -88,6 +92,7 @@ struct fr_ctx {
     std::vector<hipEvent_t> free_events;
     std::deque<PendingTiming> pending;
     hipEvent_t chain_tail = nullptr;        // end event of the newest step of the bubble being served
+    uint32_t cost_scale[8] = {kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne};
 
     // Overrun detection: the worker records this event behind the last work it enqueued for a bubble;
     // fr_bubble_end asks whether it has completed.  (A stream query is not used: it may report "not ready"
@@ -150,6 +155,7 @@ void resolve_timings(fr_ctx* c, bool wait)
             const uint64_t ns = (uint64_t)((double)ms * 1.0e6 + 0.5);
             if (fr_event* ev = log_at(c, p.log_seq)) ev->measured_ns = ns;
             if (c->task) c->task->prog.ns_measured += ns;
+            if (c->cfg.adapt_costs) c->cost_scale[p.cost_class & 7] = fr_cost_scale_next(c->cost_scale[p.cost_class & 7], p.task_modelled_ns, ns);
         }
         // Steps resolve in order, so nothing older still needs this begin event.  The end event lives on if a
         // later step uses (or may still come to use) it as its begin; that step releases it.
@@ -256,6 +262,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     const uint64_t max_chunk = c->cfg.max_chunk_ns ? c->cfg.max_chunk_ns : ~0ull;
     const uint32_t max_inflight = c->cfg.max_inflight ? c->cfg.max_inflight : 8;
     const bool timed = c->cfg.time_steps && !c->host_only;
+    const bool adapt = timed && c->cfg.adapt_costs;
     int64_t remaining = (int64_t)len - (int64_t)guard;
     const int64_t total = remaining;
     bool used = false, finished = false;
@@ -270,6 +277,24 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         if (rc != FR_OK) { fail = rc; break; }
         if (c->kill_current.load(std::memory_order_acquire)) break;
         if (st.finished) { finished = true; break; }
+        uint64_t scaled = st.modelled_ns;
+        if (adapt && st.modelled_ns) {
+            // plan against the scaled cost: if the step the task offers no longer fits once scaled, ask again
+            // with a budget shrunk by the same factor (plan_step is pure, so asking twice is harmless)
+            uint32_t scale;
+            { std::lock_guard<std::mutex> lk(c->mu); resolve_timings(c, false); scale = c->cost_scale[st.cost_class & 7]; }
+            auto scale_up = [&](uint64_t ns) { return (uint64_t)(((unsigned __int128)ns * scale + kScaleOne - 1) / kScaleOne); };
+            scaled = scale_up(st.modelled_ns);
+            if (scaled + launch > budget) {
+                const uint64_t room = budget > launch ? (uint64_t)(((unsigned __int128)(budget - launch) * kScaleOne) / scale) : 0;
+                c->in_callback.store(now_ns(), std::memory_order_release);
+                rc = t->ops.plan_step(t->user, room + launch, launch, &st);
+                c->in_callback.store(0, std::memory_order_release);
+                if (rc != FR_OK) { fail = rc; break; }
+                scaled = scale_up(st.modelled_ns);
+                if (scaled + launch > budget) st.modelled_ns = 0;       // rounding: treat as "does not fit"
+            }
+        }
         if (st.modelled_ns == 0) {
             // the remaining time is not enough for the next step: leave the rest of the bubble idle
             std::lock_guard<std::mutex> lk(c->mu);
@@ -281,7 +306,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             t->prog.ns_idle_insufficient += ev.modelled_ns;
             break;
         }
-        const uint64_t cost = st.modelled_ns + launch;
+        const uint64_t cost = scaled + launch;
         // real-clock check: the model says the step ends `consumed + cost` after the bubble began; if the
         // host is later than that, the step must still end before the declared end of the bubble
         const uint64_t consumed = (uint64_t)(total - remaining);
@@ -334,7 +359,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             ev.t_host_ns = now;
             const uint64_t lseq = log_push(c, ev);
             if (timed && ev_begin && ev_end) {
-                c->pending.push_back(PendingTiming{lseq, ev_begin, ev_end});
+                c->pending.push_back(PendingTiming{lseq, ev_begin, ev_end, st.cost_class, st.modelled_ns});
                 c->chain_tail = ev_end;
             }
             t->prog.steps++;
@@ -693,6 +718,26 @@ int fr_event_log_clear(fr_ctx* c)
     c->log_first_seq += c->log_count;
     c->log_head = 0;
     c->log_count = 0;
+    return FR_OK;
+}
+
+uint32_t fr_cost_scale_next(uint32_t scale_ppm, uint64_t modelled_ns, uint64_t measured_ns)
+{
+    if (scale_ppm < kScaleMin) scale_ppm = kScaleMin;
+    if (scale_ppm > kScaleMax) scale_ppm = kScaleMax;
+    if (modelled_ns == 0) return scale_ppm;
+    unsigned __int128 r128 = (unsigned __int128)measured_ns * kScaleOne / modelled_ns;
+    uint32_t r = r128 > kScaleMax ? kScaleMax : (uint32_t)r128;
+    if (r < kScaleMin) r = kScaleMin;
+    return r >= scale_ppm ? r : scale_ppm - (scale_ppm - r) / 8;
+}
+
+int fr_cost_scales(fr_ctx* c, uint32_t* out)
+{
+    if (!c || !out) return FR_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (!c->host_only) resolve_timings(c, false);
+    for (int i = 0; i < 8; ++i) out[i] = c->cost_scale[i];
     return FR_OK;
 }
 

@@ -198,3 +198,48 @@ def test_framework_enforced_limit_stops_a_task_whose_gpu_work_outlives_the_grace
         ctx.fr_task_stop(tid)
     task.fr_pagerank_destroy()
     ctx.fr_destroy()
+
+
+def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheaper_than_they_are():
+    # The task's own model is set to 40 % of the measured step times.  With the frozen model the steps planned for
+    # the end of a bubble run past it again and again; with adapt_costs the measured / modelled ratio of the first
+    # steps scales the model up and the later epochs see no overrun.  The ranks keep the standalone run's bits.
+    g = graphs.rmat_csr(21, 1 << 25, seed=9)
+    V, E, K = g.n_vertices, g.n_edges, 20
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ref = torch.zeros(V, dtype=torch.float32, device="cuda")
+    probe = fr.PageRankTask(V, E, rp, col, od, ref, iterations=K)
+    probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
+    info = probe.fr_pagerank_info()
+    probe.fr_pagerank_destroy()
+    low = 0.4
+    model = dict(fs_per_vertex=max(1, int(low * ph[0] * 1e6 / V)), fs_per_message=max(1, int(low * ph[1] / K * 1e6 / info.messages)),
+                 fs_per_edge=max(1, int(low * ph[2] / K * 1e6 / E)), hubfin_tile_ns=1000)
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 1_000_000, 2_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    late = {}
+    for adapt in (0, 1):
+        ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+        ctx = fr.Context(device_id=0, guard_ns=20_000, launch_cost_ns=5_000, time_steps=1, adapt_costs=adapt)
+        task = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K, max_runs=0, **model)
+        tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+        assert _init_bubble(ctx, tid) == fr.FR_OK
+        stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+        stage.fr_stage_run_epoch(ctx)                    # the running profiler learns here
+        late[adapt] = sum(stage.fr_stage_run_epoch(ctx).overruns for _ in range(3))
+        scales = ctx.fr_cost_scales()
+        pr = ctx.fr_query_progress(tid)
+        ctx.fr_task_stop(tid)
+        got = ranks.cpu().numpy()
+        task.fr_pagerank_destroy(); stage.fr_stage_destroy(); ctx.fr_destroy()
+        print("adapt", adapt, "overruns in epochs 2-4:", late[adapt], "scales", scales[:4], "runs", pr.runs_completed, flush=True)
+        assert pr.runs_completed >= 1
+        assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+        if adapt:
+            assert all(1_500_000 <= s <= 8_000_000 for s in scales[1:3]), scales      # scatter and gather: about 1 / 0.4
+        else:
+            assert scales == [1_000_000] * 8
+    load.fr_load_destroy()
+    assert late[0] > 0 and late[1] == 0, late

@@ -406,3 +406,19 @@ def test_framework_enforced_limit_covers_initialisation():
     pr = c.fr_query_progress(tid)
     c.fr_destroy()
     assert pr.state == fr.FR_STOPPED and pr.last_error == fr.FR_ERR_OVERRUN and pr.killed == 1
+
+
+def test_cost_scale_update_rule():
+    # rises at once, falls by an eighth of the gap per step, stays within [0.25, 16], ignores steps without a model
+    nxt = fr.binding.fr_cost_scale_next
+    assert nxt(1_000_000, 100, 250) == 2_500_000
+    assert nxt(2_500_000, 100, 100) == 2_500_000 - 1_500_000 // 8 == 2_312_500
+    assert nxt(1_000_000, 100, 1) == 1_000_000 - 750_000 // 8
+    assert nxt(1_000_000, 0, 5) == 1_000_000
+    assert nxt(1_000_000, 1, 10**9) == 16_000_000
+    assert nxt(10, 100, 100) == 1_000_000                   # an out-of-range scale is clamped first
+    s, seen = 4_000_000, []
+    for _ in range(200):                                    # constant ratio 1.3: monotone decay towards it, never below
+        s = nxt(s, 1000, 1300)
+        seen.append(s)
+    assert all(a >= b for a, b in zip(seen, seen[1:])) and 1_300_000 <= seen[-1] <= 1_300_010
