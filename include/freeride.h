@@ -81,7 +81,7 @@ typedef struct fr_config {
     uint32_t time_steps;           /* nonzero: bracket every step with HIP events and report measured GPU ns */
     uint32_t adapt_costs;          /* nonzero: the profiler keeps running (Section 4.3): every measured step updates a
                                       cost scale for its cost class (measured / modelled, taken at once when it
-                                      rises, eased by 1/8 per step when it falls) and steps are planned against the
+                                      rises, up to a doubling, and eased by 1/8 per step when it falls) and steps are planned against the
                                       scaled costs.  The plan then depends on measurements and no longer matches a
                                       plan computed ahead of time.  Needs time_steps.                          */
     uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
@@ -229,8 +229,8 @@ int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint6
  * Cost adaptation (fr_config.adapt_costs).  Scales are parts per million of the task's own modelled cost,
  * 1000000 at the start, kept within [250000, 16000000].
  * fr_cost_scale_next: the update rule as a pure function: with r = measured_ns / modelled_ns (in ppm, clamped to
- *   the range above; the old scale if modelled_ns is 0) the new scale is r if r >= scale_ppm, else
- *   scale_ppm - (scale_ppm - r) / 8.
+ *   the range above; the old scale if modelled_ns is 0) the new scale is min(r, 2 * scale_ppm) if
+ *   r >= scale_ppm, else scale_ppm - (scale_ppm - r) / 8.
  * fr_cost_scales: the context's eight current scales (host array of 8).
  */
 uint32_t fr_cost_scale_next(uint32_t scale_ppm, uint64_t modelled_ns, uint64_t measured_ns);
@@ -283,6 +283,11 @@ typedef struct fr_pagerank_desc {
        as long as one tile alone (the tiles run side by side), so the modelled cost of a step is
        max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.                   */
     uint64_t min_step_ns[4];
+    /* Partition sizes of the layout: destination rows per gather tile (8192 or 16384) and source vertices per
+       scatter tile (16384 or 32768); 0 = chosen by the library (the small pair below 2^24 vertices, the large pair
+       from there on).  Other values: FR_ERR_ARG at InitSideTask.                                                */
+    uint32_t rows_per_partition;
+    uint32_t sources_per_partition;
 } fr_pagerank_desc;
 
 /* Facts about the layout built by InitSideTask. */
@@ -293,6 +298,8 @@ typedef struct fr_pagerank_info_t {
     uint32_t hubs;                /* rows with more than hub_split in-edges                                 */
     uint32_t virtual_rows;        /* pieces the hubs' in-edges were dealt out to                            */
     uint32_t hub_split;
+    uint32_t rows_per_partition;  /* destination rows per gather tile                                       */
+    uint32_t sources_per_partition; /* source vertices per scatter tile                                     */
     uint32_t reserved;
     uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
     uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */

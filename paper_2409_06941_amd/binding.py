@@ -70,13 +70,15 @@ class fr_pagerank_desc(C.Structure):
                 ("out_degree", C.c_void_p), ("ranks_out", C.c_void_p), ("damping", C.c_float), ("iterations", C.c_int32),
                 ("max_runs", C.c_int32), ("reserved", C.c_int32), ("mem_limit_bytes", C.c_uint64),
                 ("fs_per_edge", C.c_uint64), ("fs_per_message", C.c_uint64), ("fs_per_vertex", C.c_uint64),
-                ("hubfin_tile_ns", C.c_uint64), ("min_step_ns", C.c_uint64 * 4)]
+                ("hubfin_tile_ns", C.c_uint64), ("min_step_ns", C.c_uint64 * 4),
+                ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32)]
 
 
 class fr_pagerank_info_t(C.Structure):
     _fields_ = [("messages", C.c_uint64), ("partitions", C.c_uint32), ("source_partitions", C.c_uint32),
                 ("hubs", C.c_uint32), ("virtual_rows", C.c_uint32), ("hub_split", C.c_uint32),
-                ("reserved", C.c_uint32), ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
+                ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32), ("reserved", C.c_uint32),
+                ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
 
 
 class fr_load_desc(C.Structure):
@@ -276,7 +278,7 @@ class PageRankTask:
 
     def __init__(self, n_vertices, n_edges, row_ptr, col, out_degree, ranks_out, damping=0.85, iterations=30,
                  max_runs=0, mem_limit_bytes=1 << 40, fs_per_edge=0, fs_per_message=0, fs_per_vertex=0,
-                 hubfin_tile_ns=0, min_step_ns=(0, 0, 0, 0)):
+                 hubfin_tile_ns=0, min_step_ns=(0, 0, 0, 0), rows_per_partition=0, sources_per_partition=0):
         d = fr_pagerank_desc()
         d.n_vertices, d.n_edges = n_vertices, n_edges
         d.row_ptr, d.col, d.out_degree, d.ranks_out = _ptr(row_ptr), _ptr(col), _ptr(out_degree), _ptr(ranks_out)
@@ -286,6 +288,7 @@ class PageRankTask:
         d.hubfin_tile_ns = hubfin_tile_ns
         for k in range(4):
             d.min_step_ns[k] = int(min_step_ns[k])
+        d.rows_per_partition, d.sources_per_partition = rows_per_partition, sources_per_partition
         self.desc = d
         self._keep = (row_ptr, col, out_degree, ranks_out)
         self.ops = fr_task_ops()

@@ -106,6 +106,7 @@ struct DevArgs {
     int64_t V, E;
     uint32_t M, Q, P, n_hubs, n_vrows, n_dpart;
     uint32_t scatter_shape;       // lanes per bin x messages per lane in the scatter sweep (kShape_*)
+    uint32_t rows_per_part, src_per_part;
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
@@ -128,10 +129,10 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
 {
     __shared__ float red[8];
     const uint32_t q = tile0 + blockIdx.x;
-    const int64_t v0 = (int64_t)q * kRowsPerPart;
+    const int64_t v0 = (int64_t)q * A.rows_per_part;
     const float r0 = 1.0f / (float)A.V;
     float dangling = 0.0f;
-    for (uint32_t i = threadIdx.x; i < kRowsPerPart; i += kBlock) {
+    for (uint32_t i = threadIdx.x; i < A.rows_per_part; i += kBlock) {
         const int64_t v = v0 + i;
         if (v >= A.V) break;
         if (final_pass) A.ranks_out[v] = r0;
@@ -219,6 +220,7 @@ __device__ __forceinline__ void scatter_bins(const uint16_t* __restrict__ src16,
 }
 
 // `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
+template <uint32_t kSrcPerPart>
 __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
@@ -282,7 +284,6 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
 }
 
 // ---- G_k ----
-constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
 
 // One workgroup per destination partition; its accumulators (one u64 per row, plus the spare slots for hubs'
 // virtual rows) sit in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
@@ -292,8 +293,10 @@ constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
 //      to; the messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
 //   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
 //      accumulator with an LDS atomic.
+template <uint32_t kRowsPerPart>
 __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
 {
+    constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
     __shared__ unsigned long long acc[kAccSlots];
     __shared__ float red[32];
     const uint32_t q = tile0 + blockIdx.x;
@@ -499,7 +502,7 @@ struct PrTask {
     }
     uint64_t rows_of_q(uint32_t q) const
     {
-        return std::min<uint64_t>(kRowsPerPart, (uint64_t)L.V - (uint64_t)q * kRowsPerPart);
+        return std::min<uint64_t>(L.rows_per_part, (uint64_t)L.V - (uint64_t)q * L.rows_per_part);
     }
 };
 
@@ -513,7 +516,7 @@ void build_cost_tables(PrTask* p)
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
     s.assign(L.P + 1, 0);
     for (uint32_t i = 0; i < L.P; ++i) {
-        const uint64_t srcs = std::min<uint64_t>(kSrcPerPart, (uint64_t)L.V - (uint64_t)i * kSrcPerPart);
+        const uint64_t srcs = std::min<uint64_t>(L.src_per_part, (uint64_t)L.V - (uint64_t)i * L.src_per_part);
         s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.msgs_of_p[i] * pm + (unsigned __int128)srcs * pv);
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
@@ -538,10 +541,19 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
         hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, tile0, (int)((K - 1) & 1u), 1);
     } else {
         const uint32_t k = (g - 1) / 2;
-        if (kind == FR_PR_SEG_SCATTER)      // S_k finishes the hubs of r_k with D_{k-1}: set (k-1) & 1
-            hipLaunchKernelGGL(k_scatter, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, (int)((k + 1) & 1u), k == 0 ? 1 : 0);
-        else
-            hipLaunchKernelGGL(k_gather, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, (int)(k & 1u), (k + 1 == K) ? 1 : 0);
+        if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes the hubs of r_k with D_{k-1}: set (k-1) & 1
+            const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
+            if (p->L.src_per_part == kSrcLarge)
+                hipLaunchKernelGGL(k_scatter<kSrcLarge>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, parity, first);
+            else
+                hipLaunchKernelGGL(k_scatter<kSrcSmall>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, parity, first);
+        } else {
+            const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
+            if (p->L.rows_per_part == kRowsLarge)
+                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
+            else
+                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
+        }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
@@ -576,7 +588,8 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     // caller-provided buffers count against the task's limit: row_ptr, col, out_degree, ranks_out
     const uint64_t caller = 4ull * (uint64_t)(V + 1) + 4ull * (uint64_t)E + 4ull * (uint64_t)V + 4ull * (uint64_t)V;
     if (fr_alloc_charge(a, caller) != FR_OK) return FR_ERR_OOM;
-    int rc = pr_build_layout(&p->L, V, E, p->d.row_ptr, p->d.col, p->d.out_degree, a, stream, &p->hip_error);
+    int rc = pr_build_layout(&p->L, V, E, p->d.row_ptr, p->d.col, p->d.out_degree, p->d.rows_per_partition,
+                             p->d.sources_per_partition, a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
     p->n_dpart = L.Q + L.P;                  // one slot per gather tile, one per scatter tile (its hubs)
@@ -587,6 +600,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.P = L.P; A.n_hubs = L.n_hubs; A.n_vrows = L.n_vrows;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.scatter_shape = scatter_shape_for(L.M, (uint64_t)L.P * L.Q);
+    A.rows_per_part = L.rows_per_part; A.src_per_part = L.src_per_part;
     A.ids16 = L.ids16; A.src16 = L.src16; A.eoff = L.eoff; A.mbase = L.mbase; A.bins = L.bins;
     A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.hub_of_p = L.hub_of_p; A.inv_tag = L.inv_tag;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.vacc = p->vacc; A.ranks_out = p->d.ranks_out;
@@ -704,6 +718,8 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out)
     out->messages = p->L.M;
     out->partitions = p->L.Q;
     out->hub_split = p->L.hub_split;
+    out->rows_per_partition = p->L.rows_per_part;
+    out->sources_per_partition = p->L.src_per_part;
     out->source_partitions = p->L.P;
     out->hubs = p->L.n_hubs;
     out->virtual_rows = p->L.n_vrows;

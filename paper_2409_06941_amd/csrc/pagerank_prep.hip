@@ -93,10 +93,10 @@ __global__ __launch_bounds__(kBlk) void k_inv_tag(int64_t V, uint32_t split, con
     inv_tag[v] = inv;
 }
 
-// Virtual row hv of a hub goes to partition hv % Q, accumulator slot kRowsPerPart + hv / Q.
+// Virtual row hv of a hub goes to partition hv % Q, accumulator slot rows_per_part + hv / Q.
 __global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, uint32_t split, const int32_t* __restrict__ row_ptr,
                                                const int32_t* __restrict__ col, const uint64_t* __restrict__ scanned,
-                                               uint32_t Q, uint64_t* __restrict__ keys)
+                                               uint32_t Q, uint32_t rows_per_part, uint64_t* __restrict__ keys)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= E) return;
@@ -107,10 +107,10 @@ __global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, uint32_t sp
     if (indeg > split) {
         const uint64_t hv = (scanned[v] >> 32) + (uint64_t)(e - begin) / split;
         q = hv % Q;
-        local = kRowsPerPart + hv / Q;
+        local = rows_per_part + hv / Q;
     } else {
-        q = (uint64_t)v / kRowsPerPart;
-        local = (uint64_t)v % kRowsPerPart;
+        q = (uint64_t)v / rows_per_part;
+        local = (uint64_t)v % rows_per_part;
     }
     keys[e] = (q << (kKeyLocalBits + kKeySrcBits)) | ((uint64_t)(uint32_t)col[e] << kKeyLocalBits) | local;
 }
@@ -136,7 +136,7 @@ __device__ __forceinline__ int64_t id_slot(int64_t e)
 }
 
 __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
-                                               const uint32_t* __restrict__ incl,
+                                               const uint32_t* __restrict__ incl, uint32_t src_per_part,
                                                uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64
     if (f) {
         const uint64_t m = (uint64_t)incl[e] - 1;
         const uint32_t u = (uint32_t)((k >> kKeyLocalBits) & 0x7fffffffu);
-        if (m < M) src16[m] = (uint16_t)(u % kSrcPerPart);
+        if (m < M) src16[m] = (uint16_t)(u % src_per_part);
     }
 }
 
@@ -181,15 +181,16 @@ __global__ __launch_bounds__(kBlk) void k_eoff(uint32_t Q, int64_t E, const uint
 
 // bins[p * Q + q] = message range of the edges of partition q whose source lies in source partition p.
 // The first edge of a bin always starts a message, so "messages before it" = incl - 1 there.
-__global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E, uint32_t M, const uint64_t* __restrict__ keys,
-                                               const uint32_t* __restrict__ incl, uint2* __restrict__ bins)
+__global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E, uint32_t M, uint64_t src_per_part,
+                                               const uint64_t* __restrict__ keys, const uint32_t* __restrict__ incl,
+                                               uint2* __restrict__ bins)
 {
     const uint64_t idx = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
     if (idx >= (uint64_t)P * Q) return;
     const uint64_t p = idx / Q, q = idx % Q;
     const uint64_t base = q << (kKeyLocalBits + kKeySrcBits);
-    const int64_t lo = lower_bound_key(keys, E, base + ((p * kSrcPerPart) << kKeyLocalBits));
-    const int64_t hi = lower_bound_key(keys, E, base + (((p + 1) * kSrcPerPart) << kKeyLocalBits));
+    const int64_t lo = lower_bound_key(keys, E, base + ((p * src_per_part) << kKeyLocalBits));
+    const int64_t hi = lower_bound_key(keys, E, base + (((p + 1) * src_per_part) << kKeyLocalBits));
     uint2 r;
     r.x = lo < E ? incl[lo] - 1 : M;
     r.y = hi < E ? incl[hi] - 1 : M;
@@ -197,12 +198,13 @@ __global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E
     bins[idx] = r;
 }
 
-// hub_of_p[p] = first hub whose row id is >= p * kSrcPerPart (hub_row is ascending).
-__global__ __launch_bounds__(kBlk) void k_hub_of_p(uint32_t P, uint32_t n_hubs, const int32_t* __restrict__ hub_row, uint32_t* __restrict__ hub_of_p)
+// hub_of_p[p] = first hub whose row id is >= p * src_per_part (hub_row is ascending).
+__global__ __launch_bounds__(kBlk) void k_hub_of_p(uint32_t P, uint32_t n_hubs, uint32_t src_per_part, const int32_t* __restrict__ hub_row,
+                                                   uint32_t* __restrict__ hub_of_p)
 {
     const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
     if (p > P) return;
-    const int64_t target = (int64_t)p * kSrcPerPart;
+    const int64_t target = (int64_t)p * src_per_part;
     uint32_t lo = 0, hi = n_hubs;
     while (lo < hi) {
         const uint32_t mid = (lo + hi) >> 1;
@@ -262,11 +264,17 @@ bool keep(fr_alloc* a, T** out, uint64_t count)
     } while (0)
 
 int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
-                    const int32_t* out_degree, fr_alloc* a, hipStream_t stream, int* hip_error)
+                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, fr_alloc* a,
+                    hipStream_t stream, int* hip_error)
 {
+    if (!rows_per_part) rows_per_part = V >= kLargePartsFrom ? kRowsLarge : kRowsSmall;
+    if (!src_per_part) src_per_part = V >= kLargePartsFrom ? kSrcLarge : kSrcSmall;
+    if ((rows_per_part != kRowsSmall && rows_per_part != kRowsLarge) || (src_per_part != kSrcSmall && src_per_part != kSrcLarge))
+        return FR_ERR_ARG;
     L->V = V; L->E = E;
-    L->Q = (uint32_t)((V + kRowsPerPart - 1) / kRowsPerPart);
-    L->P = (uint32_t)((V + kSrcPerPart - 1) / kSrcPerPart);
+    L->rows_per_part = rows_per_part; L->src_per_part = src_per_part;
+    L->Q = (uint32_t)((V + rows_per_part - 1) / rows_per_part);
+    L->P = (uint32_t)((V + src_per_part - 1) / src_per_part);
     L->n_chunks = (uint32_t)((E + kIdChunk - 1) / kIdChunk);
     const int64_t padded = (int64_t)std::max<uint32_t>(L->n_chunks, 1) * kIdChunk;
     const uint32_t Q = L->Q;
@@ -318,7 +326,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                        L->n_vrows, L->hub_row, L->hub_vbase);
     hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, out_degree, L->inv_tag);
     if (!keep(a, &L->hub_of_p, (uint64_t)L->P + 1)) PREP_NEED((void*)nullptr);
-    hipLaunchKernelGGL(k_hub_of_p, dim3(blocks_for((uint64_t)L->P + 1)), dim3(kBlk), 0, stream, L->P, L->n_hubs, L->hub_row, L->hub_of_p);
+    hipLaunchKernelGGL(k_hub_of_p, dim3(blocks_for((uint64_t)L->P + 1)), dim3(kBlk), 0, stream, L->P, L->n_hubs, src_per_part, L->hub_row, L->hub_of_p);
 
     tmp.drop(packed);
     tmp.drop(scan_tmp);
@@ -331,7 +339,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         uint64_t* keys_a = tmp.take<uint64_t>((uint64_t)E);
         uint64_t* keys_b = tmp.take<uint64_t>((uint64_t)E);
         PREP_NEED(keys_a); PREP_NEED(keys_b);
-        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, keys_a);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, rows_per_part, keys_a);
         unsigned end_bit = kKeyLocalBits + kKeySrcBits;
         while (end_bit < 63 && (1ull << (end_bit - kKeyLocalBits - kKeySrcBits)) < (uint64_t)Q) ++end_bit;
         {
@@ -371,10 +379,10 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     if (!keep(a, &L->src16, (uint64_t)M)) PREP_NEED((void*)nullptr);
 
     hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
-                       L->ids16, L->src16);
+                       src_per_part, L->ids16, L->src16);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, L->eoff);
-    hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->P * Q)), dim3(kBlk), 0, stream, L->P, Q, E, M, keys, incl, L->bins);
+    hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->P * Q)), dim3(kBlk), 0, stream, L->P, Q, E, M, (uint64_t)src_per_part, keys, incl, L->bins);
     uint64_t* mp = tmp.take<uint64_t>(L->P);
     PREP_NEED(mp);
     hipLaunchKernelGGL(k_msgs_of_p, dim3(blocks_for(L->P)), dim3(kBlk), 0, stream, L->P, Q, L->bins, mp);

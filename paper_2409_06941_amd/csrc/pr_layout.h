@@ -5,7 +5,11 @@
 // two streaming sweeps whose random accesses all land in LDS (the two-phase partition-centric idea of Beamer et
 // al., "propagation blocking", 2017, and Lakhotia et al., "PCPM", 2018, rebuilt around CDNA's 160 KB LDS):
 //
-//   * destination rows are cut into partitions of kRowsPerPart rows; sources into partitions of kSrcPerPart;
+//   * destination rows are cut into partitions of rows_per_part rows; sources into partitions of src_per_part
+//     (8192 and 16384, or 16384 and 32768 for graphs of 2^24 vertices and more: the bins of message traffic
+//     between a source and a destination partition hold M * rows_per_part * src_per_part / V^2 messages and must
+//     not get too short to stream; the large sizes leave room for one workgroup per CU only, which costs the
+//     small graphs more than the longer bins gain them);
 //   * all in-edges of one destination partition q are stored together, ordered by source u and then by row;
 //     one MESSAGE is made per distinct (q, u) pair, however many rows of q the source u points to;
 //   * scatter sweep, one workgroup per source partition p: the p-slice of contrib sits in LDS; for every q the
@@ -27,21 +31,16 @@
 
 #include "common.h"
 
-#ifndef FR_ROWS_PER_PART
-#define FR_ROWS_PER_PART 8192
-#endif
-#ifndef FR_SRC_PER_PART
-#define FR_SRC_PER_PART 16384
-#endif
-constexpr uint32_t kRowsPerPart = FR_ROWS_PER_PART;   // destination rows per regular partition (8 B each in LDS)
-constexpr uint32_t kSrcPerPart = FR_SRC_PER_PART;     // source vertices per scatter partition (4 B each in LDS)
+constexpr uint32_t kRowsSmall = 8192, kRowsLarge = 16384;   // destination rows per partition (8 B each in LDS)
+constexpr uint32_t kSrcSmall = 16384, kSrcLarge = 32768;    // source vertices per scatter partition (4 B each in LDS)
+constexpr int64_t kLargePartsFrom = int64_t(1) << 24;       // vertex count from which the large sizes are used
 constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub_split are split into virtual rows
 constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
 constexpr uint32_t kHubsPerTile = 16;        // hubs finished per workgroup (16 lanes each)
 constexpr int kKeyLocalBits = 15;            // sort key = partition << 46 | source << 15 | local row
 constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
-static_assert(kRowsPerPart + kMaxVrowsPerPart <= (1u << kKeyLocalBits) && kSrcPerPart <= 65536, "id fields");
+static_assert(kRowsLarge + kMaxVrowsPerPart <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
 
 struct PrLayout {
@@ -49,6 +48,7 @@ struct PrLayout {
     uint64_t M = 0;                  // messages = distinct (destination partition, source) pairs
     uint32_t Q = 0;                  // destination partitions
     uint32_t P = 0;                  // source partitions
+    uint32_t rows_per_part = kRowsSmall, src_per_part = kSrcSmall;
     uint32_t n_hubs = 0, n_vrows = 0;
     uint32_t hub_split = kHubSplitMin;
     uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
@@ -75,7 +75,9 @@ struct PrLayout {
 };
 
 // Builds the layout on `stream` from the caller's in-edge CSR (device pointers) and waits for it.
+// rows_per_part / src_per_part: 0 = chosen from V, else one of the two sizes above (FR_ERR_ARG otherwise).
 // Temporary memory is taken from and returned to `a`.  Returns FR_OK, FR_ERR_OOM, FR_ERR_HIP or FR_ERR_ARG
 // (malformed CSR).  `hip_error` receives the failing HIP code, if any.
 int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
-                    const int32_t* out_degree, fr_alloc* a, hipStream_t stream, int* hip_error);
+                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, fr_alloc* a,
+                    hipStream_t stream, int* hip_error);

@@ -729,7 +729,8 @@ uint32_t fr_cost_scale_next(uint32_t scale_ppm, uint64_t modelled_ns, uint64_t m
     unsigned __int128 r128 = (unsigned __int128)measured_ns * kScaleOne / modelled_ns;
     uint32_t r = r128 > kScaleMax ? kScaleMax : (uint32_t)r128;
     if (r < kScaleMin) r = kScaleMin;
-    return r >= scale_ppm ? r : scale_ppm - (scale_ppm - r) / 8;
+    if (r >= scale_ppm) return r > 2 * scale_ppm ? 2 * scale_ppm : r;     // one late step at most doubles the scale
+    return scale_ppm - (scale_ppm - r) / 8;
 }
 
 int fr_cost_scales(fr_ctx* c, uint32_t* out)

@@ -238,7 +238,7 @@ def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheape
         assert pr.runs_completed >= 1
         assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
         if adapt:
-            assert all(1_500_000 <= s <= 8_000_000 for s in scales[1:3]), scales      # scatter and gather: about 1 / 0.4
+            assert all(s >= 1_500_000 for s in scales[1:3]), scales      # scatter and gather: about 1 / 0.4, or above
         else:
             assert scales == [1_000_000] * 8
     load.fr_load_destroy()

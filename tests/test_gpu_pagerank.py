@@ -70,6 +70,47 @@ def test_every_scatter_shape(edges, lo, hi):
     _check(g, iterations=7)
 
 
+@pytest.mark.parametrize("rows,srcs", [(8192, 16384), (16384, 16384), (8192, 32768), (16384, 32768)])
+def test_every_partition_size(rows, srcs):
+    # graphs of 2^24 vertices and more get 16384-row gather tiles and 32768-source scatter tiles; here the sizes
+    # are forced on a graph of 100003 vertices (ragged last tiles, hubs present)
+    src, dst = graphs.rmat_edges(17, 1_500_007, seed=21)
+    g = graphs.csr_from_edges(100_003, src % 100_003, dst % 100_003)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=9, rows_per_partition=rows,
+                        sources_per_partition=srcs)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), 3)
+    info = t.fr_pagerank_info()
+    t.fr_pagerank_destroy()
+    assert (info.rows_per_partition, info.sources_per_partition) == (rows, srcs) and info.hubs > 0
+    assert info.partitions == -(-g.n_vertices // rows) and info.source_partitions == -(-g.n_vertices // srcs)
+    got = ranks.cpu().numpy()
+    want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 9)
+    assert np.abs(got.astype(np.float64) - want).max() <= TOL
+    big = want > 1.0 / g.n_vertices
+    assert (np.abs(got[big] - want[big]) / want[big]).max() <= 1e-4
+    # same sizes, one launch per segment: same bits (across sizes the float sum of the dangling mass is grouped
+    # differently, so the last bit may differ)
+    ref = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ref, iterations=9, rows_per_partition=rows,
+                        sources_per_partition=srcs)
+    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), 0)
+    t.fr_pagerank_destroy()
+    assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+
+
+def test_partition_sizes_other_than_the_two_supported_are_refused():
+    g = graphs.rmat_csr(10, 3000, seed=8)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=2, rows_per_partition=4096)
+    with pytest.raises(fr.FreeRideError) as e:
+        t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    assert e.value.code == fr.FR_ERR_ARG
+    t.fr_pagerank_destroy()
+
+
 def test_non_power_of_two_vertices_fixed_outdeg():
     _check(graphs.fixed_outdeg_csr(10_007, 32, seed=3), iterations=20)
 

@@ -409,14 +409,16 @@ def test_framework_enforced_limit_covers_initialisation():
 
 
 def test_cost_scale_update_rule():
-    # rises at once, falls by an eighth of the gap per step, stays within [0.25, 16], ignores steps without a model
+    # rises at once (at most doubling per step), falls by an eighth of the gap per step, stays within [0.25, 16],
+    # ignores steps without a model
     nxt = fr.binding.fr_cost_scale_next
-    assert nxt(1_000_000, 100, 250) == 2_500_000
+    assert nxt(1_000_000, 100, 150) == 1_500_000
+    assert nxt(1_000_000, 100, 250) == 2_000_000 and nxt(2_000_000, 100, 250) == 2_500_000
     assert nxt(2_500_000, 100, 100) == 2_500_000 - 1_500_000 // 8 == 2_312_500
     assert nxt(1_000_000, 100, 1) == 1_000_000 - 750_000 // 8
     assert nxt(1_000_000, 0, 5) == 1_000_000
-    assert nxt(1_000_000, 1, 10**9) == 16_000_000
-    assert nxt(10, 100, 100) == 1_000_000                   # an out-of-range scale is clamped first
+    assert nxt(1_000_000, 1, 10**9) == 2_000_000 and nxt(12_000_000, 1, 10**9) == 16_000_000
+    assert nxt(10, 100, 100) == 500_000                     # an out-of-range scale is clamped (to 0.25) first, then doubles
     s, seen = 4_000_000, []
     for _ in range(200):                                    # constant ratio 1.3: monotone decay towards it, never below
         s = nxt(s, 1000, 1300)
