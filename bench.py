@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
     ap.add_argument("--margin", type=float, default=1.05, help="final model = measured in-bubble step cost x margin")
     ap.add_argument("--guard-ns", type=int, default=100_000)
+    ap.add_argument("--time-steps", type=int, default=8,
+                    help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
     args = ap.parse_args()
@@ -107,7 +109,7 @@ def main():
     ph1 = one.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 1, want_phase_ns=True)
     n_tiles_kind = [one.fr_pagerank_tiles(k) for k in range(4)]
     one.fr_pagerank_destroy()
-    floors = [int(args.derate * ph1[k] / max(1, n_tiles_kind[k])) for k in range(4)]
+    one_tile_ns = [ph1[k] / max(1, n_tiles_kind[k]) for k in range(4)]
     side_probe.fr_destroy()
     M = max(1, info.messages)
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3]      # V0 and H run once per run
@@ -117,13 +119,14 @@ def main():
         pm = max(1, int((s_ns * 1e6 * derate - V * pv) / M))
         pe = max(1, int((g_ns * 1e6 * derate - V * pv) / max(1, E)))
         return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe,
-                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)), min_step_ns=floors)
+                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)),
+                    min_step_ns=[int(derate * x) for x in one_tile_ns])
     log("layout: M/E=%.3f, %d destination partitions, %d source partitions, %d hubs in %d virtual rows, init+first run %.2fs" %
         (info.messages / max(1, E), info.partitions, info.source_partitions, info.hubs, info.virtual_rows, t_init))
     log("standalone per iteration: scatter %.1f us, gather %.1f us (once per run: first vertex pass %.1f us, hub finish %.1f us)" %
         (s_ns / 1e3, g_ns / 1e3, v_ns / 1e3, h_ns / 1e3))
-    log("shortest steps (one tile per launch, x %.2f): vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
-        ((args.derate,) + tuple(x / 1e3 for x in floors)))
+    log("shortest steps (one tile per launch): vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
+        tuple(x / 1e3 for x in one_tile_ns))
     standalone_iter_ns = s_ns + g_ns
 
     # ---- runtime, task, stage
@@ -134,10 +137,10 @@ def main():
     seg_kind = lambda g: (fr.FR_PR_SEG_VERTEX if g == 0 else fr.FR_PR_SEG_HUBFIN if g == n_segs - 1
                           else fr.FR_PR_SEG_SCATTER + ((g - 1) & 1))
 
-    def start_task(launch_cost_ns, model):
+    def start_task(launch_cost_ns, model, time_steps):
         ctx = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0,
                          mem_available_bytes=mem_cap + 1, guard_ns=args.guard_ns, launch_cost_ns=launch_cost_ns,
-                         max_chunk_ns=0, max_inflight=32, time_steps=1, event_log_capacity=1 << 18)
+                         max_chunk_ns=0, max_inflight=32, time_steps=time_steps, event_log_capacity=1 << 18)
         task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
                                mem_limit_bytes=mem_cap, **model)
         tid = ctx.fr_task_register(task.ops, task.user, task.profile)
@@ -150,19 +153,33 @@ def main():
 
     # Second profiling pass, in place: one epoch with the standalone model (generously derated) shows what a
     # step costs inside real bubbles, launch gaps included; the final model is that cost plus a small margin.
-    ctx, task, tid = start_task(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate))
+    ts = max(1, args.time_steps)
+    ctx, task, tid = start_task(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate), ts)
     stage.fr_stage_run_epoch(ctx)
     time.sleep(0.02)
     n_tiles = [task.fr_pagerank_tiles(k) for k in range(4)]
-    prof = [[], [], [], []]
+    # timing groups made of whole sweeps only: measured time against what the standalone profile says they cost
+    ratios, group = [], []
+    standalone = (v_ns, s_ns, g_ns, h_ns)
     for e in ctx.fr_event_log(1 << 18):
-        if e.kind == fr.FR_EV_CHUNK and e.measured_ns > 0 and e.tile0 == 0 and e.tile1 == n_tiles[seg_kind(e.segment)]:
-            prof[seg_kind(e.segment)].append(e.measured_ns)
+        if e.kind != fr.FR_EV_CHUNK:
+            group = []
+            continue
+        if group and group[-1].bubble != e.bubble:
+            group = []
+        group.append(e)
+        if e.measured_ns > 0:
+            if all(x.tile0 == 0 and x.tile1 == n_tiles[seg_kind(x.segment)] for x in group) and \
+               all(seg_kind(x.segment) in (fr.FR_PR_SEG_SCATTER, fr.FR_PR_SEG_GATHER) for x in group) and len(group) == ts:
+                ratios.append(e.measured_ns / sum(standalone[seg_kind(x.segment)] for x in group))
+            group = []
     ctx.fr_task_stop(tid); task.fr_pagerank_destroy(); ctx.fr_destroy()
-    insitu = [statistics.median(p) if p else x for p, x in zip(prof, (v_ns, s_ns, g_ns, h_ns))]
-    log("in-bubble step times: vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
-        tuple(x / 1e3 for x in insitu))
-    ctx, task, tid = start_task(1_000, rates(*insitu, args.margin))
+    in_bubble = statistics.median(ratios) if ratios else args.derate
+    insitu = [x * in_bubble for x in standalone]
+    log("in-bubble step times = standalone x %.3f (%d timing groups of %d whole sweeps): scatter %.1f us, gather %.1f us" %
+        (in_bubble, len(ratios), ts, insitu[1] / 1e3, insitu[2] / 1e3))
+    one_tile_ns = [x * in_bubble for x in one_tile_ns]
+    ctx, task, tid = start_task(1_000, rates(*insitu, args.margin), ts)
     def epochs(n, with_task):
         out = []
         for _ in range(n):
@@ -172,6 +189,7 @@ def main():
     epochs(max(1, args.warmup), True)            # includes the bubble that initialises the task
     torch.cuda.synchronize()
     base_a = epochs((args.steps + 1) // 2, False)
+    epochs(1, True)                              # untimed: the side task's first bubbles after a pause run ~6 % slower
     ctx.fr_event_log_clear()
     p0 = ctx.fr_query_progress(tid)
     torch.cuda.synchronize()
@@ -200,14 +218,24 @@ def main():
     bubble_ns = sum(r.bubble_ns for r in with_task)
     chunk_ns = sum(e.measured_ns for e in events if e.kind == fr.FR_EV_CHUNK)
     idle_ns = sum(e.modelled_ns for e in events if e.kind == fr.FR_EV_IDLE)
-    timed = [e for e in events if e.kind == fr.FR_EV_CHUNK and e.measured_ns > 0]
-    per_kind_ns = [sum(e.measured_ns for e in timed if seg_kind(e.segment) == k) for k in range(4)]
+    # Steps are timed in groups (HIP events on the side stream around every --time-steps consecutive steps of a bubble);
+    # a group's time sits on its last step's record.  Only groups that have resolved count, with all their steps.
+    timed, group = [], []
+    for e in events:
+        if e.kind != fr.FR_EV_CHUNK:
+            continue
+        if group and group[-1].bubble != e.bubble:
+            group = []                               # a group never spans two bubbles
+        group.append(e)
+        if e.measured_ns > 0:
+            timed += group
+            group = []
     per_kind_n = [sum(1 for e in timed if seg_kind(e.segment) == k) for k in range(4)]
     timed_edges = sum(e.work_units for e in timed)
     # One iteration = one scatter + one gather launch and moves 4E + 24V + 4 algorithmic bytes (col entries, row starts, one
     # compulsory read of every contribution, the rank write, and the vertex pass); iterations done = edges / E.
     iters_done = timed_edges / E
-    pull_ns = sum(per_kind_ns)
+    pull_ns = sum(e.measured_ns for e in timed)
     pull_bytes = iters_done * (4.0 * E + 24.0 * V + 4.0)
     pull_gbs = pull_bytes / pull_ns if pull_ns else 0.0
     iter_bytes = 4.0 * E + 24.0 * V + 4.0
@@ -255,9 +283,10 @@ def main():
                      "achieved": pull_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pull_gbs / HBM_PEAK_GBS,
                      "traffic": CFG2_TRAFFIC_BYTES if cfg.name == "cfg2" else None, "iterations": iters_done,
                      "avg_iteration_us": (pull_ns / iters_done / 1e3) if iters_done else None,
-                     "avg_launch_us": {"k_scatter": per_kind_ns[1] / max(1, per_kind_n[1]) / 1e3,
-                                       "k_gather": per_kind_ns[2] / max(1, per_kind_n[2]) / 1e3,
-                                       "k_hubfin": per_kind_ns[3] / max(1, per_kind_n[3]) / 1e3},
+                     "timing": "HIP events on the side stream around groups of %d steps, all inside the timed epochs" % max(1, args.time_steps),
+                     "standalone_launch_us": {"k_scatter": s_ns / 1e3, "k_gather": g_ns / 1e3,
+                                              "note": "whole sweeps outside bubbles, one event pair per launch"},
+                     "in_bubble_over_standalone": in_bubble,
                      "launches": {"k_scatter": per_kind_n[1], "k_gather": per_kind_n[2], "k_hubfin": per_kind_n[3]},
                      "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0},
         "layout": {"messages_per_edge": info.messages / max(1, E), "hubs": info.hubs,

@@ -58,6 +58,7 @@ extern "C" {
 #define FR_EV_CHUNK 2   /* one step (a run of tiles) was enqueued in the bubble                             */
 #define FR_EV_IDLE  3   /* the next step did not fit: rest of the bubble left idle ("insufficient time")    */
 #define FR_EV_MISS  4   /* the step fitted the modelled budget but not the real clock; it was not launched  */
+#define FR_EV_OVERRUN 5 /* fr_bubble_end found side work of the bubble still going on (written by that call) */
 
 typedef struct fr_ctx fr_ctx;
 typedef struct fr_alloc fr_alloc;
@@ -78,7 +79,10 @@ typedef struct fr_config {
     uint64_t max_chunk_ns;         /* upper bound on one step's modelled cost; 0 = unbounded                 */
     uint32_t max_inflight;         /* steps enqueued but not yet finished on the GPU; 0 = default (8)        */
     uint32_t event_log_capacity;   /* records kept (oldest dropped first); 0 = default (65536)               */
-    uint32_t time_steps;           /* nonzero: bracket every step with HIP events and report measured GPU ns */
+    uint32_t time_steps;           /* N > 0: measure GPU time with HIP events around every group of N consecutive
+                                      steps of a bubble (the last group of a bubble may be shorter); the group's time
+                                      is reported on its last step's record.  1 times every step, at the price of
+                                      about 3 us of GPU idle time between steps; 0 = no timing.                 */
     uint32_t adapt_costs;          /* nonzero: the profiler keeps running (Section 4.3): every measured step updates a
                                       cost scale for its cost class (measured / modelled, taken at once when it
                                       rises, up to a doubling, and eased by 1/8 per step when it falls) and steps are planned against the
@@ -208,8 +212,9 @@ typedef struct fr_event {
     uint64_t modelled_ns;   /* CHUNK/MISS: step cost + launch_cost; IDLE: modelled time left; INIT: 0       */
     uint64_t work_units;
     uint64_t t_host_ns;     /* host clock when the record was made                                          */
-    uint64_t measured_ns;   /* CHUNK: GPU time between the previous step's end (or the bubble's first
-                               launch) and this step's end; 0 if not timed or not finished yet              */
+    uint64_t measured_ns;   /* CHUNK, last step of a timing group (every step if time_steps == 1): GPU time of the
+                               group, from the previous group's end (or the bubble's first launch) to this step's
+                               end; 0 on the group's other steps, if not timed, or if not finished yet      */
 } fr_event;
 /* Copies up to `cap` of the oldest retained records in order; *n_out = number copied.  Resolves finished
    step timings first.  Does not consume the log; fr_event_log_clear does. */

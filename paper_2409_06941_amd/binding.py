@@ -8,7 +8,7 @@ LIB_PATH = _build.LIB
 
 FR_OK, FR_ERR_ARG, FR_ERR_STATE, FR_ERR_NOMEM, FR_ERR_OOM, FR_ERR_OVERRUN, FR_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 FR_SUBMITTED, FR_CREATED, FR_PAUSED, FR_RUNNING, FR_STOPPED = range(5)
-FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS = 1, 2, 3, 4
+FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS, FR_EV_OVERRUN = 1, 2, 3, 4, 5
 FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_HUBFIN = 0, 1, 2, 3
 FR_LOAD_BUSYWAIT, FR_LOAD_GPT = 0, 1
 FR_SCHED_1F1B, FR_SCHED_GPIPE = 0, 1

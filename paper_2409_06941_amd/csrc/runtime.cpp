@@ -23,14 +23,16 @@ inline void cpu_relax()
     __builtin_ia32_pause();
 }
 
-// A step's GPU time is measured between two events.  Inside a bubble the steps form a chain: the end event
-// of one step is the begin event of the next, so the measured times add up to the chain's span.
+// GPU time is measured between two events around a group of consecutive steps (time_steps steps per group; an
+// event between two kernels costs about 3 us of GPU idle time, so timing every step is for profiling passes).
+// Inside a bubble the groups form a chain: the end event of one group is the begin event of the next, so the
+// measured times add up to the chain's span.
 struct PendingTiming {
-    uint64_t log_seq;        // sequence number of the CHUNK record this timing belongs to
+    uint64_t log_seq;        // sequence number of the group's last CHUNK record, which receives the measured time
     hipEvent_t begin;
     hipEvent_t end;
-    uint32_t cost_class;     // for cost adaptation: the step's class and the task's own (unscaled) modelled cost
-    uint64_t task_modelled_ns;
+    uint32_t class_mask;     // for cost adaptation: the cost classes in the group and the task's own (unscaled)
+    uint64_t task_modelled_ns;   // modelled cost of its steps
 };
 
 constexpr uint32_t kScaleOne = 1000000, kScaleMin = 250000, kScaleMax = 16000000;
@@ -155,7 +157,9 @@ void resolve_timings(fr_ctx* c, bool wait)
             const uint64_t ns = (uint64_t)((double)ms * 1.0e6 + 0.5);
             if (fr_event* ev = log_at(c, p.log_seq)) ev->measured_ns = ns;
             if (c->task) c->task->prog.ns_measured += ns;
-            if (c->cfg.adapt_costs) c->cost_scale[p.cost_class & 7] = fr_cost_scale_next(c->cost_scale[p.cost_class & 7], p.task_modelled_ns, ns);
+            if (c->cfg.adapt_costs)
+                for (int k = 0; k < 8; ++k)
+                    if ((p.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], p.task_modelled_ns, ns);
         }
         // Steps resolve in order, so nothing older still needs this begin event.  The end event lives on if a
         // later step uses (or may still come to use) it as its begin; that step releases it.
@@ -267,6 +271,22 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     const int64_t total = remaining;
     bool used = false, finished = false;
     int fail = FR_OK;
+    // the group of steps being timed together
+    const uint32_t group_size = c->cfg.time_steps ? c->cfg.time_steps : 1;
+    uint32_t group_n = 0, group_mask = 0;
+    uint64_t group_modelled = 0, group_last_seq = 0;
+    hipEvent_t group_begin = nullptr;
+    auto close_group = [&]() {
+        // an end event behind the group's last step; the interval goes to that step's record
+        hipEvent_t ev_end;
+        { std::lock_guard<std::mutex> lk(c->mu); ev_end = event_get(c); }
+        if (ev_end && group_begin && hipEventRecord(ev_end, c->side) == hipSuccess) {
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->pending.push_back(PendingTiming{group_last_seq, group_begin, ev_end, group_mask, group_modelled});
+            c->chain_tail = ev_end;
+        }
+        group_n = 0; group_mask = 0; group_modelled = 0; group_begin = nullptr;
+    };
 
     while (!stop_now()) {
         const uint64_t budget = remaining > 0 ? ((uint64_t)remaining < max_chunk ? (uint64_t)remaining : max_chunk) : 0;
@@ -338,41 +358,42 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             }
             if (left) break;
         }
-        hipEvent_t ev_begin = nullptr, ev_end = nullptr;
-        bool chain_head = false;
-        if (timed) {
-            std::lock_guard<std::mutex> lk(c->mu);
-            if (c->chain_tail) ev_begin = c->chain_tail;
-            else { ev_begin = event_get(c); chain_head = true; }
-            ev_end = event_get(c);
+        if (timed && group_n == 0) {
+            // a new group begins where the previous one ended, or, at the head of the chain, at an event of its own
+            bool chain_head = false;
+            {
+                std::lock_guard<std::mutex> lk(c->mu);
+                if (c->chain_tail) group_begin = c->chain_tail;
+                else { group_begin = event_get(c); chain_head = true; }
+            }
+            if (chain_head && group_begin) (void)hipEventRecord(group_begin, c->side);
         }
-        if (timed && chain_head && ev_begin) (void)hipEventRecord(ev_begin, c->side);
         c->in_callback.store(now_ns(), std::memory_order_release);
         rc = t->ops.run_step(t->user, (void*)c->side, &st);
         c->in_callback.store(0, std::memory_order_release);
-        if (timed && ev_end) (void)hipEventRecord(ev_end, c->side);
         {
             std::lock_guard<std::mutex> lk(c->mu);
             fr_event ev{};
             ev.kind = FR_EV_CHUNK; ev.bubble = index; ev.run = st.run; ev.segment = st.segment;
             ev.tile0 = st.tile0; ev.tile1 = st.tile1; ev.modelled_ns = cost; ev.work_units = st.work_units;
             ev.t_host_ns = now;
-            const uint64_t lseq = log_push(c, ev);
-            if (timed && ev_begin && ev_end) {
-                c->pending.push_back(PendingTiming{lseq, ev_begin, ev_end, st.cost_class, st.modelled_ns});
-                c->chain_tail = ev_end;
-            }
+            group_last_seq = log_push(c, ev);
             t->prog.steps++;
             t->prog.work_units_done += st.work_units;
             t->prog.ns_modelled += cost;
             if (st.completes_run) t->prog.runs_completed++;
             if (!used) { used = true; t->prog.bubbles_used++; }
         }
+        if (timed) {
+            group_n++; group_mask |= 1u << (st.cost_class & 7); group_modelled += st.modelled_ns;
+            if (group_n >= group_size) close_group();
+        }
         if (rc != FR_OK) { fail = rc; break; }
         if (c->kill_current.load(std::memory_order_acquire)) break;
         remaining -= (int64_t)cost;
     }
     (void)seq;
+    if (timed && group_n) close_group();
     if (used && !c->host_only && c->tail_event) c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->chain_tail) {
@@ -423,6 +444,15 @@ void worker_main(fr_ctx* c)
         }
         c->ack_seq.store(seq, std::memory_order_release);
     }
+}
+
+// ctx->mu held; stage thread, the bubble in question is the one being closed.
+void note_overrun(fr_ctx* c)
+{
+    if (c->task) c->task->prog.overruns++;
+    fr_event ev{};
+    ev.kind = FR_EV_OVERRUN; ev.bubble = c->cur_index; ev.t_host_ns = now_ns();
+    log_push(c, ev);
 }
 
 // How long fr_bubble_end waits for a step callback that is still running after the bubble's end.
@@ -664,7 +694,7 @@ int fr_bubble_end(fr_ctx* c)
                 c->enforce_deadline = now + c->cfg.grace_ns;
             }
             std::lock_guard<std::mutex> lk(c->mu);
-            if (c->task) c->task->prog.overruns++;
+            note_overrun(c);
             return FR_ERR_OVERRUN;
         }
         cpu_relax();
@@ -678,7 +708,7 @@ int fr_bubble_end(fr_ctx* c)
             c->enforce_deadline = now_ns() + c->cfg.grace_ns;
         }
         std::lock_guard<std::mutex> lk(c->mu);
-        if (c->task) c->task->prog.overruns++;
+        note_overrun(c);
         return FR_ERR_OVERRUN;
     }
     if (q != hipSuccess) { c->hip_error = (int)q; return FR_ERR_HIP; }

@@ -11,7 +11,7 @@ from oracle import planner, schedule       # noqa: E402
 from oracle.pagerank import pagerank       # noqa: E402
 from workloads import configs, graphs      # noqa: E402
 
-NAMES = {fr.FR_EV_INIT: "INIT", fr.FR_EV_CHUNK: "CHUNK", fr.FR_EV_IDLE: "IDLE", fr.FR_EV_MISS: "MISS"}
+NAMES = {fr.FR_EV_INIT: "INIT", fr.FR_EV_CHUNK: "CHUNK", fr.FR_EV_IDLE: "IDLE", fr.FR_EV_MISS: "MISS", fr.FR_EV_OVERRUN: "OVERRUN"}
 
 
 def _dev(a, dtype):

@@ -84,7 +84,7 @@ def _bubble(ctx, length_ns, hold_s=0.004):
 
 
 def _log(ctx):
-    names = {fr.FR_EV_INIT: "INIT", fr.FR_EV_CHUNK: "CHUNK", fr.FR_EV_IDLE: "IDLE", fr.FR_EV_MISS: "MISS"}
+    names = {fr.FR_EV_INIT: "INIT", fr.FR_EV_CHUNK: "CHUNK", fr.FR_EV_IDLE: "IDLE", fr.FR_EV_MISS: "MISS", fr.FR_EV_OVERRUN: "OVERRUN"}
     return [(names[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in ctx.fr_event_log()]
 
 
