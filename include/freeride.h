@@ -178,7 +178,7 @@ uint64_t fr_alloc_peak(const fr_alloc* a);   /* highest value fr_alloc_used has 
  *   it is initialised in this bubble; if PAUSED it is started and steps are planned against
  *   duration_ns - guard_ns.  FR_ERR_STATE if a bubble is already open.
  * fr_bubble_end: PauseSideTask().  Returns once the worker has stopped enqueuing.  FR_ERR_OVERRUN (also
- *   counted) if side work is still in flight on the GPU at that moment, or if InitSideTask or a step callback is
+ *   counted) if side work is still in flight on the GPU (and stays so for 20 us), or if InitSideTask or a step callback is
  *   still running (the call does not wait for InitSideTask at all and for a step callback only 0.2 ms past the
  *   bubble's declared end; bubbles that open before it returns are seen but not used).  With grace_ns set, work
  *   that is still going on grace_ns later gets the task stopped.  FR_ERR_STATE if no bubble is open.

@@ -38,10 +38,6 @@ namespace {
 constexpr int kBlock = 512;                     // threads per workgroup of the first vertex pass
 constexpr int kGatherBlock = FR_GATHER_BLOCK;   // threads per workgroup of the gather sweep
 constexpr int kGatherWaves = kGatherBlock / 64;
-#ifndef FR_GATHER_UNROLL
-#define FR_GATHER_UNROLL 1
-#endif
-constexpr int kGatherUnroll = FR_GATHER_UNROLL;  // chunks per wavefront per pipeline stage
 constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the scatter sweep
 constexpr int kScatterWaves = kScatterBlock / 64;
 constexpr float kFixScale = 4611686018427387904.0f;        // 2^62: contrib sums are <= 1, so they fit u64
@@ -285,6 +281,22 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
 
 // ---- G_k ----
 
+// floor(x * 2^62) for 0 <= x <= 1, exactly: x * 2^30 is exact, its integer part is the high word, its
+// fraction times 2^32 (exact again, then truncated) the low word.
+__device__ __forceinline__ unsigned long long to_fixed(float x)
+{
+    const float t = x * 1073741824.0f;
+    const uint32_t hi = (uint32_t)t;
+    const uint32_t lo = (uint32_t)(__builtin_amdgcn_fractf(t) * 4294967296.0f);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
+{
+    const uint32_t w = (j >> 1) == 0 ? raw.x : (j >> 1) == 1 ? raw.y : (j >> 1) == 2 ? raw.z : raw.w;
+    return (j & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
 // One workgroup per destination partition; its accumulators (one u64 per row, plus the spare slots for hubs'
 // virtual rows) sit in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
 // three-stage software pipeline over the wavefront's chunks, so that no step waits on a load it has just issued:
@@ -293,102 +305,111 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
 //      to; the messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
 //   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
 //      accumulator with an LDS atomic.
+// The sweep is bound by vector instruction issue, not by memory (about 30 instructions per 64 edges when every id
+// is checked), so chunks that lie wholly inside the partition's edge range and whose messages cannot pass the end
+// of the message array - all but the first and last chunk of a partition - take a path without per-id checks:
+// ids out of range (which a sound layout never holds) are sent to a sink slot behind the accumulators.
 template <uint32_t kRowsPerPart>
 __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
 {
     constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
-    __shared__ unsigned long long acc[kAccSlots];
+    __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[32];
     const uint32_t q = tile0 + blockIdx.x;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
-    for (uint32_t i = threadIdx.x; i < kAccSlots; i += kGatherBlock) acc[i] = 0ull;
+    for (uint32_t i = threadIdx.x; i < kAccSlots + 1; i += kGatherBlock) acc[i] = 0ull;
     const float d_part = dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     __syncthreads();
 
     const uint32_t e0 = A.eoff[q], e1 = A.eoff[q + 1];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (e1 > e0) {
-        constexpr int U = kGatherUnroll;         // chunks a wavefront has in each pipeline stage
         const uint32_t c0 = e0 / kIdChunk, c1 = (e1 - 1) / kIdChunk;
         const uint4* ids4 = reinterpret_cast<const uint4*>(A.ids16);
-        uint32_t cA[U];                          // chunks whose ids are in rawA
-        uint4 rawA[U];
-        uint32_t mbA[U];
-        uint4 rawP[U];                           // chunks waiting for stage C
-        float valP[U][8];
-        uint32_t okP[U];
+        // stage A's result: chunk cA, its ids and the number of messages begun before it
+        uint32_t cA = c0 + wave;
+        uint4 rawA = make_uint4(0, 0, 0, 0);
+        uint32_t mbA = 0;
+        if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
+        // stage B's result, waiting for stage C
+        uint4 rawP = make_uint4(0, 0, 0, 0);
+        float valP[8];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            cA[u] = c0 + wave + kGatherWaves * u;
-            rawA[u] = make_uint4(0, 0, 0, 0);
-            mbA[u] = 0;
-            if (cA[u] <= c1) { rawA[u] = ids4[(uint64_t)cA[u] * (kIdChunk / 8) + lane]; mbA[u] = A.mbase[cA[u]]; }
-            rawP[u] = make_uint4(0, 0, 0, 0);
-            okP[u] = 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) valP[u][j] = 0.0f;
-        }
-        while (cA[0] <= c1) {
-            // ---- stage B on chunks cA[]: lane l holds the ids at stream positions 64 j + l of a chunk, so for a
+        for (int j = 0; j < 8; ++j) valP[j] = 0.0f;
+        uint32_t okP = 0;            // per-id validity bits of a checked chunk
+        bool fastP = false;          // the chunk took the unchecked path (wavefront-uniform)
+        while (cA <= c1) {
+            // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a
             // fixed j the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set
             // bits below the lane tells every id how many messages have begun up to it.
-            float valN[U][8];
-            uint32_t okN[U];
-            uint4 rawN[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t w[4] = {rawA[u].x, rawA[u].y, rawA[u].z, rawA[u].w};
-                const uint32_t ebase = cA[u] * kIdChunk + lane;
-                const bool live = cA[u] <= c1;
-                uint32_t begun = mbA[u];                                   // messages begun before row j of the chunk
-                okN[u] = 0;
+            float valN[8];
+            uint32_t okN = 0;
+            const uint32_t mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)mbA);
+            const uint64_t first = (uint64_t)cA * kIdChunk;
+            // mb >= 1: an id without a flag then still has a message before it (index >= 0 below)
+            const bool fast = first >= e0 && first + kIdChunk <= e1 && mb >= 1 && (uint64_t)mb + kIdChunk <= A.M;
+            if (fast) {
+                uint32_t begun_m1 = mb - 1u;                               // messages begun before row j, minus one
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t id = (j & 1) ? (w[j >> 1] >> 16) : (w[j >> 1] & 0xffffu);
+                    const uint32_t f = id_of(rawA, j) >> 15;
+                    const unsigned long long ballot = __ballot(f != 0);
+                    const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
+                    valN[j] = A.msg[begun_m1 + below + f];                 // in [mb - 1, mb + 511], inside [0, M)
+                    begun_m1 += (uint32_t)__popcll(ballot);
+                }
+            } else {
+                const uint32_t ebase = cA * kIdChunk + lane;
+                uint32_t begun = mb;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t id = id_of(rawA, j);
                     const uint32_t f = id >> 15;
                     const unsigned long long ballot = __ballot(f != 0);
                     const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
                     const uint32_t mi = begun + below + f - 1;             // this id's message
                     begun += (uint32_t)__popcll(ballot);
                     const uint32_t e = ebase + 64 * j;
-                    const bool ok = live && e >= e0 && e < e1 && (id & kLocalMask) < kAccSlots && mi < A.M;
-                    okN[u] |= (ok ? 1u : 0u) << j;
-                    valN[u][j] = A.msg[ok ? mi : 0u];
+                    const bool ok = e >= e0 && e < e1 && (id & kLocalMask) < kAccSlots && mi < A.M;
+                    okN |= (ok ? 1u : 0u) << j;
+                    valN[j] = A.msg[ok ? mi : 0u];
                 }
-                rawN[u] = rawA[u];
             }
-            // ---- stage A on this wavefront's next chunks
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                cA[u] += kGatherWaves * U;
-                if (cA[u] <= c1) { rawA[u] = ids4[(uint64_t)cA[u] * (kIdChunk / 8) + lane]; mbA[u] = A.mbase[cA[u]]; }
-                else rawA[u] = make_uint4(0, 0, 0, 0);
-            }
-            // ---- stage C on the previous chunks
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t wp[4] = {rawP[u].x, rawP[u].y, rawP[u].z, rawP[u].w};
+            const uint4 rawN = rawA;
+            // ---- stage A on this wavefront's next chunk
+            cA += kGatherWaves;
+            if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
+            else rawA = make_uint4(0, 0, 0, 0);
+            // ---- stage C on the previous chunk
+            if (fastP) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
-                    if ((okP[u] >> j) & 1u) atomicAdd(&acc[id & kLocalMask], (unsigned long long)(valP[u][j] * kFixScale));
+                    const uint32_t local = id_of(rawP, j) & kLocalMask;
+                    atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(valP[j]));
                 }
-                rawP[u] = rawN[u];
-                okP[u] = okN[u];
+            } else {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) valP[u][j] = valN[u][j];
+                for (int j = 0; j < 8; ++j)
+                    if ((okP >> j) & 1u) atomicAdd(&acc[id_of(rawP, j) & kLocalMask], to_fixed(valP[j]));
             }
-        }
-        // drain: stage C on the last chunks
+            rawP = rawN;
+            okP = okN;
+            fastP = fast;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t wp[4] = {rawP[u].x, rawP[u].y, rawP[u].z, rawP[u].w};
+            for (int j = 0; j < 8; ++j) valP[j] = valN[j];
+        }
+        // drain: stage C on the last chunk
+        if (fastP) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t id = (j & 1) ? (wp[j >> 1] >> 16) : (wp[j >> 1] & 0xffffu);
-                if ((okP[u] >> j) & 1u) atomicAdd(&acc[id & kLocalMask], (unsigned long long)(valP[u][j] * kFixScale));
+                const uint32_t local = id_of(rawP, j) & kLocalMask;
+                atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(valP[j]));
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if ((okP >> j) & 1u) atomicAdd(&acc[id_of(rawP, j) & kLocalMask], to_fixed(valP[j]));
         }
     }
     __syncthreads();

@@ -457,6 +457,8 @@ void note_overrun(fr_ctx* c)
 
 // How long fr_bubble_end waits for a step callback that is still running after the bubble's end.
 constexpr uint64_t kCallbackPatienceNs = 200000;
+// How long fr_bubble_end re-asks whether the marker behind the bubble's last step has retired.
+constexpr uint64_t kTailPatienceNs = 20000;
 
 // Stage thread, between bubbles or at a bubble's edge: has the work that was late at an earlier bubble end
 // finished meanwhile?  If not and the grace period is over, ask the worker to stop the task.
@@ -701,7 +703,13 @@ int fr_bubble_end(fr_ctx* c)
     }
     c->bubble_open = false;
     if (c->host_only || !c->tail_armed) return FR_OK;     // nothing was enqueued for this bubble
+    // The marker behind the bubble's last step may have been submitted microseconds ago and needs a moment to
+    // retire even on an idle stream, so "not ready" is only believed if it persists for kTailPatienceNs.
     hipError_t q = hipEventQuery(c->tail_event);
+    for (const uint64_t t0 = now_ns(); q == hipErrorNotReady && now_ns() - t0 < kTailPatienceNs;) {
+        cpu_relax();
+        q = hipEventQuery(c->tail_event);
+    }
     if (q == hipErrorNotReady) {
         if (c->cfg.grace_ns && !c->enforce_armed) {
             c->enforce_armed = true; c->enforce_gpu = true;
