@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it.", file=sys.stderr)
+        print("bench.py runs on one GPU only (--gpus 1).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

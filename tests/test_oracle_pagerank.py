@@ -67,7 +67,7 @@ def test_out_star_closed_form(n, k):
     assert np.allclose(r[1:], (1 - c) / n, atol=1e-14, rtol=0)
 
 
-def test_survey_values_for_seven_leaf_stars():
+def test_hand_evaluated_values_for_seven_leaf_stars():
     # hand-evaluated from the closed forms above with d = 0.85, n = 7, k = 30 (and k = 1, 2)
     g = graphs.star_csr(7, "both")
     assert pagerank(g.row_ptr, g.col, g.out_degree, D, 1)[0] == pytest.approx(0.7625, abs=1e-15)
