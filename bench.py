@@ -298,7 +298,7 @@ def main():
 
     if not args.no_cpu_baseline:
         from oracle.pagerank import pagerank
-        cpu_iters = 200
+        cpu_iters = 600
         tc = time.perf_counter()
         _, used = pagerank(g.row_ptr, g.col, g.out_degree, cfg.damping, cpu_iters, n_threads=0, return_threads=True)
         dt = time.perf_counter() - tc
