@@ -39,6 +39,8 @@ def main():
     ap.add_argument("--guard-ns", type=int, default=100_000)
     ap.add_argument("--time-steps", type=int, default=8,
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
+    ap.add_argument("--device-gate", type=int, default=0,
+                    help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
     args = ap.parse_args()
@@ -140,7 +142,8 @@ def main():
     def start_task(launch_cost_ns, model, time_steps):
         ctx = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0,
                          mem_available_bytes=mem_cap + 1, guard_ns=args.guard_ns, launch_cost_ns=launch_cost_ns,
-                         max_chunk_ns=0, max_inflight=32, time_steps=time_steps, event_log_capacity=1 << 18)
+                         max_chunk_ns=0, max_inflight=32, time_steps=time_steps, event_log_capacity=1 << 18,
+                         device_gate=args.device_gate)
         task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
                                mem_limit_bytes=mem_cap, **model)
         tid = ctx.fr_task_register(task.ops, task.user, task.profile)
@@ -275,6 +278,7 @@ def main():
         "mean_step_us": (chunk_ns / len(timed) / 1e3) if timed else None,
         "overruns": int(p1.overruns - p0.overruns), "deadline_misses": int(p1.deadline_misses - p0.deadline_misses),
         "runs_completed": int(p1.runs_completed - p0.runs_completed),
+        "device_gate": args.device_gate, "steps_refused": int(p1.steps_refused - p0.steps_refused),
         "iterations_per_s_wall": (edges / E) / wall_s,
         "standalone_iteration_us": standalone_iter_ns / 1e3,
         "standalone_gbs": iter_bytes / standalone_iter_ns,

@@ -59,6 +59,8 @@ extern "C" {
 #define FR_EV_IDLE  3   /* the next step did not fit: rest of the bubble left idle ("insufficient time")    */
 #define FR_EV_MISS  4   /* the step fitted the modelled budget but not the real clock; it was not launched  */
 #define FR_EV_OVERRUN 5 /* fr_bubble_end found side work of the bubble still going on (written by that call) */
+#define FR_EV_REFUSED 6 /* device gate: this step, enqueued in the bubble, found too little time left when its kernel
+                           started and did nothing; the task was rewound to it (one record per refused step)       */
 
 typedef struct fr_ctx fr_ctx;
 typedef struct fr_alloc fr_alloc;
@@ -88,6 +90,11 @@ typedef struct fr_config {
                                       rises, up to a doubling, and eased by 1/8 per step when it falls) and steps are planned against the
                                       scaled costs.  The plan then depends on measurements and no longer matches a
                                       plan computed ahead of time.  Needs time_steps.                          */
+    uint32_t device_gate;          /* nonzero: every step also checks the GPU clock when its kernel starts and does
+                                      nothing if it could not end guard_ns before the bubble's declared end
+                                      (freeride_device.h); refused steps are taken back (fr_task_ops.rewind) and
+                                      logged as FR_EV_REFUSED.  Only for tasks that provide rewind.             */
+    uint32_t reserved2;
     uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
                                       callback or InitSideTask -- is still going on this long after the end of the
                                       bubble it belongs to is stopped (FR_STOPPED, last_error FR_ERR_OVERRUN, memory
@@ -115,6 +122,11 @@ typedef struct fr_step {
     int32_t  completes_run; /* plan_step sets 1 when this step ends a run (PageRank: the K-th iteration)    */
     uint32_t cost_class;    /* 0..7: steps of one class share a cost scale when costs adapt (PageRank: the
                                segment kind)                                                                */
+    /* filled in by the runtime before run_step when the device gate is on (gate == NULL otherwise): the
+       arguments of fr_gate_admit for this step's kernels                                                    */
+    uint32_t gate_slot;
+    void*    gate;          /* device pointer to the context's fr_gate                                      */
+    uint32_t gate_need_ticks;   /* the step's modelled duration in GPU wall-clock ticks                     */
     uint32_t reserved;
 } fr_step;
 
@@ -127,6 +139,8 @@ typedef struct fr_step {
  *            Sets modelled_ns = 0 when not even the smallest step fits.
  * run_step : RunNextStep(): enqueue exactly the planned step on `stream` and advance the cursor.
  * stop     : -> STOPPED, release everything taken in init (the accounting allocator frees what it handed out).
+ * rewind   : optional (may be NULL).  The step `first_undone`, run_step of which has returned, and every step after
+ *            it did nothing on the GPU (refused by the device gate): the task's cursor goes back to its start.
  * Each returns FR_OK or an FR_ERR_* code; a failure stops the task.
  */
 typedef struct fr_task_ops {
@@ -135,6 +149,7 @@ typedef struct fr_task_ops {
     int (*plan_step)(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* out);
     int (*run_step)(void* user, void* stream, const fr_step* planned);
     int (*stop)(void* user);
+    int (*rewind)(void* user, const fr_step* first_undone);
 } fr_task_ops;
 
 /* The side-task profile (Section 4.3): memory need and shortest step. */
@@ -202,6 +217,7 @@ typedef struct fr_progress {
     uint64_t deadline_misses;
     uint64_t mem_used_bytes;
     uint64_t killed;                /* 1 if the framework-enforced limit stopped the task                  */
+    uint64_t steps_refused;         /* steps the device gate refused (not counted in steps / work_units)   */
 } fr_progress;
 int fr_query_progress(fr_ctx* ctx, fr_task_id id, fr_progress* out);
 

@@ -8,7 +8,7 @@ LIB_PATH = _build.LIB
 
 FR_OK, FR_ERR_ARG, FR_ERR_STATE, FR_ERR_NOMEM, FR_ERR_OOM, FR_ERR_OVERRUN, FR_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 FR_SUBMITTED, FR_CREATED, FR_PAUSED, FR_RUNNING, FR_STOPPED = range(5)
-FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS, FR_EV_OVERRUN = 1, 2, 3, 4, 5
+FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS, FR_EV_OVERRUN, FR_EV_REFUSED = 1, 2, 3, 4, 5, 6
 FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_HUBFIN = 0, 1, 2, 3
 FR_LOAD_BUSYWAIT, FR_LOAD_GPT = 0, 1
 FR_SCHED_1F1B, FR_SCHED_GPIPE = 0, 1
@@ -27,13 +27,15 @@ class fr_config(C.Structure):
     _fields_ = [("device_id", C.c_int32), ("cu_count", C.c_uint32), ("cu_mask", C.c_uint32 * 8),
                 ("mem_available_bytes", C.c_uint64), ("guard_ns", C.c_uint64), ("launch_cost_ns", C.c_uint64),
                 ("max_chunk_ns", C.c_uint64), ("max_inflight", C.c_uint32), ("event_log_capacity", C.c_uint32),
-                ("time_steps", C.c_uint32), ("adapt_costs", C.c_uint32), ("grace_ns", C.c_uint64)]
+                ("time_steps", C.c_uint32), ("adapt_costs", C.c_uint32), ("device_gate", C.c_uint32), ("reserved2", C.c_uint32),
+                ("grace_ns", C.c_uint64)]
 
 
 class fr_step(C.Structure):
     _fields_ = [("modelled_ns", C.c_uint64), ("work_units", C.c_uint64), ("run", C.c_uint32), ("segment", C.c_uint32),
                 ("tile0", C.c_uint32), ("tile1", C.c_uint32), ("finished", C.c_int32), ("completes_run", C.c_int32),
-                ("cost_class", C.c_uint32), ("reserved", C.c_uint32)]
+                ("cost_class", C.c_uint32), ("gate_slot", C.c_uint32), ("gate", C.c_void_p), ("gate_need_ticks", C.c_uint32),
+                ("reserved", C.c_uint32)]
 
 
 CREATE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p)
@@ -41,10 +43,12 @@ INIT_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p, C.c_void_p)
 PLAN_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(fr_step))
 RUN_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p, C.POINTER(fr_step))
 STOP_FN = C.CFUNCTYPE(C.c_int, C.c_void_p)
+REWIND_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(fr_step))
 
 
 class fr_task_ops(C.Structure):
-    _fields_ = [("create", CREATE_FN), ("init", INIT_FN), ("plan_step", PLAN_FN), ("run_step", RUN_FN), ("stop", STOP_FN)]
+    _fields_ = [("create", CREATE_FN), ("init", INIT_FN), ("plan_step", PLAN_FN), ("run_step", RUN_FN), ("stop", STOP_FN),
+                ("rewind", REWIND_FN)]
 
 
 class fr_task_profile(C.Structure):
@@ -56,7 +60,8 @@ class fr_progress(C.Structure):
                 ("work_units_done", C.c_uint64), ("steps", C.c_uint64), ("bubbles_seen", C.c_uint64),
                 ("bubbles_used", C.c_uint64), ("ns_bubble_declared", C.c_uint64), ("ns_modelled", C.c_uint64),
                 ("ns_measured", C.c_uint64), ("ns_idle_insufficient", C.c_uint64), ("overruns", C.c_uint64),
-                ("deadline_misses", C.c_uint64), ("mem_used_bytes", C.c_uint64), ("killed", C.c_uint64)]
+                ("deadline_misses", C.c_uint64), ("mem_used_bytes", C.c_uint64), ("killed", C.c_uint64),
+                ("steps_refused", C.c_uint64)]
 
 
 class fr_event(C.Structure):
@@ -210,7 +215,7 @@ class Context:
 
     def __init__(self, device_id=0, cu_count=0, cu_mask=None, mem_available_bytes=1 << 62, guard_ns=0,
                  launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0, grace_ns=0,
-                 adapt_costs=0):
+                 adapt_costs=0, device_gate=0):
         cfg = fr_config()
         cfg.device_id = device_id
         cfg.cu_count = cu_count
@@ -219,7 +224,7 @@ class Context:
         cfg.mem_available_bytes = mem_available_bytes
         cfg.guard_ns, cfg.launch_cost_ns, cfg.max_chunk_ns = guard_ns, launch_cost_ns, max_chunk_ns
         cfg.max_inflight, cfg.event_log_capacity, cfg.time_steps = max_inflight, event_log_capacity, time_steps
-        cfg.grace_ns, cfg.adapt_costs = grace_ns, adapt_costs
+        cfg.grace_ns, cfg.adapt_costs, cfg.device_gate = grace_ns, adapt_costs, device_gate
         self.handle = C.c_void_p()
         _check(lib().fr_create(C.byref(cfg), C.byref(self.handle)), "fr_create")
         self._keep = []

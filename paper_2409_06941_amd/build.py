@@ -26,7 +26,8 @@ def is_stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = sources() + [os.path.join(CSRC, "common.h"), os.path.join(CSRC, "pr_layout.h"),
-                        os.path.join(ROOT, "include", "freeride.h")]
+                        os.path.join(ROOT, "include", "freeride.h"),
+                        os.path.join(ROOT, "include", "freeride_device.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

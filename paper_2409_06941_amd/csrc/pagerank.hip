@@ -25,6 +25,7 @@
 #include <cstring>
 #include <new>
 
+#include "freeride_device.h"
 #include "pr_layout.h"
 
 namespace {
@@ -40,7 +41,7 @@ constexpr int kGatherBlock = FR_GATHER_BLOCK;   // threads per workgroup of the 
 constexpr int kGatherWaves = kGatherBlock / 64;
 constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the scatter sweep
 constexpr int kScatterWaves = kScatterBlock / 64;
-constexpr float kFixScale = 4611686018427387904.0f;        // 2^62: contrib sums are <= 1, so they fit u64
+// row sums are kept as 64-bit fixed point with scale 2^62: contrib sums are <= 1, so they fit
 constexpr float kFixInv = 1.0f / 4611686018427387904.0f;
 
 // ---- fixed-order reductions ----
@@ -120,10 +121,17 @@ struct DevArgs {
     float* ranks_out;
 };
 
+// What a step's kernels need to ask the device gate (Section 4.5's check, made by the GPU when the kernel starts).
+struct GateArg {
+    fr_gate* gate;                // NULL: no gate
+    uint32_t slot, need_ticks;
+};
+
 // ---- V0 ----
-__global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, int final_pass)
+__global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, GateArg G, uint32_t tile0, int final_pass)
 {
     __shared__ float red[8];
+    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t q = tile0 + blockIdx.x;
     const int64_t v0 = (int64_t)q * A.rows_per_part;
     const float r0 = 1.0f / (float)A.V;
@@ -144,6 +152,7 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, uint32_t tile0, i
         if (q == 0)
             for (uint32_t i = A.Q + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;   // hub slots
     }
+    fr_gate_done(G.gate);
 }
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), and every XCD has an L2 of its
@@ -217,11 +226,12 @@ __device__ __forceinline__ void scatter_bins(const uint16_t* __restrict__ src16,
 
 // `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
 template <uint32_t kSrcPerPart>
-__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t tile0, int parity, int first)
+__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
     __shared__ uint2 desc[kDescBatch];
     __shared__ float red[32];
+    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t p = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
     const int64_t v0 = (int64_t)p * kSrcPerPart;
     const uint32_t n = (uint32_t)((A.V - v0) < (int64_t)kSrcPerPart ? (A.V - v0) : (int64_t)kSrcPerPart);
@@ -277,6 +287,7 @@ __global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, uint32_t t
         default: scatter_bins<64, 8>(A.src16, A.msg, desc, nb, slice, n); break;
         }
     }
+    fr_gate_done(G.gate);
 }
 
 // ---- G_k ----
@@ -309,12 +320,15 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 // is checked), so chunks that lie wholly inside the partition's edge range and whose messages cannot pass the end
 // of the message array - all but the first and last chunk of a partition - take a path without per-id checks:
 // ids out of range (which a sound layout never holds) are sent to a sink slot behind the accumulators.
+// (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 template <uint32_t kRowsPerPart>
-__global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t tile0, int parity, int final_pass)
+__global__ __launch_bounds__(kGatherBlock) __attribute__((amdgpu_waves_per_eu(kRowsPerPart == kRowsSmall ? 8 : 4, kRowsPerPart == kRowsSmall ? 8 : 4)))
+void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
 {
     constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[32];
+    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t q = tile0 + blockIdx.x;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
@@ -447,14 +461,16 @@ __global__ __launch_bounds__(kGatherBlock) void k_gather(DevArgs A, uint32_t til
         const float total = block_sum(dangling, red + 8);
         if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + q] = total;
     }
+    fr_gate_done(G.gate);
 }
 
 // ---- H_k ----
 // 16 hubs per workgroup, 16 lanes per hub: the lanes add up the hub's virtual rows (integers, any order), the
 // group's first lane applies the vertex-pass arithmetic.
-__global__ __launch_bounds__(256) void k_hubfin(DevArgs A, uint32_t tile0, int parity, int final_pass)
+__global__ __launch_bounds__(256) void k_hubfin(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
 {
     __shared__ float red[24];
+    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t t = tile0 + blockIdx.x;
     const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
@@ -479,6 +495,7 @@ __global__ __launch_bounds__(256) void k_hubfin(DevArgs A, uint32_t tile0, int p
         }
     }
     (void)dangling;          // H only runs after the last iteration: nothing reads its dangling sum
+    fr_gate_done(G.gate);
 }
 
 uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
@@ -549,31 +566,31 @@ void build_cost_tables(PrTask* p)
     for (uint32_t t = 0; t < L.n_hub_tiles; ++t) h[t + 1] = h[t] + std::max<uint64_t>(1, p->d.hubfin_tile_ns);
 }
 
-int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream)
+int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0})
 {
     const int kind = p->kind_of(g);
     if (tile1 <= tile0 || tile1 > p->tiles_of(kind)) return FR_ERR_ARG;
     const uint32_t n = tile1 - tile0;
     const uint32_t K = (uint32_t)p->d.iterations;
     if (kind == FR_PR_SEG_VERTEX) {
-        hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, p->args, tile0, K == 0 ? 1 : 0);
+        hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, p->args, G, tile0, K == 0 ? 1 : 0);
     } else if (kind == FR_PR_SEG_HUBFIN) {
         // after G_{K-1}: the dangling partials of r_{K-1} sit in set (K-1) & 1
-        hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, tile0, (int)((K - 1) & 1u), 1);
+        hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, G, tile0, (int)((K - 1) & 1u), 1);
     } else {
         const uint32_t k = (g - 1) / 2;
         if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes the hubs of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
             if (p->L.src_per_part == kSrcLarge)
-                hipLaunchKernelGGL(k_scatter<kSrcLarge>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, parity, first);
+                hipLaunchKernelGGL(k_scatter<kSrcLarge>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
             else
-                hipLaunchKernelGGL(k_scatter<kSrcSmall>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, tile0, parity, first);
+                hipLaunchKernelGGL(k_scatter<kSrcSmall>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
         } else {
             const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
             if (p->L.rows_per_part == kRowsLarge)
-                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
+                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass);
             else
-                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, tile0, parity, final_pass);
+                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass);
         }
     }
     hipError_t e = hipGetLastError();
@@ -670,13 +687,24 @@ int pr_run(void* user, void* stream, const fr_step* st)
 {
     PrTask* p = static_cast<PrTask*>(user);
     if (!p->inited || st->run != p->run || st->segment != p->seg || st->tile0 != p->tile) return FR_ERR_STATE;
-    int rc = pr_launch(p, p->seg, st->tile0, st->tile1, (hipStream_t)stream);
+    int rc = pr_launch(p, p->seg, st->tile0, st->tile1, (hipStream_t)stream,
+                       GateArg{static_cast<fr_gate*>(st->gate), st->gate_slot, st->gate_need_ticks});
     if (rc != FR_OK) return rc;
     p->tile = st->tile1;
     if (p->tile == p->tiles_of(p->kind_of(p->seg))) {
         p->tile = 0;
         if (++p->seg == p->n_segments()) { p->seg = 0; p->run++; }
     }
+    return FR_OK;
+}
+
+// The device gate refused `first` and every step after it: they did nothing, so the cursor goes back to its start.
+int pr_rewind(void* user, const fr_step* first)
+{
+    PrTask* p = static_cast<PrTask*>(user);
+    if (!p->inited || !first || first->segment >= p->n_segments() || first->tile0 >= p->tiles_of(p->kind_of(first->segment)))
+        return FR_ERR_ARG;
+    p->run = first->run; p->seg = first->segment; p->tile = first->tile0;
     return FR_OK;
 }
 
@@ -711,6 +739,7 @@ int fr_pagerank_make(const fr_pagerank_desc* d, fr_task_ops* ops_out, void** use
     ops_out->plan_step = pr_plan;
     ops_out->run_step = pr_run;
     ops_out->stop = pr_stop;
+    ops_out->rewind = pr_rewind;
     prof_out->mem_limit_bytes = d->mem_limit_bytes;
     prof_out->min_step_ns = 1;
     *user_out = p;

@@ -15,8 +15,20 @@
 #include <thread>
 
 #include "common.h"
+#include "freeride_device.h"
 
 namespace {
+
+// ---- device gate (freeride_device.h): opened at the start of every bubble the task runs in
+__global__ void k_gate_open(fr_gate* g, unsigned long long deadline_ticks)
+{
+    g->deadline_ticks = deadline_ticks;
+    g->opened_ticks = wall_clock64();
+    g->closed = 0u;
+    g->first_refused = 0xffffffffu;
+}
+
+__global__ void k_gate_clock(fr_gate* g) { g->deadline_ticks = wall_clock64(); }
 
 inline void cpu_relax()
 {
@@ -95,6 +107,14 @@ struct fr_ctx {
     std::deque<PendingTiming> pending;
     hipEvent_t chain_tail = nullptr;        // end event of the newest step of the bubble being served
     uint32_t cost_scale[8] = {kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne};
+
+    // device gate
+    fr_gate* gate = nullptr;                // device memory, NULL when the gate is off
+    double ticks_per_ns = 0.0;              // GPU wall clock
+    int64_t gpu_minus_host_ns = 0;          // wall_clock64() / ticks_per_ns - CLOCK_MONOTONIC
+    std::vector<fr_step> gate_steps;        // steps enqueued since the gate was last opened, by slot (worker only)
+    std::vector<uint32_t> gate_bubble;      //   and the bubble each belongs to
+    bool gate_pending = false;              // their verdicts have not been read back yet (worker only)
 
     // Overrun detection: the worker records this event behind the last work it enqueued for a bubble;
     // fr_bubble_end asks whether it has completed.  (A stream query is not used: it may report "not ready"
@@ -177,6 +197,7 @@ void stop_task_locked(fr_ctx* c, Task* t, int error)
     if (!c->host_only && c->side) (void)hipStreamSynchronize(c->side);
     resolve_timings(c, true);
     if (t->ops.stop) t->ops.stop(t->user);
+    if (t == c->task) { c->gate_steps.clear(); c->gate_bubble.clear(); c->gate_pending = false; }
     t->prog.mem_used_bytes = t->alloc.used;
     fr_alloc_release(&t->alloc);
     t->state = FR_STOPPED;
@@ -217,6 +238,37 @@ bool killed_if_asked(fr_ctx* c, Task* t)
         promote_locked(c);
     }
     return true;
+}
+
+// Reads back which steps the device gate refused and takes them back: the task's cursor is rewound to the first
+// of them, the counters forget them and one FR_EV_REFUSED record is written for each.  Waits for the side stream
+// (its work belongs to a bubble that is over).  Worker thread, work_mu held, ctx->mu not held.
+void gate_settle(fr_ctx* c, Task* t)
+{
+    if (!c->gate_pending) return;
+    c->gate_pending = false;
+    uint32_t first = 0xffffffffu;
+    if (hipStreamSynchronize(c->side) != hipSuccess ||
+        hipMemcpy(&first, &c->gate->first_refused, sizeof(first), hipMemcpyDeviceToHost) != hipSuccess)
+        first = 0xffffffffu;
+    if (first < c->gate_steps.size() && t && t->state != FR_STOPPED && t->ops.rewind) {
+        const int rc = t->ops.rewind(t->user, &c->gate_steps[first]);
+        std::lock_guard<std::mutex> lk(c->mu);
+        for (size_t i = first; i < c->gate_steps.size(); ++i) {
+            const fr_step& st = c->gate_steps[i];
+            fr_event ev{};
+            ev.kind = FR_EV_REFUSED; ev.bubble = c->gate_bubble[i]; ev.run = st.run; ev.segment = st.segment;
+            ev.tile0 = st.tile0; ev.tile1 = st.tile1; ev.work_units = st.work_units; ev.t_host_ns = now_ns();
+            log_push(c, ev);
+            t->prog.steps--;
+            t->prog.steps_refused++;
+            t->prog.work_units_done -= st.work_units;
+            if (st.completes_run) t->prog.runs_completed--;
+        }
+        if (rc != FR_OK) stop_task_locked(c, t, rc);
+    }
+    c->gate_steps.clear();
+    c->gate_bubble.clear();
 }
 
 // One bubble, on the worker thread, work_mu held.
@@ -267,6 +319,14 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     const uint32_t max_inflight = c->cfg.max_inflight ? c->cfg.max_inflight : 8;
     const bool timed = c->cfg.time_steps && !c->host_only;
     const bool adapt = timed && c->cfg.adapt_costs;
+    const bool gated = c->gate && t->ops.rewind;
+    if (gated) {
+        gate_settle(c, t);                                   // the previous bubble's verdicts, if still unread
+        if (t->state != FR_RUNNING) return;                  // a failing rewind stopped the task
+        const int64_t end_gpu_ns = (int64_t)(t_begin + len) - (int64_t)guard + c->gpu_minus_host_ns;
+        const unsigned long long deadline = end_gpu_ns > 0 ? (unsigned long long)((double)end_gpu_ns * c->ticks_per_ns) : 0ull;
+        hipLaunchKernelGGL(k_gate_open, dim3(1), dim3(1), 0, c->side, c->gate, deadline);
+    }
     int64_t remaining = (int64_t)len - (int64_t)guard;
     const int64_t total = remaining;
     bool used = false, finished = false;
@@ -368,6 +428,12 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             }
             if (chain_head && group_begin) (void)hipEventRecord(group_begin, c->side);
         }
+        if (gated) {
+            st.gate = c->gate;
+            st.gate_slot = (uint32_t)c->gate_steps.size();
+            const double need = (double)scaled * c->ticks_per_ns;
+            st.gate_need_ticks = need < 4.0e9 ? (uint32_t)need : 4000000000u;
+        }
         c->in_callback.store(now_ns(), std::memory_order_release);
         rc = t->ops.run_step(t->user, (void*)c->side, &st);
         c->in_callback.store(0, std::memory_order_release);
@@ -384,6 +450,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             if (st.completes_run) t->prog.runs_completed++;
             if (!used) { used = true; t->prog.bubbles_used++; }
         }
+        if (gated) { c->gate_steps.push_back(st); c->gate_bubble.push_back(index); }
         if (timed) {
             group_n++; group_mask |= 1u << (st.cost_class & 7); group_modelled += st.modelled_ns;
             if (group_n >= group_size) close_group();
@@ -394,6 +461,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     }
     (void)seq;
     if (timed && group_n) close_group();
+    if (gated) c->gate_pending = !c->gate_steps.empty();
     if (used && !c->host_only && c->tail_event) c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->chain_tail) {
@@ -419,6 +487,12 @@ void worker_main(fr_ctx* c)
     uint32_t idle_spins = 0;
     while (!c->quit.load(std::memory_order_acquire)) {
         const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
+        if (seq == seen && c->gate_pending && c->tail_armed && hipEventQuery(c->tail_event) == hipSuccess) {
+            std::lock_guard<std::mutex> wl(c->work_mu);      // the bubble's work has drained: read its verdicts
+            Task* t;
+            { std::lock_guard<std::mutex> lk(c->mu); t = c->task; }
+            gate_settle(c, t);
+        }
         if (seq == seen) {
             // Spin while a live task may be handed a bubble at any moment; back off otherwise.
             if (++idle_spins > 20000) {
@@ -453,6 +527,32 @@ void note_overrun(fr_ctx* c)
     fr_event ev{};
     ev.kind = FR_EV_OVERRUN; ev.bubble = c->cur_index; ev.t_host_ns = now_ns();
     log_push(c, ev);
+}
+
+// Allocates the gate and measures how the GPU's wall clock relates to the host's: a one-thread kernel stores
+// wall_clock64(), the host notes its own clock before the launch and after the wait; the tightest of a few
+// such windows gives the offset (good to a few microseconds, which guard_ns must cover).
+int gate_setup(fr_ctx* c)
+{
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->cfg.device_id) != hipSuccess || khz <= 0) return FR_ERR_HIP;
+    c->ticks_per_ns = (double)khz * 1.0e-6;
+    if (hipMalloc(reinterpret_cast<void**>(&c->gate), sizeof(fr_gate)) != hipSuccess) { c->gate = nullptr; return FR_ERR_HIP; }
+    if (hipMemset(c->gate, 0, sizeof(fr_gate)) != hipSuccess) return FR_ERR_HIP;
+    uint64_t best_window = ~0ull;
+    for (int i = 0; i < 12; ++i) {
+        const uint64_t t0 = now_ns();
+        hipLaunchKernelGGL(k_gate_clock, dim3(1), dim3(1), 0, c->side, c->gate);
+        if (hipStreamSynchronize(c->side) != hipSuccess) return FR_ERR_HIP;
+        const uint64_t t1 = now_ns();
+        unsigned long long ticks = 0;
+        if (hipMemcpy(&ticks, &c->gate->deadline_ticks, sizeof(ticks), hipMemcpyDeviceToHost) != hipSuccess) return FR_ERR_HIP;
+        if (i >= 2 && t1 - t0 < best_window) {                  // the first launches pay one-time costs
+            best_window = t1 - t0;
+            c->gpu_minus_host_ns = (int64_t)((double)ticks / c->ticks_per_ns) - (int64_t)(t0 + (t1 - t0) / 2);
+        }
+    }
+    return FR_OK;
 }
 
 // How long fr_bubble_end waits for a step callback that is still running after the bubble's end.
@@ -574,6 +674,12 @@ int fr_create(const fr_config* cfg, fr_ctx** out)
         if (e != hipSuccess) { delete c; return FR_ERR_HIP; }
         e = hipEventCreateWithFlags(&c->tail_event, hipEventDisableTiming);
         if (e != hipSuccess) { (void)hipStreamDestroy(c->side); delete c; return FR_ERR_HIP; }
+        if (cfg->device_gate && gate_setup(c) != FR_OK) {
+            (void)hipEventDestroy(c->tail_event); (void)hipStreamDestroy(c->side);
+            if (c->gate) (void)hipFree(c->gate);
+            delete c;
+            return FR_ERR_HIP;
+        }
     }
     c->worker = std::thread(worker_main, c);
     *out = c;
@@ -600,6 +706,7 @@ int fr_destroy(fr_ctx* c)
     }
     if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
     if (c->tail_event) (void)hipEventDestroy(c->tail_event);
+    if (c->gate) (void)hipFree(c->gate);
     delete c;
     return FR_OK;
 }

@@ -25,7 +25,7 @@ def test_every_declared_function_is_exported_and_bound():
     assert declared == set(fr.binding.SIGNATURES), declared ^ set(fr.binding.SIGNATURES)
 
 
-STRUCTS = ["fr_config", "fr_step", "fr_task_profile", "fr_progress", "fr_event", "fr_pagerank_desc", "fr_pagerank_info_t",
+STRUCTS = ["fr_config", "fr_step", "fr_task_ops", "fr_task_profile", "fr_progress", "fr_event", "fr_pagerank_desc", "fr_pagerank_info_t",
            "fr_load_desc", "fr_stage_desc", "fr_stage_op", "fr_epoch_result"]
 
 
@@ -41,5 +41,6 @@ def test_struct_sizes_match_the_header_layout(tmp_path):
     sizes = dict((line.split()[0], int(line.split()[1])) for line in out.splitlines())
     for n in STRUCTS:
         assert ctypes.sizeof(getattr(fr.binding, n)) == sizes[n], n
-    assert sizes["fr_config"] == 4 + 4 + 32 + 8 * 4 + 4 * 4 + 8
-    assert sizes["fr_progress"] == 8 + 13 * 8
+    assert sizes["fr_config"] == 4 + 4 + 32 + 8 * 4 + 4 * 6 + 8
+    assert sizes["fr_progress"] == 8 + 14 * 8
+    assert sizes["fr_step"] == 64

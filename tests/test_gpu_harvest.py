@@ -243,3 +243,55 @@ def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheape
             assert scales == [1_000_000] * 8
     load.fr_load_destroy()
     assert late[0] > 0 and late[1] == 0, late
+
+
+def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back():
+    # The model claims 40 % of the real step times, so the host keeps enqueueing steps that cannot end inside the
+    # bubble.  With the device gate each step asks the GPU clock when its kernel starts: the late ones do nothing,
+    # are logged, and the task is rewound to the first of them.  The ranks keep the standalone run's bits.
+    g = graphs.rmat_csr(21, 1 << 25, seed=9)
+    V, E, K = g.n_vertices, g.n_edges, 20
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ref = torch.zeros(V, dtype=torch.float32, device="cuda")
+    probe = fr.PageRankTask(V, E, rp, col, od, ref, iterations=K)
+    probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
+    info = probe.fr_pagerank_info()
+    probe.fr_pagerank_destroy()
+    low = 0.4
+    model = dict(fs_per_vertex=max(1, int(low * ph[0] * 1e6 / V)), fs_per_message=max(1, int(low * ph[1] / K * 1e6 / info.messages)),
+                 fs_per_edge=max(1, int(low * ph[2] / K * 1e6 / E)), hubfin_tile_ns=1000)
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 1_000_000, 2_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    late = {}
+    for gate in (0, 1):
+        ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+        ctx = fr.Context(device_id=0, guard_ns=60_000, launch_cost_ns=5_000, time_steps=4, device_gate=gate)
+        task = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K, max_runs=0, **model)
+        tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+        assert _init_bubble(ctx, tid) == fr.FR_OK
+        stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+        late[gate] = sum(stage.fr_stage_run_epoch(ctx).overruns for _ in range(4))
+        import time
+        time.sleep(0.05)                                  # the last bubble's verdicts are read once its work has drained
+        pr = ctx.fr_query_progress(tid)
+        log = ctx.fr_event_log()
+        ctx.fr_task_stop(tid)
+        got = ranks.cpu().numpy()
+        task.fr_pagerank_destroy(); stage.fr_stage_destroy(); ctx.fr_destroy()
+        chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
+        refused = [e for e in log if e.kind == fr.FR_EV_REFUSED]
+        print("gate", gate, "overruns", late[gate], "steps", pr.steps, "refused", pr.steps_refused, "runs", pr.runs_completed, flush=True)
+        assert pr.runs_completed >= 1
+        assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+        assert len(refused) == pr.steps_refused and len(chunks) == pr.steps + pr.steps_refused
+        assert pr.work_units_done == sum(e.work_units for e in chunks) - sum(e.work_units for e in refused)
+        # the work that counts covers the completed runs (and the run in progress), refused steps excluded
+        assert K * E * pr.runs_completed <= pr.work_units_done < K * E * (pr.runs_completed + 1)
+        if gate:
+            assert pr.steps_refused > 0
+        else:
+            assert pr.steps_refused == 0
+    load.fr_load_destroy()
+    assert late[0] > 0 and late[1] <= late[0], late
