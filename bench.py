@@ -285,7 +285,10 @@ def main():
         "stage_tflops": ((fp_flops + bp_flops) * cfg.m / (busy_with / 1e9) / 1e12) if fp_flops else None,
         "roofline": {"kernel": "k_scatter + k_gather (one PageRank iteration)", "bound": "hbm",
                      "achieved": pull_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pull_gbs / HBM_PEAK_GBS,
-                     "traffic": CFG2_TRAFFIC_BYTES if cfg.name == "cfg2" else None, "iterations": iters_done,
+                     "traffic": CFG2_TRAFFIC_BYTES if cfg.name == "cfg2" else None,
+                     "traffic_gbs": (CFG2_TRAFFIC_BYTES * iters_done / pull_ns) if (cfg.name == "cfg2" and pull_ns) else None,
+                     "traffic_frac_of_peak": (CFG2_TRAFFIC_BYTES * iters_done / pull_ns / HBM_PEAK_GBS) if (cfg.name == "cfg2" and pull_ns) else None,
+                     "iterations": iters_done,
                      "avg_iteration_us": (pull_ns / iters_done / 1e3) if iters_done else None,
                      "timing": "HIP events on the side stream around groups of %d steps, all inside the timed epochs" % max(1, args.time_steps),
                      "standalone_launch_us": {"k_scatter": s_ns / 1e3, "k_gather": g_ns / 1e3,

@@ -217,7 +217,8 @@ typedef struct fr_progress {
     uint64_t deadline_misses;
     uint64_t mem_used_bytes;
     uint64_t killed;                /* 1 if the framework-enforced limit stopped the task                  */
-    uint64_t steps_refused;         /* steps the device gate refused (not counted in steps / work_units)   */
+    uint64_t steps_refused;         /* steps the device gate refused; they leave steps / work_units_done /
+                                       runs_completed again once the bubble's GPU work has drained        */
 } fr_progress;
 int fr_query_progress(fr_ctx* ctx, fr_task_id id, fr_progress* out);
 
