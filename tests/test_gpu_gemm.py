@@ -16,7 +16,9 @@ def _to_dev_bf16(x32):
     return torch.from_numpy(bits).cuda()
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 192), (768, 256, 4096), (512, 1280, 320)])
+# from two tiles to more than two tiles per CU; tile counts that are and are not multiples of the 8 XCDs
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 192), (768, 256, 4096), (512, 1280, 320),
+                                   (2048, 8192, 128), (1024, 16384 + 256, 192)])
 def test_gemm_matches_oracle(M, N, K):
     print("gemm", M, N, K, flush=True)
     a, b = gemm_inputs.operands(M, N, K, seed=M + N + K)
