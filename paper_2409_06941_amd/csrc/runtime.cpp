@@ -114,7 +114,7 @@ struct fr_ctx {
     int64_t gpu_minus_host_ns = 0;          // wall_clock64() / ticks_per_ns - CLOCK_MONOTONIC
     std::vector<fr_step> gate_steps;        // steps enqueued since the gate was last opened, by slot (worker only)
     std::vector<uint32_t> gate_bubble;      //   and the bubble each belongs to
-    bool gate_pending = false;              // their verdicts have not been read back yet (worker only)
+    std::atomic<bool> gate_pending{false};  // their verdicts have not been read back yet
 
     // Overrun detection: the worker records this event behind the last work it enqueued for a bubble;
     // fr_bubble_end asks whether it has completed.  (A stream query is not used: it may report "not ready"
@@ -245,8 +245,7 @@ bool killed_if_asked(fr_ctx* c, Task* t)
 // (its work belongs to a bubble that is over).  Worker thread, work_mu held, ctx->mu not held.
 void gate_settle(fr_ctx* c, Task* t)
 {
-    if (!c->gate_pending) return;
-    c->gate_pending = false;
+    if (!c->gate_pending.exchange(false)) return;
     uint32_t first = 0xffffffffu;
     if (hipStreamSynchronize(c->side) != hipSuccess ||
         hipMemcpy(&first, &c->gate->first_refused, sizeof(first), hipMemcpyDeviceToHost) != hipSuccess)
@@ -265,7 +264,7 @@ void gate_settle(fr_ctx* c, Task* t)
             t->prog.work_units_done -= st.work_units;
             if (st.completes_run) t->prog.runs_completed--;
         }
-        if (rc != FR_OK) stop_task_locked(c, t, rc);
+        if (rc != FR_OK) { stop_task_locked(c, t, rc); promote_locked(c); }
     }
     c->gate_steps.clear();
     c->gate_bubble.clear();
@@ -461,7 +460,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     }
     (void)seq;
     if (timed && group_n) close_group();
-    if (gated) c->gate_pending = !c->gate_steps.empty();
+    if (gated) c->gate_pending.store(!c->gate_steps.empty());
     if (used && !c->host_only && c->tail_event) c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->chain_tail) {
@@ -487,7 +486,7 @@ void worker_main(fr_ctx* c)
     uint32_t idle_spins = 0;
     while (!c->quit.load(std::memory_order_acquire)) {
         const uint64_t seq = c->bubble_seq.load(std::memory_order_acquire);
-        if (seq == seen && c->gate_pending && c->tail_armed && hipEventQuery(c->tail_event) == hipSuccess) {
+        if (seq == seen && c->gate_pending.load() && c->tail_armed && hipEventQuery(c->tail_event) == hipSuccess) {
             std::lock_guard<std::mutex> wl(c->work_mu);      // the bubble's work has drained: read its verdicts
             Task* t;
             { std::lock_guard<std::mutex> lk(c->mu); t = c->task; }
