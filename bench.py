@@ -182,7 +182,7 @@ def main():
     log("in-bubble step times = standalone x %.3f (%d timing groups of %d whole sweeps): scatter %.1f us, gather %.1f us" %
         (in_bubble, len(ratios), ts, insitu[1] / 1e3, insitu[2] / 1e3))
     one_tile_ns = [x * in_bubble for x in one_tile_ns]
-    ctx, task, tid = start_task(1_000, rates(*insitu, args.margin), ts)
+    ctx, task, tid = start_task(0, rates(*insitu, args.margin), ts)     # the measured group times already hold the launch gaps
     def epochs(n, with_task):
         out = []
         for _ in range(n):
