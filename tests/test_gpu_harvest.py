@@ -295,3 +295,38 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
             assert pr.steps_refused == 0
     load.fr_load_destroy()
     assert late[0] > 0 and late[1] <= late[0], late
+
+
+def test_steps_are_timed_in_groups_of_time_steps():
+    # time_steps = 3: inside a bubble every third step, and the bubble's last one, carries the GPU time of its group
+    import time
+    cfg = configs.by_name("cfg1")
+    g = cfg.build_graph()
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    ctx = fr.Context(device_id=0, guard_ns=300_000, launch_cost_ns=25_000, max_chunk_ns=500_000, time_steps=3)
+    task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=cfg.iterations, max_runs=2,
+                           fs_per_edge=400_000, fs_per_message=2_500_000, fs_per_vertex=300_000, hubfin_tile_ns=15000)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    stream = torch.cuda.Stream()
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=cfg.busy_fp_ns, bp_ns=cfg.busy_bp_ns)
+    stage = fr.Stage(fr.FR_SCHED_1F1B, cfg.p, cfg.m, cfg.stage, cfg.busy_fp_ns, cfg.busy_bp_ns, load, stream)
+    for _ in range(2):
+        stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.05)
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    ctx.fr_task_stop(tid)
+    task.fr_pagerank_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    by_bubble = {}
+    for e in log:
+        if e.kind == fr.FR_EV_CHUNK:
+            by_bubble.setdefault(e.bubble, []).append(e)
+    assert pr.runs_completed == 2 and len(by_bubble) >= 2
+    for chunks in by_bubble.values():
+        for i, e in enumerate(chunks):
+            closes_group = (i + 1) % 3 == 0 or i + 1 == len(chunks)
+            assert (e.measured_ns > 0) == closes_group, (i, len(chunks), e.measured_ns)
+    total = sum(e.measured_ns for c in by_bubble.values() for e in c)
+    assert total == pr.ns_measured and total > 0
