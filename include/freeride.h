@@ -306,8 +306,8 @@ typedef struct fr_pagerank_desc {
        max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.                   */
     uint64_t min_step_ns[4];
     /* Partition sizes of the layout: destination rows per gather tile (8192 or 16384) and source vertices per
-       scatter tile (16384 or 32768); 0 = chosen by the library (the small pair below 2^24 vertices, the large pair
-       from there on).  Other values: FR_ERR_ARG at InitSideTask.                                                */
+       scatter tile (16384 or 32768); 0 = chosen by the library (16384 rows from 2^22 vertices on, 32768 sources
+       from 2^24 vertices on).  Other values: FR_ERR_ARG at InitSideTask.                                                */
     uint32_t rows_per_partition;
     uint32_t sources_per_partition;
 } fr_pagerank_desc;

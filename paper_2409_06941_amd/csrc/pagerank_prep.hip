@@ -267,8 +267,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                     const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, fr_alloc* a,
                     hipStream_t stream, int* hip_error)
 {
-    if (!rows_per_part) rows_per_part = V >= kLargePartsFrom ? kRowsLarge : kRowsSmall;
-    if (!src_per_part) src_per_part = V >= kLargePartsFrom ? kSrcLarge : kSrcSmall;
+    if (!rows_per_part) rows_per_part = V >= kLargeRowsFrom ? kRowsLarge : kRowsSmall;
+    if (!src_per_part) src_per_part = V >= kLargeSrcFrom ? kSrcLarge : kSrcSmall;
     if ((rows_per_part != kRowsSmall && rows_per_part != kRowsLarge) || (src_per_part != kSrcSmall && src_per_part != kSrcLarge))
         return FR_ERR_ARG;
     L->V = V; L->E = E;

@@ -5,11 +5,12 @@
 // two streaming sweeps whose random accesses all land in LDS (the two-phase partition-centric idea of Beamer et
 // al., "propagation blocking", 2017, and Lakhotia et al., "PCPM", 2018, rebuilt around CDNA's 160 KB LDS):
 //
-//   * destination rows are cut into partitions of rows_per_part rows; sources into partitions of src_per_part
-//     (8192 and 16384, or 16384 and 32768 for graphs of 2^24 vertices and more: the bins of message traffic
-//     between a source and a destination partition hold M * rows_per_part * src_per_part / V^2 messages and must
-//     not get too short to stream; the large sizes leave room for one workgroup per CU only, which costs the
-//     small graphs more than the longer bins gain them);
+//   * destination rows are cut into partitions of rows_per_part rows (8192, or 16384 from 2^22 vertices on);
+//     sources into partitions of src_per_part (16384, or 32768 from 2^24 vertices on).  Larger partitions mean
+//     fewer messages (more edges of a source fall into one partition) and longer bins of message traffic between
+//     a source and a destination partition (M * rows_per_part * src_per_part / V^2 messages, which must not get
+//     too short to stream), but only one workgroup per CU, and they must still leave every CU a tile: hence the
+//     thresholds (256 gather tiles, 512 scatter tiles);
 //   * all in-edges of one destination partition q are stored together, ordered by source u and then by row;
 //     one MESSAGE is made per distinct (q, u) pair, however many rows of q the source u points to;
 //   * scatter sweep, one workgroup per source partition p: the p-slice of contrib sits in LDS; for every q the
@@ -33,7 +34,8 @@
 
 constexpr uint32_t kRowsSmall = 8192, kRowsLarge = 16384;   // destination rows per partition (8 B each in LDS)
 constexpr uint32_t kSrcSmall = 16384, kSrcLarge = 32768;    // source vertices per scatter partition (4 B each in LDS)
-constexpr int64_t kLargePartsFrom = int64_t(1) << 24;       // vertex count from which the large sizes are used
+constexpr int64_t kLargeRowsFrom = int64_t(1) << 22;        // vertex counts from which the large sizes are used
+constexpr int64_t kLargeSrcFrom = int64_t(1) << 24;
 constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub_split are split into virtual rows
 constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
