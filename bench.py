@@ -103,7 +103,15 @@ def main():
     t_init = time.time() - t_init
     ph = cal.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 0, want_phase_ns=True)
     info = cal.fr_pagerank_info()
-    n_hub_tiles = cal.fr_pagerank_tiles(fr.FR_PR_SEG_HUBFIN)
+    n_finish_tiles = cal.fr_pagerank_tiles(fr.FR_PR_SEG_FINISH)
+    # multiplicands of the task's cost formulas, summed over a sweep
+    gather_weight = sum(cal.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER))
+    scatter_weight = sum(cal.fr_pagerank_tile_weights(fr.FR_PR_SEG_SCATTER))
+    gather_fixed = info.gather_tiles * info.rows_per_partition
+    tile_cost_spread = []
+    for kind in range(4):
+        c = cal.fr_pagerank_tile_costs(kind)
+        tile_cost_spread.append(max(c) * len(c) / max(1, sum(c)))      # heaviest tile / mean tile
     cal.fr_pagerank_destroy()
     # shortest steps: one iteration launched one tile at a time; a launch of a few tiles takes about as long as
     # one tile alone, which the additive tile costs cannot express (min_step_ns of the task's cost model)
@@ -111,23 +119,25 @@ def main():
     ph1 = one.fr_pagerank_run_standalone(0, side_probe.fr_side_stream(), 1, want_phase_ns=True)
     n_tiles_kind = [one.fr_pagerank_tiles(k) for k in range(4)]
     one.fr_pagerank_destroy()
-    one_tile_ns = [ph1[k] / max(1, n_tiles_kind[k]) for k in range(4)]
+    # (mean over the tiles, scaled to the heaviest tile by the default cost model's spread)
+    one_tile_ns = [ph1[k] / max(1, n_tiles_kind[k]) * tile_cost_spread[k] for k in range(4)]
     side_probe.fr_destroy()
     M = max(1, info.messages)
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3]      # V0 and H run once per run
     def rates(v_ns, s_ns, g_ns, h_ns, derate):
         """Femtosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
         pv = max(1, int(v_ns * 1e6 * derate / V))
-        pm = max(1, int((s_ns * 1e6 * derate - V * pv) / M))
-        pe = max(1, int((g_ns * 1e6 * derate - V * pv) / max(1, E)))
+        pm = max(1, int((s_ns * 1e6 * derate - scatter_weight * pv) / M))
+        pe = max(1, int((g_ns * 1e6 * derate - gather_fixed * pv) / max(1, gather_weight)))
         return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe,
-                    hubfin_tile_ns=max(1, int(h_ns * derate / n_hub_tiles)),
+                    finish_tile_ns=max(1, int(h_ns * derate / n_finish_tiles)),
                     min_step_ns=[int(derate * x) for x in one_tile_ns])
-    log("layout: M/E=%.3f, %d destination partitions, %d source partitions, %d hubs in %d virtual rows, init+first run %.2fs" %
-        (info.messages / max(1, E), info.partitions, info.source_partitions, info.hubs, info.virtual_rows, t_init))
-    log("standalone per iteration: scatter %.1f us, gather %.1f us (once per run: first vertex pass %.1f us, hub finish %.1f us)" %
+    log("layout: M/E=%.3f, %d ranges (%d with edges, %d merged), %d gather tiles, %d scatter tiles, init+first run %.2fs" %
+        (info.messages / max(1, E), info.ranges, info.nonempty_ranges, info.merged_ranges, info.gather_tiles,
+         info.scatter_tiles, t_init))
+    log("standalone per iteration: scatter %.1f us, gather %.1f us (once per run: first vertex pass %.1f us, finish %.1f us)" %
         (s_ns / 1e3, g_ns / 1e3, v_ns / 1e3, h_ns / 1e3))
-    log("shortest steps (one tile per launch): vertex %.1f us, scatter %.1f us, gather %.1f us, hub finish %.1f us" %
+    log("shortest steps (one tile per launch): vertex %.1f us, scatter %.1f us, gather %.1f us, finish %.1f us" %
         tuple(x / 1e3 for x in one_tile_ns))
     standalone_iter_ns = s_ns + g_ns
 
@@ -136,7 +146,7 @@ def main():
     kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
     stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
     n_segs = 2 * K + 2
-    seg_kind = lambda g: (fr.FR_PR_SEG_VERTEX if g == 0 else fr.FR_PR_SEG_HUBFIN if g == n_segs - 1
+    seg_kind = lambda g: (fr.FR_PR_SEG_VERTEX if g == 0 else fr.FR_PR_SEG_FINISH if g == n_segs - 1
                           else fr.FR_PR_SEG_SCATTER + ((g - 1) & 1))
 
     def start_task(launch_cost_ns, model, time_steps):
@@ -294,10 +304,11 @@ def main():
                      "standalone_launch_us": {"k_scatter": s_ns / 1e3, "k_gather": g_ns / 1e3,
                                               "note": "whole sweeps outside bubbles, one event pair per launch"},
                      "in_bubble_over_standalone": in_bubble,
-                     "launches": {"k_scatter": per_kind_n[1], "k_gather": per_kind_n[2], "k_hubfin": per_kind_n[3]},
+                     "launches": {"k_scatter": per_kind_n[1], "k_gather": per_kind_n[2], "k_finish": per_kind_n[3]},
                      "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0},
-        "layout": {"messages_per_edge": info.messages / max(1, E), "hubs": info.hubs,
-                   "destination_partitions": info.partitions, "source_partitions": info.source_partitions,
+        "layout": {"messages_per_edge": info.messages / max(1, E), "ranges": info.ranges,
+                   "merged_ranges": info.merged_ranges, "gather_tiles": info.gather_tiles,
+                   "scatter_tiles": info.scatter_tiles,
                    "bytes_resident": info.bytes_resident, "bytes_peak_init": info.bytes_peak},
         "paper_context": {"bubble_rate_pct": 42.4, "cost_savings_pct": 7.8, "overhead_pct": 1.1,
                           "pagerank_iterations_per_s": 333.9, "hardware": "4x RTX 6000 Ada (paper, Section 6)"},

@@ -262,22 +262,24 @@ int fr_cost_scales(fr_ctx* ctx, uint32_t* scales_ppm_out);
 /*
  * Pull-based PageRank over an in-edge CSR, fp32 ranks, fixed iteration count, dangling mass spread uniformly,
  * Jacobi iterations (the paper's graph-analytics side task, Section 6.1.4; one iteration = one pass over the
- * graph, Section 6.2).  InitSideTask rebuilds the CSR into a partition-centric layout on the GPU; work is cut
- * into tiles fixed at that point and results do not depend on how tiles are grouped into launches.
- * A run is the segment sequence  V0, S_0, G_0, S_1, G_1, ..., S_{K-1}, G_{K-1}, H  where
- *   V0  (vertex pass)  r_0 = 1/V, contrib_0 = r_0 / outdeg, per-tile partial sums of dangling r_0;
- *   S_k (scatter)      one message contrib_k[u] per (destination partition, source u) pair; for k > 0 it first
- *                      finishes the rows whose in-edges were dealt out to virtual rows (hubs);
- *   G_k (gather)       acc_k[v] = sum over v's in-edges of the source's message, then for the partition's rows
- *                      r_{k+1} = base_k + d * acc_k, contrib_{k+1}, dangling partials;
+ * graph, Section 6.2).  InitSideTask rebuilds the CSR into a partition-centric layout on the GPU (vertices
+ * renumbered by in-degree, rows cut into ranges); work is cut into tiles fixed at that point and results do not
+ * depend on how tiles are grouped into launches.
+ * A run is the segment sequence  V0, S_0, G_0, S_1, G_1, ..., S_{K-1}, G_{K-1}, F  where
+ *   V0  (vertex pass)  r_0 = 1/V: per-tile partial sums of dangling r_0;
+ *   S_k (scatter)      one message contrib_k[u] = r_k[u] / outdeg[u] per (range, source u) pair; for k > 0 it first
+ *                      finishes the rows that no gather tile could finish alone (ranges cut into several gather
+ *                      tiles, and ranges without in-edges);
+ *   G_k (gather)       acc_k[v] = sum over v's in-edges of the source's message, then for the rows of a range with
+ *                      one gather tile r_{k+1} = base_k + d * acc_k, contrib_{k+1}, dangling partials;
  *                      base_k = (1 - d)/V + d * D_k / V, D_k = sum of the dangling partials of r_k;
- *   H   (hub finish)   r_K of the hubs, once, after the last iteration.
+ *   F   (finish)       r_K of the rows S would have finished, once, after the last iteration.
  * The last iteration writes r_K to ranks_out.  With K = 0 the run is V0 alone, which writes r_0 there.
  */
 #define FR_PR_SEG_VERTEX  0
 #define FR_PR_SEG_SCATTER 1
 #define FR_PR_SEG_GATHER  2
-#define FR_PR_SEG_HUBFIN  3
+#define FR_PR_SEG_FINISH  3
 
 typedef struct fr_pagerank_desc {
     int64_t  n_vertices;          /* V >= 1                                                                 */
@@ -294,18 +296,19 @@ typedef struct fr_pagerank_desc {
     /* cost model, integer femtoseconds (a streaming kernel spends about 1000 fs on an edge, so picoseconds would
        be too coarse), fixed for the task's life (0 = library default); tile cost in ns = ceil(sum / 10^6), at least 1:
          vertex tile  : rows * fs_per_vertex
-         scatter tile : messages * fs_per_message + sources * fs_per_vertex
-         gather tile  : edges * fs_per_edge + rows * fs_per_vertex
-         hub tile     : hubfin_tile_ns (already ns)                                                         */
+         scatter tile : messages * fs_per_message + (sources + partial sums it adds up) * fs_per_vertex
+         gather tile  : (edges + 2 * messages + 3 * repeated edges) * fs_per_edge + rows_per_partition * fs_per_vertex
+                        (a repeated edge has the same source and row as the edge before it)
+         finish tile  : finish_tile_ns (already ns)                                                         */
     uint64_t fs_per_edge;
     uint64_t fs_per_message;
     uint64_t fs_per_vertex;
-    uint64_t hubfin_tile_ns;
+    uint64_t finish_tile_ns;
     /* Shortest step per segment kind (indexed by FR_PR_SEG_*), ns; 0 = none.  A launch of a few tiles takes about
        as long as one tile alone (the tiles run side by side), so the modelled cost of a step is
        max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.                   */
     uint64_t min_step_ns[4];
-    /* Partition sizes of the layout: destination rows per gather tile (8192 or 16384) and source vertices per
+    /* Partition sizes of the layout: destination rows per range (8192 or 16384) and the most source vertices of a
        scatter tile (16384 or 32768); 0 = chosen by the library (16384 rows from 2^22 vertices on, 32768 sources
        from 2^24 vertices on).  Other values: FR_ERR_ARG at InitSideTask.                                                */
     uint32_t rows_per_partition;
@@ -314,15 +317,15 @@ typedef struct fr_pagerank_desc {
 
 /* Facts about the layout built by InitSideTask. */
 typedef struct fr_pagerank_info_t {
-    uint64_t messages;            /* distinct (destination partition, source) pairs                         */
-    uint32_t partitions;          /* destination partitions (gather tiles)                                  */
-    uint32_t source_partitions;   /* scatter tiles                                                          */
-    uint32_t hubs;                /* rows with more than hub_split in-edges                                 */
-    uint32_t virtual_rows;        /* pieces the hubs' in-edges were dealt out to                            */
-    uint32_t hub_split;
-    uint32_t rows_per_partition;  /* destination rows per gather tile                                       */
-    uint32_t sources_per_partition; /* source vertices per scatter tile                                     */
-    uint32_t reserved;
+    uint64_t messages;            /* distinct (range, source) pairs                                         */
+    uint32_t ranges;              /* row ranges, ceil(V / rows_per_partition)                               */
+    uint32_t scatter_tiles;       /* source intervals of about equal numbers of messages                    */
+    uint32_t gather_tiles;        /* runs of edges of one range, about equal in length                      */
+    uint32_t merged_ranges;       /* ranges cut into several gather tiles                                   */
+    uint32_t nonempty_ranges;     /* ranges with in-edges (they come first: rows are ordered by in-degree)  */
+    uint32_t rows_per_partition;  /* destination rows per range                                             */
+    uint32_t sources_per_partition; /* most source vertices of a scatter tile                               */
+    uint32_t partial_rows;        /* gather tiles of merged ranges (rows of fp32 partial sums)              */
     uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
     uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */
 } fr_pagerank_info_t;
@@ -334,10 +337,13 @@ int fr_pagerank_destroy(void* user);
 /* The four calls below need the layout, so they return FR_ERR_STATE until InitSideTask has run. */
 int fr_pagerank_info(void* user, fr_pagerank_info_t* out);
 /* Number of tiles of a segment kind (FR_PR_SEG_*), their modelled costs in ns, and the work they hold
-   (vertex: rows, scatter: messages, gather: edges, hub: 0). */
+   (vertex: rows, scatter: messages, gather: edges, finish: 0). */
 int fr_pagerank_tiles(void* user, int32_t seg_kind, uint32_t* n_tiles_out);
 int fr_pagerank_tile_costs(void* user, int32_t seg_kind, uint32_t* costs_host, size_t cap, size_t* n_out);
 int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work_host, size_t cap, size_t* n_out);
+/* The tiles' multiplicands in the cost formulas above: gather: edges + 2 * messages + 3 * repeated edges;
+   scatter: sources + partial sums added up (the factor of fs_per_vertex); vertex: rows; finish: 0. */
+int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights_host, size_t cap, size_t* n_out);
 /*
  * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_tiles_per_launch` tiles per
  * kernel launch (0 = a whole segment per launch), waits for it and leaves r_K in ranks_out.  Same kernels and

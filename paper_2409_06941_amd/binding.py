@@ -9,7 +9,7 @@ LIB_PATH = _build.LIB
 FR_OK, FR_ERR_ARG, FR_ERR_STATE, FR_ERR_NOMEM, FR_ERR_OOM, FR_ERR_OVERRUN, FR_ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 FR_SUBMITTED, FR_CREATED, FR_PAUSED, FR_RUNNING, FR_STOPPED = range(5)
 FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS, FR_EV_OVERRUN, FR_EV_REFUSED = 1, 2, 3, 4, 5, 6
-FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_HUBFIN = 0, 1, 2, 3
+FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_FINISH = 0, 1, 2, 3
 FR_LOAD_BUSYWAIT, FR_LOAD_GPT = 0, 1
 FR_SCHED_1F1B, FR_SCHED_GPIPE = 0, 1
 
@@ -75,14 +75,14 @@ class fr_pagerank_desc(C.Structure):
                 ("out_degree", C.c_void_p), ("ranks_out", C.c_void_p), ("damping", C.c_float), ("iterations", C.c_int32),
                 ("max_runs", C.c_int32), ("reserved", C.c_int32), ("mem_limit_bytes", C.c_uint64),
                 ("fs_per_edge", C.c_uint64), ("fs_per_message", C.c_uint64), ("fs_per_vertex", C.c_uint64),
-                ("hubfin_tile_ns", C.c_uint64), ("min_step_ns", C.c_uint64 * 4),
+                ("finish_tile_ns", C.c_uint64), ("min_step_ns", C.c_uint64 * 4),
                 ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32)]
 
 
 class fr_pagerank_info_t(C.Structure):
-    _fields_ = [("messages", C.c_uint64), ("partitions", C.c_uint32), ("source_partitions", C.c_uint32),
-                ("hubs", C.c_uint32), ("virtual_rows", C.c_uint32), ("hub_split", C.c_uint32),
-                ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32), ("reserved", C.c_uint32),
+    _fields_ = [("messages", C.c_uint64), ("ranges", C.c_uint32), ("scatter_tiles", C.c_uint32),
+                ("gather_tiles", C.c_uint32), ("merged_ranges", C.c_uint32), ("nonempty_ranges", C.c_uint32),
+                ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32), ("partial_rows", C.c_uint32),
                 ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
 
 
@@ -135,6 +135,7 @@ SIGNATURES = {
     "fr_pagerank_tiles": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32)]),
     "fr_pagerank_tile_costs": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_pagerank_tile_work": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
+    "fr_pagerank_tile_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_pagerank_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
     "fr_load_workspace_bytes": (C.c_int, [C.POINTER(fr_load_desc), C.POINTER(C.c_uint64)]),
     "fr_load_make": (C.c_int, [C.POINTER(fr_load_desc), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -283,14 +284,14 @@ class PageRankTask:
 
     def __init__(self, n_vertices, n_edges, row_ptr, col, out_degree, ranks_out, damping=0.85, iterations=30,
                  max_runs=0, mem_limit_bytes=1 << 40, fs_per_edge=0, fs_per_message=0, fs_per_vertex=0,
-                 hubfin_tile_ns=0, min_step_ns=(0, 0, 0, 0), rows_per_partition=0, sources_per_partition=0):
+                 finish_tile_ns=0, min_step_ns=(0, 0, 0, 0), rows_per_partition=0, sources_per_partition=0):
         d = fr_pagerank_desc()
         d.n_vertices, d.n_edges = n_vertices, n_edges
         d.row_ptr, d.col, d.out_degree, d.ranks_out = _ptr(row_ptr), _ptr(col), _ptr(out_degree), _ptr(ranks_out)
         d.damping, d.iterations, d.max_runs = damping, iterations, max_runs
         d.mem_limit_bytes = mem_limit_bytes
         d.fs_per_edge, d.fs_per_message, d.fs_per_vertex = fs_per_edge, fs_per_message, fs_per_vertex
-        d.hubfin_tile_ns = hubfin_tile_ns
+        d.finish_tile_ns = finish_tile_ns
         for k in range(4):
             d.min_step_ns[k] = int(min_step_ns[k])
         d.rows_per_partition, d.sources_per_partition = rows_per_partition, sources_per_partition
@@ -317,6 +318,13 @@ class PageRankTask:
         buf = (C.c_uint64 * n)()
         got = C.c_size_t()
         _check(lib().fr_pagerank_tile_work(self.user, seg_kind, buf, n, C.byref(got)), "fr_pagerank_tile_work")
+        return list(buf)
+
+    def fr_pagerank_tile_weights(self, seg_kind):
+        n = self.fr_pagerank_tiles(seg_kind)
+        buf = (C.c_uint64 * n)()
+        got = C.c_size_t()
+        _check(lib().fr_pagerank_tile_weights(self.user, seg_kind, buf, n, C.byref(got)), "fr_pagerank_tile_weights")
         return list(buf)
 
     def fr_pagerank_tiles(self, seg_kind):

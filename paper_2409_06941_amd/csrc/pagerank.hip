@@ -5,19 +5,20 @@
 // that are fixed at init, a step is a run of consecutive tiles of one segment, and every tile computes the same
 // bits whichever launch carries it, so pausing and resuming at any tile boundary cannot change the result.
 //
-// The pull pass runs on the partition-centric layout of pr_layout.h.  One run = segments
-//     V0, S_0 G_0, S_1 G_1, ..., S_{K-1} G_{K-1}, H
-//   V0   vertex pass (tile = destination partition): r_0 = 1/V, contrib_0 = r_0 / outdeg, dangling partials
-//   S_k  scatter     (tile = source partition): contrib_k slice in LDS -> one message per (partition, source);
-//                    for k > 0 the hubs that live in the slice are finished first (their virtual rows, summed by
-//                    G_{k-1}, are added up and run through the vertex-pass arithmetic)
-//   G_k  gather      (tile = destination partition): id stream + messages -> 64-bit fixed-point sums in LDS;
-//                    then, fused, the next vertex pass for the partition's rows:
-//                    r_{k+1} = base_k + d * sum, contrib_{k+1} = r_{k+1} / outdeg, dangling partials
-//                    (sums of hubs' virtual rows are only stored)
-//   H    hub finish  (tile = 16 hubs): after the last iteration, the hubs' r_K
+// The pull pass runs on the partition-centric layout of pr_layout.h (vertices renumbered by in-degree).  One run =
+//     V0, S_0 G_0, S_1 G_1, ..., S_{K-1} G_{K-1}, F
+//   V0   vertex pass (tile = row range): dangling partials of r_0 = 1/V
+//   S_k  scatter     (tile = source interval): contrib_k of the interval goes into LDS - r_0 / outdeg for k = 0,
+//                    read back for rows of direct ranges, made on the spot for rows of merged ranges (partial
+//                    sums of G_{k-1} added in tile order, then the vertex-pass arithmetic) and of empty ranges
+//                    (r = base) - then one message per (range, source) is written
+//   G_k  gather      (tile = run of edges of one range): id stream + messages -> 64-bit fixed-point sums in LDS;
+//                    direct range: fused, the next vertex pass for its rows,
+//                    r_{k+1} = base_k + d * sum, contrib_{k+1} = r_{k+1} / outdeg, dangling partials;
+//                    merged range: the sums are stored as one row of fp32 partial sums
+//   F    finish      (tile = merged or empty range): after the last iteration, r_K of their rows
 // base_k = (1 - d)/V + d * D_k / V, D_k = fixed-order sum of the dangling partials of r_k.
-// In the last iteration G writes r_K to ranks_out instead of contrib; H does the same for the hubs.
+// In the last iteration G writes r_K to ranks_out (through perm) instead of contrib; F does the same.
 // No floating-point atomics anywhere: float sums have a fixed order, the LDS atomics add integers.
 
 #include <algorithm>
@@ -32,6 +33,9 @@ namespace {
 
 #ifndef FR_GATHER_BLOCK
 #define FR_GATHER_BLOCK 1024
+#endif
+#ifndef FR_AHEAD
+#define FR_AHEAD 4
 #endif
 #ifndef FR_SCATTER_BLOCK
 #define FR_SCATTER_BLOCK 1024
@@ -94,30 +98,25 @@ __device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 flo
     return (lds[0] + lds[1]) + (lds[2] + lds[3]);
 }
 
-__device__ __forceinline__ bool is_hub_tag(float tag) { return (__float_as_uint(tag) >> 31) != 0; }
-__device__ __forceinline__ float inv_of_tag(float tag) { return __uint_as_float(__float_as_uint(tag) & 0x7fffffffu); }
-
-enum : uint32_t { kShape_64x8 = 0, kShape_64x4, kShape_32x4, kShape_32x2 };
-
 struct DevArgs {
     int64_t V, E;
-    uint32_t M, Q, P, n_hubs, n_vrows, n_dpart;
-    uint32_t scatter_shape;       // lanes per bin x messages per lane in the scatter sweep (kShape_*)
-    uint32_t rows_per_part, src_per_part;
+    uint32_t M, Q, Qe, n_gather, n_scatter, n_finish, n_dpart;
+    uint32_t rows_per_part, rows_shift;           // rows per range and its log2
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
-    const uint32_t* eoff;
     const uint32_t* mbase;
     const uint2* bins;
-    const int32_t* hub_row;
-    const uint32_t* hub_vbase;
-    const uint32_t* hub_of_p;
-    const float* inv_tag;
+    const float* inv_out;
+    const int32_t* perm;
+    const RangeInfo* range_info;
+    const GatherTile* gather_tiles;
+    const ScatterTile* scatter_tiles;
+    const uint32_t* finish_ranges;
     float* msg;
     float* contrib;
     float* dpart;                 // [2][n_dpart]
-    unsigned long long* vacc;     // [n_vrows]
+    float* partials;              // [n_partials][rows_per_part]
     float* ranks_out;
 };
 
@@ -127,30 +126,117 @@ struct GateArg {
     uint32_t slot, need_ticks;
 };
 
+// Sum of a merged row's partial sums p_0 .. p_{nt-1}.  The order is fixed: sixteen leaves, leaf g = p_g + p_{g+16} +
+// ... in rising order, joined by a balanced tree over g.  kLanes lanes (a power of two up to 16, consecutive in
+// the wavefront, all active) share the row: lane `sub` owns the leaves sub * 16 / kLanes onwards, joins them, and
+// the lanes' results are joined by butterfly exchanges, which is the same tree.  Every lane gets the sum.  Sixteen
+// loads per row are in flight at a time.
+template <int kLanes>
+__device__ __forceinline__ float merged_sum(const DevArgs& A, RangeInfo info, uint32_t local, uint32_t sub)
+{
+    constexpr int kLeaves = 16 / kLanes;
+    const uint32_t nt = info.cls_tiles >> 2;
+    const float* p = A.partials + ((size_t)info.partial0 << A.rows_shift) + local;
+    float s[kLeaves];
+#pragma unroll
+    for (int k = 0; k < kLeaves; ++k) s[k] = 0.0f;
+    for (uint32_t t0 = 0; t0 < nt; t0 += 16) {
+        float x[kLeaves];
+#pragma unroll
+        for (int k = 0; k < kLeaves; ++k) {
+            const uint32_t t = t0 + sub * kLeaves + k;
+            x[k] = t < nt ? p[(size_t)t << A.rows_shift] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < kLeaves; ++k) s[k] += x[k];
+    }
+#pragma unroll
+    for (int w = 1; w < kLeaves; w <<= 1)
+#pragma unroll
+        for (int k = 0; k + w < kLeaves; k += 2 * w) s[k] += s[k + w];
+    float r = s[0];
+#pragma unroll
+    for (int off = 1; off < kLanes; off <<= 1) r += __shfl_xor(r, off, 64);
+    return r;
+}
+
+// Rows [i0, i1) of a scatter tile's slice, all in one merged range: r = base + d * (sum of the row's partial sums),
+// contrib = r / outdeg.  kLanes lanes work on a row.  Returns this thread's share of the dangling mass.
+template <int kLanes, int kThreads>
+__device__ __forceinline__ float fill_merged(const DevArgs& A, RangeInfo info, uint32_t u0, uint32_t i0, uint32_t i1, float base, float* slice)
+{
+    const uint32_t sub = threadIdx.x % kLanes;
+    float dangling = 0.0f;
+    for (uint32_t ib = i0; ib < i1; ib += kThreads / kLanes) {       // uniform trip count: the lanes exchange values
+        const uint32_t i = ib + threadIdx.x / kLanes;
+        if (i >= i1) continue;                                       // (all lanes of a row leave together)
+        const uint32_t u = u0 + i;
+        const float inv = A.inv_out[u];
+        const float r = fmaf(A.damping, merged_sum<kLanes>(A, info, u & (A.rows_per_part - 1), sub), base);
+        if (sub == 0) {
+            slice[i] = r * inv;
+            dangling += (inv == 0.0f ? r : 0.0f);
+        }
+    }
+    return dangling;
+}
+
+// contrib of the sources [u0, u0 + n) of a scatter tile for an iteration after the first, into `slice`; returns
+// this thread's share of the dangling mass among the rows finished here.  The tile is walked range by range (a
+// handful at most), so that each loop has one kind of row and its loads can be issued back to back.
+template <int kThreads>
+__device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint32_t n, float base, float* slice)
+{
+    float dangling = 0.0f;
+    for (uint32_t i0 = 0; i0 < n;) {
+        const uint32_t q = (u0 + i0) >> A.rows_shift;
+        const uint32_t range_end = ((q + 1) << A.rows_shift) - u0;
+        const uint32_t i1 = range_end < n ? range_end : n;
+        const RangeInfo info = A.range_info[q];
+        const uint32_t cls = info.cls_tiles & 3u;
+        if (cls == kRangeDirect) {                                   // finished by its gather tile
+#pragma unroll 4
+            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) slice[i] = A.contrib[u0 + i];
+        } else if (cls == kRangeEmpty) {
+#pragma unroll 4
+            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
+                const float inv = A.inv_out[u0 + i];
+                slice[i] = base * inv;
+                dangling += (inv == 0.0f ? base : 0.0f);
+            }
+        } else {
+            // few rows (sources with many messages; their rows are the ones with many partial sums): several lanes a row
+            const uint32_t len = i1 - i0;
+            if (len * 16 <= kThreads) dangling += fill_merged<16, kThreads>(A, info, u0, i0, i1, base, slice);
+            else if (len * 4 <= kThreads) dangling += fill_merged<4, kThreads>(A, info, u0, i0, i1, base, slice);
+            else if (len * 2 <= kThreads) dangling += fill_merged<2, kThreads>(A, info, u0, i0, i1, base, slice);
+            else dangling += fill_merged<1, kThreads>(A, info, u0, i0, i1, base, slice);
+        }
+        i0 = i1;
+    }
+    return dangling;
+}
+
 // ---- V0 ----
 __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, GateArg G, uint32_t tile0, int final_pass)
 {
     __shared__ float red[8];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t q = tile0 + blockIdx.x;
-    const int64_t v0 = (int64_t)q * A.rows_per_part;
+    const int64_t v0 = (int64_t)q << A.rows_shift;
     const float r0 = 1.0f / (float)A.V;
     float dangling = 0.0f;
     for (uint32_t i = threadIdx.x; i < A.rows_per_part; i += kBlock) {
         const int64_t v = v0 + i;
         if (v >= A.V) break;
-        if (final_pass) A.ranks_out[v] = r0;
-        else {
-            const float inv = inv_of_tag(A.inv_tag[v]);
-            A.contrib[v] = r0 * inv;
-            dangling += (inv == 0.0f ? r0 : 0.0f);
-        }
+        if (final_pass) A.ranks_out[v] = r0;              // every vertex gets the same value: no need for perm
+        else dangling += (A.inv_out[v] == 0.0f ? r0 : 0.0f);
     }
     if (!final_pass) {
         const float total = block_sum(dangling, red);
         if (threadIdx.x == 0) A.dpart[q] = total;
         if (q == 0)
-            for (uint32_t i = A.Q + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;   // hub slots
+            for (uint32_t i = A.Q + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;
     }
     fr_gate_done(G.gate);
 }
@@ -167,124 +253,141 @@ __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t n)
 }
 
 // ---- S_k ----
-// One workgroup per source partition: its slice of contrib sits in LDS, and for every destination partition q
-// the messages of bin (p, q) are written in order.  Bin descriptors are staged in LDS a batch at a time; each
-// wavefront works on two bins at once, eight messages per lane per step, so that sixteen independent loads are
-// in flight before the first one is needed.
-constexpr uint32_t kDescBatch = 1024;
+// One workgroup per scatter tile: contrib of its sources sits in LDS, and for every range j the messages of bin
+// (tile, j) - a contiguous run [x, y) of message numbers - are written.  The unit of work is a GROUP of eight
+// consecutive message numbers, aligned to eight: one 16-byte load brings the eight sources, eight LDS reads their
+// contrib, two 16-byte stores write the messages (groups cut by the ends of a bin store element by element).
+// The groups of all bins of a batch are numbered consecutively (prefix sums in LDS) and dealt to the threads
+// round-robin, so bins of any length keep all lanes busy; a thread finds a group's bin by binary search.
+// The load for a thread's next group is issued before the current one is worked on.
+constexpr uint32_t kDescBatch = 1024;       // bins per batch
+constexpr uint32_t kGroup = 8;
 
-// The messages of `nb` bins (ranges [x, y) of message numbers, staged in LDS) are produced from the slice.
-// L lanes share a bin and move up to T messages each per step, for 16 / T bins at a time: a wavefront keeps
-// sixteen loads per lane in flight over (16 / T) * (64 / L) bins.  Short bins (large graphs) want small L * T,
-// so that lanes and issue slots are not spent on messages that are not there; long bins want L = 64, T = 8.
-// The values written do not depend on L and T.
-template <uint32_t L, uint32_t T>
-__device__ __forceinline__ void scatter_bins(const uint16_t* __restrict__ src16, float* __restrict__ msg, const uint2* desc,
-                                             uint32_t nb, const float* slice, uint32_t n)
+// Exclusive prefix sums of one value per thread over the workgroup (kScatterBlock threads); out[i] = sum of the
+// values of threads < i for i <= kScatterBlock.  `wave_tot` holds kScatterWaves + 1 words.
+__device__ __forceinline__ void block_exclusive_scan(uint32_t value, uint32_t* out, uint32_t* wave_tot)
 {
-    constexpr uint32_t H = 16 / T, kGroups = 64 / L;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t grp = lane / L, sub = lane % L;
-    for (uint32_t i = H * kGroups * wave; i < nb; i += H * kGroups * kScatterWaves) {
-        uint32_t pos[H], end[H];
-        bool more = false;
+    uint32_t incl = value;
 #pragma unroll
-        for (uint32_t h = 0; h < H; ++h) {
-            const uint32_t b = i + h * kGroups + grp;
-            pos[h] = 0; end[h] = 0;
-            if (b < nb) { pos[h] = desc[b].x; end[h] = desc[b].y; }
-            more = more || pos[h] < end[h];
-        }
-        while (more) {
-            uint32_t src[H][T];
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
+        if (lane >= (uint32_t)off) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int w = 0; w < kScatterWaves; ++w) { const uint32_t x = wave_tot[w]; wave_tot[w] = run; run += x; }
+        wave_tot[kScatterWaves] = run;
+    }
+    __syncthreads();
+    out[threadIdx.x] = wave_tot[wave] + incl - value;
+    if (threadIdx.x == 0) out[kScatterBlock] = wave_tot[kScatterWaves];
+    __syncthreads();
+}
+
+struct GroupRef {
+    uint32_t m0;      // first message number of the group (multiple of kGroup)
+    uint32_t bin;     // its bin in the batch
+};
+
+// Group number k of the batch: its bin is the last one whose first group number is <= k.
+__device__ __forceinline__ GroupRef locate_group(uint32_t k, const uint32_t* gpre, const uint2* desc, uint32_t nb)
+{
+    uint32_t lo = 0, hi = nb;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (gpre[mid] <= k) lo = mid;
+        else hi = mid;
+    }
+    GroupRef g;
+    g.bin = lo;
+    g.m0 = (desc[lo].x / kGroup + (k - gpre[lo])) * kGroup;
+    return g;
+}
+
+__device__ __forceinline__ void emit_group(const GroupRef& ref, const uint2* desc, const uint4& raw, const float* slice, uint32_t n,
+                                           float* __restrict__ msg)
+{
+    struct { uint32_t m0, x, y; } g = {ref.m0, desc[ref.bin].x, desc[ref.bin].y};
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    float val[kGroup];
 #pragma unroll
-            for (uint32_t h = 0; h < H; ++h)
+    for (int e = 0; e < (int)kGroup; ++e) {
+        const uint32_t src = (e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu);
+        val[e] = src < n ? slice[src] : 0.0f;
+    }
+    if (g.m0 >= g.x && g.m0 + kGroup <= g.y) {
+        float4* out = reinterpret_cast<float4*>(msg + g.m0);
+        out[0] = make_float4(val[0], val[1], val[2], val[3]);
+        out[1] = make_float4(val[4], val[5], val[6], val[7]);
+    } else {
 #pragma unroll
-                for (uint32_t t = 0; t < T; ++t) {
-                    const uint32_t m = pos[h] + sub + L * t;
-                    src[h][t] = m < end[h] ? src16[m] : 0u;
-                }
-            float val[H][T];
-#pragma unroll
-            for (uint32_t h = 0; h < H; ++h)
-#pragma unroll
-                for (uint32_t t = 0; t < T; ++t) val[h][t] = src[h][t] < n ? slice[src[h][t]] : 0.0f;
-            more = false;
-#pragma unroll
-            for (uint32_t h = 0; h < H; ++h) {
-#pragma unroll
-                for (uint32_t t = 0; t < T; ++t) {
-                    const uint32_t m = pos[h] + sub + L * t;
-                    if (m < end[h]) msg[m] = val[h][t];
-                }
-                pos[h] = pos[h] + T * L < end[h] ? pos[h] + T * L : end[h];
-                more = more || pos[h] < end[h];
-            }
-        }
+        for (int e = 0; e < (int)kGroup; ++e)
+            if (g.m0 + e >= g.x && g.m0 + e < g.y) msg[g.m0 + e] = val[e];
     }
 }
 
 // `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
+// (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 template <uint32_t kSrcPerPart>
-__global__ __launch_bounds__(kScatterBlock) void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
+__global__ __launch_bounds__(kScatterBlock) __attribute__((amdgpu_waves_per_eu(kSrcPerPart == kSrcSmall ? 8 : 4, kSrcPerPart == kSrcSmall ? 8 : 4)))
+void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
     __shared__ uint2 desc[kDescBatch];
+    __shared__ uint32_t gpre[kScatterBlock + 1];          // groups before each bin of the batch; [kScatterBlock] = all
+    __shared__ uint32_t wave_tot[kScatterWaves + 1];
     __shared__ float red[32];
+    static_assert(kDescBatch <= kScatterBlock, "one bin per thread");
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t p = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
-    const int64_t v0 = (int64_t)p * kSrcPerPart;
-    const uint32_t n = (uint32_t)((A.V - v0) < (int64_t)kSrcPerPart ? (A.V - v0) : (int64_t)kSrcPerPart);
-    const float d_part = first ? 0.0f : dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
-    for (uint32_t i = threadIdx.x * 4; i < n; i += kScatterBlock * 4) {
-        if (i + 3 < n) *reinterpret_cast<float4*>(&slice[i]) = *reinterpret_cast<const float4*>(A.contrib + v0 + i);
-        else
-            for (uint32_t c = i; c < n; ++c) slice[c] = A.contrib[v0 + c];
-    }
-    if (!first) {
-        // finish the hubs of this slice: 16 lanes add up a hub's virtual rows, the first of them applies
-        // r = base + d * sum and puts contrib = r / outdeg into the slice
-        const float D = dangling_finish(d_part, red);              // (its barriers also order the slice loads)
+    const uint32_t t = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
+    const ScatterTile T = A.scatter_tiles[t];
+    const uint32_t Qe = A.Qe;
+    // the first batch of bin descriptors is asked for now and used after the slice is filled
+    uint2 d_first = make_uint2(0, 0);
+    if (threadIdx.x < Qe) d_first = A.bins[(uint64_t)t * Qe + threadIdx.x];
+    const uint32_t u0 = T.u0;
+    const uint32_t n = T.u1 - T.u0 < kSrcPerPart ? T.u1 - T.u0 : kSrcPerPart;
+    if (first) {
+        const float r0 = 1.0f / (float)A.V;
+#pragma unroll 4
+        for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i];
+    } else {
+        const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
         const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
-        const uint32_t h0 = A.hub_of_p[p], h1 = A.hub_of_p[p + 1];
-        const uint32_t sub = threadIdx.x & 15;
-        float dangling = 0.0f;
-        for (uint32_t hb = h0; hb < h1; hb += kScatterBlock / 16) {      // uniform trip count for the whole workgroup
-            const uint32_t h = hb + (threadIdx.x >> 4);
-            unsigned long long s = 0ull;
-            if (h < h1 && h < A.n_hubs) {
-                const uint32_t a = A.hub_vbase[h], b = A.hub_vbase[h + 1];
-                for (uint32_t i = a + sub; i < b && i < A.n_vrows; i += 16) s += A.vacc[i];
+        const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
+        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_gather + t] = total;
+    }
+    const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
+    for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
+        const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
+        __syncthreads();                                   // slice filled / previous batch consumed
+        uint32_t groups = 0;
+        if (threadIdx.x < nb) {
+            uint2 d = qb == 0 ? d_first : A.bins[(uint64_t)t * Qe + qb + threadIdx.x];
+            if (d.y > A.M) d.y = A.M;
+            if (d.x > d.y) d.x = d.y;
+            desc[threadIdx.x] = d;
+            if (d.y > d.x) groups = (d.y - 1) / kGroup - d.x / kGroup + 1;
+        }
+        block_exclusive_scan(groups, gpre, wave_tot);
+        const uint32_t total = gpre[kScatterBlock];
+        constexpr int kAhead = FR_AHEAD;                         // groups a thread has in flight
+        for (uint32_t k0 = threadIdx.x; k0 < total; k0 += kAhead * kScatterBlock) {
+            GroupRef ref[kAhead];
+            uint4 raw[kAhead];
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const uint32_t k = k0 + a * kScatterBlock;
+                ref[a] = GroupRef{0, 0};
+                raw[a] = make_uint4(0, 0, 0, 0);
+                if (k < total) { ref[a] = locate_group(k, gpre, desc, nb); raw[a] = src8[ref[a].m0 / kGroup]; }
             }
 #pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) s += (unsigned long long)__shfl_xor((long long)s, off, 64);
-            if (h < h1 && h < A.n_hubs && sub == 0) {
-                const int64_t v = A.hub_row[h];
-                const float inv = inv_of_tag(A.inv_tag[v]);
-                const float r = fmaf(A.damping, (float)s * kFixInv, base);
-                if (v >= v0 && v < v0 + (int64_t)n) slice[v - v0] = r * inv;
-                dangling += (inv == 0.0f ? r : 0.0f);
-            }
-        }
-        const float total = block_sum(dangling, red + 8);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.Q + p] = total;
-    }
-    const uint32_t Q = A.Q;
-    for (uint32_t qb = 0; qb < Q; qb += kDescBatch) {
-        const uint32_t nb = Q - qb < kDescBatch ? Q - qb : kDescBatch;
-        __syncthreads();                                   // slice loaded / previous batch consumed
-        for (uint32_t i = threadIdx.x; i < nb; i += kScatterBlock) {
-            uint2 b = A.bins[(uint64_t)p * Q + qb + i];
-            if (b.y > A.M) b.y = A.M;
-            if (b.x > b.y) b.x = b.y;
-            desc[i] = b;
-        }
-        __syncthreads();
-        switch (A.scatter_shape) {
-        case kShape_64x4: scatter_bins<64, 4>(A.src16, A.msg, desc, nb, slice, n); break;
-        case kShape_32x4: scatter_bins<32, 4>(A.src16, A.msg, desc, nb, slice, n); break;
-        case kShape_32x2: scatter_bins<32, 2>(A.src16, A.msg, desc, nb, slice, n); break;
-        default: scatter_bins<64, 8>(A.src16, A.msg, desc, nb, slice, n); break;
+            for (int a = 0; a < kAhead; ++a)
+                if (k0 + a * kScatterBlock < total) emit_group(ref[a], desc, raw[a], slice, n, A.msg);
         }
     }
     fr_gate_done(G.gate);
@@ -308,9 +411,9 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-// One workgroup per destination partition; its accumulators (one u64 per row, plus the spare slots for hubs'
-// virtual rows) sit in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
-// three-stage software pipeline over the wavefront's chunks, so that no step waits on a load it has just issued:
+// One workgroup per gather tile; the accumulators of its range (one u64 per row) sit in LDS.  Per step a
+// wavefront takes one chunk of 512 ids (8 per lane).  The loop is a three-stage software pipeline over the
+// wavefront's chunks, so that no step waits on a load it has just issued:
 //   A  ids and message base of chunk i + 2 are requested;
 //   B  chunk i + 1 (ids now here): ballots of the message-start flags tell every id which message it belongs
 //      to; the messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
@@ -318,25 +421,27 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 //      accumulator with an LDS atomic.
 // The sweep is bound by vector instruction issue, not by memory (about 30 instructions per 64 edges when every id
 // is checked), so chunks that lie wholly inside the partition's edge range and whose messages cannot pass the end
-// of the message array - all but the first and last chunk of a partition - take a path without per-id checks:
+// of the message array - all but the first and last chunk of a range - take a path without per-id checks:
 // ids out of range (which a sound layout never holds) are sent to a sink slot behind the accumulators.
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 template <uint32_t kRowsPerPart>
 __global__ __launch_bounds__(kGatherBlock) __attribute__((amdgpu_waves_per_eu(kRowsPerPart == kRowsSmall ? 8 : 4, kRowsPerPart == kRowsSmall ? 8 : 4)))
 void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
 {
-    constexpr uint32_t kAccSlots = kRowsPerPart + kMaxVrowsPerPart;
+    constexpr uint32_t kAccSlots = kRowsPerPart;
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[32];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t q = tile0 + blockIdx.x;
+    const uint32_t t = tile0 + blockIdx.x;
+    const GatherTile T = A.gather_tiles[t];
+    const uint32_t q = T.range;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
     for (uint32_t i = threadIdx.x; i < kAccSlots + 1; i += kGatherBlock) acc[i] = 0ull;
     const float d_part = dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     __syncthreads();
 
-    const uint32_t e0 = A.eoff[q], e1 = A.eoff[q + 1];
+    const uint32_t e0 = T.e0, e1 = T.e1 < (uint64_t)A.E ? T.e1 : (uint32_t)A.E;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (e1 > e0) {
         const uint32_t c0 = e0 / kIdChunk, c1 = (e1 - 1) / kIdChunk;
@@ -346,31 +451,39 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
         uint4 rawA = make_uint4(0, 0, 0, 0);
         uint32_t mbA = 0;
         if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
-        // stage B's result, waiting for stage C
-        uint4 rawP = make_uint4(0, 0, 0, 0);
-        float valP[8];
+        // Stage B's result, waiting for stage C.  There are two of these and the loop below is written out twice with
+        // their roles exchanged: copying one into the other at the end of a step would make the step wait for the
+        // messages it has just asked for.
+        struct Pending {
+            uint4 raw;
+            float val[8];
+            uint32_t ok;             // per-id validity bits of a checked chunk
+            bool fast;               // the chunk took the unchecked path (wavefront-uniform)
+        };
+        Pending X, Y;
+        X.ok = 0; X.fast = false; Y.ok = 0; Y.fast = false;
+        X.raw = make_uint4(0, 0, 0, 0); Y.raw = make_uint4(0, 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) valP[j] = 0.0f;
-        uint32_t okP = 0;            // per-id validity bits of a checked chunk
-        bool fastP = false;          // the chunk took the unchecked path (wavefront-uniform)
-        while (cA <= c1) {
-            // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a
-            // fixed j the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set
-            // bits below the lane tells every id how many messages have begun up to it.
-            float valN[8];
-            uint32_t okN = 0;
+        for (int j = 0; j < 8; ++j) { X.val[j] = 0.0f; Y.val[j] = 0.0f; }
+
+        // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a fixed j
+        // the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set bits below the
+        // lane tells every id how many messages have begun up to it.
+        auto stage_b = [&](Pending& S) {
+            S.raw = rawA;
+            S.ok = 0;
             const uint32_t mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)mbA);
             const uint64_t first = (uint64_t)cA * kIdChunk;
             // mb >= 1: an id without a flag then still has a message before it (index >= 0 below)
-            const bool fast = first >= e0 && first + kIdChunk <= e1 && mb >= 1 && (uint64_t)mb + kIdChunk <= A.M;
-            if (fast) {
+            S.fast = first >= e0 && first + kIdChunk <= e1 && mb >= 1 && (uint64_t)mb + kIdChunk <= A.M;
+            if (S.fast) {
                 uint32_t begun_m1 = mb - 1u;                               // messages begun before row j, minus one
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t f = id_of(rawA, j) >> 15;
                     const unsigned long long ballot = __ballot(f != 0);
                     const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
-                    valN[j] = A.msg[begun_m1 + below + f];                 // in [mb - 1, mb + 511], inside [0, M)
+                    S.val[j] = A.msg[begun_m1 + below + f];                // in [mb - 1, mb + 511], inside [0, M)
                     begun_m1 += (uint32_t)__popcll(ballot);
                 }
             } else {
@@ -386,115 +499,113 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
                     begun += (uint32_t)__popcll(ballot);
                     const uint32_t e = ebase + 64 * j;
                     const bool ok = e >= e0 && e < e1 && (id & kLocalMask) < kAccSlots && mi < A.M;
-                    okN |= (ok ? 1u : 0u) << j;
-                    valN[j] = A.msg[ok ? mi : 0u];
+                    S.ok |= (ok ? 1u : 0u) << j;
+                    S.val[j] = A.msg[ok ? mi : 0u];
                 }
             }
-            const uint4 rawN = rawA;
-            // ---- stage A on this wavefront's next chunk
+        };
+        // ---- stage A on this wavefront's next chunk
+        auto stage_a = [&]() {
             cA += kGatherWaves;
             if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
-            else rawA = make_uint4(0, 0, 0, 0);
-            // ---- stage C on the previous chunk
-            if (fastP) {
+        };
+        // ---- stage C: the chunk's ids add their messages; leaves S empty
+        auto stage_c = [&](Pending& S) {
+            if (S.fast) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t local = id_of(rawP, j) & kLocalMask;
-                    atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(valP[j]));
+                    const uint32_t local = id_of(S.raw, j) & kLocalMask;
+                    atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(S.val[j]));
                 }
-            } else {
+            } else if (S.ok) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if ((okP >> j) & 1u) atomicAdd(&acc[id_of(rawP, j) & kLocalMask], to_fixed(valP[j]));
+                    if ((S.ok >> j) & 1u) atomicAdd(&acc[id_of(S.raw, j) & kLocalMask], to_fixed(S.val[j]));
             }
-            rawP = rawN;
-            okP = okN;
-            fastP = fast;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) valP[j] = valN[j];
+            S.fast = false; S.ok = 0;
+        };
+        while (cA <= c1) {
+            stage_b(X);
+            stage_a();
+            stage_c(Y);
+            if (cA > c1) break;
+            stage_b(Y);
+            stage_a();
+            stage_c(X);
         }
-        // drain: stage C on the last chunk
-        if (fastP) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t local = id_of(rawP, j) & kLocalMask;
-                atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(valP[j]));
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if ((okP >> j) & 1u) atomicAdd(&acc[id_of(rawP, j) & kLocalMask], to_fixed(valP[j]));
-        }
+        stage_c(X);          // drain: at most one of the two still holds a chunk
+        stage_c(Y);
     }
     __syncthreads();
 
-    // virtual rows dealt to this partition: hv = q + slot * Q
-    for (uint32_t slot = threadIdx.x; slot < kMaxVrowsPerPart; slot += kGatherBlock) {
-        const uint64_t hv = (uint64_t)q + (uint64_t)slot * A.Q;
-        if (hv < A.n_vrows) A.vacc[hv] = acc[kRowsPerPart + slot];
-    }
-    // fused vertex pass for the partition's own rows
     const float D = dangling_finish(d_part, red);
+    float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
+    if (t == 0 && !final_pass)                                  // slots no tile writes
+        for (uint32_t i = A.n_gather + A.n_scatter + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
+    if (T.partial != kNoPartial) {
+        // merged range: the sums go out as one row of partial sums; the next scatter sweep (or F) finishes the rows
+        float* out = A.partials + (size_t)T.partial * kRowsPerPart;
+        for (uint32_t i = threadIdx.x; i < kRowsPerPart; i += kGatherBlock) out[i] = (float)acc[i] * kFixInv;
+        if (threadIdx.x == 0 && !final_pass) dnext[t] = 0.0f;
+        fr_gate_done(G.gate);
+        return;
+    }
+    // direct range: fused vertex pass for its rows
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     const int64_t v0 = (int64_t)q * kRowsPerPart;
     float dangling = 0.0f;
     constexpr int kRowsPerThread = (kRowsPerPart + kGatherBlock - 1) / kGatherBlock;
-    float tag[kRowsPerThread];
+    if (final_pass) {
 #pragma unroll
-    for (int t = 0; t < kRowsPerThread; ++t) {
-        const uint32_t i = threadIdx.x + kGatherBlock * t;
-        tag[t] = i < nrows ? A.inv_tag[v0 + i] : -0.0f;           // rows past the end behave like hubs: skipped
-    }
-#pragma unroll
-    for (int t = 0; t < kRowsPerThread; ++t) {
-        const uint32_t i = threadIdx.x + kGatherBlock * t;
-        if (i >= nrows || is_hub_tag(tag[t])) continue;            // hubs are finished by H_k
-        const float s = (float)acc[i] * kFixInv;
-        const float r = fmaf(A.damping, s, base);
-        if (final_pass) A.ranks_out[v0 + i] = r;
-        else {
-            A.contrib[v0 + i] = r * tag[t];
-            dangling += (tag[t] == 0.0f ? r : 0.0f);
+        for (int k = 0; k < kRowsPerThread; ++k) {
+            const uint32_t i = threadIdx.x + kGatherBlock * k;
+            if (i < nrows) A.ranks_out[A.perm[v0 + i]] = fmaf(A.damping, (float)acc[i] * kFixInv, base);
         }
-    }
-    if (!final_pass) {
+    } else {
+        float inv[kRowsPerThread];
+#pragma unroll
+        for (int k = 0; k < kRowsPerThread; ++k) {
+            const uint32_t i = threadIdx.x + kGatherBlock * k;
+            inv[k] = i < nrows ? A.inv_out[v0 + i] : 1.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < kRowsPerThread; ++k) {
+            const uint32_t i = threadIdx.x + kGatherBlock * k;
+            if (i >= nrows) continue;
+            const float r = fmaf(A.damping, (float)acc[i] * kFixInv, base);
+            A.contrib[v0 + i] = r * inv[k];
+            dangling += (inv[k] == 0.0f ? r : 0.0f);
+        }
         const float total = block_sum(dangling, red + 8);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + q] = total;
+        if (threadIdx.x == 0) dnext[t] = total;
     }
     fr_gate_done(G.gate);
 }
 
-// ---- H_k ----
-// 16 hubs per workgroup, 16 lanes per hub: the lanes add up the hub's virtual rows (integers, any order), the
-// group's first lane applies the vertex-pass arithmetic.
-__global__ __launch_bounds__(256) void k_hubfin(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
+// ---- F ----
+// After the last iteration: r_K of kFinishRows rows of one merged range (partial sums of G_{K-1}) or of one empty
+// range (the base value) goes to ranks_out.
+constexpr uint32_t kFinishRows = 2048;
+__global__ __launch_bounds__(kBlock) void k_finish(DevArgs A, GateArg G, uint32_t tile0, int parity)
 {
-    __shared__ float red[24];
+    __shared__ float red[8];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t t = tile0 + blockIdx.x;
     const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
-    const uint32_t h = t * kHubsPerTile + (threadIdx.x >> 4);
-    const uint32_t sub = threadIdx.x & 15;
-    float dangling = 0.0f;
-    unsigned long long s = 0ull;
-    if (h < A.n_hubs) {
-        const uint32_t a = A.hub_vbase[h], b = A.hub_vbase[h + 1];
-        for (uint32_t i = a + sub; i < b && i < A.n_vrows; i += 16) s += A.vacc[i];
-    }
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) s += (unsigned long long)__shfl_xor((long long)s, off, 64);
-    if (h < A.n_hubs && sub == 0) {
-        const int32_t v = A.hub_row[h];
-        const float inv = inv_of_tag(A.inv_tag[v]);
-        const float r = fmaf(A.damping, (float)s * kFixInv, base);
-        if (final_pass) A.ranks_out[v] = r;
-        else {
-            A.contrib[v] = r * inv;
-            dangling = (inv == 0.0f ? r : 0.0f);
+    const uint32_t per_range = A.rows_per_part / kFinishRows;
+    if (t / per_range < A.n_finish) {
+        const uint32_t q = A.finish_ranges[t / per_range];
+        const RangeInfo info = A.range_info[q];
+        const bool merged = (info.cls_tiles & 3u) == kRangeMerged;
+        const int64_t v0 = (int64_t)q << A.rows_shift;
+        for (uint32_t k = threadIdx.x; k < kFinishRows; k += kBlock) {
+            const uint32_t i = (t % per_range) * kFinishRows + k;
+            const int64_t v = v0 + i;
+            if (v >= A.V) break;
+            A.ranks_out[A.perm[v]] = merged ? fmaf(A.damping, merged_sum<1>(A, info, i, 0), base) : base;
         }
     }
-    (void)dangling;          // H only runs after the last iteration: nothing reads its dangling sum
     fr_gate_done(G.gate);
 }
 
@@ -511,8 +622,7 @@ struct PrTask {
     PrLayout L;
     std::vector<uint64_t> prefix[4];      // cumulative modelled tile costs per segment kind (after init)
     uint64_t footprint_after = 0, footprint_peak = 0;
-    float *msg = nullptr, *contrib = nullptr, *dpart = nullptr;
-    unsigned long long* vacc = nullptr;
+    float *msg = nullptr, *contrib = nullptr, *dpart = nullptr, *partials = nullptr;
     uint32_t n_dpart = 0;
     DevArgs args{};
     bool inited = false;
@@ -521,21 +631,21 @@ struct PrTask {
     int hip_error = 0;
     uint32_t run = 0, seg = 0, tile = 0;  // cursor
 
-    // V0, then S_k G_k for k < K, then H (no S, G, H at all when K = 0)
+    // V0, then S_k G_k for k < K, then F (no S, G, F at all when K = 0)
     uint32_t n_segments() const { return d.iterations == 0 ? 1u : 2u + 2u * (uint32_t)d.iterations; }
     int kind_of(uint32_t g) const
     {
         if (g == 0) return FR_PR_SEG_VERTEX;
-        if (g + 1 == n_segments()) return FR_PR_SEG_HUBFIN;
+        if (g + 1 == n_segments()) return FR_PR_SEG_FINISH;
         return ((g - 1) & 1u) ? FR_PR_SEG_GATHER : FR_PR_SEG_SCATTER;
     }
     uint32_t tiles_of(int kind) const
     {
         switch (kind) {
         case FR_PR_SEG_VERTEX: return L.Q;
-        case FR_PR_SEG_SCATTER: return L.P;
-        case FR_PR_SEG_GATHER: return L.Q;
-        default: return L.n_hub_tiles;
+        case FR_PR_SEG_SCATTER: return L.n_scatter;
+        case FR_PR_SEG_GATHER: return L.n_gather;
+        default: return std::max<uint32_t>(1, L.n_finish * (L.rows_per_part / kFinishRows));
         }
     }
     uint64_t rows_of_q(uint32_t q) const
@@ -552,18 +662,21 @@ void build_cost_tables(PrTask* p)
     v.assign(L.Q + 1, 0);
     for (uint32_t q = 0; q < L.Q; ++q) v[q + 1] = v[q] + ceil_fs_to_ns((unsigned __int128)p->rows_of_q(q) * pv);
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
-    s.assign(L.P + 1, 0);
-    for (uint32_t i = 0; i < L.P; ++i) {
-        const uint64_t srcs = std::min<uint64_t>(L.src_per_part, (uint64_t)L.V - (uint64_t)i * L.src_per_part);
-        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.msgs_of_p[i] * pm + (unsigned __int128)srcs * pv);
+    s.assign(L.n_scatter + 1, 0);
+    for (uint32_t i = 0; i < L.n_scatter; ++i) {
+        const uint64_t srcs = (uint64_t)L.st[i].u1 - L.st[i].u0 + L.st_partials[i];     // a partial sum costs about a vertex
+        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.st_msgs[i] * pm + (unsigned __int128)srcs * pv);
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
-    g.assign(L.Q + 1, 0);
-    for (uint32_t q = 0; q < L.Q; ++q)
-        g[q + 1] = g[q] + ceil_fs_to_ns((unsigned __int128)L.edges_of_q[q] * pe + (unsigned __int128)p->rows_of_q(q) * pv);
-    auto& h = p->prefix[FR_PR_SEG_HUBFIN];
-    h.assign(L.n_hub_tiles + 1, 0);
-    for (uint32_t t = 0; t < L.n_hub_tiles; ++t) h[t + 1] = h[t] + std::max<uint64_t>(1, p->d.hubfin_tile_ns);
+    const uint32_t ng = p->tiles_of(FR_PR_SEG_GATHER);
+    g.assign(ng + 1, 0);
+    for (uint32_t t = 0; t < ng; ++t) {
+        g[t + 1] = g[t] + ceil_fs_to_ns((unsigned __int128)L.gt_weight[t] * pe + (unsigned __int128)L.rows_per_part * pv);
+    }
+    auto& h = p->prefix[FR_PR_SEG_FINISH];
+    const uint32_t nf = p->tiles_of(FR_PR_SEG_FINISH);
+    h.assign(nf + 1, 0);
+    for (uint32_t t = 0; t < nf; ++t) h[t + 1] = h[t] + std::max<uint64_t>(1, p->d.finish_tile_ns);
 }
 
 int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0})
@@ -574,12 +687,12 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
     const uint32_t K = (uint32_t)p->d.iterations;
     if (kind == FR_PR_SEG_VERTEX) {
         hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, p->args, G, tile0, K == 0 ? 1 : 0);
-    } else if (kind == FR_PR_SEG_HUBFIN) {
+    } else if (kind == FR_PR_SEG_FINISH) {
         // after G_{K-1}: the dangling partials of r_{K-1} sit in set (K-1) & 1
-        hipLaunchKernelGGL(k_hubfin, dim3(n), dim3(256), 0, stream, p->args, G, tile0, (int)((K - 1) & 1u), 1);
+        hipLaunchKernelGGL(k_finish, dim3(n), dim3(kBlock), 0, stream, p->args, G, tile0, (int)((K - 1) & 1u));
     } else {
         const uint32_t k = (g - 1) / 2;
-        if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes the hubs of r_k with D_{k-1}: set (k-1) & 1
+        if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes rows of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
             if (p->L.src_per_part == kSrcLarge)
                 hipLaunchKernelGGL(k_scatter<kSrcLarge>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
@@ -596,18 +709,6 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
     return FR_OK;
-}
-
-// Shape of the scatter sweep's inner loop (lanes per bin x messages per lane): the smallest step, L * T
-// messages, that covers an average bin with a third to spare (measured: 27-message bins run fastest as 32 x 2,
-// 94-message bins as 32 x 4, 305-message bins as 64 x 8).
-uint32_t scatter_shape_for(uint64_t messages, uint64_t bins)
-{
-    const uint64_t want = bins ? 4 * (messages / bins) / 3 : 0;
-    if (want <= 64) return kShape_32x2;
-    if (want <= 128) return kShape_32x4;
-    if (want <= 256) return kShape_64x4;
-    return kShape_64x8;
 }
 
 template <typename T>
@@ -630,18 +731,21 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
                              p->d.sources_per_partition, a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
-    p->n_dpart = L.Q + L.P;                  // one slot per gather tile, one per scatter tile (its hubs)
+    // dangling partials: one slot per range (V0), or one per gather tile followed by one per scatter tile
+    p->n_dpart = std::max(L.Q, L.n_gather + L.n_scatter);
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
-        !take(a, &p->vacc, (uint64_t)L.n_vrows))
+        !take(a, &p->partials, (uint64_t)L.n_partials * L.rows_per_part))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
     DevArgs& A = p->args;
-    A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.P = L.P; A.n_hubs = L.n_hubs; A.n_vrows = L.n_vrows;
+    A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.Qe = L.Qe;
+    A.n_gather = L.n_gather; A.n_scatter = L.n_scatter; A.n_finish = L.n_finish;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
-    A.scatter_shape = scatter_shape_for(L.M, (uint64_t)L.P * L.Q);
-    A.rows_per_part = L.rows_per_part; A.src_per_part = L.src_per_part;
-    A.ids16 = L.ids16; A.src16 = L.src16; A.eoff = L.eoff; A.mbase = L.mbase; A.bins = L.bins;
-    A.hub_row = L.hub_row; A.hub_vbase = L.hub_vbase; A.hub_of_p = L.hub_of_p; A.inv_tag = L.inv_tag;
-    A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.vacc = p->vacc; A.ranks_out = p->d.ranks_out;
+    A.rows_per_part = L.rows_per_part;
+    A.rows_shift = L.rows_per_part == kRowsLarge ? 14 : 13;
+    A.ids16 = L.ids16; A.src16 = L.src16; A.mbase = L.mbase; A.bins = L.bins;
+    A.inv_out = L.inv_out; A.perm = L.perm; A.range_info = L.range_info;
+    A.gather_tiles = L.gather_tiles; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
+    A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.partials = p->partials; A.ranks_out = p->d.ranks_out;
     build_cost_tables(p);
     p->footprint_after = fr_alloc_used(a);
     p->footprint_peak = fr_alloc_peak(a);
@@ -676,7 +780,7 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     if (kind == FR_PR_SEG_GATHER) {
         uint64_t edges = 0;
-        for (uint32_t q = p->tile; q < p->tile + n; ++q) edges += p->L.edges_of_q[q];
+        for (uint32_t t = p->tile; t < p->tile + n && t < p->L.n_gather; ++t) edges += (uint64_t)p->L.gt[t].e1 - p->L.gt[t].e0;
         out->work_units = edges;
     }
     out->completes_run = (p->seg + 1 == p->n_segments() && out->tile1 == p->tiles_of(kind)) ? 1 : 0;
@@ -733,7 +837,7 @@ int fr_pagerank_make(const fr_pagerank_desc* d, fr_task_ops* ops_out, void** use
     if (!p->d.fs_per_edge) p->d.fs_per_edge = 2000;
     if (!p->d.fs_per_message) p->d.fs_per_message = 2000;
     if (!p->d.fs_per_vertex) p->d.fs_per_vertex = 4000;
-    if (!p->d.hubfin_tile_ns) p->d.hubfin_tile_ns = 2000;
+    if (!p->d.finish_tile_ns) p->d.finish_tile_ns = 2000;
     ops_out->create = pr_create;
     ops_out->init = pr_init;
     ops_out->plan_step = pr_plan;
@@ -766,13 +870,14 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out)
     if (p->prefix[0].empty()) return FR_ERR_STATE;       // known once InitSideTask has run
     std::memset(out, 0, sizeof(*out));
     out->messages = p->L.M;
-    out->partitions = p->L.Q;
-    out->hub_split = p->L.hub_split;
+    out->ranges = p->L.Q;
+    out->nonempty_ranges = p->L.Qe;
+    out->merged_ranges = p->L.n_merged;
+    out->partial_rows = p->L.n_partials;
+    out->gather_tiles = p->L.n_gather;
+    out->scatter_tiles = p->L.n_scatter;
     out->rows_per_partition = p->L.rows_per_part;
     out->sources_per_partition = p->L.src_per_part;
-    out->source_partitions = p->L.P;
-    out->hubs = p->L.n_hubs;
-    out->virtual_rows = p->L.n_vrows;
     out->bytes_resident = p->footprint_after;
     out->bytes_peak = p->footprint_peak;
     return FR_OK;
@@ -806,10 +911,26 @@ int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work, size_t c
     if (p->prefix[0].empty()) return FR_ERR_STATE;
     const size_t n = p->tiles_of(seg_kind);
     for (size_t t = 0; t < std::min(n, cap); ++t) {
-        if (seg_kind == FR_PR_SEG_GATHER) work[t] = p->L.edges_of_q[t];
-        else if (seg_kind == FR_PR_SEG_SCATTER) work[t] = p->L.msgs_of_p[t];
+        if (seg_kind == FR_PR_SEG_GATHER) work[t] = t < p->L.n_gather ? (uint64_t)p->L.gt[t].e1 - p->L.gt[t].e0 : 0;
+        else if (seg_kind == FR_PR_SEG_SCATTER) work[t] = p->L.st_msgs[t];
         else if (seg_kind == FR_PR_SEG_VERTEX) work[t] = p->rows_of_q((uint32_t)t);
         else work[t] = 0;
+    }
+    *n_out = n;
+    return FR_OK;
+}
+
+int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights, size_t cap, size_t* n_out)
+{
+    PrTask* p = static_cast<PrTask*>(user);
+    if (!p || !n_out || seg_kind < 0 || seg_kind > 3 || (!weights && cap)) return FR_ERR_ARG;
+    if (p->prefix[0].empty()) return FR_ERR_STATE;
+    const size_t n = p->tiles_of(seg_kind);
+    for (size_t t = 0; t < std::min(n, cap); ++t) {
+        if (seg_kind == FR_PR_SEG_GATHER) weights[t] = p->L.gt_weight[t];
+        else if (seg_kind == FR_PR_SEG_SCATTER) weights[t] = (uint64_t)p->L.st[t].u1 - p->L.st[t].u0 + p->L.st_partials[t];
+        else if (seg_kind == FR_PR_SEG_VERTEX) weights[t] = p->rows_of_q((uint32_t)t);
+        else weights[t] = 0;
     }
     *n_out = n;
     return FR_OK;

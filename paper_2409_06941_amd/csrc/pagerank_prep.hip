@@ -1,10 +1,11 @@
 // Builds the partition-centric layout (pr_layout.h) of the PageRank side task on the GPU, once, in InitSideTask
 // (Section 4.1 of the paper: the transition that loads the task's context into GPU memory).
 //
-// Pipeline: check the CSR -> mark hubs and number their virtual rows (scan) -> one 64-bit key per edge
-// (partition, source, local row) -> radix sort -> message starts (flags, scan) -> id stream, message sources,
-// per-partition offsets, per-bin message ranges.  rocPRIM supplies the device-wide sort and scans; they run
-// once per task and are not part of any iteration.
+// Pipeline: check the CSR -> order the vertices by in-degree (radix sort; perm and its inverse) -> one 64-bit key
+// per edge (range, source, local row) in new ids -> radix sort -> message starts (flags, scan) -> messages per
+// source (histogram, scan) -> scatter tiles (host) -> id stream, message sources, edge offsets of the ranges ->
+// gather tiles and range classes (host) -> message range of every (scatter tile, range).  rocPRIM supplies the
+// device-wide sorts and scans; they run once per task and are not part of any iteration.
 
 #include <cstring>
 
@@ -53,66 +54,38 @@ __global__ __launch_bounds__(kBlk) void k_validate(int64_t V, int64_t E, const i
     if (err) *bad = 1;
 }
 
-// packed[v] = (virtual rows of v) << 32 | (1 if v is a hub)
-__global__ __launch_bounds__(kBlk) void k_hub_mark(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ packed)
+// Sort key of a vertex: larger in-degree first, ties by the caller's id.
+__global__ __launch_bounds__(kBlk) void k_vertex_keys(int64_t V, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ keys)
 {
     const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (v >= V) return;
     const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
-    const bool hub = indeg > split;
-    const uint64_t nsplit = hub ? ((uint64_t)indeg + split - 1) / split : 0;
-    packed[v] = (nsplit << 32) | (hub ? 1u : 0u);
+    keys[v] = ((uint64_t)(0x7fffffffu - indeg) << 32) | (uint64_t)(uint32_t)v;
 }
 
-__global__ __launch_bounds__(kBlk) void k_hub_tables(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr,
-                                                     const uint64_t* __restrict__ scanned, uint32_t n_hubs,
-                                                     uint32_t n_vrows, int32_t* __restrict__ hub_row,
-                                                     uint32_t* __restrict__ hub_vbase)
+// perm[new] = old, inv[old] = new, inv_out[new] = 1/outdeg (0 for dangling vertices)
+__global__ __launch_bounds__(kBlk) void k_perm(int64_t V, const uint64_t* __restrict__ sorted, const int32_t* __restrict__ outdeg,
+                                               int32_t* __restrict__ perm, int32_t* __restrict__ inv, float* __restrict__ inv_out)
 {
-    const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
-    if (v == 0) hub_vbase[n_hubs] = n_vrows;
-    if (v >= V) return;
-    const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
-    if (indeg <= split) return;
-    const uint32_t h = (uint32_t)(scanned[v] & 0xffffffffu);
-    if (h < n_hubs) {
-        hub_row[h] = (int32_t)v;
-        hub_vbase[h] = (uint32_t)(scanned[v] >> 32);
-    }
+    const int64_t n = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (n >= V) return;
+    uint32_t old = (uint32_t)(sorted[n] & 0xffffffffu);
+    if ((int64_t)old >= V) old = 0;                    // cannot happen: the keys hold 0 .. V-1
+    perm[n] = (int32_t)old;
+    inv[old] = (int32_t)n;
+    const int32_t d = outdeg[old];
+    inv_out[n] = d > 0 ? 1.0f / (float)d : 0.0f;
 }
 
-// 1/outdeg (0 for dangling vertices) with the sign bit marking hub rows.
-__global__ __launch_bounds__(kBlk) void k_inv_tag(int64_t V, uint32_t split, const int32_t* __restrict__ row_ptr,
-                                                  const int32_t* __restrict__ outdeg, float* __restrict__ inv_tag)
-{
-    const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
-    if (v >= V) return;
-    const int32_t d = outdeg[v];
-    float inv = d > 0 ? 1.0f / (float)d : 0.0f;
-    if ((uint32_t)(row_ptr[v + 1] - row_ptr[v]) > split) inv = __uint_as_float(__float_as_uint(inv) | 0x80000000u);
-    inv_tag[v] = inv;
-}
-
-// Virtual row hv of a hub goes to partition hv % Q, accumulator slot rows_per_part + hv / Q.
-__global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, uint32_t split, const int32_t* __restrict__ row_ptr,
-                                               const int32_t* __restrict__ col, const uint64_t* __restrict__ scanned,
-                                               uint32_t Q, uint32_t rows_per_part, uint64_t* __restrict__ keys)
+__global__ __launch_bounds__(kBlk) void k_keys(int64_t V, int64_t E, const int32_t* __restrict__ row_ptr,
+                                               const int32_t* __restrict__ col, const int32_t* __restrict__ inv,
+                                               uint32_t rows_per_part, uint64_t* __restrict__ keys)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= E) return;
-    const int32_t v = row_of_edge(row_ptr, V, e);
-    const int64_t begin = row_ptr[v];
-    const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - begin);
-    uint64_t q, local;
-    if (indeg > split) {
-        const uint64_t hv = (scanned[v] >> 32) + (uint64_t)(e - begin) / split;
-        q = hv % Q;
-        local = rows_per_part + hv / Q;
-    } else {
-        q = (uint64_t)v / rows_per_part;
-        local = (uint64_t)v % rows_per_part;
-    }
-    keys[e] = (q << (kKeyLocalBits + kKeySrcBits)) | ((uint64_t)(uint32_t)col[e] << kKeyLocalBits) | local;
+    const uint64_t v = (uint64_t)(uint32_t)inv[row_of_edge(row_ptr, V, e)];
+    const uint64_t u = (uint64_t)(uint32_t)inv[col[e]];
+    keys[e] = ((v / rows_per_part) << (kKeyLocalBits + kKeySrcBits)) | (u << kKeyLocalBits) | (v % rows_per_part);
 }
 
 // 1 where edge e (in sorted order) is the first of its (partition, source) group, i.e. starts a message.
@@ -135,9 +108,36 @@ __device__ __forceinline__ int64_t id_slot(int64_t e)
     return e - r + (r % 64) * (kIdChunk / 64) + r / 64;
 }
 
+// Scatter tile that holds source u: the t with ubound[t] <= u < ubound[t + 1].
+__device__ __forceinline__ uint32_t tile_of_source(const uint32_t* __restrict__ ubound, uint32_t n_tiles, uint32_t u)
+{
+    uint32_t lo = 0, hi = n_tiles;             // first index in [0, n_tiles] whose bound exceeds u
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ubound[mid] > u) hi = mid;
+        else lo = mid + 1;
+    }
+    return lo ? lo - 1 : 0;
+}
+
+// cnt[u] += 1 for every message of source u (set-up only; integer atomics)
+__global__ __launch_bounds__(kBlk) void k_count_messages(int64_t E, int64_t V, const uint64_t* __restrict__ keys, uint32_t* __restrict__ cnt)
+{
+    const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (e >= E || !flag_of(keys, e)) return;
+    const uint32_t u = (uint32_t)((keys[e] >> kKeyLocalBits) & 0x7fffffffu);
+    if ((int64_t)u < V) atomicAdd(&cnt[u], 1u);
+}
+
+__global__ __launch_bounds__(kBlk) void k_zero_u32(uint64_t n, uint32_t* p)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
-                                               const uint32_t* __restrict__ incl, uint32_t src_per_part,
-                                               uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
+                                               const uint32_t* __restrict__ incl, const uint32_t* __restrict__ ubound,
+                                               uint32_t n_tiles, uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= padded) return;
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64
     if (f) {
         const uint64_t m = (uint64_t)incl[e] - 1;
         const uint32_t u = (uint32_t)((k >> kKeyLocalBits) & 0x7fffffffu);
-        if (m < M) src16[m] = (uint16_t)(u % src_per_part);
+        if (m < M) src16[m] = (uint16_t)(u - ubound[tile_of_source(ubound, n_tiles, u)]);
     }
 }
 
@@ -159,6 +159,26 @@ __global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, ui
     if (c > n_chunks) return;
     const int64_t e = (int64_t)c * kIdChunk;
     mbase[c] = e < E ? incl[e] - flag_of(keys, e) : M;
+}
+
+// rep[c] = edges of chunk c that repeat their predecessor (same range, source and row: a multi-edge).  Adjacent in
+// the stream, they hit one accumulator from neighbouring lanes, which the LDS serialises; the tile cutter counts them.
+__global__ __launch_bounds__(kBlk) void k_chunk_repeats(int64_t E, uint32_t n_chunks, const uint64_t* __restrict__ keys,
+                                                        uint32_t* __restrict__ rep)
+{
+    const uint32_t c = blockIdx.x;
+    if (c >= n_chunks) return;
+    __shared__ uint32_t total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    uint32_t mine = 0;
+    for (uint32_t r = threadIdx.x; r < kIdChunk; r += kBlk) {
+        const int64_t e = (int64_t)c * kIdChunk + r;
+        if (e >= 1 && e < E && keys[e] == keys[e - 1]) ++mine;
+    }
+    if (mine) atomicAdd(&total, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) rep[c] = total;
 }
 
 __device__ __forceinline__ int64_t lower_bound_key(const uint64_t* __restrict__ keys, int64_t E, uint64_t target)
@@ -179,48 +199,23 @@ __global__ __launch_bounds__(kBlk) void k_eoff(uint32_t Q, int64_t E, const uint
     eoff[q] = (uint32_t)lower_bound_key(keys, E, (uint64_t)q << (kKeyLocalBits + kKeySrcBits));
 }
 
-// bins[p * Q + q] = message range of the edges of partition q whose source lies in source partition p.
+// bins[t * Qe + j] = message range of the edges of range j whose source lies in scatter tile t.
 // The first edge of a bin always starts a message, so "messages before it" = incl - 1 there.
-__global__ __launch_bounds__(kBlk) void k_bins(uint32_t P, uint32_t Q, int64_t E, uint32_t M, uint64_t src_per_part,
+__global__ __launch_bounds__(kBlk) void k_bins(uint32_t n_tiles, uint32_t Qe, int64_t E, uint32_t M, const uint32_t* __restrict__ ubound,
                                                const uint64_t* __restrict__ keys, const uint32_t* __restrict__ incl,
                                                uint2* __restrict__ bins)
 {
     const uint64_t idx = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
-    if (idx >= (uint64_t)P * Q) return;
-    const uint64_t p = idx / Q, q = idx % Q;
-    const uint64_t base = q << (kKeyLocalBits + kKeySrcBits);
-    const int64_t lo = lower_bound_key(keys, E, base + ((p * src_per_part) << kKeyLocalBits));
-    const int64_t hi = lower_bound_key(keys, E, base + (((p + 1) * src_per_part) << kKeyLocalBits));
+    if (idx >= (uint64_t)n_tiles * Qe) return;
+    const uint64_t t = idx / Qe, j = idx % Qe;
+    const uint64_t base = j << (kKeyLocalBits + kKeySrcBits);
+    const int64_t lo = lower_bound_key(keys, E, base + ((uint64_t)ubound[t] << kKeyLocalBits));
+    const int64_t hi = lower_bound_key(keys, E, base + ((uint64_t)ubound[t + 1] << kKeyLocalBits));
     uint2 r;
     r.x = lo < E ? incl[lo] - 1 : M;
     r.y = hi < E ? incl[hi] - 1 : M;
     if (r.y < r.x) r.y = r.x;
     bins[idx] = r;
-}
-
-// hub_of_p[p] = first hub whose row id is >= p * src_per_part (hub_row is ascending).
-__global__ __launch_bounds__(kBlk) void k_hub_of_p(uint32_t P, uint32_t n_hubs, uint32_t src_per_part, const int32_t* __restrict__ hub_row,
-                                                   uint32_t* __restrict__ hub_of_p)
-{
-    const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
-    if (p > P) return;
-    const int64_t target = (int64_t)p * src_per_part;
-    uint32_t lo = 0, hi = n_hubs;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if ((int64_t)hub_row[mid] < target) lo = mid + 1;
-        else hi = mid;
-    }
-    hub_of_p[p] = lo;
-}
-
-__global__ __launch_bounds__(kBlk) void k_msgs_of_p(uint32_t P, uint32_t Q, const uint2* __restrict__ bins, uint64_t* __restrict__ out)
-{
-    const uint32_t p = blockIdx.x * kBlk + threadIdx.x;
-    if (p >= P) return;
-    uint64_t s = 0;
-    for (uint32_t q = 0; q < Q; ++q) s += bins[(uint64_t)p * Q + q].y - bins[(uint64_t)p * Q + q].x;
-    out[p] = s;
 }
 
 struct Scratch {
@@ -274,7 +269,6 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     L->V = V; L->E = E;
     L->rows_per_part = rows_per_part; L->src_per_part = src_per_part;
     L->Q = (uint32_t)((V + rows_per_part - 1) / rows_per_part);
-    L->P = (uint32_t)((V + src_per_part - 1) / src_per_part);
     L->n_chunks = (uint32_t)((E + kIdChunk - 1) / kIdChunk);
     const int64_t padded = (int64_t)std::max<uint32_t>(L->n_chunks, 1) * kIdChunk;
     const uint32_t Q = L->Q;
@@ -293,45 +287,27 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_HIP(hipStreamSynchronize(stream));
     if (bad_host) return FR_ERR_ARG;
 
-    // ---- hubs and their virtual rows; the split length doubles until the spare slots hold all virtual rows
-    uint64_t* packed = tmp.take<uint64_t>((uint64_t)V);
-    uint64_t* scanned = tmp.take<uint64_t>((uint64_t)V);
-    PREP_NEED(packed); PREP_NEED(scanned);
-    void* scan_tmp = nullptr;
-    size_t scan_bytes = 0;
-    PREP_HIP(rocprim::exclusive_scan(nullptr, scan_bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
-    scan_tmp = tmp.take<uint8_t>(scan_bytes);
-    PREP_NEED(scan_tmp);
-    uint32_t split = kHubSplitMin;
-    for (;;) {
-        hipLaunchKernelGGL(k_hub_mark, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, packed);
-        PREP_HIP(rocprim::exclusive_scan(scan_tmp, scan_bytes, packed, scanned, uint64_t(0), (size_t)V, rocprim::plus<uint64_t>(), stream));
-        uint64_t last_packed = 0, last_scanned = 0;
-        PREP_HIP(hipMemcpyAsync(&last_packed, packed + (V - 1), 8, hipMemcpyDeviceToHost, stream));
-        PREP_HIP(hipMemcpyAsync(&last_scanned, scanned + (V - 1), 8, hipMemcpyDeviceToHost, stream));
+    // ---- vertices in order of falling in-degree
+    if (!keep(a, &L->perm, (uint64_t)V) || !keep(a, &L->inv_out, (uint64_t)V)) PREP_NEED((void*)nullptr);
+    int32_t* inv = tmp.take<int32_t>((uint64_t)V);
+    PREP_NEED(inv);
+    {
+        uint64_t* vk_a = tmp.take<uint64_t>((uint64_t)V);
+        uint64_t* vk_b = tmp.take<uint64_t>((uint64_t)V);
+        PREP_NEED(vk_a); PREP_NEED(vk_b);
+        hipLaunchKernelGGL(k_vertex_keys, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, vk_a);
+        rocprim::double_buffer<uint64_t> db(vk_a, vk_b);
+        size_t bytes = 0;
+        PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, db, (size_t)V, 0u, 64u, stream));
+        void* t = tmp.take<uint8_t>(bytes);
+        PREP_NEED(t);
+        PREP_HIP(rocprim::radix_sort_keys(t, bytes, db, (size_t)V, 0u, 64u, stream));
+        hipLaunchKernelGGL(k_perm, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, db.current(), out_degree, L->perm, inv, L->inv_out);
         PREP_HIP(hipStreamSynchronize(stream));
-        const uint64_t totals = last_packed + last_scanned;
-        L->n_hubs = (uint32_t)(totals & 0xffffffffu);
-        L->n_vrows = (uint32_t)(totals >> 32);
-        if ((uint64_t)L->n_vrows <= (uint64_t)kMaxVrowsPerPart * Q) break;
-        if (split >= 0x40000000u) return FR_ERR_ARG;       // cannot happen for E < 2^31
-        split *= 2;
+        tmp.drop(t); tmp.drop(vk_a); tmp.drop(vk_b);
     }
-    L->hub_split = split;
-    L->n_hub_tiles = std::max<uint32_t>(1, (L->n_hubs + kHubsPerTile - 1) / kHubsPerTile);
 
-    if (!keep(a, &L->hub_row, L->n_hubs) || !keep(a, &L->hub_vbase, (uint64_t)L->n_hubs + 1) || !keep(a, &L->inv_tag, (uint64_t)V))
-        PREP_NEED((void*)nullptr);
-    hipLaunchKernelGGL(k_hub_tables, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, scanned, L->n_hubs,
-                       L->n_vrows, L->hub_row, L->hub_vbase);
-    hipLaunchKernelGGL(k_inv_tag, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, split, row_ptr, out_degree, L->inv_tag);
-    if (!keep(a, &L->hub_of_p, (uint64_t)L->P + 1)) PREP_NEED((void*)nullptr);
-    hipLaunchKernelGGL(k_hub_of_p, dim3(blocks_for((uint64_t)L->P + 1)), dim3(kBlk), 0, stream, L->P, L->n_hubs, src_per_part, L->hub_row, L->hub_of_p);
-
-    tmp.drop(packed);
-    tmp.drop(scan_tmp);
-
-    // ---- sort the edges by (partition, source, local row); set-up scratch is returned as soon as it is done with
+    // ---- sort the edges by (range, source, local row); set-up scratch is returned as soon as it is done with
     uint64_t* keys = nullptr;
     uint32_t* incl = nullptr;
     uint32_t M = 0;
@@ -339,7 +315,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         uint64_t* keys_a = tmp.take<uint64_t>((uint64_t)E);
         uint64_t* keys_b = tmp.take<uint64_t>((uint64_t)E);
         PREP_NEED(keys_a); PREP_NEED(keys_b);
-        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, split, row_ptr, col, scanned, Q, rows_per_part, keys_a);
+        hipLaunchKernelGGL(k_keys, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, V, E, row_ptr, col, inv, rows_per_part, keys_a);
         unsigned end_bit = kKeyLocalBits + kKeySrcBits;
         while (end_bit < 63 && (1ull << (end_bit - kKeyLocalBits - kKeySrcBits)) < (uint64_t)Q) ++end_bit;
         {
@@ -354,7 +330,6 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             tmp.drop(t);
             tmp.drop(keys == keys_a ? keys_b : keys_a);
         }
-        tmp.drop(scanned);
         incl = tmp.take<uint32_t>((uint64_t)E);
         PREP_NEED(incl);
         {
@@ -364,38 +339,177 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             void* t = tmp.take<uint8_t>(bytes);
             PREP_NEED(t);
             PREP_HIP(rocprim::inclusive_scan(t, bytes, flags, incl, (size_t)E, rocprim::plus<uint32_t>(), stream));
+            PREP_HIP(hipMemcpyAsync(&M, incl + (E - 1), 4, hipMemcpyDeviceToHost, stream));
+            PREP_HIP(hipStreamSynchronize(stream));
+            tmp.drop(t);
         }
-        PREP_HIP(hipMemcpyAsync(&M, incl + (E - 1), 4, hipMemcpyDeviceToHost, stream));
-        PREP_HIP(hipStreamSynchronize(stream));
-    } else {
-        tmp.drop(scanned);
     }
+    tmp.drop(inv);
+    L->M = M;
+
+    // ---- scatter tiles: source intervals of about equal numbers of messages
+    std::vector<uint32_t> cum((size_t)V + 1, 0u);            // messages of the sources before u
+    if (E > 0) {
+        uint32_t* cnt = tmp.take<uint32_t>((uint64_t)V + 1);
+        uint32_t* cum_dev = tmp.take<uint32_t>((uint64_t)V + 1);
+        PREP_NEED(cnt); PREP_NEED(cum_dev);
+        hipLaunchKernelGGL(k_zero_u32, dim3(blocks_for((uint64_t)V + 1)), dim3(kBlk), 0, stream, (uint64_t)V + 1, cnt);
+        hipLaunchKernelGGL(k_count_messages, dim3(blocks_for((uint64_t)E)), dim3(kBlk), 0, stream, E, V, keys, cnt);
+        size_t bytes = 0;
+        PREP_HIP(rocprim::exclusive_scan(nullptr, bytes, cnt, cum_dev, 0u, (size_t)V + 1, rocprim::plus<uint32_t>(), stream));
+        void* t = tmp.take<uint8_t>(bytes);
+        PREP_NEED(t);
+        PREP_HIP(rocprim::exclusive_scan(t, bytes, cnt, cum_dev, 0u, (size_t)V + 1, rocprim::plus<uint32_t>(), stream));
+        PREP_HIP(hipMemcpyAsync(cum.data(), cum_dev, ((size_t)V + 1) * 4, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipStreamSynchronize(stream));
+        tmp.drop(t); tmp.drop(cnt); tmp.drop(cum_dev);
+        if (cum[(size_t)V] != M) return FR_ERR_ARG;
+    }
+    std::vector<uint32_t> ubound;
+    {
+        const uint64_t target = std::max<uint64_t>(kMinTileMessages, ((uint64_t)M + kTilesPerSweep - 1) / kTilesPerSweep);
+        uint64_t u = 0;
+        while (u < (uint64_t)V) {
+            const uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
+            const uint64_t want = (uint64_t)cum[u] + target;
+            uint64_t hi = limit;
+            if ((uint64_t)cum[limit] >= want)
+                hi = (uint64_t)(std::lower_bound(cum.begin() + (long)u + 1, cum.begin() + (long)limit + 1, want,
+                                                 [](uint32_t c, uint64_t w) { return (uint64_t)c < w; }) - cum.begin());
+            ubound.push_back((uint32_t)u);
+            u = hi;
+        }
+        ubound.push_back((uint32_t)V);
+    }
+    L->n_scatter = (uint32_t)ubound.size() - 1;
 
     // ---- the arrays that stay
-    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->eoff, (uint64_t)Q + 1) ||
-        !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->bins, (uint64_t)L->P * Q))
+    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
         PREP_NEED((void*)nullptr);
-    L->M = M;
-    if (!keep(a, &L->src16, (uint64_t)M)) PREP_NEED((void*)nullptr);
-
+    uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
+    uint32_t* eoff = tmp.take<uint32_t>((uint64_t)Q + 1);
+    PREP_NEED(ubound_dev); PREP_NEED(eoff);
+    PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
-                       src_per_part, L->ids16, L->src16);
+                       ubound_dev, L->n_scatter, L->ids16, L->src16);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
-    hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, L->eoff);
-    hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->P * Q)), dim3(kBlk), 0, stream, L->P, Q, E, M, (uint64_t)src_per_part, keys, incl, L->bins);
-    uint64_t* mp = tmp.take<uint64_t>(L->P);
-    PREP_NEED(mp);
-    hipLaunchKernelGGL(k_msgs_of_p, dim3(blocks_for(L->P)), dim3(kBlk), 0, stream, L->P, Q, L->bins, mp);
-    PREP_HIP(hipGetLastError());
-
-    // ---- host copies for the cost model
+    hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, eoff);
     std::vector<uint32_t> eoff_host((size_t)Q + 1);
-    L->msgs_of_p.assign(L->P, 0);
-    PREP_HIP(hipMemcpyAsync(eoff_host.data(), L->eoff, ((size_t)Q + 1) * 4, hipMemcpyDeviceToHost, stream));
-    PREP_HIP(hipMemcpyAsync(L->msgs_of_p.data(), mp, (size_t)L->P * 8, hipMemcpyDeviceToHost, stream));
+    PREP_HIP(hipMemcpyAsync(eoff_host.data(), eoff, ((size_t)Q + 1) * 4, hipMemcpyDeviceToHost, stream));
     PREP_HIP(hipStreamSynchronize(stream));
-    L->edges_of_q.resize(Q);
-    for (uint32_t q = 0; q < Q; ++q) L->edges_of_q[q] = eoff_host[q + 1] - eoff_host[q];
-    if (eoff_host[Q] != (uint32_t)E) return FR_ERR_ARG;
+    if (eoff_host[0] != 0 || eoff_host[Q] != (uint32_t)E) return FR_ERR_ARG;
+
+    // ---- gather tiles and range classes.  Rows are in order of falling in-degree, so the ranges with edges come first.
+    uint32_t Qe = 0;
+    for (uint32_t j = 0; j < Q; ++j)
+        if (eoff_host[j + 1] > eoff_host[j]) Qe = j + 1;
+    if (Qe == 0) Qe = 1;          // a graph without edges: range 0 still gets a (direct) gather tile
+    L->Qe = Qe;
+    // weight of the stream up to every chunk boundary: an edge counts 1, a message kGatherMessageWeight more, a
+    // repeated edge kGatherRepeatWeight more (measured on single tiles: 0.09 ns, 0.18 ns and 0.28 ns a piece)
+    std::vector<uint64_t> wcum((size_t)L->n_chunks + 1, 0);
+    if (E > 0) {
+        uint32_t* rep = tmp.take<uint32_t>((uint64_t)L->n_chunks);
+        PREP_NEED(rep);
+        hipLaunchKernelGGL(k_chunk_repeats, dim3(L->n_chunks), dim3(kBlk), 0, stream, E, L->n_chunks, keys, rep);
+        std::vector<uint32_t> rep_host(L->n_chunks), mbase_host((size_t)L->n_chunks + 1);
+        PREP_HIP(hipMemcpyAsync(rep_host.data(), rep, (size_t)L->n_chunks * 4, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipMemcpyAsync(mbase_host.data(), L->mbase, ((size_t)L->n_chunks + 1) * 4, hipMemcpyDeviceToHost, stream));
+        PREP_HIP(hipStreamSynchronize(stream));
+        tmp.drop(rep);
+        for (uint32_t c = 0; c < L->n_chunks; ++c) {
+            const uint64_t edges = std::min<uint64_t>(kIdChunk, (uint64_t)E - (uint64_t)c * kIdChunk);
+            wcum[c + 1] = wcum[c] + edges + kGatherMessageWeight * (uint64_t)(mbase_host[c + 1] - mbase_host[c]) +
+                          kGatherRepeatWeight * (uint64_t)rep_host[c];
+        }
+    }
+    auto weight_at = [&](uint64_t e) -> uint64_t {          // weight of the edges before e (linear inside a chunk)
+        const uint64_t c = e / kIdChunk;
+        if (c >= L->n_chunks) return wcum[L->n_chunks];
+        const uint64_t held = std::min<uint64_t>(kIdChunk, (uint64_t)E - c * kIdChunk);      // the last chunk may be short
+        return wcum[c] + (wcum[c + 1] - wcum[c]) * std::min(e - c * kIdChunk, held) / held;
+    };
+    L->gt.clear(); L->gt_weight.clear(); L->ri.assign(Q, RangeInfo{kRangeEmpty, 0}); L->fin.clear();
+    L->n_merged = 0; L->n_partials = 0;
+    {
+        // A tile costs its weight plus a fixed part (kTileFixedWeight: the chain of dependent loads at its start and
+        // the row pass at its end).  The target is the share of one of kTilesPerSweep equal tiles; cutting changes
+        // the number of tiles and so the sum, hence the few rounds.
+        std::vector<uint64_t> w(Qe);
+        uint64_t total = 0;
+        for (uint32_t j = 0; j < Qe; ++j) { w[j] = weight_at(eoff_host[j + 1]) - weight_at(eoff_host[j]); total += w[j]; }
+        uint64_t body = 0, n_tiles = Qe;
+        for (int round = 0; round < 8; ++round) {
+            const uint64_t target = (total + n_tiles * kTileFixedWeight + kTilesPerSweep - 1) / kTilesPerSweep;
+            body = std::max<uint64_t>(kMinTileEdges, target > kTileFixedWeight ? target - kTileFixedWeight : 0);
+            uint64_t n = 0;
+            for (uint32_t j = 0; j < Qe; ++j) n += std::max<uint64_t>(1, (w[j] + body - 1) / body);
+            if (n == n_tiles) break;
+            n_tiles = n;
+        }
+        for (uint32_t j = 0; j < Qe; ++j) {
+            const uint64_t e0 = eoff_host[j], e1 = eoff_host[j + 1];
+            const uint64_t nt = std::max<uint64_t>(1, (w[j] + body - 1) / body);
+            std::vector<uint64_t> cuts;                      // chunk boundaries strictly inside (e0, e1)
+            const uint64_t w0 = weight_at(e0);
+            for (uint64_t i = 1; i < nt; ++i) {
+                const uint64_t want = w0 + w[j] * i / nt;
+                const uint64_t c = (uint64_t)(std::lower_bound(wcum.begin(), wcum.end(), want) - wcum.begin());
+                const uint64_t cut = c * kIdChunk;
+                if (cut > (cuts.empty() ? e0 : cuts.back()) && cut < e1) cuts.push_back(cut);
+            }
+            if (cuts.empty()) {
+                L->gt.push_back(GatherTile{j, (uint32_t)e0, (uint32_t)e1, kNoPartial});
+                L->gt_weight.push_back(w[j]);
+                L->ri[j] = RangeInfo{kRangeDirect | (1u << 2), 0};
+                continue;
+            }
+            L->ri[j] = RangeInfo{kRangeMerged | ((uint32_t)(cuts.size() + 1) << 2), L->n_partials};
+            L->fin.push_back(j);
+            L->n_merged++;
+            cuts.push_back(e1);
+            uint64_t lo = e0;
+            for (uint64_t hi : cuts) {
+                L->gt.push_back(GatherTile{j, (uint32_t)lo, (uint32_t)hi, L->n_partials++});
+                L->gt_weight.push_back(weight_at(hi) - weight_at(lo));
+                lo = hi;
+            }
+        }
+        for (uint32_t j = Qe; j < Q; ++j) L->fin.push_back(j);
+    }
+    L->n_gather = (uint32_t)L->gt.size();
+    L->n_finish = (uint32_t)L->fin.size();
+
+    // ---- scatter tiles: partial sums to add up
+    L->st.clear(); L->st_partials.clear();
+    for (uint32_t t = 0; t < L->n_scatter; ++t) {
+        const uint64_t u0 = ubound[t], u1 = ubound[t + 1];
+        uint64_t partials = 0;
+        for (uint64_t j = u0 / rows_per_part; j < Q && j * rows_per_part < u1; ++j) {
+            if ((L->ri[j].cls_tiles & 3u) != kRangeMerged) continue;
+            const uint64_t lo = std::max<uint64_t>(u0, j * rows_per_part), hi = std::min<uint64_t>(u1, (j + 1) * (uint64_t)rows_per_part);
+            partials += (hi - lo) * (L->ri[j].cls_tiles >> 2);
+        }
+        L->st_partials.push_back(partials);
+        L->st.push_back(ScatterTile{(uint32_t)u0, (uint32_t)u1});
+    }
+    L->st_msgs.resize(L->n_scatter);
+    for (uint32_t t = 0; t < L->n_scatter; ++t) L->st_msgs[t] = (uint64_t)cum[ubound[t + 1]] - cum[ubound[t]];
+
+    if (!keep(a, &L->bins, (uint64_t)L->n_scatter * Qe) || !keep(a, &L->range_info, (uint64_t)Q) ||
+        !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||
+        !keep(a, &L->finish_ranges, (uint64_t)L->n_finish))
+        PREP_NEED((void*)nullptr);
+    if (Qe)
+        hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->n_scatter * Qe)), dim3(kBlk), 0, stream, L->n_scatter, Qe, E, M, ubound_dev,
+                           keys, incl, L->bins);
+    PREP_HIP(hipGetLastError());
+    PREP_HIP(hipMemcpyAsync(L->range_info, L->ri.data(), (size_t)Q * sizeof(RangeInfo), hipMemcpyHostToDevice, stream));
+    if (L->n_gather)
+        PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(GatherTile), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(ScatterTile), hipMemcpyHostToDevice, stream));
+    if (L->n_finish)
+        PREP_HIP(hipMemcpyAsync(L->finish_ranges, L->fin.data(), (size_t)L->n_finish * 4, hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipStreamSynchronize(stream));       // the host vectors and `tmp` go away after this
     return FR_OK;     // `tmp` returns the scratch blocks to the allocator
 }

@@ -5,26 +5,35 @@
 // two streaming sweeps whose random accesses all land in LDS (the two-phase partition-centric idea of Beamer et
 // al., "propagation blocking", 2017, and Lakhotia et al., "PCPM", 2018, rebuilt around CDNA's 160 KB LDS):
 //
-//   * destination rows are cut into partitions of rows_per_part rows (8192, or 16384 from 2^22 vertices on);
-//     sources into partitions of src_per_part (16384, or 32768 from 2^24 vertices on).  Larger partitions mean
-//     fewer messages (more edges of a source fall into one partition) and longer bins of message traffic between
-//     a source and a destination partition (M * rows_per_part * src_per_part / V^2 messages, which must not get
-//     too short to stream), but only one workgroup per CU, and they must still leave every CU a tile: hence the
-//     thresholds (256 gather tiles, 512 scatter tiles);
-//   * all in-edges of one destination partition q are stored together, ordered by source u and then by row;
-//     one MESSAGE is made per distinct (q, u) pair, however many rows of q the source u points to;
-//   * scatter sweep, one workgroup per source partition p: the p-slice of contrib sits in LDS; for every q the
-//     messages of bin (p, q) are written, msg[m] = contrib[src of m] -- sequential writes;
-//   * gather sweep, one workgroup per destination partition q: 64-bit fixed-point accumulators for q's rows
-//     sit in LDS; the id stream of q (one 16-bit local row id per edge, top bit set where a new message starts)
-//     and q's messages are read sequentially and added into LDS with integer atomics.  Integer addition is
-//     associative, so the sums do not depend on the order the hardware performs them in.
+//   * vertices are renumbered by in-degree, largest first (ties by old id); everything below is in new ids, and
+//     perm[] leads back to the caller's ids when the final ranks are written.  With this order the rows that
+//     receive most edges sit together, so that many edges of one source fall into one row range and share one
+//     message: on an R-MAT graph of 2^22 vertices and 2^26 edges the messages drop from 0.50 to 0.20 per edge;
+//   * destination rows are cut into RANGES of rows_per_part consecutive rows (8192, or 16384 from 2^22 vertices
+//     on); sources into partitions of src_per_part (16384, or 32768 from 2^24 vertices on);
+//   * all in-edges of one range j are stored together, ordered by source u and then by row; one MESSAGE is made
+//     per distinct (j, u) pair, however many rows of j the source u points to;
+//   * scatter sweep: the p-slice of contrib sits in LDS; for the ranges j of the tile the messages of bin (p, j)
+//     are written, msg[m] = contrib[src of m] -- sequential writes;
+//   * gather sweep: 64-bit fixed-point accumulators for the rows of one range sit in LDS; the id stream of the
+//     tile (one 16-bit local row id per edge, top bit set where a new message starts) and its messages are read
+//     sequentially and added into LDS with integer atomics.  Integer addition is associative, so the sums do
+//     not depend on the order the hardware performs them in.
 //
-// Rows with more than hub_split in-edges ("hubs") would both unbalance their partition and serialise the LDS
-// atomics, so each hub's in-edges are dealt out to virtual rows of at most hub_split edges, and the virtual rows
-// are dealt round-robin over all partitions (each partition has kMaxVrowsPerPart spare accumulator slots behind
-// its own rows); a small finishing step adds a hub's virtual rows up.  hub_split is kHubSplitMin unless the
-// graph has so many hub edges that the spare slots would not hold them, in which case it is doubled until they do.
+// Ordering by degree makes the ranges very unequal (the first range of that graph holds 42 % of the edges), so
+// the unit of work is not the range but a TILE of about equal work:
+//   * a gather tile is a run of consecutive edges of one range (hence a source interval of it).  A range that
+//     needs several tiles is a MERGED range: each of its tiles stores its row sums as one row of fp32 partial
+//     sums (plain stores, no global atomics: 2.5 million 64-bit atomics from 150 workgroups were measured at 22 us
+//     on an otherwise idle chip), and the rows are finished - partial sums added in tile order, then r and contrib -
+//     at the start of the next scatter sweep.  This also spreads rows with very many in-edges over many
+//     workgroups; no other treatment of such rows is needed.  A range with one tile is DIRECT: its tile
+//     finishes its rows itself;
+//   * a scatter tile is an interval of at most src_per_part consecutive sources with about equal numbers of
+//     messages (narrow for the sources that point into many ranges); every source belongs to exactly one scatter
+//     tile, so the finishing of merged rows is done once per row;
+//   * ranges behind the last row with an in-edge are EMPTY and have no gather tile: their rows' rank is the
+//     iteration's base value, which the scatter sweep puts into its slice without reading a sum.
 #pragma once
 
 #include <cstdint>
@@ -32,48 +41,68 @@
 
 #include "common.h"
 
-constexpr uint32_t kRowsSmall = 8192, kRowsLarge = 16384;   // destination rows per partition (8 B each in LDS)
+constexpr uint32_t kRowsSmall = 8192, kRowsLarge = 16384;   // destination rows per range (8 B each in LDS)
 constexpr uint32_t kSrcSmall = 16384, kSrcLarge = 32768;    // source vertices per scatter partition (4 B each in LDS)
 constexpr int64_t kLargeRowsFrom = int64_t(1) << 22;        // vertex counts from which the large sizes are used
 constexpr int64_t kLargeSrcFrom = int64_t(1) << 24;
-constexpr uint32_t kHubSplitMin = 2048;      // rows with more in-edges than hub_split are split into virtual rows
-constexpr uint32_t kMaxVrowsPerPart = 128;   // spare accumulator slots per partition for hubs' virtual rows
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
-constexpr uint32_t kHubsPerTile = 16;        // hubs finished per workgroup (16 lanes each)
-constexpr int kKeyLocalBits = 15;            // sort key = partition << 46 | source << 15 | local row
+constexpr int kKeyLocalBits = 15;            // sort key = range << 46 | source << 15 | local row
 constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
-static_assert(kRowsLarge + kMaxVrowsPerPart <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
+static_assert(kRowsLarge <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
+constexpr uint32_t kTilesPerSweep = 256;     // a sweep is cut into tiles of the cost 1/256 of the sweep's ...
+constexpr uint64_t kMinTileEdges = 32768;    // ... but no smaller than this
+constexpr uint64_t kMinTileMessages = 16384;
+// weight of a gather tile = edges + kGatherMessageWeight * messages + kGatherRepeatWeight * repeated edges; its cost
+// in the cutter adds kTileFixedWeight
+#ifndef FR_W_MSG
+#define FR_W_MSG 2
+#define FR_W_REP 3
+#define FR_W_FIX 131072
+#endif
+constexpr uint64_t kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP, kTileFixedWeight = FR_W_FIX;
+
+enum : uint32_t { kRangeDirect = 0, kRangeMerged = 1, kRangeEmpty = 2 };
+
+constexpr uint32_t kNoPartial = 0xffffffffu;
+struct GatherTile { uint32_t range, e0, e1, partial; };    // edges [e0, e1) of the sorted edge array; row of partial
+                                                           // sums the tile writes (kNoPartial: direct range)
+struct ScatterTile { uint32_t u0, u1; };                   // sources [u0, u1)
+struct RangeInfo { uint32_t cls_tiles, partial0; };        // class | gather tiles << 2; first row of partial sums
 
 struct PrLayout {
     int64_t V = 0, E = 0;
-    uint64_t M = 0;                  // messages = distinct (destination partition, source) pairs
-    uint32_t Q = 0;                  // destination partitions
-    uint32_t P = 0;                  // source partitions
+    uint64_t M = 0;                  // messages = distinct (range, source) pairs
     uint32_t rows_per_part = kRowsSmall, src_per_part = kSrcSmall;
-    uint32_t n_hubs = 0, n_vrows = 0;
-    uint32_t hub_split = kHubSplitMin;
+    uint32_t Q = 0;                  // ranges, ceil(V / rows_per_part)
+    uint32_t Qe = 0;                 // ranges with at least one in-edge (they come first)
+    uint32_t n_gather = 0, n_scatter = 0;
+    uint32_t n_merged = 0;           // ranges cut into several gather tiles
+    uint32_t n_partials = 0;         // gather tiles of merged ranges = rows of partial sums
+    uint32_t n_finish = 0;           // merged + empty ranges (the tiles of the pass after the last iteration)
     uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
-    uint32_t n_hub_tiles = 1;
 
     // device arrays (allocated through the task's accounting allocator)
+    int32_t* perm = nullptr;         // [V] caller's id of new id v
     uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id, bit 15 = first edge of a message;
                                      // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
-    uint16_t* src16 = nullptr;       // [M] source id relative to its source partition
-    uint32_t* eoff = nullptr;        // [Q + 1] first edge (in sorted order) of every destination partition
+    uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter tile
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
-    uint2* bins = nullptr;           // [P * Q] message range [x, y) of bin (p, q), p-major
-    int32_t* hub_row = nullptr;      // [n_hubs] row id of hub h
-    uint32_t* hub_vbase = nullptr;   // [n_hubs + 1] first virtual row of hub h
-    uint32_t* hub_of_p = nullptr;    // [P + 1] first hub (hubs are numbered in row order) of every source partition
-    float* inv_tag = nullptr;        // [V] 1/outdeg (0 if dangling), sign bit set for hub rows
+    uint2* bins = nullptr;           // [n_scatter * Qe] message range [x, y) of (scatter tile, range), tile-major
+    float* inv_out = nullptr;        // [V] 1/outdeg (0 if dangling)
+    RangeInfo* range_info = nullptr; // [Q]
+    GatherTile* gather_tiles = nullptr;    // [n_gather], heaviest ranges first
+    ScatterTile* scatter_tiles = nullptr;  // [n_scatter]
+    uint32_t* finish_ranges = nullptr;     // [n_finish] merged ranges, then empty ranges
 
-    // host copies used by the cost model
-    std::vector<uint32_t> edges_of_q;    // [Q]
-    std::vector<uint64_t> msgs_of_p;     // [P]
-
-    // virtual rows dealt to partition q: those hv < n_vrows with hv % Q == q; hv sits in slot hv / Q
-    uint32_t vrows_of_q(uint32_t q) const { return n_vrows > q ? (n_vrows - q + Q - 1) / Q : 0; }
+    // host copies for the cost model
+    std::vector<GatherTile> gt;
+    std::vector<uint64_t> gt_weight;     // weight of each gather tile
+    std::vector<ScatterTile> st;
+    std::vector<uint64_t> st_msgs;       // messages of each scatter tile
+    std::vector<uint64_t> st_partials;   // partial sums each scatter tile adds up
+    std::vector<RangeInfo> ri;           // [Q]
+    std::vector<uint32_t> fin;           // [n_finish]
 };
 
 // Builds the layout on `stream` from the caller's in-edge CSR (device pointers) and waits for it.

@@ -19,16 +19,16 @@ from workloads import configs              # noqa: E402
 # model about twice what the kernels need, so that no step overruns its bubble
 CASES = {
     "cfg2": dict(K=50, f_ns=4_500_000, b_ns=9_000_000, epochs=3,
-                 model=dict(fs_per_edge=2000, fs_per_message=3000, fs_per_vertex=2000, hubfin_tile_ns=200,
+                 model=dict(fs_per_edge=2000, fs_per_message=3000, fs_per_vertex=2000, finish_tile_ns=200,
                             min_step_ns=(30_000, 100_000, 100_000, 30_000))),
     "cfg3": dict(K=8, f_ns=4_500_000, b_ns=9_000_000, epochs=2,
-                 model=dict(fs_per_edge=2500, fs_per_message=3500, fs_per_vertex=4000, hubfin_tile_ns=200,
+                 model=dict(fs_per_edge=2500, fs_per_message=3500, fs_per_vertex=4000, finish_tile_ns=200,
                             min_step_ns=(30_000, 150_000, 100_000, 30_000))),
     "cfg4": dict(K=6, f_ns=4_500_000, b_ns=9_000_000, epochs=2,
-                 model=dict(fs_per_edge=6000, fs_per_message=8000, fs_per_vertex=12000, hubfin_tile_ns=500,
+                 model=dict(fs_per_edge=6000, fs_per_message=8000, fs_per_vertex=12000, finish_tile_ns=500,
                             min_step_ns=(30_000, 300_000, 200_000, 50_000))),
     "cfg5": dict(K=4, f_ns=36_000_000, b_ns=72_000_000, epochs=1,
-                 model=dict(fs_per_edge=2500, fs_per_message=5000, fs_per_vertex=4000, hubfin_tile_ns=200,
+                 model=dict(fs_per_edge=2500, fs_per_message=5000, fs_per_vertex=4000, finish_tile_ns=200,
                             min_step_ns=(30_000, 300_000, 100_000, 30_000))),
 }
 

@@ -32,11 +32,22 @@ def _segments(task, iterations):
     v = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX)
     s = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_SCATTER)
     g = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER)
-    h = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN)
+    h = task.fr_pagerank_tile_costs(fr.FR_PR_SEG_FINISH)
     segs = [v]
     for _ in range(iterations):
         segs += [s, g]
     return segs + [h]
+
+
+def _scaled_model(share, phase_ns, iterations, gather_weight, scatter_weight, info):
+    """Rates that make the task's cost model claim `share` of the measured time of every sweep."""
+    V0_rows = info.ranges * info.rows_per_partition
+    pv = max(1, int(share * phase_ns[0] * 1e6 / V0_rows))
+    s_fs = share * phase_ns[1] / iterations * 1e6
+    g_fs = share * phase_ns[2] / iterations * 1e6
+    pm = max(1, int((s_fs - scatter_weight * pv) / max(1, info.messages)))
+    pe = max(1, int((g_fs - info.gather_tiles * info.rows_per_partition * pv) / max(1, gather_weight)))
+    return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe, finish_tile_ns=1000)
 
 
 def _floors(min_step_ns, iterations):
@@ -50,8 +61,16 @@ def _check_cost_rule(task, pe, pm, pv, hub_ns):
     assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_VERTEX) == [max(1, -(-r * pv // 10**6)) for r in rows]
     info = task.fr_pagerank_info()
     edges = task.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(e * pe + r * pv) // 10**6)) for e, r in zip(edges, rows)]
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_HUBFIN) == [hub_ns] * max(1, -(-info.hubs // 16))
+    R = info.rows_per_partition
+    weights = task.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER)
+    assert all(w >= e for w, e in zip(weights, edges))          # edges + 2 messages + 3 repeated edges
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(w * pe + R * pv) // 10**6)) for w in weights]
+    msgs = task.fr_pagerank_tile_work(fr.FR_PR_SEG_SCATTER)
+    srcs = task.fr_pagerank_tile_weights(fr.FR_PR_SEG_SCATTER)
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_SCATTER) == [max(1, -(-(m * pm + s * pv) // 10**6)) for m, s in zip(msgs, srcs)]
+    assert len(edges) == info.gather_tiles
+    empty = info.ranges - info.nonempty_ranges
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_FINISH) == [hub_ns] * max(1, (info.merged_ranges + empty) * (R // 2048))
 
 
 def test_config1_harvest_matches_plan_and_oracle_bits():
@@ -67,14 +86,14 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     t_ref.fr_pagerank_destroy()
 
     guard, launch, max_chunk = 300_000, 25_000, 500_000
-    # shortest-step floors (vertex, scatter, gather, hub finish): above one tile's cost for scatter and gather, so
-    # that single-tile steps are charged the floor and two-tile steps the sum
+    # shortest-step floors (vertex, scatter, gather, finish): above one tile's cost for scatter and gather, so
+    # that steps of a tile or two are charged the floor and longer steps the sum
     floors = (9_000, 60_000, 80_000, 20_000)
     ctx = fr.Context(device_id=0, guard_ns=guard, launch_cost_ns=launch, max_chunk_ns=max_chunk, time_steps=1,
                      mem_available_bytes=1 << 40)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=cfg.iterations, max_runs=3,
                            mem_limit_bytes=1 << 30, fs_per_edge=400_000, fs_per_message=2_500_000, fs_per_vertex=300_000,
-                           hubfin_tile_ns=15000, min_step_ns=floors)
+                           finish_tile_ns=15000, min_step_ns=floors)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     assert _init_bubble(ctx, tid) == fr.FR_OK
     assert ctx.fr_query_progress(tid).state == fr.FR_PAUSED
@@ -105,9 +124,8 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     assert pr.bubbles_seen == len(lengths)
 
     want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=3, floors=_floors(floors, cfg.iterations))
-    # the one scatter tile costs less than its floor, so scatter steps are charged the floor; two gather tiles cost more
-    assert all(r.modelled_ns == launch + 60_000 for r in want if r.kind == "CHUNK" and r.segment == 1)
-    assert any(r.modelled_ns > launch + 80_000 for r in want if r.kind == "CHUNK" and r.segment == 2)
+    # (the two rules of the step cost, floor and sum, are pinned on the planner by the CPU tests; here the log
+    # must follow whatever the plan says)
     got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
     want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
     assert got_log == want_log
@@ -179,7 +197,7 @@ def test_framework_enforced_limit_stops_a_task_whose_gpu_work_outlives_the_grace
     ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
     ctx = fr.Context(device_id=0, guard_ns=0, launch_cost_ns=0, time_steps=1, max_inflight=32, grace_ns=grace_ns)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=50, max_runs=0,
-                           fs_per_edge=1, fs_per_message=1, fs_per_vertex=1, hubfin_tile_ns=1)
+                           fs_per_edge=1, fs_per_message=1, fs_per_vertex=1, finish_tile_ns=1)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     assert _init_bubble(ctx, tid) == fr.FR_OK
     ctx.fr_bubble_begin(fr.fr_now_ns(), 500_000)
@@ -212,10 +230,10 @@ def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheape
     probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
     info = probe.fr_pagerank_info()
+    gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
     probe.fr_pagerank_destroy()
     low = 0.4
-    model = dict(fs_per_vertex=max(1, int(low * ph[0] * 1e6 / V)), fs_per_message=max(1, int(low * ph[1] / K * 1e6 / info.messages)),
-                 fs_per_edge=max(1, int(low * ph[2] / K * 1e6 / E)), hubfin_tile_ns=1000)
+    model = _scaled_model(low, ph, K, gw, sw, info)
     stream = torch.cuda.Stream()
     f_ns, b_ns = 1_000_000, 2_000_000
     load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
@@ -257,10 +275,10 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
     probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
     info = probe.fr_pagerank_info()
+    gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
     probe.fr_pagerank_destroy()
     low = 0.4
-    model = dict(fs_per_vertex=max(1, int(low * ph[0] * 1e6 / V)), fs_per_message=max(1, int(low * ph[1] / K * 1e6 / info.messages)),
-                 fs_per_edge=max(1, int(low * ph[2] / K * 1e6 / E)), hubfin_tile_ns=1000)
+    model = _scaled_model(low, ph, K, gw, sw, info)
     stream = torch.cuda.Stream()
     f_ns, b_ns = 1_000_000, 2_000_000
     load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
@@ -287,8 +305,9 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
         assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
         assert len(refused) == pr.steps_refused and len(chunks) == pr.steps + pr.steps_refused
         assert pr.work_units_done == sum(e.work_units for e in chunks) - sum(e.work_units for e in refused)
-        # the work that counts covers the completed runs (and the run in progress), refused steps excluded
-        assert K * E * pr.runs_completed <= pr.work_units_done < K * E * (pr.runs_completed + 1)
+        # the work that counts covers the completed runs (and the run in progress, which may have all its gather
+        # sweeps behind it and only the finishing pass to go), refused steps excluded
+        assert K * E * pr.runs_completed <= pr.work_units_done <= K * E * (pr.runs_completed + 1)
         if gate:
             assert pr.steps_refused > 0
         else:
@@ -306,7 +325,7 @@ def test_steps_are_timed_in_groups_of_time_steps():
     ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
     ctx = fr.Context(device_id=0, guard_ns=300_000, launch_cost_ns=25_000, max_chunk_ns=500_000, time_steps=3)
     task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=cfg.iterations, max_runs=2,
-                           fs_per_edge=400_000, fs_per_message=2_500_000, fs_per_vertex=300_000, hubfin_tile_ns=15000)
+                           fs_per_edge=400_000, fs_per_message=2_500_000, fs_per_vertex=300_000, finish_tile_ns=15000)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     assert _init_bubble(ctx, tid) == fr.FR_OK
     stream = torch.cuda.Stream()

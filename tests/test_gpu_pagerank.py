@@ -53,27 +53,19 @@ def test_ragged_sizes_span_tiles_and_tails(scale, edges, seed):
     _check(graphs.rmat_csr(scale, edges, seed=seed), iterations=12)
 
 
-@pytest.mark.parametrize("edges,lo,hi", [(1200, 1, 48), (2400, 49, 96), (5000, 97, 192), (40_000, 193, 1 << 20)])
-def test_every_scatter_shape(edges, lo, hi):
-    # the scatter sweep picks its inner-loop shape from the average bin length (messages per source partition x
-    # destination partition): one case per shape, on 2^16 vertices = 4 x 8 bins
+@pytest.mark.parametrize("edges", [120, 300, 1200, 40_000])
+def test_scatter_bins_of_any_length(edges):
+    # the scatter sweep deals groups of eight message numbers to its threads whatever the bins' lengths:
+    # from bins of a few messages (most groups cut by a bin's end) to bins of thousands, on 2^16 vertices
     src, dst = graphs.rmat_edges(16, edges, seed=12)
     g = graphs.csr_from_edges(1 << 16, src, dst)
-    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
-    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
-    t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=1)
-    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
-    info = t.fr_pagerank_info()
-    t.fr_pagerank_destroy()
-    avg = info.messages // (info.partitions * info.source_partitions)
-    assert lo <= avg <= hi, avg
     _check(g, iterations=7)
 
 
 @pytest.mark.parametrize("rows,srcs", [(8192, 16384), (16384, 16384), (8192, 32768), (16384, 32768)])
 def test_every_partition_size(rows, srcs):
     # graphs of 2^24 vertices and more get 16384-row gather tiles and 32768-source scatter tiles; here the sizes
-    # are forced on a graph of 100003 vertices (ragged last tiles, hubs present)
+    # are forced on a graph of 100003 vertices (ragged last tiles, merged ranges present)
     src, dst = graphs.rmat_edges(17, 1_500_007, seed=21)
     g = graphs.csr_from_edges(100_003, src % 100_003, dst % 100_003)
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
@@ -83,8 +75,8 @@ def test_every_partition_size(rows, srcs):
     t.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), 3)
     info = t.fr_pagerank_info()
     t.fr_pagerank_destroy()
-    assert (info.rows_per_partition, info.sources_per_partition) == (rows, srcs) and info.hubs > 0
-    assert info.partitions == -(-g.n_vertices // rows) and info.source_partitions == -(-g.n_vertices // srcs)
+    assert (info.rows_per_partition, info.sources_per_partition) == (rows, srcs) and info.merged_ranges > 0
+    assert info.ranges == -(-g.n_vertices // rows) and info.scatter_tiles >= -(-g.n_vertices // srcs)
     got = ranks.cpu().numpy()
     want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 9)
     assert np.abs(got.astype(np.float64) - want).max() <= TOL
@@ -171,8 +163,22 @@ def test_memory_limit_refuses_the_task():
     t.fr_pagerank_destroy()
 
 
+def _host_layout(g, rows_per_range):
+    """Vertices renumbered by in-degree (largest first, ties by id); sorted (range, source, row) keys of the edges."""
+    V = g.n_vertices
+    indeg = np.diff(g.row_ptr)
+    order = np.argsort(-indeg, kind="stable")
+    new_id = np.empty(V, dtype=np.int64)
+    new_id[order] = np.arange(V)
+    row = new_id[np.repeat(np.arange(V), indeg)]
+    src = new_id[g.col.astype(np.int64)]
+    key = np.sort(((row // rows_per_range) << 46) | (src << 15) | (row % rows_per_range))
+    return key
+
+
 def test_layout_facts_match_the_graph():
-    # messages = distinct (destination partition, source) pairs; hubs = rows with more than 2048 in-edges
+    # messages = distinct (range, source) pairs; the weight of a run of edges = edges + 2 * messages that begin in
+    # it + 3 * edges that repeat their predecessor; gather tiles are cut on multiples of 512 edges
     g = graphs.rmat_csr(15, 1 << 19, seed=6)
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
     ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
@@ -180,30 +186,56 @@ def test_layout_facts_match_the_graph():
     t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     info = t.fr_pagerank_info()
     edges = t.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
+    weights = t.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER)
     msgs = t.fr_pagerank_tile_work(fr.FR_PR_SEG_SCATTER)
+    srcs = t.fr_pagerank_tile_weights(fr.FR_PR_SEG_SCATTER)
     t.fr_pagerank_destroy()
-    indeg = np.diff(g.row_ptr)
-    hub = indeg > 2048
-    Q = -(-g.n_vertices // 8192)
-    assert info.hub_split == 2048 and info.hubs == int(hub.sum()) and info.hubs > 0
-    nsplit = np.ceil(indeg[hub] / 2048).astype(np.int64)
-    assert info.virtual_rows == int(nsplit.sum())
-    assert info.partitions == Q and info.source_partitions == -(-g.n_vertices // 16384)
-    assert sum(edges) == g.n_edges and sum(msgs) == info.messages and len(edges) == Q
-    # recount the messages on the host: a regular row lives in partition row // 8192, virtual row hv in hv % Q
-    row = np.repeat(np.arange(g.n_vertices), indeg)
-    pos = np.arange(g.n_edges) - np.repeat(g.row_ptr[:-1], indeg)
-    vbase = np.zeros(g.n_vertices, dtype=np.int64)
-    vbase[hub] = np.cumsum(nsplit) - nsplit
-    part = np.where(hub[row], (vbase[row] + pos // 2048) % Q, row // 8192)
-    assert np.array_equal(np.bincount(part, minlength=Q), np.array(edges))
-    want = np.unique(part.astype(np.int64) * g.n_vertices + g.col).size
-    assert info.messages == want
+    V, E = g.n_vertices, g.n_edges
+    key = _host_layout(g, 8192)
+    rng = key >> 46
+    Q = -(-V // 8192)
+    per_range = np.bincount(rng, minlength=Q)
+    assert info.ranges == Q and info.nonempty_ranges == int((per_range > 0).sum())
+    assert np.all(per_range[:info.nonempty_ranges] > 0)                 # ranges with edges come first
+    starts = np.ones(E, dtype=bool)
+    starts[1:] = (key[1:] >> 15) != (key[:-1] >> 15)
+    repeats = np.zeros(E, dtype=bool)
+    repeats[1:] = key[1:] == key[:-1]
+    assert info.messages == int(starts.sum())
+    assert info.gather_tiles == len(edges) and sum(edges) == E
+    # every tile lies inside one range; tiles of a merged range are cut on multiples of 512
+    bounds = np.concatenate([[0], np.cumsum(edges)])
+    range_end = np.cumsum(per_range)
+    merged = partial_rows = 0
+    at = 0
+    for j in range(info.nonempty_ranges):
+        n = 0
+        while bounds[at + n] < range_end[j]:
+            n += 1
+        assert bounds[at + n] == range_end[j]
+        assert all(bounds[at + i] % 512 == 0 for i in range(1, n))
+        if n > 1:
+            merged += 1
+            partial_rows += n
+        at += n
+    assert at == len(edges) and (info.merged_ranges, info.partial_rows) == (merged, partial_rows) and merged > 0
+    # weights: exact for tiles that begin and end on multiples of 512 or at the ends of the stream (inside a chunk of
+    # 512 the weight is spread evenly); their sum is exact up to that rounding
+    w_edge = 1 + 2 * starts.astype(np.int64) + 3 * repeats.astype(np.int64)
+    cum = np.concatenate([[0], np.cumsum(w_edge)])
+    for i, w in enumerate(weights):
+        a, b = bounds[i], bounds[i + 1]
+        if (a % 512 == 0 or a == 0) and (b % 512 == 0 or b == E):
+            assert w == cum[b] - cum[a]
+    assert abs(sum(weights) - cum[E]) <= info.nonempty_ranges          # (rounding where a range ends inside a chunk)
+    assert sum(msgs) == info.messages and len(msgs) == info.scatter_tiles
+    assert max(msgs) <= max(16384, -(-info.messages // 256)) + info.nonempty_ranges
+    assert all(s >= 1 for s in srcs) and sum(srcs) >= V                 # sources + partial sums added up
 
 
-def test_hub_split_grows_when_spare_slots_would_overflow():
-    # 3 vertices, one row with 1.2 million in-edges (multi-edges): at the default split of 2048 that row alone
-    # would need 586 virtual rows but one partition has only 128 spare slots, so the split doubles to 16384
+def test_one_row_with_over_a_million_in_edges():
+    # 3 vertices, one row with 1.2 million in-edges (multi-edges): its range is cut into several gather tiles whose
+    # partial sums the scatter sweep (and, after the last iteration, the finishing pass) adds up
     n = 1_200_000
     src = np.concatenate([np.full(n, 1, np.int32), np.array([0, 2], np.int32)])
     dst = np.concatenate([np.zeros(n, np.int32), np.array([1, 1], np.int32)])
@@ -213,8 +245,12 @@ def test_hub_split_grows_when_spare_slots_would_overflow():
     t = fr.PageRankTask(3, g.n_edges, rp, col, od, ranks, iterations=6)
     t.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
     info = t.fr_pagerank_info()
+    weights = t.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER)
     t.fr_pagerank_destroy()
-    assert info.hub_split == 16384 and info.hubs == 1 and info.virtual_rows == -(-n // 16384)
+    # all but one of the edges into the heavy row repeat their predecessor: weight 4 apiece
+    assert info.merged_ranges == 1 and info.gather_tiles == info.partial_rows > 10
+    assert sum(weights) == (n + 2) + 2 * 3 + 3 * (n - 1)          # edges + 2 * messages + 3 * repeats
+    assert max(weights) <= 1.1 * sum(weights) / len(weights)            # tiles of about equal weight
     want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 6)
     assert np.abs(ranks.cpu().numpy().astype(np.float64) - want).max() <= TOL
 
