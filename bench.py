@@ -107,7 +107,6 @@ def main():
     # multiplicands of the task's cost formulas, summed over a sweep
     gather_weight = sum(cal.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER))
     scatter_weight = sum(cal.fr_pagerank_tile_weights(fr.FR_PR_SEG_SCATTER))
-    gather_fixed = info.gather_tiles * info.rows_per_partition
     tile_cost_spread = []
     for kind in range(4):
         c = cal.fr_pagerank_tile_costs(kind)
@@ -128,7 +127,7 @@ def main():
         """Femtosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
         pv = max(1, int(v_ns * 1e6 * derate / V))
         pm = max(1, int((s_ns * 1e6 * derate - scatter_weight * pv) / M))
-        pe = max(1, int((g_ns * 1e6 * derate - gather_fixed * pv) / max(1, gather_weight)))
+        pe = max(1, int(2 * g_ns * 1e6 * derate / max(1, gather_weight)))
         return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe,
                     finish_tile_ns=max(1, int(h_ns * derate / n_finish_tiles)),
                     min_step_ns=[int(derate * x) for x in one_tile_ns])

@@ -297,8 +297,11 @@ typedef struct fr_pagerank_desc {
        be too coarse), fixed for the task's life (0 = library default); tile cost in ns = ceil(sum / 10^6), at least 1:
          vertex tile  : rows * fs_per_vertex
          scatter tile : messages * fs_per_message + (sources + partial sums it adds up) * fs_per_vertex
-         gather tile  : (edges + 2 * messages + 3 * repeated edges) * fs_per_edge + rows_per_partition * fs_per_vertex
-                        (a repeated edge has the same source and row as the edge before it)
+         gather tile  : weight * fs_per_edge / 2, weight = 2 * edges + 5 * repeated edges + 98304 per piece
+                        (a piece is a run of edges of one range: a heavy range is cut into several, each a tile of
+                        its own; light ones share a tile.  A repeated edge has the same source and row as the edge
+                        before it: the two collide in the accumulator.  The constant stands for the start and the
+                        row pass of a piece.)
          finish tile  : finish_tile_ns (already ns)                                                         */
     uint64_t fs_per_edge;
     uint64_t fs_per_message;
@@ -320,12 +323,12 @@ typedef struct fr_pagerank_info_t {
     uint64_t messages;            /* distinct (range, source) pairs                                         */
     uint32_t ranges;              /* row ranges, ceil(V / rows_per_partition)                               */
     uint32_t scatter_tiles;       /* source intervals of about equal numbers of messages                    */
-    uint32_t gather_tiles;        /* runs of edges of one range, about equal in length                      */
-    uint32_t merged_ranges;       /* ranges cut into several gather tiles                                   */
+    uint32_t gather_tiles;        /* one heavy piece (a run of edges of one range) or several light ones    */
+    uint32_t merged_ranges;       /* ranges cut into several gather pieces                                  */
     uint32_t nonempty_ranges;     /* ranges with in-edges (they come first: rows are ordered by in-degree)  */
     uint32_t rows_per_partition;  /* destination rows per range                                             */
     uint32_t sources_per_partition; /* most source vertices of a scatter tile                               */
-    uint32_t partial_rows;        /* gather tiles of merged ranges (rows of fp32 partial sums)              */
+    uint32_t partial_rows;        /* gather pieces of merged ranges (rows of fp32 partial sums)             */
     uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
     uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */
 } fr_pagerank_info_t;
@@ -341,8 +344,8 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out);
 int fr_pagerank_tiles(void* user, int32_t seg_kind, uint32_t* n_tiles_out);
 int fr_pagerank_tile_costs(void* user, int32_t seg_kind, uint32_t* costs_host, size_t cap, size_t* n_out);
 int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work_host, size_t cap, size_t* n_out);
-/* The tiles' multiplicands in the cost formulas above: gather: edges + 2 * messages + 3 * repeated edges;
-   scatter: sources + partial sums added up (the factor of fs_per_vertex); vertex: rows; finish: 0. */
+/* The tiles' multiplicands in the cost formulas above: gather: the weight; scatter: sources + partial sums added
+   up (the factor of fs_per_vertex); vertex: rows; finish: 0. */
 int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights_host, size_t cap, size_t* n_out);
 /*
  * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_tiles_per_launch` tiles per

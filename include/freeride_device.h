@@ -41,8 +41,9 @@ __device__ __forceinline__ bool fr_gate_admit(fr_gate* gate, unsigned int slot, 
         threadIdx.x == 0 && threadIdx.y == 0 && threadIdx.z == 0) {
         /* the one writer; the other workgroups of this kernel may still read closed == 0 and reach the same
            verdict from the clock values, which nobody changes while a refused kernel runs */
+        /* (no fence between the two stores: their readers - later kernels on the stream, and the host once the
+           stream has drained - only look after this kernel has ended) */
         gate->first_refused = slot;
-        __threadfence();
         gate->closed = 1u;
     }
     return admit;

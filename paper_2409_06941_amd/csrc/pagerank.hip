@@ -100,17 +100,19 @@ __device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 flo
 
 struct DevArgs {
     int64_t V, E;
-    uint32_t M, Q, Qe, n_gather, n_scatter, n_finish, n_dpart;
+    uint32_t M, Q, Qe, n_gather, n_pieces, n_scatter, n_finish, n_dpart;
     uint32_t rows_per_part, rows_shift;           // rows per range and its log2
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
     const uint32_t* mbase;
+    const uint64_t* starts;
     const uint2* bins;
     const float* inv_out;
     const int32_t* perm;
     const RangeInfo* range_info;
-    const GatherTile* gather_tiles;
+    const GatherPiece* gather_pieces;
+    const uint2* gather_tiles;
     const ScatterTile* scatter_tiles;
     const uint32_t* finish_ranges;
     float* msg;
@@ -358,7 +360,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
         const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
         const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
         const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_gather + t] = total;
+        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
     }
     const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
     for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
@@ -405,6 +407,11 @@ __device__ __forceinline__ unsigned long long to_fixed(float x)
     return ((unsigned long long)hi << 32) | lo;
 }
 
+__device__ __forceinline__ unsigned long long* acc_at(unsigned long long* acc, uint32_t byte_offset)
+{
+    return reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(acc) + byte_offset);
+}
+
 __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 {
     const uint32_t w = (j >> 1) == 0 ? raw.x : (j >> 1) == 1 ? raw.y : (j >> 1) == 2 ? raw.z : raw.w;
@@ -415,30 +422,39 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 // wavefront takes one chunk of 512 ids (8 per lane).  The loop is a three-stage software pipeline over the
 // wavefront's chunks, so that no step waits on a load it has just issued:
 //   A  ids and message base of chunk i + 2 are requested;
-//   B  chunk i + 1 (ids now here): ballots of the message-start flags tell every id which message it belongs
-//      to; the messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
+//   B  chunk i + 1 (ids now here): the message-start bits tell every id which message it belongs to; the
+//      messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
 //   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
 //      accumulator with an LDS atomic.
-// The sweep is bound by vector instruction issue, not by memory (about 30 instructions per 64 edges when every id
-// is checked), so chunks that lie wholly inside the partition's edge range and whose messages cannot pass the end
-// of the message array - all but the first and last chunk of a range - take a path without per-id checks:
-// ids out of range (which a sound layout never holds) are sent to a sink slot behind the accumulators.
+// The sweep is bound by vector instruction issue, not by memory, so chunks that lie wholly inside the tile's edge
+// range and whose messages cannot pass the end of the message array - all but the first and last chunk of a tile -
+// take a path without per-id checks (about 10 vector instructions per 64 edges instead of 25).
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 template <uint32_t kRowsPerPart>
 __global__ __launch_bounds__(kGatherBlock) __attribute__((amdgpu_waves_per_eu(kRowsPerPart == kRowsSmall ? 8 : 4, kRowsPerPart == kRowsSmall ? 8 : 4)))
-void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
+void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, const uint64_t* __restrict__ starts,
+              const uint32_t* __restrict__ mbase)
 {
     constexpr uint32_t kAccSlots = kRowsPerPart;
+    constexpr uint32_t kIdScale = id_scale_for(kRowsPerPart);
+    static_assert(65535u * (8 / kIdScale) + 8 <= (kAccSlots + 1) * 8, "any id addresses a slot of acc");
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[32];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t t = tile0 + blockIdx.x;
-    const GatherTile T = A.gather_tiles[t];
+    const uint32_t tile = tile0 + blockIdx.x;
+    const uint2 span = A.gather_tiles[tile];                     // the tile's pieces, worked on one after the other
+    const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
+    const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
+    float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
+    if (tile == 0 && !final_pass)                                // slots no piece and no scatter tile writes
+        for (uint32_t i = A.n_pieces + A.n_scatter + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
+    for (uint32_t t = span.x; t < span.y; ++t) {
+    const GatherPiece T = A.gather_pieces[t];
     const uint32_t q = T.range;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
+    __syncthreads();                                             // the piece before is done with acc
     for (uint32_t i = threadIdx.x; i < kAccSlots + 1; i += kGatherBlock) acc[i] = 0ull;
-    const float d_part = dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     __syncthreads();
 
     const uint32_t e0 = T.e0, e1 = T.e1 < (uint64_t)A.E ? T.e1 : (uint32_t)A.E;
@@ -446,14 +462,29 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
     if (e1 > e0) {
         const uint32_t c0 = e0 / kIdChunk, c1 = (e1 - 1) / kIdChunk;
         const uint4* ids4 = reinterpret_cast<const uint4*>(A.ids16);
-        // stage A's result: chunk cA, its ids and the number of messages begun before it
-        uint32_t cA = c0 + wave;
-        uint4 rawA = make_uint4(0, 0, 0, 0);
-        uint32_t mbA = 0;
-        if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
-        // Stage B's result, waiting for stage C.  There are two of these and the loop below is written out twice with
-        // their roles exchanged: copying one into the other at the end of a step would make the step wait for the
-        // messages it has just asked for.
+        // Stage A's result: a chunk's ids, its message-start bits and the number of messages begun before it.  The
+        // chunk number is the same in all lanes of a wavefront; saying so lets the bits and the count come through
+        // the scalar unit, which leaves them where the arithmetic of stage B wants them.  There are kRing of these:
+        // a buffer is asked for its next chunk as soon as stage B has used it, kRing - 1 steps before that chunk's
+        // turn, so a wavefront has that many steps of work to cover the latency of the request.
+        struct Ids {
+            uint4 raw;
+            uint32_t mb;
+            uint64_t starts[8];
+        };
+        constexpr int kRing = kRowsPerPart == kRowsSmall ? 2 : 3;     // (the small size has fewer registers)
+        const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave);
+        auto load_ids = [&](Ids& I, uint32_t c) {
+            if (c <= c1) {
+                I.raw = ids4[(uint64_t)c * (kIdChunk / 8) + lane];
+                I.mb = mbase[c];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) I.starts[j] = starts[(uint64_t)c * 8 + j];
+            }
+        };
+        // Stage B's result, waiting for stage C.  There are two of these, used in turn: copying one into the other
+        // at the end of a step would make the step wait for the messages it has just asked for.  For the same reason
+        // the loop below is written out once per combination of buffers.
         struct Pending {
             uint4 raw;
             float val[8];
@@ -466,92 +497,92 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
 #pragma unroll
         for (int j = 0; j < 8; ++j) { X.val[j] = 0.0f; Y.val[j] = 0.0f; }
 
-        // ---- stage B on chunk cA: lane l holds the ids at stream positions 64 j + l of the chunk, so for a fixed j
-        // the wavefront covers 64 consecutive ids; a ballot of their flags plus a count of the set bits below the
-        // lane tells every id how many messages have begun up to it.
-        auto stage_b = [&](Pending& S) {
-            S.raw = rawA;
+        // ---- stage B on chunk c: lane l holds the ids at stream positions 64 j + l of the chunk, so for a fixed j
+        // the wavefront covers 64 consecutive ids, whose message-start bits are word j.  The message of the id in
+        // lane l is the last one begun up to it: (messages begun before the row) + (bits 0 .. l of the word) - 1.
+        // The count of the bits 1 .. l is what mbcnt gives for the word shifted down by one; bit 0 is added on
+        // the scalar side.
+        auto stage_b = [&](Pending& S, const Ids& I, uint32_t c) {
+            S.raw = I.raw;
             S.ok = 0;
-            const uint32_t mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)mbA);
-            const uint64_t first = (uint64_t)cA * kIdChunk;
-            // mb >= 1: an id without a flag then still has a message before it (index >= 0 below)
+            const uint32_t mb = I.mb;
+            const uint64_t first = (uint64_t)c * kIdChunk;
+            // mb >= 1: an id before the first start of its row then still has a message before it (index >= 0 below)
             S.fast = first >= e0 && first + kIdChunk <= e1 && mb >= 1 && (uint64_t)mb + kIdChunk <= A.M;
+            uint32_t begun_m1 = mb - 1u;                                   // messages begun before row j, minus one
             if (S.fast) {
-                uint32_t begun_m1 = mb - 1u;                               // messages begun before row j, minus one
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t f = id_of(rawA, j) >> 15;
-                    const unsigned long long ballot = __ballot(f != 0);
-                    const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
-                    S.val[j] = A.msg[begun_m1 + below + f];                // in [mb - 1, mb + 511], inside [0, M)
-                    begun_m1 += (uint32_t)__popcll(ballot);
+                    const uint64_t bits = I.starts[j], upper = bits >> 1;
+                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(upper >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)upper, begun_m1 + (uint32_t)(bits & 1u)));
+                    S.val[j] = A.msg[mi];                                  // in [mb - 1, mb + 511], inside [0, M)
+                    begun_m1 += (uint32_t)__popcll(bits);
                 }
             } else {
-                const uint32_t ebase = cA * kIdChunk + lane;
-                uint32_t begun = mb;
+                const uint32_t ebase = c * kIdChunk + lane;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint32_t id = id_of(rawA, j);
-                    const uint32_t f = id >> 15;
-                    const unsigned long long ballot = __ballot(f != 0);
-                    const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)ballot, 0u));
-                    const uint32_t mi = begun + below + f - 1;             // this id's message
-                    begun += (uint32_t)__popcll(ballot);
+                    const uint64_t bits = I.starts[j], upper = bits >> 1;
+                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(upper >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)upper, begun_m1 + (uint32_t)(bits & 1u)));
+                    begun_m1 += (uint32_t)__popcll(bits);
                     const uint32_t e = ebase + 64 * j;
-                    const bool ok = e >= e0 && e < e1 && (id & kLocalMask) < kAccSlots && mi < A.M;
+                    const bool ok = e >= e0 && e < e1 && id_of(I.raw, j) < kAccSlots * kIdScale && mi < A.M;   // (mi wraps if no message precedes)
                     S.ok |= (ok ? 1u : 0u) << j;
                     S.val[j] = A.msg[ok ? mi : 0u];
                 }
             }
         };
-        // ---- stage A on this wavefront's next chunk
-        auto stage_a = [&]() {
-            cA += kGatherWaves;
-            if (cA <= c1) { rawA = ids4[(uint64_t)cA * (kIdChunk / 8) + lane]; mbA = A.mbase[cA]; }
-        };
-        // ---- stage C: the chunk's ids add their messages; leaves S empty
+        // ---- stage C: the chunk's ids add their messages; leaves S empty.  An id is the byte offset of its row's
+        // accumulator divided by 8 / kIdScale, so any 16-bit value stays inside `acc` (the sink slot is its end).
         auto stage_c = [&](Pending& S) {
             if (S.fast) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t local = id_of(S.raw, j) & kLocalMask;
-                    atomicAdd(&acc[local < kAccSlots ? local : kAccSlots], to_fixed(S.val[j]));
-                }
+                for (int j = 0; j < 8; ++j) atomicAdd(acc_at(acc, id_of(S.raw, j) * (8 / kIdScale)), to_fixed(S.val[j]));
             } else if (S.ok) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if ((S.ok >> j) & 1u) atomicAdd(&acc[id_of(S.raw, j) & kLocalMask], to_fixed(S.val[j]));
+                    if ((S.ok >> j) & 1u) atomicAdd(acc_at(acc, id_of(S.raw, j) * (8 / kIdScale)), to_fixed(S.val[j]));
             }
             S.fast = false; S.ok = 0;
         };
-        while (cA <= c1) {
-            stage_b(X);
-            stage_a();
-            stage_c(Y);
-            if (cA > c1) break;
-            stage_b(Y);
-            stage_a();
-            stage_c(X);
+        // one step: B on chunk c out of buffer I into `fresh`, I asked for the chunk kRing steps on, C on `due`
+        uint32_t c = c0 + wave_u;
+        auto step = [&](Ids& I, Pending& fresh, Pending& due) -> bool {
+            if (c > c1) return false;
+            stage_b(fresh, I, c);
+            load_ids(I, c + kRing * kGatherWaves);
+            stage_c(due);
+            c += kGatherWaves;
+            return true;
+        };
+        Ids I0, I1, I2;
+        I0.raw = I1.raw = I2.raw = make_uint4(0, 0, 0, 0);
+        I0.mb = I1.mb = I2.mb = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) I0.starts[j] = I1.starts[j] = I2.starts[j] = 0;
+        load_ids(I0, c);
+        load_ids(I1, c + kGatherWaves);
+        if (kRing == 3) {
+            load_ids(I2, c + 2 * kGatherWaves);
+            while (step(I0, X, Y) && step(I1, Y, X) && step(I2, X, Y) && step(I0, Y, X) && step(I1, X, Y) && step(I2, Y, X)) {}
+        } else {
+            while (step(I0, X, Y) && step(I1, Y, X)) {}
         }
         stage_c(X);          // drain: at most one of the two still holds a chunk
         stage_c(Y);
     }
     __syncthreads();
 
-    const float D = dangling_finish(d_part, red);
-    float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
-    if (t == 0 && !final_pass)                                  // slots no tile writes
-        for (uint32_t i = A.n_gather + A.n_scatter + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
     if (T.partial != kNoPartial) {
         // merged range: the sums go out as one row of partial sums; the next scatter sweep (or F) finishes the rows
         float* out = A.partials + (size_t)T.partial * kRowsPerPart;
         for (uint32_t i = threadIdx.x; i < kRowsPerPart; i += kGatherBlock) out[i] = (float)acc[i] * kFixInv;
         if (threadIdx.x == 0 && !final_pass) dnext[t] = 0.0f;
-        fr_gate_done(G.gate);
-        return;
+        continue;
     }
     // direct range: fused vertex pass for its rows
-    const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     const int64_t v0 = (int64_t)q * kRowsPerPart;
     float dangling = 0.0f;
     constexpr int kRowsPerThread = (kRowsPerPart + kGatherBlock - 1) / kGatherBlock;
@@ -579,6 +610,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass)
         const float total = block_sum(dangling, red + 8);
         if (threadIdx.x == 0) dnext[t] = total;
     }
+    }       // pieces
     fr_gate_done(G.gate);
 }
 
@@ -671,7 +703,7 @@ void build_cost_tables(PrTask* p)
     const uint32_t ng = p->tiles_of(FR_PR_SEG_GATHER);
     g.assign(ng + 1, 0);
     for (uint32_t t = 0; t < ng; ++t) {
-        g[t + 1] = g[t] + ceil_fs_to_ns((unsigned __int128)L.gt_weight[t] * pe + (unsigned __int128)L.rows_per_part * pv);
+        g[t + 1] = g[t] + ceil_fs_to_ns((unsigned __int128)L.gt_weight[t] * pe / 2);
     }
     auto& h = p->prefix[FR_PR_SEG_FINISH];
     const uint32_t nf = p->tiles_of(FR_PR_SEG_FINISH);
@@ -701,9 +733,11 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
         } else {
             const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
             if (p->L.rows_per_part == kRowsLarge)
-                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass);
+                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass,
+                                   p->args.starts, p->args.mbase);
             else
-                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass);
+                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass,
+                                   p->args.starts, p->args.mbase);
         }
     }
     hipError_t e = hipGetLastError();
@@ -731,20 +765,20 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
                              p->d.sources_per_partition, a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
-    // dangling partials: one slot per range (V0), or one per gather tile followed by one per scatter tile
-    p->n_dpart = std::max(L.Q, L.n_gather + L.n_scatter);
+    // dangling partials: one slot per range (V0), or one per gather piece followed by one per scatter tile
+    p->n_dpart = std::max(L.Q, L.n_pieces + L.n_scatter);
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
         !take(a, &p->partials, (uint64_t)L.n_partials * L.rows_per_part))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
     DevArgs& A = p->args;
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.Qe = L.Qe;
-    A.n_gather = L.n_gather; A.n_scatter = L.n_scatter; A.n_finish = L.n_finish;
+    A.n_gather = L.n_gather; A.n_pieces = L.n_pieces; A.n_scatter = L.n_scatter; A.n_finish = L.n_finish;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.rows_per_part = L.rows_per_part;
     A.rows_shift = L.rows_per_part == kRowsLarge ? 14 : 13;
-    A.ids16 = L.ids16; A.src16 = L.src16; A.mbase = L.mbase; A.bins = L.bins;
+    A.ids16 = L.ids16; A.src16 = L.src16; A.mbase = L.mbase; A.starts = L.starts; A.bins = L.bins;
     A.inv_out = L.inv_out; A.perm = L.perm; A.range_info = L.range_info;
-    A.gather_tiles = L.gather_tiles; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
+    A.gather_pieces = L.gather_pieces; A.gather_tiles = L.gather_tiles; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.partials = p->partials; A.ranks_out = p->d.ranks_out;
     build_cost_tables(p);
     p->footprint_after = fr_alloc_used(a);
@@ -780,7 +814,7 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     if (kind == FR_PR_SEG_GATHER) {
         uint64_t edges = 0;
-        for (uint32_t t = p->tile; t < p->tile + n && t < p->L.n_gather; ++t) edges += (uint64_t)p->L.gt[t].e1 - p->L.gt[t].e0;
+        for (uint32_t t = p->tile; t < p->tile + n && t < p->L.n_gather; ++t) edges += p->L.gt_edges[t];
         out->work_units = edges;
     }
     out->completes_run = (p->seg + 1 == p->n_segments() && out->tile1 == p->tiles_of(kind)) ? 1 : 0;
@@ -911,7 +945,7 @@ int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work, size_t c
     if (p->prefix[0].empty()) return FR_ERR_STATE;
     const size_t n = p->tiles_of(seg_kind);
     for (size_t t = 0; t < std::min(n, cap); ++t) {
-        if (seg_kind == FR_PR_SEG_GATHER) work[t] = t < p->L.n_gather ? (uint64_t)p->L.gt[t].e1 - p->L.gt[t].e0 : 0;
+        if (seg_kind == FR_PR_SEG_GATHER) work[t] = t < p->L.n_gather ? p->L.gt_edges[t] : 0;
         else if (seg_kind == FR_PR_SEG_SCATTER) work[t] = p->L.st_msgs[t];
         else if (seg_kind == FR_PR_SEG_VERTEX) work[t] = p->rows_of_q((uint32_t)t);
         else work[t] = 0;

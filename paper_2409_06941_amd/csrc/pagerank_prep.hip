@@ -15,6 +15,10 @@
 
 #include "pr_layout.h"
 
+#ifndef FR_SMALL_SLOTS
+#define FR_SMALL_SLOTS 2
+#endif
+
 namespace {
 
 constexpr int kBlk = 256;
@@ -137,19 +141,33 @@ __global__ __launch_bounds__(kBlk) void k_zero_u32(uint64_t n, uint32_t* p)
 
 __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64_t M, const uint64_t* __restrict__ keys,
                                                const uint32_t* __restrict__ incl, const uint32_t* __restrict__ ubound,
-                                               uint32_t n_tiles, uint16_t* __restrict__ ids16, uint16_t* __restrict__ src16)
+                                               uint32_t n_tiles, uint32_t id_scale, uint16_t* __restrict__ ids16,
+                                               uint16_t* __restrict__ src16)
 {
     const int64_t e = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (e >= padded) return;
     if (e >= E) { ids16[id_slot(e)] = 0; return; }
     const uint64_t k = keys[e];
     const uint32_t f = flag_of(keys, e);
-    ids16[id_slot(e)] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) | (f << 15));
+    ids16[id_slot(e)] = (uint16_t)((k & ((1u << kKeyLocalBits) - 1)) * id_scale);
     if (f) {
         const uint64_t m = (uint64_t)incl[e] - 1;
         const uint32_t u = (uint32_t)((k >> kKeyLocalBits) & 0x7fffffffu);
         if (m < M) src16[m] = (uint16_t)(u - ubound[tile_of_source(ubound, n_tiles, u)]);
     }
+}
+
+// starts[8 c + j]: bit l is set where stream position 64 j + l of chunk c begins a message.
+__global__ __launch_bounds__(kBlk) void k_starts(int64_t E, uint64_t n_words, const uint64_t* __restrict__ keys, uint64_t* __restrict__ starts)
+{
+    const uint64_t w = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (w >= n_words) return;
+    uint64_t bits = 0;
+    for (int l = 0; l < 64; ++l) {
+        const int64_t e = (int64_t)(w * 64) + l;
+        if (e < E && flag_of(keys, e)) bits |= 1ull << l;
+    }
+    starts[w] = bits;
 }
 
 __global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint64_t* __restrict__ keys,
@@ -384,14 +402,15 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     L->n_scatter = (uint32_t)ubound.size() - 1;
 
     // ---- the arrays that stay
-    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
+    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->starts, (uint64_t)padded / 64) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
         PREP_NEED((void*)nullptr);
     uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
     uint32_t* eoff = tmp.take<uint32_t>((uint64_t)Q + 1);
     PREP_NEED(ubound_dev); PREP_NEED(eoff);
     PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
-                       ubound_dev, L->n_scatter, L->ids16, L->src16);
+                       ubound_dev, L->n_scatter, id_scale_for(rows_per_part), L->ids16, L->src16);
+    hipLaunchKernelGGL(k_starts, dim3(blocks_for((uint64_t)padded / 64)), dim3(kBlk), 0, stream, E, (uint64_t)padded / 64, keys, L->starts);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, eoff);
     std::vector<uint32_t> eoff_host((size_t)Q + 1);
@@ -419,7 +438,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         tmp.drop(rep);
         for (uint32_t c = 0; c < L->n_chunks; ++c) {
             const uint64_t edges = std::min<uint64_t>(kIdChunk, (uint64_t)E - (uint64_t)c * kIdChunk);
-            wcum[c + 1] = wcum[c] + edges + kGatherMessageWeight * (uint64_t)(mbase_host[c + 1] - mbase_host[c]) +
+            wcum[c + 1] = wcum[c] + kGatherEdgeWeight * edges + kGatherMessageWeight * (uint64_t)(mbase_host[c + 1] - mbase_host[c]) +
                           kGatherRepeatWeight * (uint64_t)rep_host[c];
         }
     }
@@ -429,54 +448,77 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         const uint64_t held = std::min<uint64_t>(kIdChunk, (uint64_t)E - c * kIdChunk);      // the last chunk may be short
         return wcum[c] + (wcum[c + 1] - wcum[c]) * std::min(e - c * kIdChunk, held) / held;
     };
-    L->gt.clear(); L->gt_weight.clear(); L->ri.assign(Q, RangeInfo{kRangeEmpty, 0}); L->fin.clear();
-    L->n_merged = 0; L->n_partials = 0;
+    L->gp.clear(); L->gt.clear(); L->gt_weight.clear(); L->gt_edges.clear();
+    L->ri.assign(Q, RangeInfo{kRangeEmpty, 0}); L->fin.clear();
     {
-        // A tile costs its weight plus a fixed part (kTileFixedWeight: the chain of dependent loads at its start and
-        // the row pass at its end).  The target is the share of one of kTilesPerSweep equal tiles; cutting changes
-        // the number of tiles and so the sum, hence the few rounds.
+        // A piece costs its weight plus a fixed part (kTileFixedWeight: the chain of dependent loads at its start and
+        // the row pass at its end).  Ranges are cut into pieces of at most `body` weight; pieces are then grouped, in
+        // order, into tiles of at most body + kTileFixedWeight.  `body` is the smallest (to 2 %) that gives no more
+        // tiles than workgroups run side by side.
+        const uint64_t slots = (uint64_t)kTilesPerSweep * (rows_per_part == kRowsSmall ? FR_SMALL_SLOTS : 1);
         std::vector<uint64_t> w(Qe);
         uint64_t total = 0;
         for (uint32_t j = 0; j < Qe; ++j) { w[j] = weight_at(eoff_host[j + 1]) - weight_at(eoff_host[j]); total += w[j]; }
-        uint64_t body = 0, n_tiles = Qe;
-        for (int round = 0; round < 8; ++round) {
-            const uint64_t target = (total + n_tiles * kTileFixedWeight + kTilesPerSweep - 1) / kTilesPerSweep;
-            body = std::max<uint64_t>(kMinTileEdges, target > kTileFixedWeight ? target - kTileFixedWeight : 0);
-            uint64_t n = 0;
-            for (uint32_t j = 0; j < Qe; ++j) n += std::max<uint64_t>(1, (w[j] + body - 1) / body);
-            if (n == n_tiles) break;
-            n_tiles = n;
-        }
-        for (uint32_t j = 0; j < Qe; ++j) {
-            const uint64_t e0 = eoff_host[j], e1 = eoff_host[j + 1];
-            const uint64_t nt = std::max<uint64_t>(1, (w[j] + body - 1) / body);
-            std::vector<uint64_t> cuts;                      // chunk boundaries strictly inside (e0, e1)
-            const uint64_t w0 = weight_at(e0);
-            for (uint64_t i = 1; i < nt; ++i) {
-                const uint64_t want = w0 + w[j] * i / nt;
-                const uint64_t c = (uint64_t)(std::lower_bound(wcum.begin(), wcum.end(), want) - wcum.begin());
-                const uint64_t cut = c * kIdChunk;
-                if (cut > (cuts.empty() ? e0 : cuts.back()) && cut < e1) cuts.push_back(cut);
+        std::vector<GatherPiece> pieces;
+        std::vector<uint64_t> piece_w;
+        std::vector<uint2> tiles;
+        uint64_t body = std::max<uint64_t>(kMinTileEdges * kGatherEdgeWeight, (total + slots - 1) / slots);
+        for (int round = 0; round < 400; ++round, body += body / 50 + 1) {
+            pieces.clear(); piece_w.clear(); tiles.clear();
+            L->ri.assign(Q, RangeInfo{kRangeEmpty, 0});
+            L->fin.clear();
+            L->n_merged = 0; L->n_partials = 0;
+            for (uint32_t j = 0; j < Qe; ++j) {
+                const uint64_t e0 = eoff_host[j], e1 = eoff_host[j + 1];
+                const uint64_t nt = std::max<uint64_t>(1, (w[j] + body - 1) / body);
+                std::vector<uint64_t> cuts;                      // chunk boundaries strictly inside (e0, e1)
+                const uint64_t w0 = weight_at(e0);
+                for (uint64_t i = 1; i < nt; ++i) {
+                    const uint64_t want = w0 + w[j] * i / nt;
+                    const uint64_t c = (uint64_t)(std::lower_bound(wcum.begin(), wcum.end(), want) - wcum.begin());
+                    const uint64_t cut = c * kIdChunk;
+                    if (cut > (cuts.empty() ? e0 : cuts.back()) && cut < e1) cuts.push_back(cut);
+                }
+                if (cuts.empty()) {
+                    pieces.push_back(GatherPiece{j, (uint32_t)e0, (uint32_t)e1, kNoPartial});
+                    piece_w.push_back(w[j] + kTileFixedWeight);
+                    L->ri[j] = RangeInfo{kRangeDirect | (1u << 2), 0};
+                    continue;
+                }
+                L->ri[j] = RangeInfo{kRangeMerged | ((uint32_t)(cuts.size() + 1) << 2), L->n_partials};
+                L->fin.push_back(j);
+                L->n_merged++;
+                cuts.push_back(e1);
+                uint64_t lo = e0;
+                for (uint64_t hi : cuts) {
+                    pieces.push_back(GatherPiece{j, (uint32_t)lo, (uint32_t)hi, L->n_partials++});
+                    piece_w.push_back(weight_at(hi) - weight_at(lo) + kTileFixedWeight);
+                    lo = hi;
+                }
             }
-            if (cuts.empty()) {
-                L->gt.push_back(GatherTile{j, (uint32_t)e0, (uint32_t)e1, kNoPartial});
-                L->gt_weight.push_back(w[j]);
-                L->ri[j] = RangeInfo{kRangeDirect | (1u << 2), 0};
-                continue;
+            uint64_t in_tile = 0;
+            uint32_t first = 0;
+            for (uint32_t i = 0; i < pieces.size(); ++i) {
+                if (i > first && in_tile + piece_w[i] > body + kTileFixedWeight) {
+                    tiles.push_back(make_uint2(first, i));
+                    first = i; in_tile = 0;
+                }
+                in_tile += piece_w[i];
             }
-            L->ri[j] = RangeInfo{kRangeMerged | ((uint32_t)(cuts.size() + 1) << 2), L->n_partials};
-            L->fin.push_back(j);
-            L->n_merged++;
-            cuts.push_back(e1);
-            uint64_t lo = e0;
-            for (uint64_t hi : cuts) {
-                L->gt.push_back(GatherTile{j, (uint32_t)lo, (uint32_t)hi, L->n_partials++});
-                L->gt_weight.push_back(weight_at(hi) - weight_at(lo));
-                lo = hi;
-            }
+            tiles.push_back(make_uint2(first, (uint32_t)pieces.size()));
+            if (tiles.size() <= slots) break;
         }
         for (uint32_t j = Qe; j < Q; ++j) L->fin.push_back(j);
+        L->gp = pieces;
+        L->gt = tiles;
+        for (const uint2& t : tiles) {
+            uint64_t wsum = 0, esum = 0;
+            for (uint32_t i = t.x; i < t.y; ++i) { wsum += piece_w[i]; esum += (uint64_t)pieces[i].e1 - pieces[i].e0; }
+            L->gt_weight.push_back(wsum);
+            L->gt_edges.push_back(esum);
+        }
     }
+    L->n_pieces = (uint32_t)L->gp.size();
     L->n_gather = (uint32_t)L->gt.size();
     L->n_finish = (uint32_t)L->fin.size();
 
@@ -497,7 +539,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     for (uint32_t t = 0; t < L->n_scatter; ++t) L->st_msgs[t] = (uint64_t)cum[ubound[t + 1]] - cum[ubound[t]];
 
     if (!keep(a, &L->bins, (uint64_t)L->n_scatter * Qe) || !keep(a, &L->range_info, (uint64_t)Q) ||
-        !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||
+        !keep(a, &L->gather_pieces, (uint64_t)L->n_pieces) || !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||
         !keep(a, &L->finish_ranges, (uint64_t)L->n_finish))
         PREP_NEED((void*)nullptr);
     if (Qe)
@@ -505,8 +547,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                            keys, incl, L->bins);
     PREP_HIP(hipGetLastError());
     PREP_HIP(hipMemcpyAsync(L->range_info, L->ri.data(), (size_t)Q * sizeof(RangeInfo), hipMemcpyHostToDevice, stream));
-    if (L->n_gather)
-        PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(GatherTile), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->gather_pieces, L->gp.data(), (size_t)L->n_pieces * sizeof(GatherPiece), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(uint2), hipMemcpyHostToDevice, stream));
     PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(ScatterTile), hipMemcpyHostToDevice, stream));
     if (L->n_finish)
         PREP_HIP(hipMemcpyAsync(L->finish_ranges, L->fin.data(), (size_t)L->n_finish * 4, hipMemcpyHostToDevice, stream));

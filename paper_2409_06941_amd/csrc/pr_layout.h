@@ -16,23 +16,27 @@
 //   * scatter sweep: the p-slice of contrib sits in LDS; for the ranges j of the tile the messages of bin (p, j)
 //     are written, msg[m] = contrib[src of m] -- sequential writes;
 //   * gather sweep: 64-bit fixed-point accumulators for the rows of one range sit in LDS; the id stream of the
-//     tile (one 16-bit local row id per edge, top bit set where a new message starts) and its messages are read
-//     sequentially and added into LDS with integer atomics.  Integer addition is associative, so the sums do
+//     tile (one 16-bit local row id per edge, and one bit per edge that says where a new message starts) and its
+//     messages are read sequentially and added into LDS with integer atomics.  Integer addition is associative, so the sums do
 //     not depend on the order the hardware performs them in.
 //
 // Ordering by degree makes the ranges very unequal (the first range of that graph holds 42 % of the edges), so
 // the unit of work is not the range but a TILE of about equal work:
-//   * a gather tile is a run of consecutive edges of one range (hence a source interval of it).  A range that
-//     needs several tiles is a MERGED range: each of its tiles stores its row sums as one row of fp32 partial
+//   * the gather sweep works in PIECES, runs of consecutive edges of one range (hence a source interval of it).
+//     A gather tile is one heavy piece, or several light pieces in a row that one workgroup takes one after the
+//     other: all tiles cost about the same, and there are no more of them than workgroups run side by side
+//     (a second round of workgroups only starts where a whole first-round workgroup has ended, which was
+//     measured to leave a quarter of the sweep's time half idle).  A range that
+//     needs several pieces is a MERGED range: each of its pieces stores its row sums as one row of fp32 partial
 //     sums (plain stores, no global atomics: 2.5 million 64-bit atomics from 150 workgroups were measured at 22 us
 //     on an otherwise idle chip), and the rows are finished - partial sums added in tile order, then r and contrib -
 //     at the start of the next scatter sweep.  This also spreads rows with very many in-edges over many
-//     workgroups; no other treatment of such rows is needed.  A range with one tile is DIRECT: its tile
+//     workgroups; no other treatment of such rows is needed.  A range with one piece is DIRECT: its piece
 //     finishes its rows itself;
 //   * a scatter tile is an interval of at most src_per_part consecutive sources with about equal numbers of
 //     messages (narrow for the sources that point into many ranges); every source belongs to exactly one scatter
 //     tile, so the finishing of merged rows is done once per row;
-//   * ranges behind the last row with an in-edge are EMPTY and have no gather tile: their rows' rank is the
+//   * ranges behind the last row with an in-edge are EMPTY and have no gather piece: their rows' rank is the
 //     iteration's base value, which the scatter sweep puts into its slice without reading a sum.
 #pragma once
 
@@ -51,22 +55,27 @@ constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
 static_assert(kRowsLarge <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
 constexpr uint32_t kTilesPerSweep = 256;     // a sweep is cut into tiles of the cost 1/256 of the sweep's ...
-constexpr uint64_t kMinTileEdges = 32768;    // ... but no smaller than this
+constexpr uint64_t kMinTileEdges = 32768;    // ... but no smaller than this (in weight: times kGatherEdgeWeight)
 constexpr uint64_t kMinTileMessages = 16384;
-// weight of a gather tile = edges + kGatherMessageWeight * messages + kGatherRepeatWeight * repeated edges; its cost
-// in the cutter adds kTileFixedWeight
-#ifndef FR_W_MSG
-#define FR_W_MSG 2
-#define FR_W_REP 3
-#define FR_W_FIX 131072
+// weight of a gather tile = kGatherEdgeWeight * edges + kGatherMessageWeight * messages + kGatherRepeatWeight *
+// repeated edges; its cost in the cutter adds kTileFixedWeight
+#ifndef FR_W_EDGE
+#define FR_W_EDGE 2
+#define FR_W_MSG 0
+#define FR_W_REP 5
+#define FR_W_FIX 98304
 #endif
-constexpr uint64_t kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP, kTileFixedWeight = FR_W_FIX;
+constexpr uint64_t kGatherEdgeWeight = FR_W_EDGE, kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP,
+                   kTileFixedWeight = FR_W_FIX;
+
+// An id is stored as the byte offset of its row's 8-byte accumulator, or half of it where that needs 17 bits.
+constexpr uint32_t id_scale_for(uint32_t rows_per_part) { return rows_per_part <= 8192 ? 8u : 4u; }
 
 enum : uint32_t { kRangeDirect = 0, kRangeMerged = 1, kRangeEmpty = 2 };
 
 constexpr uint32_t kNoPartial = 0xffffffffu;
-struct GatherTile { uint32_t range, e0, e1, partial; };    // edges [e0, e1) of the sorted edge array; row of partial
-                                                           // sums the tile writes (kNoPartial: direct range)
+struct GatherPiece { uint32_t range, e0, e1, partial; };   // edges [e0, e1) of the sorted edge array; row of partial
+                                                           // sums the piece writes (kNoPartial: direct range)
 struct ScatterTile { uint32_t u0, u1; };                   // sources [u0, u1)
 struct RangeInfo { uint32_t cls_tiles, partial0; };        // class | gather tiles << 2; first row of partial sums
 
@@ -76,28 +85,33 @@ struct PrLayout {
     uint32_t rows_per_part = kRowsSmall, src_per_part = kSrcSmall;
     uint32_t Q = 0;                  // ranges, ceil(V / rows_per_part)
     uint32_t Qe = 0;                 // ranges with at least one in-edge (they come first)
-    uint32_t n_gather = 0, n_scatter = 0;
-    uint32_t n_merged = 0;           // ranges cut into several gather tiles
-    uint32_t n_partials = 0;         // gather tiles of merged ranges = rows of partial sums
+    uint32_t n_pieces = 0;           // gather pieces: runs of edges of one range
+    uint32_t n_gather = 0, n_scatter = 0;   // tiles (a gather tile is one heavy piece or several light ones in a row)
+    uint32_t n_merged = 0;           // ranges cut into several gather pieces
+    uint32_t n_partials = 0;         // gather pieces of merged ranges = rows of partial sums
     uint32_t n_finish = 0;           // merged + empty ranges (the tiles of the pass after the last iteration)
     uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
 
     // device arrays (allocated through the task's accounting allocator)
     int32_t* perm = nullptr;         // [V] caller's id of new id v
-    uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id, bit 15 = first edge of a message;
+    uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id times id_scale_for(rows_per_part);
                                      // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
+    uint64_t* starts = nullptr;      // [n_chunks * 8] bit l of word 8 c + j: position 64 j + l of chunk c begins a message
     uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter tile
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
     uint2* bins = nullptr;           // [n_scatter * Qe] message range [x, y) of (scatter tile, range), tile-major
     float* inv_out = nullptr;        // [V] 1/outdeg (0 if dangling)
     RangeInfo* range_info = nullptr; // [Q]
-    GatherTile* gather_tiles = nullptr;    // [n_gather], heaviest ranges first
+    GatherPiece* gather_pieces = nullptr;  // [n_pieces], heaviest ranges first
+    uint2* gather_tiles = nullptr;         // [n_gather] pieces [x, y) of each tile
     ScatterTile* scatter_tiles = nullptr;  // [n_scatter]
     uint32_t* finish_ranges = nullptr;     // [n_finish] merged ranges, then empty ranges
 
     // host copies for the cost model
-    std::vector<GatherTile> gt;
-    std::vector<uint64_t> gt_weight;     // weight of each gather tile
+    std::vector<GatherPiece> gp;
+    std::vector<uint2> gt;               // pieces of each gather tile
+    std::vector<uint64_t> gt_weight;     // weight of each gather tile (its pieces' weights, kTileFixedWeight a piece included)
+    std::vector<uint64_t> gt_edges;      // edges of each gather tile
     std::vector<ScatterTile> st;
     std::vector<uint64_t> st_msgs;       // messages of each scatter tile
     std::vector<uint64_t> st_partials;   // partial sums each scatter tile adds up

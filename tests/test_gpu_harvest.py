@@ -46,7 +46,7 @@ def _scaled_model(share, phase_ns, iterations, gather_weight, scatter_weight, in
     s_fs = share * phase_ns[1] / iterations * 1e6
     g_fs = share * phase_ns[2] / iterations * 1e6
     pm = max(1, int((s_fs - scatter_weight * pv) / max(1, info.messages)))
-    pe = max(1, int((g_fs - info.gather_tiles * info.rows_per_partition * pv) / max(1, gather_weight)))
+    pe = max(1, int(2 * g_fs / max(1, gather_weight)))
     return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe, finish_tile_ns=1000)
 
 
@@ -63,8 +63,8 @@ def _check_cost_rule(task, pe, pm, pv, hub_ns):
     edges = task.fr_pagerank_tile_work(fr.FR_PR_SEG_GATHER)
     R = info.rows_per_partition
     weights = task.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER)
-    assert all(w >= e for w, e in zip(weights, edges))          # edges + 2 messages + 3 repeated edges
-    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(w * pe + R * pv) // 10**6)) for w in weights]
+    assert all(w >= 2 * e + 98304 for w, e in zip(weights, edges))     # 2 edges + 5 repeated edges + 98304 a piece
+    assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_GATHER) == [max(1, -(-(w * pe // 2) // 10**6)) for w in weights]
     msgs = task.fr_pagerank_tile_work(fr.FR_PR_SEG_SCATTER)
     srcs = task.fr_pagerank_tile_weights(fr.FR_PR_SEG_SCATTER)
     assert task.fr_pagerank_tile_costs(fr.FR_PR_SEG_SCATTER) == [max(1, -(-(m * pm + s * pv) // 10**6)) for m, s in zip(msgs, srcs)]
