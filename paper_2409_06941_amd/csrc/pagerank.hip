@@ -100,7 +100,7 @@ __device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 flo
 
 struct DevArgs {
     int64_t V, E;
-    uint32_t M, Q, Qe, n_gather, n_pieces, n_scatter, n_finish, n_dpart;
+    uint32_t M, Q, Qe, n_gather, n_pieces, n_scatter, n_spieces, n_finish, n_dpart;
     uint32_t rows_per_part, rows_shift;           // rows per range and its log2
     float damping;
     const uint16_t* ids16;
@@ -113,7 +113,8 @@ struct DevArgs {
     const RangeInfo* range_info;
     const GatherPiece* gather_pieces;
     const uint2* gather_tiles;
-    const ScatterTile* scatter_tiles;
+    const ScatterPiece* scatter_pieces;
+    const uint4* scatter_tiles;
     const uint32_t* finish_ranges;
     float* msg;
     float* contrib;
@@ -131,8 +132,8 @@ struct GateArg {
 // Sum of a merged row's partial sums p_0 .. p_{nt-1}.  The order is fixed: sixteen leaves, leaf g = p_g + p_{g+16} +
 // ... in rising order, joined by a balanced tree over g.  kLanes lanes (a power of two up to 16, consecutive in
 // the wavefront, all active) share the row: lane `sub` owns the leaves sub * 16 / kLanes onwards, joins them, and
-// the lanes' results are joined by butterfly exchanges, which is the same tree.  Every lane gets the sum.  Sixteen
-// loads per row are in flight at a time.
+// the lanes' results are joined by butterfly exchanges, which is the same tree.  Every lane gets the sum.  Up to
+// eight loads per lane are in flight at a time.
 template <int kLanes>
 __device__ __forceinline__ float merged_sum(const DevArgs& A, RangeInfo info, uint32_t local, uint32_t sub)
 {
@@ -142,15 +143,19 @@ __device__ __forceinline__ float merged_sum(const DevArgs& A, RangeInfo info, ui
     float s[kLeaves];
 #pragma unroll
     for (int k = 0; k < kLeaves; ++k) s[k] = 0.0f;
+    constexpr int kBatch = kLeaves < 8 ? kLeaves : 8;          // loads in flight (registers)
     for (uint32_t t0 = 0; t0 < nt; t0 += 16) {
-        float x[kLeaves];
 #pragma unroll
-        for (int k = 0; k < kLeaves; ++k) {
-            const uint32_t t = t0 + sub * kLeaves + k;
-            x[k] = t < nt ? p[(size_t)t << A.rows_shift] : 0.0f;
+        for (int k0 = 0; k0 < kLeaves; k0 += kBatch) {
+            float x[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const uint32_t t = t0 + sub * kLeaves + k0 + k;
+                x[k] = t < nt ? p[(size_t)t << A.rows_shift] : 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) s[k0 + k] += x[k];
         }
-#pragma unroll
-        for (int k = 0; k < kLeaves; ++k) s[k] += x[k];
     }
 #pragma unroll
     for (int w = 1; w < kLeaves; w <<= 1)
@@ -333,7 +338,9 @@ __device__ __forceinline__ void emit_group(const GroupRef& ref, const uint2* des
 
 // `parity` names the set of dangling partials that belongs to the iteration just finished (ignored when first).
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
-template <uint32_t kSrcPerPart>
+// kPacked: some tile has more than one piece (kept apart: the loop over pieces costs the small size registers it
+// does not have).
+template <uint32_t kSrcPerPart, bool kPacked>
 __global__ __launch_bounds__(kScatterBlock) __attribute__((amdgpu_waves_per_eu(kSrcPerPart == kSrcSmall ? 8 : 4, kSrcPerPart == kSrcSmall ? 8 : 4)))
 void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
 {
@@ -344,52 +351,66 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
     __shared__ float red[32];
     static_assert(kDescBatch <= kScatterBlock, "one bin per thread");
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t t = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
-    const ScatterTile T = A.scatter_tiles[t];
+    const uint32_t tile = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
+    const uint4 span = A.scatter_tiles[tile];                    // the tile's pieces [x, y), worked on one after the other;
+                                                                 // z, w: the sources of the first (saves a dependent load)
     const uint32_t Qe = A.Qe;
-    // the first batch of bin descriptors is asked for now and used after the slice is filled
-    uint2 d_first = make_uint2(0, 0);
-    if (threadIdx.x < Qe) d_first = A.bins[(uint64_t)t * Qe + threadIdx.x];
-    const uint32_t u0 = T.u0;
-    const uint32_t n = T.u1 - T.u0 < kSrcPerPart ? T.u1 - T.u0 : kSrcPerPart;
-    if (first) {
-        const float r0 = 1.0f / (float)A.V;
-#pragma unroll 4
-        for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i];
-    } else {
+    float base = 0.0f;
+    if (!first) {
         const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
-        const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
-        const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
-        if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
+        base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     }
     const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
-    for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
-        const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
-        __syncthreads();                                   // slice filled / previous batch consumed
-        uint32_t groups = 0;
-        if (threadIdx.x < nb) {
-            uint2 d = qb == 0 ? d_first : A.bins[(uint64_t)t * Qe + qb + threadIdx.x];
-            if (d.y > A.M) d.y = A.M;
-            if (d.x > d.y) d.x = d.y;
-            desc[threadIdx.x] = d;
-            if (d.y > d.x) groups = (d.y - 1) / kGroup - d.x / kGroup + 1;
+    auto do_piece = [&](uint32_t t, ScatterPiece T) {
+        // the first batch of bin descriptors is asked for now and used after the slice is filled
+        uint2 d_first = make_uint2(0, 0);
+        if (threadIdx.x < Qe) d_first = A.bins[(uint64_t)t * Qe + threadIdx.x];
+        const uint32_t u0 = T.u0;
+        const uint32_t n = T.u1 - T.u0 < kSrcPerPart ? T.u1 - T.u0 : kSrcPerPart;
+        if (first) {
+            const float r0 = 1.0f / (float)A.V;
+#pragma unroll 4
+            for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i];
+        } else {
+            const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
+            if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
         }
-        block_exclusive_scan(groups, gpre, wave_tot);
-        const uint32_t total = gpre[kScatterBlock];
-        constexpr int kAhead = FR_AHEAD;                         // groups a thread has in flight
-        for (uint32_t k0 = threadIdx.x; k0 < total; k0 += kAhead * kScatterBlock) {
-            GroupRef ref[kAhead];
-            uint4 raw[kAhead];
-#pragma unroll
-            for (int a = 0; a < kAhead; ++a) {
-                const uint32_t k = k0 + a * kScatterBlock;
-                ref[a] = GroupRef{0, 0};
-                raw[a] = make_uint4(0, 0, 0, 0);
-                if (k < total) { ref[a] = locate_group(k, gpre, desc, nb); raw[a] = src8[ref[a].m0 / kGroup]; }
+        for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
+            const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
+            __syncthreads();                                     // slice filled / previous batch consumed
+            uint32_t groups = 0;
+            if (threadIdx.x < nb) {
+                uint2 d = qb == 0 ? d_first : A.bins[(uint64_t)t * Qe + qb + threadIdx.x];
+                if (d.y > A.M) d.y = A.M;
+                if (d.x > d.y) d.x = d.y;
+                desc[threadIdx.x] = d;
+                if (d.y > d.x) groups = (d.y - 1) / kGroup - d.x / kGroup + 1;
             }
+            block_exclusive_scan(groups, gpre, wave_tot);
+            const uint32_t total = gpre[kScatterBlock];
+            constexpr int kAhead = FR_AHEAD;                     // groups a thread has in flight
+            for (uint32_t k0 = threadIdx.x; k0 < total; k0 += kAhead * kScatterBlock) {
+                GroupRef ref[kAhead];
+                uint4 raw[kAhead];
 #pragma unroll
-            for (int a = 0; a < kAhead; ++a)
-                if (k0 + a * kScatterBlock < total) emit_group(ref[a], desc, raw[a], slice, n, A.msg);
+                for (int a = 0; a < kAhead; ++a) {
+                    const uint32_t k = k0 + a * kScatterBlock;
+                    ref[a] = GroupRef{0, 0};
+                    raw[a] = make_uint4(0, 0, 0, 0);
+                    if (k < total) { ref[a] = locate_group(k, gpre, desc, nb); raw[a] = src8[ref[a].m0 / kGroup]; }
+                }
+#pragma unroll
+                for (int a = 0; a < kAhead; ++a)
+                    if (k0 + a * kScatterBlock < total) emit_group(ref[a], desc, raw[a], slice, n, A.msg);
+            }
+        }
+    };
+    if constexpr (!kPacked) {
+        do_piece(span.x, ScatterPiece{span.z, span.w});
+    } else {
+        for (uint32_t t = span.x; t < span.y; ++t) {
+            __syncthreads();                                     // the piece before is done with slice and desc
+            do_piece(t, t == span.x ? ScatterPiece{span.z, span.w} : A.scatter_pieces[t]);
         }
     }
     fr_gate_done(G.gate);
@@ -447,7 +468,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
     if (tile == 0 && !final_pass)                                // slots no piece and no scatter tile writes
-        for (uint32_t i = A.n_pieces + A.n_scatter + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
+        for (uint32_t i = A.n_pieces + A.n_spieces + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
     for (uint32_t t = span.x; t < span.y; ++t) {
     const GatherPiece T = A.gather_pieces[t];
     const uint32_t q = T.range;
@@ -696,8 +717,7 @@ void build_cost_tables(PrTask* p)
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
     s.assign(L.n_scatter + 1, 0);
     for (uint32_t i = 0; i < L.n_scatter; ++i) {
-        const uint64_t srcs = (uint64_t)L.st[i].u1 - L.st[i].u0 + L.st_partials[i];     // a partial sum costs about a vertex
-        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.st_msgs[i] * pm + (unsigned __int128)srcs * pv);
+        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.st_msgs[i] * pm + (unsigned __int128)L.st_rows[i] * pv);   // a partial sum costs about a vertex
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
     const uint32_t ng = p->tiles_of(FR_PR_SEG_GATHER);
@@ -726,10 +746,13 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
         const uint32_t k = (g - 1) / 2;
         if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes rows of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
+            const bool packed = p->L.n_scatter != p->L.n_spieces;
             if (p->L.src_per_part == kSrcLarge)
-                hipLaunchKernelGGL(k_scatter<kSrcLarge>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+                hipLaunchKernelGGL((k_scatter<kSrcLarge, true>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+            else if (packed)
+                hipLaunchKernelGGL((k_scatter<kSrcSmall, true>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
             else
-                hipLaunchKernelGGL(k_scatter<kSrcSmall>, dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+                hipLaunchKernelGGL((k_scatter<kSrcSmall, false>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
         } else {
             const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
             if (p->L.rows_per_part == kRowsLarge)
@@ -752,6 +775,23 @@ bool take(fr_alloc* a, T** out, uint64_t count)
     return *out != nullptr;
 }
 
+// Compute units the stream may use (its CU mask, if it has one): the sweeps are cut into that many tiles.
+uint32_t stream_cus(hipStream_t stream)
+{
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+        cus = (int)kDefaultCus;
+    uint32_t mask[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (hipExtStreamGetCUMask(stream, 8, mask) == hipSuccess) {
+        int masked = 0;
+        for (uint32_t w : mask) masked += __builtin_popcount(w);
+        if (masked > 0 && masked < cus) cus = masked;
+    } else {
+        (void)hipGetLastError();          // a stream without a mask of its own
+    }
+    return (uint32_t)cus;
+}
+
 int pr_init(void* user, fr_alloc* a, void* stream_v)
 {
     PrTask* p = static_cast<PrTask*>(user);
@@ -762,23 +802,25 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     const uint64_t caller = 4ull * (uint64_t)(V + 1) + 4ull * (uint64_t)E + 4ull * (uint64_t)V + 4ull * (uint64_t)V;
     if (fr_alloc_charge(a, caller) != FR_OK) return FR_ERR_OOM;
     int rc = pr_build_layout(&p->L, V, E, p->d.row_ptr, p->d.col, p->d.out_degree, p->d.rows_per_partition,
-                             p->d.sources_per_partition, a, stream, &p->hip_error);
+                             p->d.sources_per_partition, stream_cus(stream), a, stream, &p->hip_error);
     if (rc != FR_OK) return rc;
     PrLayout& L = p->L;
-    // dangling partials: one slot per range (V0), or one per gather piece followed by one per scatter tile
-    p->n_dpart = std::max(L.Q, L.n_pieces + L.n_scatter);
+    // dangling partials: one slot per range (V0), or one per gather piece followed by one per scatter piece
+    p->n_dpart = std::max(L.Q, L.n_pieces + L.n_spieces);
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
         !take(a, &p->partials, (uint64_t)L.n_partials * L.rows_per_part))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
     DevArgs& A = p->args;
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.Qe = L.Qe;
-    A.n_gather = L.n_gather; A.n_pieces = L.n_pieces; A.n_scatter = L.n_scatter; A.n_finish = L.n_finish;
+    A.n_gather = L.n_gather; A.n_pieces = L.n_pieces; A.n_scatter = L.n_scatter; A.n_spieces = L.n_spieces;
+    A.n_finish = L.n_finish;
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.rows_per_part = L.rows_per_part;
     A.rows_shift = L.rows_per_part == kRowsLarge ? 14 : 13;
     A.ids16 = L.ids16; A.src16 = L.src16; A.mbase = L.mbase; A.starts = L.starts; A.bins = L.bins;
     A.inv_out = L.inv_out; A.perm = L.perm; A.range_info = L.range_info;
-    A.gather_pieces = L.gather_pieces; A.gather_tiles = L.gather_tiles; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
+    A.gather_pieces = L.gather_pieces; A.gather_tiles = L.gather_tiles;
+    A.scatter_pieces = L.scatter_pieces; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.partials = p->partials; A.ranks_out = p->d.ranks_out;
     build_cost_tables(p);
     p->footprint_after = fr_alloc_used(a);
@@ -962,7 +1004,7 @@ int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights, si
     const size_t n = p->tiles_of(seg_kind);
     for (size_t t = 0; t < std::min(n, cap); ++t) {
         if (seg_kind == FR_PR_SEG_GATHER) weights[t] = p->L.gt_weight[t];
-        else if (seg_kind == FR_PR_SEG_SCATTER) weights[t] = (uint64_t)p->L.st[t].u1 - p->L.st[t].u0 + p->L.st_partials[t];
+        else if (seg_kind == FR_PR_SEG_SCATTER) weights[t] = p->L.st_rows[t];
         else if (seg_kind == FR_PR_SEG_VERTEX) weights[t] = p->rows_of_q((uint32_t)t);
         else weights[t] = 0;
     }

@@ -277,9 +277,10 @@ bool keep(fr_alloc* a, T** out, uint64_t count)
     } while (0)
 
 int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
-                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, fr_alloc* a,
+                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, uint32_t cus, fr_alloc* a,
                     hipStream_t stream, int* hip_error)
 {
+    if (!cus) cus = kDefaultCus;
     if (!rows_per_part) rows_per_part = V >= kLargeRowsFrom ? kRowsLarge : kRowsSmall;
     if (!src_per_part) src_per_part = V >= kLargeSrcFrom ? kSrcLarge : kSrcSmall;
     if ((rows_per_part != kRowsSmall && rows_per_part != kRowsLarge) || (src_per_part != kSrcSmall && src_per_part != kSrcLarge))
@@ -365,7 +366,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     tmp.drop(inv);
     L->M = M;
 
-    // ---- scatter tiles: source intervals of about equal numbers of messages
+    // ---- scatter pieces: source intervals of about equal numbers of messages
     std::vector<uint32_t> cum((size_t)V + 1, 0u);            // messages of the sources before u
     if (E > 0) {
         uint32_t* cnt = tmp.take<uint32_t>((uint64_t)V + 1);
@@ -385,7 +386,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     }
     std::vector<uint32_t> ubound;
     {
-        const uint64_t target = std::max<uint64_t>(kMinTileMessages, ((uint64_t)M + kTilesPerSweep - 1) / kTilesPerSweep);
+        // (one heavy piece per CU; where two workgroups share a CU, the other places take the light pieces)
+        const uint64_t target = std::max<uint64_t>(kMinTileMessages, ((uint64_t)M + cus - 1) / cus);
         uint64_t u = 0;
         while (u < (uint64_t)V) {
             const uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
@@ -399,7 +401,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         }
         ubound.push_back((uint32_t)V);
     }
-    L->n_scatter = (uint32_t)ubound.size() - 1;
+    L->n_spieces = (uint32_t)ubound.size() - 1;
 
     // ---- the arrays that stay
     if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->starts, (uint64_t)padded / 64) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
@@ -409,7 +411,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_NEED(ubound_dev); PREP_NEED(eoff);
     PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
-                       ubound_dev, L->n_scatter, id_scale_for(rows_per_part), L->ids16, L->src16);
+                       ubound_dev, L->n_spieces, id_scale_for(rows_per_part), L->ids16, L->src16);
     hipLaunchKernelGGL(k_starts, dim3(blocks_for((uint64_t)padded / 64)), dim3(kBlk), 0, stream, E, (uint64_t)padded / 64, keys, L->starts);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, eoff);
@@ -455,7 +457,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         // the row pass at its end).  Ranges are cut into pieces of at most `body` weight; pieces are then grouped, in
         // order, into tiles of at most body + kTileFixedWeight.  `body` is the smallest (to 2 %) that gives no more
         // tiles than workgroups run side by side.
-        const uint64_t slots = (uint64_t)kTilesPerSweep * (rows_per_part == kRowsSmall ? FR_SMALL_SLOTS : 1);
+        const uint64_t slots = (uint64_t)cus * (rows_per_part == kRowsSmall ? FR_SMALL_SLOTS : 1);
         std::vector<uint64_t> w(Qe);
         uint64_t total = 0;
         for (uint32_t j = 0; j < Qe; ++j) { w[j] = weight_at(eoff_host[j + 1]) - weight_at(eoff_host[j]); total += w[j]; }
@@ -522,34 +524,70 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     L->n_gather = (uint32_t)L->gt.size();
     L->n_finish = (uint32_t)L->fin.size();
 
-    // ---- scatter tiles: partial sums to add up
-    L->st.clear(); L->st_partials.clear();
-    for (uint32_t t = 0; t < L->n_scatter; ++t) {
-        const uint64_t u0 = ubound[t], u1 = ubound[t + 1];
-        uint64_t partials = 0;
-        for (uint64_t j = u0 / rows_per_part; j < Q && j * rows_per_part < u1; ++j) {
-            if ((L->ri[j].cls_tiles & 3u) != kRangeMerged) continue;
-            const uint64_t lo = std::max<uint64_t>(u0, j * rows_per_part), hi = std::min<uint64_t>(u1, (j + 1) * (uint64_t)rows_per_part);
-            partials += (hi - lo) * (L->ri[j].cls_tiles >> 2);
+    // ---- scatter tiles: a heavy piece, or light pieces in a row, packed only as far as it takes to have no more
+    // tiles than workgroups run side by side.  Cost of a piece: 2 a message, 3 a source or partial sum
+    // added up, kScatterFixedWeight for its start.
+    L->sp.clear(); L->st.clear(); L->st_msgs.clear(); L->st_rows.clear();
+    {
+        std::vector<uint64_t> msgs(L->n_spieces), rows(L->n_spieces), cost(L->n_spieces);
+        uint64_t limit = 0;
+        for (uint32_t t = 0; t < L->n_spieces; ++t) {
+            const uint64_t u0 = ubound[t], u1 = ubound[t + 1];
+            uint64_t partials = 0;
+            for (uint64_t j = u0 / rows_per_part; j < Q && j * rows_per_part < u1; ++j) {
+                if ((L->ri[j].cls_tiles & 3u) != kRangeMerged) continue;
+                const uint64_t lo = std::max<uint64_t>(u0, j * rows_per_part), hi = std::min<uint64_t>(u1, (j + 1) * (uint64_t)rows_per_part);
+                partials += (hi - lo) * (L->ri[j].cls_tiles >> 2);
+            }
+            L->sp.push_back(ScatterPiece{(uint32_t)u0, (uint32_t)u1});
+            msgs[t] = (uint64_t)cum[u1] - cum[u0];
+            rows[t] = (u1 - u0) + partials;
+            cost[t] = 2 * msgs[t] + 3 * rows[t] + kScatterFixedWeight;
+            limit = std::max(limit, cost[t]);
         }
-        L->st_partials.push_back(partials);
-        L->st.push_back(ScatterTile{(uint32_t)u0, (uint32_t)u1});
+        const uint64_t slots = (uint64_t)cus * (src_per_part == kSrcSmall ? 2 : 1);
+        std::vector<uint2> tiles;
+        // (no packing at all if the pieces are few enough; else the smallest limit, to 2 %, that gives few enough tiles)
+        uint64_t all = 0;
+        for (uint64_t c : cost) all += c;
+        limit = 0;
+        for (int round = 0; round < 600; ++round, limit = round == 1 ? all / slots + 1 : limit + limit / 50 + 1) {
+            tiles.clear();
+            uint64_t in_tile = 0;
+            uint32_t first = 0;
+            for (uint32_t i = 0; i < L->n_spieces; ++i) {
+                if (i > first && in_tile + cost[i] > limit) {
+                    tiles.push_back(make_uint2(first, i));
+                    first = i; in_tile = 0;
+                }
+                in_tile += cost[i];
+            }
+            tiles.push_back(make_uint2(first, L->n_spieces));
+            if (tiles.size() <= slots) break;
+        }
+        for (const uint2& t : tiles) {
+            L->st.push_back(make_uint4(t.x, t.y, L->sp[t.x].u0, L->sp[t.x].u1));
+            uint64_t m = 0, r = 0;
+            for (uint32_t i = t.x; i < t.y; ++i) { m += msgs[i]; r += rows[i]; }
+            L->st_msgs.push_back(m);
+            L->st_rows.push_back(r);
+        }
     }
-    L->st_msgs.resize(L->n_scatter);
-    for (uint32_t t = 0; t < L->n_scatter; ++t) L->st_msgs[t] = (uint64_t)cum[ubound[t + 1]] - cum[ubound[t]];
+    L->n_scatter = (uint32_t)L->st.size();
 
-    if (!keep(a, &L->bins, (uint64_t)L->n_scatter * Qe) || !keep(a, &L->range_info, (uint64_t)Q) ||
-        !keep(a, &L->gather_pieces, (uint64_t)L->n_pieces) || !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||
+    if (!keep(a, &L->bins, (uint64_t)L->n_spieces * Qe) || !keep(a, &L->range_info, (uint64_t)Q) ||
+        !keep(a, &L->gather_pieces, (uint64_t)L->n_pieces) || !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_pieces, (uint64_t)L->n_spieces) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||
         !keep(a, &L->finish_ranges, (uint64_t)L->n_finish))
         PREP_NEED((void*)nullptr);
     if (Qe)
-        hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->n_scatter * Qe)), dim3(kBlk), 0, stream, L->n_scatter, Qe, E, M, ubound_dev,
+        hipLaunchKernelGGL(k_bins, dim3(blocks_for((uint64_t)L->n_spieces * Qe)), dim3(kBlk), 0, stream, L->n_spieces, Qe, E, M, ubound_dev,
                            keys, incl, L->bins);
     PREP_HIP(hipGetLastError());
     PREP_HIP(hipMemcpyAsync(L->range_info, L->ri.data(), (size_t)Q * sizeof(RangeInfo), hipMemcpyHostToDevice, stream));
     PREP_HIP(hipMemcpyAsync(L->gather_pieces, L->gp.data(), (size_t)L->n_pieces * sizeof(GatherPiece), hipMemcpyHostToDevice, stream));
     PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(uint2), hipMemcpyHostToDevice, stream));
-    PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(ScatterTile), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->scatter_pieces, L->sp.data(), (size_t)L->n_spieces * sizeof(ScatterPiece), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(uint4), hipMemcpyHostToDevice, stream));
     if (L->n_finish)
         PREP_HIP(hipMemcpyAsync(L->finish_ranges, L->fin.data(), (size_t)L->n_finish * 4, hipMemcpyHostToDevice, stream));
     PREP_HIP(hipStreamSynchronize(stream));       // the host vectors and `tmp` go away after this

@@ -33,9 +33,10 @@
 //     at the start of the next scatter sweep.  This also spreads rows with very many in-edges over many
 //     workgroups; no other treatment of such rows is needed.  A range with one piece is DIRECT: its piece
 //     finishes its rows itself;
-//   * a scatter tile is an interval of at most src_per_part consecutive sources with about equal numbers of
-//     messages (narrow for the sources that point into many ranges); every source belongs to exactly one scatter
-//     tile, so the finishing of merged rows is done once per row;
+//   * the scatter sweep works in pieces too: intervals of at most src_per_part consecutive sources with about
+//     equal numbers of messages (narrow for the sources that point into many ranges), heavy ones a tile each, light
+//     ones several to a tile; every source belongs to exactly one piece, so the finishing of merged rows is done
+//     once per row;
 //   * ranges behind the last row with an in-edge are EMPTY and have no gather piece: their rows' rank is the
 //     iteration's base value, which the scatter sweep puts into its slice without reading a sum.
 #pragma once
@@ -54,7 +55,7 @@ constexpr int kKeyLocalBits = 15;            // sort key = range << 46 | source 
 constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
 static_assert(kRowsLarge <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
-constexpr uint32_t kTilesPerSweep = 256;     // a sweep is cut into tiles of the cost 1/256 of the sweep's ...
+constexpr uint32_t kDefaultCus = 256;        // a sweep is cut into as many tiles as workgroups run side by side ...
 constexpr uint64_t kMinTileEdges = 32768;    // ... but no smaller than this (in weight: times kGatherEdgeWeight)
 constexpr uint64_t kMinTileMessages = 16384;
 // weight of a gather tile = kGatherEdgeWeight * edges + kGatherMessageWeight * messages + kGatherRepeatWeight *
@@ -65,6 +66,7 @@ constexpr uint64_t kMinTileMessages = 16384;
 #define FR_W_REP 5
 #define FR_W_FIX 98304
 #endif
+constexpr uint64_t kScatterFixedWeight = 16384;
 constexpr uint64_t kGatherEdgeWeight = FR_W_EDGE, kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP,
                    kTileFixedWeight = FR_W_FIX;
 
@@ -76,7 +78,7 @@ enum : uint32_t { kRangeDirect = 0, kRangeMerged = 1, kRangeEmpty = 2 };
 constexpr uint32_t kNoPartial = 0xffffffffu;
 struct GatherPiece { uint32_t range, e0, e1, partial; };   // edges [e0, e1) of the sorted edge array; row of partial
                                                            // sums the piece writes (kNoPartial: direct range)
-struct ScatterTile { uint32_t u0, u1; };                   // sources [u0, u1)
+struct ScatterPiece { uint32_t u0, u1; };                  // sources [u0, u1)
 struct RangeInfo { uint32_t cls_tiles, partial0; };        // class | gather tiles << 2; first row of partial sums
 
 struct PrLayout {
@@ -86,7 +88,8 @@ struct PrLayout {
     uint32_t Q = 0;                  // ranges, ceil(V / rows_per_part)
     uint32_t Qe = 0;                 // ranges with at least one in-edge (they come first)
     uint32_t n_pieces = 0;           // gather pieces: runs of edges of one range
-    uint32_t n_gather = 0, n_scatter = 0;   // tiles (a gather tile is one heavy piece or several light ones in a row)
+    uint32_t n_spieces = 0;          // scatter pieces: intervals of sources
+    uint32_t n_gather = 0, n_scatter = 0;   // tiles (a tile is one heavy piece or several light ones in a row)
     uint32_t n_merged = 0;           // ranges cut into several gather pieces
     uint32_t n_partials = 0;         // gather pieces of merged ranges = rows of partial sums
     uint32_t n_finish = 0;           // merged + empty ranges (the tiles of the pass after the last iteration)
@@ -97,14 +100,15 @@ struct PrLayout {
     uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id times id_scale_for(rows_per_part);
                                      // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
     uint64_t* starts = nullptr;      // [n_chunks * 8] bit l of word 8 c + j: position 64 j + l of chunk c begins a message
-    uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter tile
+    uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter piece
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
-    uint2* bins = nullptr;           // [n_scatter * Qe] message range [x, y) of (scatter tile, range), tile-major
+    uint2* bins = nullptr;           // [n_spieces * Qe] message range [x, y) of (scatter piece, range), piece-major
     float* inv_out = nullptr;        // [V] 1/outdeg (0 if dangling)
     RangeInfo* range_info = nullptr; // [Q]
     GatherPiece* gather_pieces = nullptr;  // [n_pieces], heaviest ranges first
     uint2* gather_tiles = nullptr;         // [n_gather] pieces [x, y) of each tile
-    ScatterTile* scatter_tiles = nullptr;  // [n_scatter]
+    ScatterPiece* scatter_pieces = nullptr;  // [n_spieces]
+    uint4* scatter_tiles = nullptr;        // [n_scatter] pieces [x, y) of each tile; z, w = sources [u0, u1) of piece x
     uint32_t* finish_ranges = nullptr;     // [n_finish] merged ranges, then empty ranges
 
     // host copies for the cost model
@@ -112,9 +116,10 @@ struct PrLayout {
     std::vector<uint2> gt;               // pieces of each gather tile
     std::vector<uint64_t> gt_weight;     // weight of each gather tile (its pieces' weights, kTileFixedWeight a piece included)
     std::vector<uint64_t> gt_edges;      // edges of each gather tile
-    std::vector<ScatterTile> st;
+    std::vector<ScatterPiece> sp;
+    std::vector<uint4> st;               // pieces of each scatter tile (and the first piece's sources)
     std::vector<uint64_t> st_msgs;       // messages of each scatter tile
-    std::vector<uint64_t> st_partials;   // partial sums each scatter tile adds up
+    std::vector<uint64_t> st_rows;       // sources + partial sums added up, of each scatter tile
     std::vector<RangeInfo> ri;           // [Q]
     std::vector<uint32_t> fin;           // [n_finish]
 };
@@ -123,6 +128,7 @@ struct PrLayout {
 // rows_per_part / src_per_part: 0 = chosen from V, else one of the two sizes above (FR_ERR_ARG otherwise).
 // Temporary memory is taken from and returned to `a`.  Returns FR_OK, FR_ERR_OOM, FR_ERR_HIP or FR_ERR_ARG
 // (malformed CSR).  `hip_error` receives the failing HIP code, if any.
+// cus: compute units the sweeps will have (tiles are made for that many workgroups side by side).
 int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
-                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, fr_alloc* a,
+                    const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, uint32_t cus, fr_alloc* a,
                     hipStream_t stream, int* hip_error);

@@ -76,7 +76,7 @@ def test_every_partition_size(rows, srcs):
     info = t.fr_pagerank_info()
     t.fr_pagerank_destroy()
     assert (info.rows_per_partition, info.sources_per_partition) == (rows, srcs) and info.merged_ranges > 0
-    assert info.ranges == -(-g.n_vertices // rows) and info.scatter_tiles >= -(-g.n_vertices // srcs)
+    assert info.ranges == -(-g.n_vertices // rows) and 1 <= info.scatter_tiles <= 512
     got = ranks.cpu().numpy()
     want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 9)
     assert np.abs(got.astype(np.float64) - want).max() <= TOL
@@ -221,7 +221,7 @@ def test_layout_facts_match_the_graph():
     n_direct = info.nonempty_ranges - info.merged_ranges
     assert pieces_total == n_direct + info.partial_rows
     assert sum(msgs) == info.messages and len(msgs) == info.scatter_tiles
-    assert max(msgs) <= max(16384, -(-info.messages // 256)) + info.nonempty_ranges
+    assert len(msgs) <= 512                                             # no more tiles than workgroups side by side
     assert all(s >= 1 for s in srcs) and sum(srcs) >= V                 # sources + partial sums added up
 
 
