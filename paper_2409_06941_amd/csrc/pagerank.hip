@@ -47,6 +47,8 @@ constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the 
 constexpr int kScatterWaves = kScatterBlock / 64;
 // row sums are kept as 64-bit fixed point with scale 2^62: contrib sums are <= 1, so they fit
 constexpr float kFixInv = 1.0f / 4611686018427387904.0f;
+// messages are contrib * 2^30: see to_fixed
+constexpr float kMsgScale = 1073741824.0f;
 
 // ---- fixed-order reductions ----
 __device__ __forceinline__ float wave_sum(float x)
@@ -181,7 +183,7 @@ __device__ __forceinline__ float fill_merged(const DevArgs& A, RangeInfo info, u
         const float inv = A.inv_out[u];
         const float r = fmaf(A.damping, merged_sum<kLanes>(A, info, u & (A.rows_per_part - 1), sub), base);
         if (sub == 0) {
-            slice[i] = r * inv;
+            slice[i] = r * inv * kMsgScale;
             dangling += (inv == 0.0f ? r : 0.0f);
         }
     }
@@ -203,12 +205,12 @@ __device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint3
         const uint32_t cls = info.cls_tiles & 3u;
         if (cls == kRangeDirect) {                                   // finished by its gather tile
 #pragma unroll 4
-            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) slice[i] = A.contrib[u0 + i];
+            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) slice[i] = A.contrib[u0 + i] * kMsgScale;
         } else if (cls == kRangeEmpty) {
 #pragma unroll 4
             for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
                 const float inv = A.inv_out[u0 + i];
-                slice[i] = base * inv;
+                slice[i] = base * inv * kMsgScale;
                 dangling += (inv == 0.0f ? base : 0.0f);
             }
         } else {
@@ -370,7 +372,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
         if (first) {
             const float r0 = 1.0f / (float)A.V;
 #pragma unroll 4
-            for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i];
+            for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i] * kMsgScale;
         } else {
             const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
@@ -418,11 +420,11 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
 
 // ---- G_k ----
 
-// floor(x * 2^62) for 0 <= x <= 1, exactly: x * 2^30 is exact, its integer part is the high word, its
-// fraction times 2^32 (exact again, then truncated) the low word.
-__device__ __forceinline__ unsigned long long to_fixed(float x)
+// floor(x * 2^62) for 0 <= x <= 1, exactly, from t = x * 2^30 (the scatter sweep writes its messages scaled so: a
+// power of two, hence exact, and one multiplication less per edge here): the integer part of t is the high word,
+// its fraction times 2^32 (exact again, then truncated) the low word.
+__device__ __forceinline__ unsigned long long to_fixed(float t)
 {
-    const float t = x * 1073741824.0f;
     const uint32_t hi = (uint32_t)t;
     const uint32_t lo = (uint32_t)(__builtin_amdgcn_fractf(t) * 4294967296.0f);
     return ((unsigned long long)hi << 32) | lo;
