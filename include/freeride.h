@@ -297,7 +297,7 @@ typedef struct fr_pagerank_desc {
        be too coarse), fixed for the task's life (0 = library default); tile cost in ns = ceil(sum / 10^6), at least 1:
          vertex tile  : rows * fs_per_vertex
          scatter tile : messages * fs_per_message + (sources + partial sums it adds up) * fs_per_vertex
-         gather tile  : weight * fs_per_edge / 2, weight = 2 * edges + 5 * repeated edges + 98304 per piece
+         gather tile  : weight * fs_per_edge / 2, weight = 2 * edges + 6 * repeated edges + 147456 per piece
                         (a piece is a run of edges of one range: a heavy range is cut into several, each a tile of
                         its own; light ones share a tile.  A repeated edge has the same source and row as the edge
                         before it: the two collide in the accumulator.  The constant stands for the start and the

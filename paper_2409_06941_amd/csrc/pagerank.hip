@@ -493,16 +493,20 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
         struct Ids {
             uint4 raw;
             uint32_t mb;
-            uint64_t starts[8];
+            uint64_t starts[8];      // row j: start bits of its positions 1 .. 63
+            uint32_t first[8];       // row j: message of its position 0
         };
-        constexpr int kRing = kRowsPerPart == kRowsSmall ? 2 : 3;     // (the small size has fewer registers)
+        constexpr int kRing = 2;     // (the records live in scalar registers: there is room for two)
         const uint32_t wave_u = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave);
         auto load_ids = [&](Ids& I, uint32_t c) {
             if (c <= c1) {
                 I.raw = ids4[(uint64_t)c * (kIdChunk / 8) + lane];
                 I.mb = mbase[c];
+                const uint64_t* rec = starts + (uint64_t)c * kStartWords;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) I.starts[j] = starts[(uint64_t)c * 8 + j];
+                for (int j = 0; j < 8; ++j) I.starts[j] = rec[j];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) I.first[j] = reinterpret_cast<const uint32_t*>(rec + 8)[j];
             }
         };
         // Stage B's result, waiting for stage C.  There are two of these, used in turn: copying one into the other
@@ -521,35 +525,28 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
         for (int j = 0; j < 8; ++j) { X.val[j] = 0.0f; Y.val[j] = 0.0f; }
 
         // ---- stage B on chunk c: lane l holds the ids at stream positions 64 j + l of the chunk, so for a fixed j
-        // the wavefront covers 64 consecutive ids, whose message-start bits are word j.  The message of the id in
-        // lane l is the last one begun up to it: (messages begun before the row) + (bits 0 .. l of the word) - 1.
-        // The count of the bits 1 .. l is what mbcnt gives for the word shifted down by one; bit 0 is added on
-        // the scalar side.
+        // the wavefront covers 64 consecutive ids (row j).  The message of the id in lane l is the message of the
+        // row's first id plus the messages begun at positions 1 .. l, which is what mbcnt counts in the row's word.
         auto stage_b = [&](Pending& S, const Ids& I, uint32_t c) {
             S.raw = I.raw;
             S.ok = 0;
             const uint32_t mb = I.mb;
             const uint64_t first = (uint64_t)c * kIdChunk;
-            // mb >= 1: an id before the first start of its row then still has a message before it (index >= 0 below)
+            // mb >= 1: the chunk's first id then has a message at or before it
             S.fast = first >= e0 && first + kIdChunk <= e1 && mb >= 1 && (uint64_t)mb + kIdChunk <= A.M;
-            uint32_t begun_m1 = mb - 1u;                                   // messages begun before row j, minus one
             if (S.fast) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint64_t bits = I.starts[j], upper = bits >> 1;
-                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(upper >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)upper, begun_m1 + (uint32_t)(bits & 1u)));
+                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(I.starts[j] >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)I.starts[j], I.first[j]));
                     S.val[j] = A.msg[mi];                                  // in [mb - 1, mb + 511], inside [0, M)
-                    begun_m1 += (uint32_t)__popcll(bits);
                 }
             } else {
                 const uint32_t ebase = c * kIdChunk + lane;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint64_t bits = I.starts[j], upper = bits >> 1;
-                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(upper >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)upper, begun_m1 + (uint32_t)(bits & 1u)));
-                    begun_m1 += (uint32_t)__popcll(bits);
+                    const uint32_t mi = __builtin_amdgcn_mbcnt_hi((uint32_t)(I.starts[j] >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)I.starts[j], I.first[j]));
                     const uint32_t e = ebase + 64 * j;
                     const bool ok = e >= e0 && e < e1 && id_of(I.raw, j) < kAccSlots * kIdScale && mi < A.M;   // (mi wraps if no message precedes)
                     S.ok |= (ok ? 1u : 0u) << j;
@@ -584,7 +581,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
         I0.raw = I1.raw = I2.raw = make_uint4(0, 0, 0, 0);
         I0.mb = I1.mb = I2.mb = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) I0.starts[j] = I1.starts[j] = I2.starts[j] = 0;
+        for (int j = 0; j < 8; ++j) { I0.starts[j] = I1.starts[j] = I2.starts[j] = 0; I0.first[j] = I1.first[j] = I2.first[j] = 0; }
         load_ids(I0, c);
         load_ids(I1, c + kGatherWaves);
         if (kRing == 3) {

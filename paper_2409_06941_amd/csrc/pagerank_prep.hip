@@ -157,17 +157,24 @@ __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64
     }
 }
 
-// starts[8 c + j]: bit l is set where stream position 64 j + l of chunk c begins a message.
-__global__ __launch_bounds__(kBlk) void k_starts(int64_t E, uint64_t n_words, const uint64_t* __restrict__ keys, uint64_t* __restrict__ starts)
+// Message-start record of chunk c, kStartWords 64-bit words: words 0 .. 7 = for row j (stream positions 64 j .. 64 j + 63
+// of the chunk) the start bits of positions 1 .. 63 in bits 0 .. 62 (bit l set: position l + 1 begins a message);
+// words 8 .. 11 = eight 32-bit message numbers, that of the first position of each row.  The message of position l of
+// row j is then: first[j] + (set bits below l in word j).
+__global__ __launch_bounds__(kBlk) void k_starts(int64_t E, uint64_t n_rows, const uint64_t* __restrict__ keys,
+                                                 const uint32_t* __restrict__ incl, uint64_t* __restrict__ starts)
 {
     const uint64_t w = (uint64_t)blockIdx.x * kBlk + threadIdx.x;
-    if (w >= n_words) return;
+    if (w >= n_rows) return;
     uint64_t bits = 0;
-    for (int l = 0; l < 64; ++l) {
+    for (int l = 1; l < 64; ++l) {
         const int64_t e = (int64_t)(w * 64) + l;
-        if (e < E && flag_of(keys, e)) bits |= 1ull << l;
+        if (e < E && flag_of(keys, e)) bits |= 1ull << (l - 1);
     }
-    starts[w] = bits;
+    const int64_t e0 = (int64_t)(w * 64);
+    uint64_t* rec = starts + (w / 8) * kStartWords;
+    rec[w % 8] = bits;
+    reinterpret_cast<uint32_t*>(rec + 8)[w % 8] = e0 < E ? incl[e0] - 1u : 0u;
 }
 
 __global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint64_t* __restrict__ keys,
@@ -404,7 +411,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     L->n_spieces = (uint32_t)ubound.size() - 1;
 
     // ---- the arrays that stay
-    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->starts, (uint64_t)padded / 64) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
+    if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->starts, (uint64_t)padded / kIdChunk * kStartWords) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
         PREP_NEED((void*)nullptr);
     uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
     uint32_t* eoff = tmp.take<uint32_t>((uint64_t)Q + 1);
@@ -412,7 +419,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
     hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
                        ubound_dev, L->n_spieces, id_scale_for(rows_per_part), L->ids16, L->src16);
-    hipLaunchKernelGGL(k_starts, dim3(blocks_for((uint64_t)padded / 64)), dim3(kBlk), 0, stream, E, (uint64_t)padded / 64, keys, L->starts);
+    hipLaunchKernelGGL(k_starts, dim3(blocks_for((uint64_t)padded / 64)), dim3(kBlk), 0, stream, E, (uint64_t)padded / 64, keys, incl, L->starts);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, eoff);
     std::vector<uint32_t> eoff_host((size_t)Q + 1);

@@ -51,6 +51,7 @@ constexpr uint32_t kSrcSmall = 16384, kSrcLarge = 32768;    // source vertices p
 constexpr int64_t kLargeRowsFrom = int64_t(1) << 22;        // vertex counts from which the large sizes are used
 constexpr int64_t kLargeSrcFrom = int64_t(1) << 24;
 constexpr uint32_t kIdChunk = 512;           // ids per wavefront step (8 per lane, 64 apart)
+constexpr uint32_t kStartWords = 12;         // 64-bit words of a chunk's message-start record
 constexpr int kKeyLocalBits = 15;            // sort key = range << 46 | source << 15 | local row
 constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
 static_assert(kRowsLarge <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
@@ -63,8 +64,8 @@ constexpr uint64_t kMinTileMessages = 16384;
 #ifndef FR_W_EDGE
 #define FR_W_EDGE 2
 #define FR_W_MSG 0
-#define FR_W_REP 5
-#define FR_W_FIX 98304
+#define FR_W_REP 6
+#define FR_W_FIX 147456
 #endif
 constexpr uint64_t kScatterFixedWeight = 16384;
 constexpr uint64_t kGatherEdgeWeight = FR_W_EDGE, kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP,
@@ -99,7 +100,8 @@ struct PrLayout {
     int32_t* perm = nullptr;         // [V] caller's id of new id v
     uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id times id_scale_for(rows_per_part);
                                      // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
-    uint64_t* starts = nullptr;      // [n_chunks * 8] bit l of word 8 c + j: position 64 j + l of chunk c begins a message
+    uint64_t* starts = nullptr;      // [n_chunks * kStartWords] per chunk: eight words of message-start bits (one per 64
+                                     // positions, shifted down by one) and the message numbers of the eight first positions
     uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter piece
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
     uint2* bins = nullptr;           // [n_spieces * Qe] message range [x, y) of (scatter piece, range), piece-major

@@ -207,17 +207,17 @@ def test_layout_facts_match_the_graph():
     range_end = set(np.cumsum(per_range).tolist())
     assert all(int(b) in range_end or b % 512 == 0 for b in bounds[1:])
     assert info.merged_ranges > 0 and info.partial_rows >= 2 * info.merged_ranges
-    # weights: 2 an edge, 5 more for an edge that repeats its predecessor, 98304 a piece; exact for tiles that begin
+    # weights: 2 an edge, 6 more for an edge that repeats its predecessor, 147456 a piece; exact for tiles that begin
     # and end on multiples of 512 or at the ends of the stream (inside a chunk of 512 the weight is spread evenly)
-    w_edge = 2 + 5 * repeats.astype(np.int64)
+    w_edge = 2 + 6 * repeats.astype(np.int64)
     cum = np.concatenate([[0], np.cumsum(w_edge)])
     pieces_total = 0
     for i, w in enumerate(weights):
         a, b = int(bounds[i]), int(bounds[i + 1])
         extra = w - (cum[b] - cum[a])
         if (a % 512 == 0) and (b % 512 == 0 or b == E):
-            assert extra > 0 and extra % 98304 == 0
-        pieces_total += round(extra / 98304)
+            assert extra > 0 and extra % 147456 == 0
+        pieces_total += round(extra / 147456)
     n_direct = info.nonempty_ranges - info.merged_ranges
     assert pieces_total == n_direct + info.partial_rows
     assert sum(msgs) == info.messages and len(msgs) == info.scatter_tiles
@@ -239,9 +239,9 @@ def test_one_row_with_over_a_million_in_edges():
     info = t.fr_pagerank_info()
     weights = t.fr_pagerank_tile_weights(fr.FR_PR_SEG_GATHER)
     t.fr_pagerank_destroy()
-    # all but one of the edges into the heavy row repeat their predecessor: weight 7 apiece
+    # all but one of the edges into the heavy row repeat their predecessor: weight 8 apiece
     assert info.merged_ranges == 1 and info.gather_tiles == info.partial_rows > 10
-    assert sum(weights) == 2 * (n + 2) + 5 * (n - 1) + 98304 * info.partial_rows
+    assert sum(weights) == 2 * (n + 2) + 6 * (n - 1) + 147456 * info.partial_rows
     assert max(weights) <= 1.1 * sum(weights) / len(weights)            # tiles of about equal weight
     want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 6)
     assert np.abs(ranks.cpu().numpy().astype(np.float64) - want).max() <= TOL
