@@ -441,14 +441,14 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
     return (j & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-// One workgroup per gather tile; the accumulators of its range (one u64 per row) sit in LDS.  Per step a
-// wavefront takes one chunk of 512 ids (8 per lane).  The loop is a three-stage software pipeline over the
-// wavefront's chunks, so that no step waits on a load it has just issued:
-//   A  ids and message base of chunk i + 2 are requested;
-//   B  chunk i + 1 (ids now here): the message-start bits tell every id which message it belongs to; the
+// One workgroup per gather tile; it takes the tile's pieces one after the other, the accumulators of the piece's
+// range (one u64 per row) in LDS.  Per step a wavefront takes one chunk of 512 ids (8 per lane).  The loop is a
+// three-stage software pipeline over the wavefront's chunks, so that no step waits on a load it has just issued:
+//   A  ids, message-start record and message base of the chunk two steps on are requested;
+//   B  this step's chunk (ids now here): the start bits tell every id which message it belongs to; the
 //      messages are requested (64 consecutive ids per load, so the addresses are all but contiguous);
-//   C  chunk i (messages now here): each id adds its message, as a 64-bit fixed-point integer, to its row's
-//      accumulator with an LDS atomic.
+//   C  the chunk of the step before (messages now here): each id adds its message, as a 64-bit fixed-point
+//      integer, to its row's accumulator with an LDS atomic.
 // The sweep is bound by vector instruction issue, not by memory, so chunks that lie wholly inside the tile's edge
 // range and whose messages cannot pass the end of the message array - all but the first and last chunk of a tile -
 // take a path without per-id checks (about 10 vector instructions per 64 edges instead of 25).

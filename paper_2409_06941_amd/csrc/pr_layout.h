@@ -10,15 +10,15 @@
 //     receive most edges sit together, so that many edges of one source fall into one row range and share one
 //     message: on an R-MAT graph of 2^22 vertices and 2^26 edges the messages drop from 0.50 to 0.20 per edge;
 //   * destination rows are cut into RANGES of rows_per_part consecutive rows (8192, or 16384 from 2^22 vertices
-//     on); sources into partitions of src_per_part (16384, or 32768 from 2^24 vertices on);
+//     on); sources into intervals of at most src_per_part (16384, or 32768 from 2^24 vertices on);
 //   * all in-edges of one range j are stored together, ordered by source u and then by row; one MESSAGE is made
 //     per distinct (j, u) pair, however many rows of j the source u points to;
-//   * scatter sweep: the p-slice of contrib sits in LDS; for the ranges j of the tile the messages of bin (p, j)
-//     are written, msg[m] = contrib[src of m] -- sequential writes;
-//   * gather sweep: 64-bit fixed-point accumulators for the rows of one range sit in LDS; the id stream of the
-//     tile (one 16-bit local row id per edge, and one bit per edge that says where a new message starts) and its
-//     messages are read sequentially and added into LDS with integer atomics.  Integer addition is associative, so the sums do
-//     not depend on the order the hardware performs them in.
+//   * scatter sweep: contrib of a source interval p sits in LDS; for every range j the messages of bin (p, j)
+//     are written, msg[m] = contrib[src of m] * 2^30 -- sequential writes;
+//   * gather sweep: 64-bit fixed-point accumulators for the rows of one range sit in LDS; the id stream (one
+//     16-bit local row id per edge, and one bit per edge that says where a new message starts) and the messages
+//     are read sequentially and added into LDS with integer atomics.  Integer addition is associative, so the
+//     sums do not depend on the order the hardware performs them in.
 //
 // Ordering by degree makes the ranges very unequal (the first range of that graph holds 42 % of the edges), so
 // the unit of work is not the range but a TILE of about equal work:
@@ -26,11 +26,11 @@
 //     A gather tile is one heavy piece, or several light pieces in a row that one workgroup takes one after the
 //     other: all tiles cost about the same, and there are no more of them than workgroups run side by side
 //     (a second round of workgroups only starts where a whole first-round workgroup has ended, which was
-//     measured to leave a quarter of the sweep's time half idle).  A range that
-//     needs several pieces is a MERGED range: each of its pieces stores its row sums as one row of fp32 partial
-//     sums (plain stores, no global atomics: 2.5 million 64-bit atomics from 150 workgroups were measured at 22 us
-//     on an otherwise idle chip), and the rows are finished - partial sums added in tile order, then r and contrib -
-//     at the start of the next scatter sweep.  This also spreads rows with very many in-edges over many
+//     measured to leave a quarter of the sweep's time half idle).  A range that needs several pieces is a MERGED
+//     range: each of its pieces stores its row sums as one row of fp32 partial sums (plain stores, no global
+//     atomics: 2.5 million 64-bit atomics from 150 workgroups were measured at 22 us on an otherwise idle chip),
+//     and the rows are finished - partial sums added in a fixed tree order, then r and contrib - at the start
+//     of the next scatter sweep.  This also spreads rows with very many in-edges over many
 //     workgroups; no other treatment of such rows is needed.  A range with one piece is DIRECT: its piece
 //     finishes its rows itself;
 //   * the scatter sweep works in pieces too: intervals of at most src_per_part consecutive sources with about

@@ -139,6 +139,34 @@ def test_any_chunking_gives_identical_bits():
     assert np.array_equal(whole.view(np.uint32), again.view(np.uint32))
 
 
+def test_tiles_follow_the_cu_mask_of_the_stream():
+    # On a stream confined to 16 CUs the sweeps are cut into no more tiles than 16 CUs run side by side (two
+    # workgroups per CU at these sizes), so light pieces share tiles in both sweeps; same ranks as the oracle, same
+    # bits whatever the chunking.
+    src, dst = graphs.rmat_edges(20, 8_000_000, seed=33)
+    g = graphs.csr_from_edges(1 << 20, src, dst)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ctx = fr.Context(device_id=0, cu_count=16)
+    out = []
+    for max_tiles in (0, 1, 3):
+        ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+        t = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=6)
+        t.fr_pagerank_run_standalone(0, ctx.fr_side_stream(), max_tiles)
+        info = t.fr_pagerank_info()
+        t.fr_pagerank_destroy()
+        out.append(ranks.cpu().numpy())
+    ctx.fr_destroy()
+    assert info.gather_tiles <= 32 and info.scatter_tiles <= 32
+    assert info.nonempty_ranges + info.partial_rows - info.merged_ranges > info.gather_tiles      # pieces share tiles
+    assert -(-g.n_vertices // 16384) > info.scatter_tiles
+    want = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, 6)
+    assert np.abs(out[0].astype(np.float64) - want).max() <= TOL
+    big = want > 1.0 / g.n_vertices
+    assert (np.abs(out[0][big] - want[big]) / want[big]).max() <= 1e-4
+    assert np.array_equal(out[0].view(np.uint32), out[1].view(np.uint32))
+    assert np.array_equal(out[0].view(np.uint32), out[2].view(np.uint32))
+
+
 def test_memory_limit_refuses_the_task():
     g = graphs.rmat_csr(12, 1 << 15, seed=2)
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
