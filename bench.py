@@ -37,7 +37,7 @@ def main():
     ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
     ap.add_argument("--margin", type=float, default=1.02, help="final model = measured in-bubble step cost x margin")
     ap.add_argument("--guard-ns", type=int, default=100_000)
-    ap.add_argument("--time-steps", type=int, default=8,
+    ap.add_argument("--time-steps", type=int, default=16,
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--device-gate", type=int, default=0,
                     help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
@@ -163,10 +163,15 @@ def main():
         ctx.fr_bubble_end()
         return ctx, task, tid
 
-    # Second profiling pass, in place: one epoch with the standalone model (generously derated) shows what a
-    # step costs inside real bubbles, launch gaps included; the final model is that cost plus a small margin.
+    # Second profiling pass, in place: an epoch (the fourth after the start) with the standalone model (generously
+    # derated) shows what a step costs inside real bubbles, launch gaps included; the final model is that cost plus
+    # a small margin.
     ts = max(1, args.time_steps)
     ctx, task, tid = start_task(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate), ts)
+    for _ in range(3):                           # untimed: right after a start the steps run a few percent slower
+        stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.02)
+    ctx.fr_event_log_clear()
     stage.fr_stage_run_epoch(ctx)
     time.sleep(0.02)
     n_tiles = [task.fr_pagerank_tiles(k) for k in range(4)]
@@ -190,6 +195,8 @@ def main():
     insitu = [x * in_bubble for x in standalone]
     log("in-bubble step times = standalone x %.3f (%d timing groups of %d whole sweeps): scatter %.1f us, gather %.1f us" %
         (in_bubble, len(ratios), ts, insitu[1] / 1e3, insitu[2] / 1e3))
+    if ratios:
+        log("  group ratios min %.3f quartiles %.3f %.3f %.3f max %.3f" % ((min(ratios),) + tuple(statistics.quantiles(ratios, n=4)) + (max(ratios),)))
     one_tile_ns = [x * in_bubble for x in one_tile_ns]
     ctx, task, tid = start_task(0, rates(*insitu, args.margin), ts)     # the measured group times already hold the launch gaps
     def epochs(n, with_task):
