@@ -126,7 +126,7 @@ def main():
     def rates(v_ns, s_ns, g_ns, h_ns, derate):
         """Femtosecond rates of the task's cost model from per-segment times (ns) of one iteration."""
         pv = max(1, int(v_ns * 1e6 * derate / V))
-        pm = max(1, int((s_ns * 1e6 * derate - scatter_weight * pv) / M))
+        pm = max(1, int(s_ns * 1e6 * derate / (M + scatter_weight)))
         pe = max(1, int(2 * g_ns * 1e6 * derate / max(1, gather_weight)))
         return dict(fs_per_vertex=pv, fs_per_message=pm, fs_per_edge=pe,
                     finish_tile_ns=max(1, int(h_ns * derate / n_finish_tiles)),

@@ -296,7 +296,9 @@ typedef struct fr_pagerank_desc {
     /* cost model, integer femtoseconds (a streaming kernel spends about 1000 fs on an edge, so picoseconds would
        be too coarse), fixed for the task's life (0 = library default); tile cost in ns = ceil(sum / 10^6), at least 1:
          vertex tile  : rows * fs_per_vertex
-         scatter tile : messages * fs_per_message + (sources + partial sums it adds up) * fs_per_vertex
+         scatter tile : (messages + values read for its sources) * fs_per_message, where a source costs one
+                        value (its contribution or 1/outdeg) and, in a range cut into several gather
+                        pieces, one partial sum per piece more (the weight the tiles are cut by)
          gather tile  : weight * fs_per_edge / 2, weight = 2 * edges + 6 * repeated edges + 147456 per piece
                         (a piece is a run of edges of one range: a heavy range is cut into several, each a tile of
                         its own; light ones share a tile.  A repeated edge has the same source and row as the edge
@@ -344,8 +346,8 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out);
 int fr_pagerank_tiles(void* user, int32_t seg_kind, uint32_t* n_tiles_out);
 int fr_pagerank_tile_costs(void* user, int32_t seg_kind, uint32_t* costs_host, size_t cap, size_t* n_out);
 int fr_pagerank_tile_work(void* user, int32_t seg_kind, uint64_t* work_host, size_t cap, size_t* n_out);
-/* The tiles' multiplicands in the cost formulas above: gather: the weight; scatter: sources + partial sums added
-   up (the factor of fs_per_vertex); vertex: rows; finish: 0. */
+/* The tiles' multiplicands in the cost formulas above: gather: the weight; scatter: values read for the sources
+   (messages not included: those are the tile's work); vertex: rows; finish: 0. */
 int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights_host, size_t cap, size_t* n_out);
 /*
  * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_tiles_per_launch` tiles per

@@ -59,7 +59,7 @@ __device__ __forceinline__ float wave_sum(float x)
 }
 
 // Sum of a per-thread value over the workgroup, same association for a given blockDim.  All threads call.
-__device__ __forceinline__ float block_sum(float x, float* lds /* >= 8 floats */)
+__device__ __forceinline__ float block_sum(float x, float* lds /* one float per wavefront */)
 {
     x = wave_sum(x);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -72,32 +72,23 @@ __device__ __forceinline__ float block_sum(float x, float* lds /* >= 8 floats */
     return s;
 }
 
-// D = sum of dpart[0 .. n), in two halves so that the loads can be issued long before the sum is needed:
-// dangling_partial (threads 0..255 each add up a strided share) and dangling_finish (fixed tree over those 256
-// partial sums).  Every kernel that uses the pair gets the same bits whatever its workgroup size (>= 256).
-__device__ __forceinline__ float dangling_partial(const float* __restrict__ dpart, uint32_t n)
+// D = sum of dpart[0 .. n).  Every wavefront adds the whole array up by itself, in one fixed order (lane l takes
+// the elements l, l + 64, l + 128, ... into four running sums in turn; the four are joined pairwise, the lanes by
+// a butterfly), so all wavefronts of all kernels get the same bits, and no barrier stands between the loads of
+// the array and the loads of the work that follows: the sum is only waited for where it is first used.
+__device__ __forceinline__ float dangling_total(const float* __restrict__ dpart, uint32_t n)
 {
-    float s = 0.0f;
-    if (threadIdx.x < 256) {
-        uint32_t i = threadIdx.x;
-        for (; i + 768 < n; i += 1024) {
-            const float a = dpart[i], b = dpart[i + 256], c = dpart[i + 512], d = dpart[i + 768];
-            s += a; s += b; s += c; s += d;
-        }
-        for (; i < n; i += 256) s += dpart[i];
+    const uint32_t lane = threadIdx.x & 63;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    uint32_t i = lane;
+    for (; i + 192 < n; i += 256) {
+        const float a = dpart[i], b = dpart[i + 64], c = dpart[i + 128], d = dpart[i + 192];
+        s0 += a; s1 += b; s2 += c; s3 += d;
     }
-    return s;
-}
-
-// All threads call; all get the result.
-__device__ __forceinline__ float dangling_finish(float s, float* lds /* >= 8 floats */)
-{
-    s = wave_sum(s);
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    __syncthreads();
-    if (lane == 0 && w < 4) lds[w] = s;
-    __syncthreads();
-    return (lds[0] + lds[1]) + (lds[2] + lds[3]);
+    if (i < n) s0 += dpart[i];
+    if (i + 64 < n) s1 += dpart[i + 64];
+    if (i + 128 < n) s2 += dpart[i + 128];
+    return wave_sum((s0 + s1) + (s2 + s3));
 }
 
 struct DevArgs {
@@ -114,9 +105,9 @@ struct DevArgs {
     const int32_t* perm;
     const RangeInfo* range_info;
     const GatherPiece* gather_pieces;
-    const uint2* gather_tiles;
+    const GatherTile* gather_tiles;
     const ScatterPiece* scatter_pieces;
-    const uint4* scatter_tiles;
+    const ScatterTile* scatter_tiles;
     const uint32_t* finish_ranges;
     float* msg;
     float* contrib;
@@ -134,8 +125,7 @@ struct GateArg {
 // Sum of a merged row's partial sums p_0 .. p_{nt-1}.  The order is fixed: sixteen leaves, leaf g = p_g + p_{g+16} +
 // ... in rising order, joined by a balanced tree over g.  kLanes lanes (a power of two up to 16, consecutive in
 // the wavefront, all active) share the row: lane `sub` owns the leaves sub * 16 / kLanes onwards, joins them, and
-// the lanes' results are joined by butterfly exchanges, which is the same tree.  Every lane gets the sum.  Up to
-// eight loads per lane are in flight at a time.
+// the lanes' results are joined by butterfly exchanges, which is the same tree.  Every lane gets the sum.
 template <int kLanes>
 __device__ __forceinline__ float merged_sum(const DevArgs& A, RangeInfo info, uint32_t local, uint32_t sub)
 {
@@ -145,19 +135,16 @@ __device__ __forceinline__ float merged_sum(const DevArgs& A, RangeInfo info, ui
     float s[kLeaves];
 #pragma unroll
     for (int k = 0; k < kLeaves; ++k) s[k] = 0.0f;
-    constexpr int kBatch = kLeaves < 8 ? kLeaves : 8;          // loads in flight (registers)
+    // (all loads of a round, up to sixteen, are issued before the first is used)
     for (uint32_t t0 = 0; t0 < nt; t0 += 16) {
+        float x[kLeaves];
 #pragma unroll
-        for (int k0 = 0; k0 < kLeaves; k0 += kBatch) {
-            float x[kBatch];
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const uint32_t t = t0 + sub * kLeaves + k0 + k;
-                x[k] = t < nt ? p[(size_t)t << A.rows_shift] : 0.0f;
-            }
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) s[k0 + k] += x[k];
+        for (int k = 0; k < kLeaves; ++k) {
+            const uint32_t t = t0 + sub * kLeaves + k;
+            x[k] = t < nt ? p[(size_t)t << A.rows_shift] : 0.0f;
         }
+#pragma unroll
+        for (int k = 0; k < kLeaves; ++k) s[k] += x[k];
     }
 #pragma unroll
     for (int w = 1; w < kLeaves; w <<= 1)
@@ -193,15 +180,16 @@ __device__ __forceinline__ float fill_merged(const DevArgs& A, RangeInfo info, u
 // contrib of the sources [u0, u0 + n) of a scatter tile for an iteration after the first, into `slice`; returns
 // this thread's share of the dangling mass among the rows finished here.  The tile is walked range by range (a
 // handful at most), so that each loop has one kind of row and its loads can be issued back to back.
+// `first_info`: what range_info holds for the range of u0.
 template <int kThreads>
-__device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint32_t n, float base, float* slice)
+__device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint32_t n, float base, float* slice, RangeInfo first_info)
 {
     float dangling = 0.0f;
     for (uint32_t i0 = 0; i0 < n;) {
         const uint32_t q = (u0 + i0) >> A.rows_shift;
         const uint32_t range_end = ((q + 1) << A.rows_shift) - u0;
         const uint32_t i1 = range_end < n ? range_end : n;
-        const RangeInfo info = A.range_info[q];
+        const RangeInfo info = i0 == 0 ? first_info : A.range_info[q];
         const uint32_t cls = info.cls_tiles & 3u;
         if (cls == kRangeDirect) {                                   // finished by its gather tile
 #pragma unroll 4
@@ -251,14 +239,17 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, GateArg G, uint32
 }
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), and every XCD has an L2 of its
-// own.  This map gives XCD x the x-th contiguous eighth of a launch's n tiles, in order, so that tiles which touch
-// neighbouring memory at about the same time do so through the same L2.  It is a bijection on [0, n) for any n.
-__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t b, uint32_t n)
+// own.  This map gives every XCD runs of kTileRun consecutive tiles, the runs dealt round-robin: neighbouring tiles
+// write neighbouring messages (and share the lines at the seams) through one L2, while the heaviest tiles, which
+// come first and read the most partial sums, are spread over all XCDs (in one contiguous block per XCD they were
+// measured to take twice as long to fill their slices).  It is a bijection on [0, n) for any n.
+constexpr uint32_t kTileRun = 4;
+__device__ __forceinline__ uint32_t xcd_runs(uint32_t b, uint32_t n)
 {
     constexpr uint32_t kXcds = 8;
-    const uint32_t x = b % kXcds, i = b / kXcds;
-    const uint32_t rem = n % kXcds;
-    return x * (n / kXcds) + (x < rem ? x : rem) + i;
+    const uint32_t full = n / (kXcds * kTileRun) * (kXcds * kTileRun);
+    if (b >= full) return b;
+    return ((b / kXcds / kTileRun) * kXcds + b % kXcds) * kTileRun + (b / kXcds) % kTileRun;
 }
 
 // ---- S_k ----
@@ -350,20 +341,21 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
     __shared__ uint2 desc[kDescBatch];
     __shared__ uint32_t gpre[kScatterBlock + 1];          // groups before each bin of the batch; [kScatterBlock] = all
     __shared__ uint32_t wave_tot[kScatterWaves + 1];
-    __shared__ float red[32];
+    __shared__ float red[kScatterWaves];
     static_assert(kDescBatch <= kScatterBlock, "one bin per thread");
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t tile = tile0 + xcd_contiguous(blockIdx.x, gridDim.x);
-    const uint4 span = A.scatter_tiles[tile];                    // the tile's pieces [x, y), worked on one after the other;
-                                                                 // z, w: the sources of the first (saves a dependent load)
+    const uint32_t tile = tile0 + xcd_runs(blockIdx.x, gridDim.x);
+    const uint4* rec = reinterpret_cast<const uint4*>(A.scatter_tiles + tile);
+    const uint4 span = rec[0];                                   // the tile's pieces [x, y), worked on one after the other;
+    const uint4 span_info = rec[1];                              // z, w: the sources of the first; then their range
     const uint32_t Qe = A.Qe;
     float base = 0.0f;
     if (!first) {
-        const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
+        const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
         base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     }
     const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
-    auto do_piece = [&](uint32_t t, ScatterPiece T) {
+    auto do_piece = [&](uint32_t t, ScatterPiece T, RangeInfo first_info) {
         // the first batch of bin descriptors is asked for now and used after the slice is filled
         uint2 d_first = make_uint2(0, 0);
         if (threadIdx.x < Qe) d_first = A.bins[(uint64_t)t * Qe + threadIdx.x];
@@ -374,7 +366,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
 #pragma unroll 4
             for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i] * kMsgScale;
         } else {
-            const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice), red + 8);
+            const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice, first_info), red);
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
         }
         for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
@@ -408,11 +400,16 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
         }
     };
     if constexpr (!kPacked) {
-        do_piece(span.x, ScatterPiece{span.z, span.w});
+        do_piece(span.x, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
     } else {
         for (uint32_t t = span.x; t < span.y; ++t) {
             __syncthreads();                                     // the piece before is done with slice and desc
-            do_piece(t, t == span.x ? ScatterPiece{span.z, span.w} : A.scatter_pieces[t]);
+            if (t == span.x) {
+                do_piece(t, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
+            } else {
+                const ScatterPiece T = A.scatter_pieces[t];
+                do_piece(t, T, first ? RangeInfo{kRangeEmpty, 0} : A.range_info[T.u0 >> A.rows_shift]);
+            }
         }
     }
     fr_gate_done(G.gate);
@@ -462,17 +459,19 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
     constexpr uint32_t kIdScale = id_scale_for(kRowsPerPart);
     static_assert(65535u * (8 / kIdScale) + 8 <= (kAccSlots + 1) * 8, "any id addresses a slot of acc");
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
-    __shared__ float red[32];
+    __shared__ float red[kGatherWaves];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t tile = tile0 + blockIdx.x;
-    const uint2 span = A.gather_tiles[tile];                     // the tile's pieces, worked on one after the other
-    const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
+    const uint4* rec = reinterpret_cast<const uint4*>(A.gather_tiles + tile);
+    const uint4 span = rec[0];                                   // x, y: the tile's pieces, worked on one after the other;
+    const uint4 span_more = rec[1];                              // then a copy of the first (saves a dependent load)
+    const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
     if (tile == 0 && !final_pass)                                // slots no piece and no scatter tile writes
         for (uint32_t i = A.n_pieces + A.n_spieces + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
     for (uint32_t t = span.x; t < span.y; ++t) {
-    const GatherPiece T = A.gather_pieces[t];
+    const GatherPiece T = t == span.x ? GatherPiece{span.z, span.w, span_more.x, span_more.y} : A.gather_pieces[t];
     const uint32_t q = T.range;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
@@ -627,7 +626,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
             A.contrib[v0 + i] = r * inv[k];
             dangling += (inv[k] == 0.0f ? r : 0.0f);
         }
-        const float total = block_sum(dangling, red + 8);
+        const float total = block_sum(dangling, red);
         if (threadIdx.x == 0) dnext[t] = total;
     }
     }       // pieces
@@ -640,10 +639,9 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
 constexpr uint32_t kFinishRows = 2048;
 __global__ __launch_bounds__(kBlock) void k_finish(DevArgs A, GateArg G, uint32_t tile0, int parity)
 {
-    __shared__ float red[8];
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
     const uint32_t t = tile0 + blockIdx.x;
-    const float D = dangling_finish(dangling_partial(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart), red);
+    const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     const uint32_t per_range = A.rows_per_part / kFinishRows;
     if (t / per_range < A.n_finish) {
@@ -716,7 +714,7 @@ void build_cost_tables(PrTask* p)
     auto& s = p->prefix[FR_PR_SEG_SCATTER];
     s.assign(L.n_scatter + 1, 0);
     for (uint32_t i = 0; i < L.n_scatter; ++i) {
-        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)L.st_msgs[i] * pm + (unsigned __int128)L.st_rows[i] * pv);   // a partial sum costs about a vertex
+        s[i + 1] = s[i] + ceil_fs_to_ns((unsigned __int128)(L.st_msgs[i] + L.st_rows[i]) * pm);   // a value read costs about a message
     }
     auto& g = p->prefix[FR_PR_SEG_GATHER];
     const uint32_t ng = p->tiles_of(FR_PR_SEG_GATHER);

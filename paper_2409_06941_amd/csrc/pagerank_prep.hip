@@ -391,34 +391,11 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         tmp.drop(t); tmp.drop(cnt); tmp.drop(cum_dev);
         if (cum[(size_t)V] != M) return FR_ERR_ARG;
     }
-    std::vector<uint32_t> ubound;
-    {
-        // (one heavy piece per CU; where two workgroups share a CU, the other places take the light pieces)
-        const uint64_t target = std::max<uint64_t>(kMinTileMessages, ((uint64_t)M + cus - 1) / cus);
-        uint64_t u = 0;
-        while (u < (uint64_t)V) {
-            const uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
-            const uint64_t want = (uint64_t)cum[u] + target;
-            uint64_t hi = limit;
-            if ((uint64_t)cum[limit] >= want)
-                hi = (uint64_t)(std::lower_bound(cum.begin() + (long)u + 1, cum.begin() + (long)limit + 1, want,
-                                                 [](uint32_t c, uint64_t w) { return (uint64_t)c < w; }) - cum.begin());
-            ubound.push_back((uint32_t)u);
-            u = hi;
-        }
-        ubound.push_back((uint32_t)V);
-    }
-    L->n_spieces = (uint32_t)ubound.size() - 1;
-
     // ---- the arrays that stay
     if (!keep(a, &L->ids16, (uint64_t)padded) || !keep(a, &L->starts, (uint64_t)padded / kIdChunk * kStartWords) || !keep(a, &L->mbase, (uint64_t)L->n_chunks + 1) || !keep(a, &L->src16, ((uint64_t)M + 15) / 8 * 8))     // read eight at a time
         PREP_NEED((void*)nullptr);
-    uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
     uint32_t* eoff = tmp.take<uint32_t>((uint64_t)Q + 1);
-    PREP_NEED(ubound_dev); PREP_NEED(eoff);
-    PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
-    hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
-                       ubound_dev, L->n_spieces, id_scale_for(rows_per_part), L->ids16, L->src16);
+    PREP_NEED(eoff);
     hipLaunchKernelGGL(k_starts, dim3(blocks_for((uint64_t)padded / 64)), dim3(kBlk), 0, stream, E, (uint64_t)padded / 64, keys, incl, L->starts);
     hipLaunchKernelGGL(k_mbase, dim3(blocks_for((uint64_t)L->n_chunks + 1)), dim3(kBlk), 0, stream, E, L->n_chunks, M, keys, incl, L->mbase);
     hipLaunchKernelGGL(k_eoff, dim3(blocks_for((uint64_t)Q + 1)), dim3(kBlk), 0, stream, Q, E, keys, eoff);
@@ -519,7 +496,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         }
         for (uint32_t j = Qe; j < Q; ++j) L->fin.push_back(j);
         L->gp = pieces;
-        L->gt = tiles;
+        L->gt.clear();
+        for (const uint2& t : tiles) L->gt.push_back(GatherTile{t.x, t.y, pieces[t.x], {0, 0}});
         for (const uint2& t : tiles) {
             uint64_t wsum = 0, esum = 0;
             for (uint32_t i = t.x; i < t.y; ++i) { wsum += piece_w[i]; esum += (uint64_t)pieces[i].e1 - pieces[i].e0; }
@@ -531,13 +509,91 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     L->n_gather = (uint32_t)L->gt.size();
     L->n_finish = (uint32_t)L->fin.size();
 
-    // ---- scatter tiles: a heavy piece, or light pieces in a row, packed only as far as it takes to have no more
-    // tiles than workgroups run side by side.  Cost of a piece: 2 a message, 3 a source or partial sum
-    // added up, kScatterFixedWeight for its start.
+    // ---- scatter pieces and tiles.  A piece is an interval of at most src_per_part sources and at most `target`
+    // weight, where a message weighs kScatterMessageWeight and a source kScatterRowWeight times the values read to
+    // finish it (its contrib or 1/outdeg, and the partial sums of a row of a merged range); the pieces of the sources
+    // with few messages are as wide as allowed and light whatever the target.  A tile is a run of consecutive pieces
+    // whose costs (weight + kScatterFixedWeight a piece, for the chain of dependent loads at its start) add up to at
+    // most target + kScatterFixedWeight.  The target is the smallest one (to 2 %) that leaves no more tiles than
+    // workgroups run side by side.
+    std::vector<uint32_t> ubound;
+    std::vector<uint2> stiles;
+    {
+        std::vector<uint64_t> per_row(Q), rows_before((size_t)Q + 1, 0);
+        for (uint32_t j = 0; j < Q; ++j) {
+            per_row[j] = 1 + ((L->ri[j].cls_tiles & 3u) == kRangeMerged ? (L->ri[j].cls_tiles >> 2) : 0u);
+            const uint64_t lo = (uint64_t)j * rows_per_part, hi = std::min<uint64_t>((uint64_t)V, lo + rows_per_part);
+            rows_before[j + 1] = rows_before[j] + (hi - lo) * per_row[j];
+        }
+        auto weight_before = [&](uint64_t u) -> uint64_t {
+            const uint64_t j = std::min<uint64_t>(u / rows_per_part, Q);
+            const uint64_t rows = rows_before[j] + (j < Q ? (u - j * rows_per_part) * per_row[j] : 0);
+            return kScatterMessageWeight * (uint64_t)cum[u] + kScatterRowWeight * rows;
+        };
+        auto cut = [&](uint64_t target) {
+            ubound.clear();
+            uint64_t u = 0;
+            while (u < (uint64_t)V) {
+                const uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
+                const uint64_t want = weight_before(u) + target;
+                uint64_t lo = u + 1, hi = limit;             // the first end in (u, limit] that reaches `want`, else limit
+                while (lo < hi) {
+                    const uint64_t mid = (lo + hi) / 2;
+                    if (weight_before(mid) >= want) hi = mid;
+                    else lo = mid + 1;
+                }
+                ubound.push_back((uint32_t)u);
+                u = lo;
+            }
+            ubound.push_back((uint32_t)V);
+        };
+        auto pack = [&](uint64_t limit) {                    // (limit 0: a tile per piece)
+            stiles.clear();
+            const uint32_t n = (uint32_t)ubound.size() - 1;
+            uint64_t in_tile = 0;
+            uint32_t first = 0;
+            for (uint32_t i = 0; i < n; ++i) {
+                const uint64_t c = weight_before(ubound[i + 1]) - weight_before(ubound[i]) + kScatterFixedWeight;
+                if (i > first && in_tile + c > limit) {
+                    stiles.push_back(make_uint2(first, i));
+                    first = i; in_tile = 0;
+                }
+                in_tile += c;
+            }
+            stiles.push_back(make_uint2(first, n));
+        };
+        const uint64_t slots = (uint64_t)cus * (src_per_part == kSrcSmall ? 2 : 1);
+        const uint64_t all = weight_before((uint64_t)V), least = kMinTileMessages * kScatterMessageWeight;
+        const uint64_t start = std::max<uint64_t>(least, (all + slots - 1) / slots);
+        bool done = false;
+        if (src_per_part == kSrcSmall) {
+            // the small kernel is faster without the loop over pieces: a tile per piece, if a target up to one
+            // compute unit's share of the weight leaves few enough pieces
+            const uint64_t most = std::max<uint64_t>(least, (all + cus - 1) / cus);
+            for (uint64_t target = start;; target = std::min(most, target + target / 50 + 1)) {
+                cut(target);
+                if (ubound.size() - 1 <= slots) { pack(0); done = true; break; }
+                if (target >= most) break;
+            }
+        }
+        if (!done)
+            for (uint64_t target = start;; target += target / 50 + 1) {
+                cut(target);
+                pack(target + kScatterFixedWeight);
+                if (stiles.size() <= slots) break;
+            }
+    }
+    L->n_spieces = (uint32_t)ubound.size() - 1;
+    uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
+    PREP_NEED(ubound_dev);
+    PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
+    hipLaunchKernelGGL(k_emit, dim3(blocks_for((uint64_t)padded)), dim3(kBlk), 0, stream, E, padded, (uint64_t)M, keys, incl,
+                       ubound_dev, L->n_spieces, id_scale_for(rows_per_part), L->ids16, L->src16);
+
+    // ---- what the cost model needs of every scatter tile
     L->sp.clear(); L->st.clear(); L->st_msgs.clear(); L->st_rows.clear();
     {
-        std::vector<uint64_t> msgs(L->n_spieces), rows(L->n_spieces), cost(L->n_spieces);
-        uint64_t limit = 0;
+        std::vector<uint64_t> msgs(L->n_spieces), rows(L->n_spieces);
         for (uint32_t t = 0; t < L->n_spieces; ++t) {
             const uint64_t u0 = ubound[t], u1 = ubound[t + 1];
             uint64_t partials = 0;
@@ -549,31 +605,9 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             L->sp.push_back(ScatterPiece{(uint32_t)u0, (uint32_t)u1});
             msgs[t] = (uint64_t)cum[u1] - cum[u0];
             rows[t] = (u1 - u0) + partials;
-            cost[t] = 2 * msgs[t] + 3 * rows[t] + kScatterFixedWeight;
-            limit = std::max(limit, cost[t]);
         }
-        const uint64_t slots = (uint64_t)cus * (src_per_part == kSrcSmall ? 2 : 1);
-        std::vector<uint2> tiles;
-        // (no packing at all if the pieces are few enough; else the smallest limit, to 2 %, that gives few enough tiles)
-        uint64_t all = 0;
-        for (uint64_t c : cost) all += c;
-        limit = 0;
-        for (int round = 0; round < 600; ++round, limit = round == 1 ? all / slots + 1 : limit + limit / 50 + 1) {
-            tiles.clear();
-            uint64_t in_tile = 0;
-            uint32_t first = 0;
-            for (uint32_t i = 0; i < L->n_spieces; ++i) {
-                if (i > first && in_tile + cost[i] > limit) {
-                    tiles.push_back(make_uint2(first, i));
-                    first = i; in_tile = 0;
-                }
-                in_tile += cost[i];
-            }
-            tiles.push_back(make_uint2(first, L->n_spieces));
-            if (tiles.size() <= slots) break;
-        }
-        for (const uint2& t : tiles) {
-            L->st.push_back(make_uint4(t.x, t.y, L->sp[t.x].u0, L->sp[t.x].u1));
+        for (const uint2& t : stiles) {
+            L->st.push_back(ScatterTile{t.x, t.y, L->sp[t.x].u0, L->sp[t.x].u1, L->ri[L->sp[t.x].u0 / rows_per_part], {0, 0}});
             uint64_t m = 0, r = 0;
             for (uint32_t i = t.x; i < t.y; ++i) { m += msgs[i]; r += rows[i]; }
             L->st_msgs.push_back(m);
@@ -592,9 +626,9 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_HIP(hipGetLastError());
     PREP_HIP(hipMemcpyAsync(L->range_info, L->ri.data(), (size_t)Q * sizeof(RangeInfo), hipMemcpyHostToDevice, stream));
     PREP_HIP(hipMemcpyAsync(L->gather_pieces, L->gp.data(), (size_t)L->n_pieces * sizeof(GatherPiece), hipMemcpyHostToDevice, stream));
-    PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(uint2), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->gather_tiles, L->gt.data(), (size_t)L->n_gather * sizeof(GatherTile), hipMemcpyHostToDevice, stream));
     PREP_HIP(hipMemcpyAsync(L->scatter_pieces, L->sp.data(), (size_t)L->n_spieces * sizeof(ScatterPiece), hipMemcpyHostToDevice, stream));
-    PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(uint4), hipMemcpyHostToDevice, stream));
+    PREP_HIP(hipMemcpyAsync(L->scatter_tiles, L->st.data(), (size_t)L->n_scatter * sizeof(ScatterTile), hipMemcpyHostToDevice, stream));
     if (L->n_finish)
         PREP_HIP(hipMemcpyAsync(L->finish_ranges, L->fin.data(), (size_t)L->n_finish * 4, hipMemcpyHostToDevice, stream));
     PREP_HIP(hipStreamSynchronize(stream));       // the host vectors and `tmp` go away after this

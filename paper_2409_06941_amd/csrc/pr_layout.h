@@ -67,7 +67,10 @@ constexpr uint64_t kMinTileMessages = 16384;
 #define FR_W_REP 6
 #define FR_W_FIX 147456
 #endif
-constexpr uint64_t kScatterFixedWeight = 16384;
+// weight of a scatter piece = messages + values read for its sources (measured: a row of partial sums costs a tile
+// about as much as a message, with one or with two workgroups per compute unit); its cost in the packer adds
+// kScatterFixedWeight
+constexpr uint64_t kScatterMessageWeight = 1, kScatterRowWeight = 1, kScatterFixedWeight = 8192;
 constexpr uint64_t kGatherEdgeWeight = FR_W_EDGE, kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP,
                    kTileFixedWeight = FR_W_FIX;
 
@@ -81,6 +84,13 @@ struct GatherPiece { uint32_t range, e0, e1, partial; };   // edges [e0, e1) of 
                                                            // sums the piece writes (kNoPartial: direct range)
 struct ScatterPiece { uint32_t u0, u1; };                  // sources [u0, u1)
 struct RangeInfo { uint32_t cls_tiles, partial0; };        // class | gather tiles << 2; first row of partial sums
+// pieces [p0, p1) of a scatter tile; the sources [u0, u1) of piece p0 and the range of u0 come along, so that the
+// workgroup's first loads of vertex data depend on one load only
+struct alignas(32) ScatterTile { uint32_t p0, p1, u0, u1; RangeInfo first; uint32_t pad[2]; };
+static_assert(sizeof(ScatterTile) == 32, "read as two 16-byte words");
+// pieces [p0, p1) of a gather tile, with a copy of piece p0 for the same reason
+struct alignas(32) GatherTile { uint32_t p0, p1; GatherPiece first; uint32_t pad[2]; };
+static_assert(sizeof(GatherTile) == 32, "read as two 16-byte words");
 
 struct PrLayout {
     int64_t V = 0, E = 0;
@@ -108,18 +118,18 @@ struct PrLayout {
     float* inv_out = nullptr;        // [V] 1/outdeg (0 if dangling)
     RangeInfo* range_info = nullptr; // [Q]
     GatherPiece* gather_pieces = nullptr;  // [n_pieces], heaviest ranges first
-    uint2* gather_tiles = nullptr;         // [n_gather] pieces [x, y) of each tile
+    GatherTile* gather_tiles = nullptr;    // [n_gather]
     ScatterPiece* scatter_pieces = nullptr;  // [n_spieces]
-    uint4* scatter_tiles = nullptr;        // [n_scatter] pieces [x, y) of each tile; z, w = sources [u0, u1) of piece x
+    ScatterTile* scatter_tiles = nullptr;  // [n_scatter]
     uint32_t* finish_ranges = nullptr;     // [n_finish] merged ranges, then empty ranges
 
     // host copies for the cost model
     std::vector<GatherPiece> gp;
-    std::vector<uint2> gt;               // pieces of each gather tile
+    std::vector<GatherTile> gt;
     std::vector<uint64_t> gt_weight;     // weight of each gather tile (its pieces' weights, kTileFixedWeight a piece included)
     std::vector<uint64_t> gt_edges;      // edges of each gather tile
     std::vector<ScatterPiece> sp;
-    std::vector<uint4> st;               // pieces of each scatter tile (and the first piece's sources)
+    std::vector<ScatterTile> st;
     std::vector<uint64_t> st_msgs;       // messages of each scatter tile
     std::vector<uint64_t> st_rows;       // sources + partial sums added up, of each scatter tile
     std::vector<RangeInfo> ri;           // [Q]
