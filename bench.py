@@ -163,41 +163,52 @@ def main():
         ctx.fr_bubble_end()
         return ctx, task, tid
 
-    # Second profiling pass, in place: an epoch (the fourth after the start) with the standalone model (generously
-    # derated) shows what a step costs inside real bubbles, launch gaps included; the final model is that cost plus
-    # a small margin.
+    # Second profiling pass, in place: an epoch (the fourth after the start) shows what a step costs inside real
+    # bubbles, launch gaps included.  It is done twice: first with the standalone model, generously derated, then
+    # with what the first pass measured - a bubble's first steps run some percent slower than its later ones, so a
+    # pass that plans fewer steps per bubble than the timed epochs will measures a slower average than theirs.
+    # The final model is the second pass's cost plus a small margin.
     ts = max(1, args.time_steps)
-    ctx, task, tid = start_task(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate), ts)
-    for _ in range(3):                           # untimed: right after a start the steps run a few percent slower
-        stage.fr_stage_run_epoch(ctx)
-    time.sleep(0.02)
-    ctx.fr_event_log_clear()
-    stage.fr_stage_run_epoch(ctx)
-    time.sleep(0.02)
-    n_tiles = [task.fr_pagerank_tiles(k) for k in range(4)]
-    # timing groups made of whole sweeps only: measured time against what the standalone profile says they cost
-    ratios, group = [], []
     standalone = (v_ns, s_ns, g_ns, h_ns)
-    for e in ctx.fr_event_log(1 << 18):
-        if e.kind != fr.FR_EV_CHUNK:
-            group = []
-            continue
-        if group and group[-1].bubble != e.bubble:
-            group = []
-        group.append(e)
-        if e.measured_ns > 0:
-            if all(x.tile0 == 0 and x.tile1 == n_tiles[seg_kind(x.segment)] for x in group) and \
-               all(seg_kind(x.segment) in (fr.FR_PR_SEG_SCATTER, fr.FR_PR_SEG_GATHER) for x in group) and len(group) == ts:
-                ratios.append(e.measured_ns / sum(standalone[seg_kind(x.segment)] for x in group))
-            group = []
-    ctx.fr_task_stop(tid); task.fr_pagerank_destroy(); ctx.fr_destroy()
-    in_bubble = statistics.median(ratios) if ratios else args.derate
+    n_tiles = None
+    def in_bubble_ratio(launch_cost_ns, model):
+        nonlocal n_tiles
+        ctx, task, tid = start_task(launch_cost_ns, model, ts)
+        for _ in range(3):                       # untimed: right after a start the steps run a few percent slower
+            stage.fr_stage_run_epoch(ctx)
+        time.sleep(0.02)
+        ctx.fr_event_log_clear()
+        stage.fr_stage_run_epoch(ctx)
+        time.sleep(0.02)
+        n_tiles = [task.fr_pagerank_tiles(k) for k in range(4)]
+        # timing groups made of whole sweeps only: measured time against what the standalone profile says they cost
+        ratios, group = [], []
+        for e in ctx.fr_event_log(1 << 18):
+            if e.kind != fr.FR_EV_CHUNK:
+                group = []
+                continue
+            if group and group[-1].bubble != e.bubble:
+                group = []
+            group.append(e)
+            if e.measured_ns > 0:
+                if all(x.tile0 == 0 and x.tile1 == n_tiles[seg_kind(x.segment)] for x in group) and \
+                   all(seg_kind(x.segment) in (fr.FR_PR_SEG_SCATTER, fr.FR_PR_SEG_GATHER) for x in group) and len(group) == ts:
+                    ratios.append(e.measured_ns / sum(standalone[seg_kind(x.segment)] for x in group))
+                group = []
+        ctx.fr_task_stop(tid); task.fr_pagerank_destroy(); ctx.fr_destroy()
+        return ratios
+    ratios = in_bubble_ratio(8_000, rates(v_ns, s_ns, g_ns, h_ns, args.derate))
+    first_pass = statistics.median(ratios) if ratios else args.derate
+    one_tile_standalone = list(one_tile_ns)
+    one_tile_ns = [x * first_pass for x in one_tile_standalone]
+    ratios = in_bubble_ratio(0, rates(*[x * first_pass for x in standalone], args.margin)) or ratios
+    in_bubble = statistics.median(ratios) if ratios else first_pass
     insitu = [x * in_bubble for x in standalone]
-    log("in-bubble step times = standalone x %.3f (%d timing groups of %d whole sweeps): scatter %.1f us, gather %.1f us" %
-        (in_bubble, len(ratios), ts, insitu[1] / 1e3, insitu[2] / 1e3))
+    log("in-bubble step times = standalone x %.3f (first pass %.3f; %d timing groups of %d whole sweeps): scatter %.1f us, gather %.1f us" %
+        (in_bubble, first_pass, len(ratios), ts, insitu[1] / 1e3, insitu[2] / 1e3))
     if ratios:
         log("  group ratios min %.3f quartiles %.3f %.3f %.3f max %.3f" % ((min(ratios),) + tuple(statistics.quantiles(ratios, n=4)) + (max(ratios),)))
-    one_tile_ns = [x * in_bubble for x in one_tile_ns]
+    one_tile_ns = [x * in_bubble for x in one_tile_standalone]
     ctx, task, tid = start_task(0, rates(*insitu, args.margin), ts)     # the measured group times already hold the launch gaps
     def epochs(n, with_task):
         out = []
