@@ -159,8 +159,9 @@ __global__ __launch_bounds__(kBlk) void k_emit(int64_t E, int64_t padded, uint64
 
 // Message-start record of chunk c, kStartWords 64-bit words: words 0 .. 7 = for row j (stream positions 64 j .. 64 j + 63
 // of the chunk) the start bits of positions 1 .. 63 in bits 0 .. 62 (bit l set: position l + 1 begins a message);
-// words 8 .. 11 = eight 32-bit message numbers, that of the first position of each row.  The message of position l of
-// row j is then: first[j] + (set bits below l in word j).
+// words 8 .. 11 = eight 32-bit words, for the first position of each row four times the distance of its message from
+// message mbase[c] - 1 (0 .. 2048: a byte offset into the messages).  The message of position l of row j is then:
+// mbase[c] - 1 + first[j] / 4 + (set bits below l in word j).
 __global__ __launch_bounds__(kBlk) void k_starts(int64_t E, uint64_t n_rows, const uint64_t* __restrict__ keys,
                                                  const uint32_t* __restrict__ incl, uint64_t* __restrict__ starts)
 {
@@ -174,7 +175,8 @@ __global__ __launch_bounds__(kBlk) void k_starts(int64_t E, uint64_t n_rows, con
     const int64_t e0 = (int64_t)(w * 64);
     uint64_t* rec = starts + (w / 8) * kStartWords;
     rec[w % 8] = bits;
-    reinterpret_cast<uint32_t*>(rec + 8)[w % 8] = e0 < E ? incl[e0] - 1u : 0u;
+    const int64_t ec = (int64_t)(w / 8) * kIdChunk;          // the chunk's first position
+    reinterpret_cast<uint32_t*>(rec + 8)[w % 8] = e0 < E ? 4u * (incl[e0] - (incl[ec] - flag_of(keys, ec))) : 0u;
 }
 
 __global__ __launch_bounds__(kBlk) void k_mbase(int64_t E, uint32_t n_chunks, uint32_t M, const uint64_t* __restrict__ keys,

@@ -111,7 +111,8 @@ struct PrLayout {
     uint16_t* ids16 = nullptr;       // [n_chunks * kIdChunk] local row id times id_scale_for(rows_per_part);
                                      // each chunk stored transposed: stream position 64 j + lane at slot 8 lane + j
     uint64_t* starts = nullptr;      // [n_chunks * kStartWords] per chunk: eight words of message-start bits (one per 64
-                                     // positions, shifted down by one) and the message numbers of the eight first positions
+                                     // positions, shifted down by one) and, for the eight first positions, the byte offsets
+                                     // of their messages from message mbase[chunk] - 1
     uint16_t* src16 = nullptr;       // [M] source id relative to the first source of its scatter piece
     uint32_t* mbase = nullptr;       // [n_chunks + 1] messages that begin before each chunk
     uint2* bins = nullptr;           // [n_spieces * Qe] message range [x, y) of (scatter piece, range), piece-major
