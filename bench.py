@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM-side bytes one PageRank iteration (k_scatter + k_gather) moves on cfg2, from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised under profiles/ (FETCH_SIZE scaled by 1.985, the factor a plain streaming kernel of known
 # size shows).  Only valid for the kernels those counters were taken on: set to None when the kernels change.
-CFG2_TRAFFIC_BYTES = 349.9e6
+CFG2_TRAFFIC_BYTES = 352.5e6
 
 
 def log(*a):

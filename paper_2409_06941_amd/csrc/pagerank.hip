@@ -450,7 +450,8 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 // all but the first and last chunk of a tile - take a path without per-id checks (8 vector instructions per 64
 // edges instead of 25).  On a graph of 2^26 edges the sweep then moves its bytes at about 4.7 TB/s, which is what
 // the memory system gives this mix of streams: taking a sixth of the vector instructions out of the loop changed
-// nothing, and a third or fourth buffer of messages in flight made it 6 to 9 % slower.
+// nothing, a third or fourth buffer of messages in flight made it 6 to 9 % slower, and so did start records that
+// come through a vector load (one dword a lane, handed to the scalar side with readlane) instead of scalar loads.
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 template <uint32_t kRowsPerPart>
 __global__ __launch_bounds__(kGatherBlock) __attribute__((amdgpu_waves_per_eu(kRowsPerPart == kRowsSmall ? 8 : 4, kRowsPerPart == kRowsSmall ? 8 : 4)))
