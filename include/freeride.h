@@ -359,6 +359,69 @@ int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights_hos
 int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint32_t max_tiles_per_launch,
                                uint64_t* phase_ns_out);
 
+/* ------------------------------------------------------------------ Graph SGD side task */
+/*
+ * Stochastic gradient descent for matrix factorization over a rating graph: the second graph workload of
+ * Section 6.1.4 (one iteration = one pass over the graph, Section 6.2).  The paper names the method only; the
+ * arithmetic is the textbook one (Koren, Bell, Volinsky 2009), for every rating r_ui, one after the other,
+ *     e = r_ui - <p_u, q_i>,   p_u += gamma (e q_i - lambda p_u),   q_i += gamma (e p_u - lambda q_i),
+ * and the order is stratified (Gemulla et al. 2011): users and items in `blocks` blocks of ceil(n / blocks)
+ * consecutive ids; cell (a, b) = ratings of user block a and item block b; an iteration = `blocks` strata, stratum
+ * s = cells (a, (a + s) mod blocks), which share no factor row and run side by side; inside a cell by user, then
+ * by item.  All roundings of an update are fixed: t_l = p_l * q_l; in rounds w = 1, 2, 4, .. t_l += t_(l xor w);
+ * e = r - t; ge = gamma * e; gl = gamma * lambda; p_l' = fma(ge, q_l, fma(-gl, p_l, p_l)); q_l' likewise from the
+ * old p_l - so the factors are the same bits however the cells are grouped into steps.
+ *
+ * As a side task: one run = `iterations` iterations = iterations * blocks segments (a segment is a stratum, a
+ * tile is a cell); the factors carry over from run to run.  work_units = ratings visited.
+ * Modelled cost of a cell = ceil(ratings * fs_per_rating / 10^6) ns, at least 1; of a step =
+ * max(sum over its cells, min_step_ns): the cells of a step run side by side, so a step of few cells takes about
+ * as long as its longest cell.
+ */
+typedef struct fr_sgd_desc {
+    int64_t  n_users;             /* U >= 1, below 2^27 - 1024                                              */
+    int64_t  n_items;             /* I >= 1, below 2^27 - 1024                                              */
+    int64_t  n_ratings;           /* E >= 0, below 2^31                                                     */
+    const int32_t* row_ptr;       /* device, U + 1 entries: ratings as CSR by user                          */
+    const int32_t* item;          /* device, E entries: ascending and distinct inside a row (FR_ERR_ARG from
+                                     InitSideTask otherwise); only read                                     */
+    const float*   rating;        /* device, E entries; only read                                           */
+    float*   P;                   /* device, U x factors, row-major: in and out                             */
+    float*   Q;                   /* device, I x factors, row-major: in and out                             */
+    int32_t  factors;             /* F: 16, 32 or 64                                                        */
+    int32_t  blocks;              /* B: 1 .. 1024; 0 = chosen by the library (cells of 32 ratings or more)   */
+    float    gamma;               /* step length, >= 0                                                      */
+    float    lambda;              /* regularisation, >= 0                                                   */
+    int32_t  iterations;          /* K >= 1 iterations per run                                              */
+    int32_t  max_runs;            /* stop harvesting after this many runs; 0 = keep training forever        */
+    uint64_t mem_limit_bytes;     /* the task's memory limit; caller buffers above are booked against it    */
+    uint64_t fs_per_rating;       /* cost model, femtoseconds (0 = library default)                         */
+    uint64_t min_step_ns;         /* shortest step, ns (0 = none)                                           */
+} fr_sgd_desc;
+
+typedef struct fr_sgd_info_t {
+    uint32_t blocks;              /* B in use                                                               */
+    uint32_t users_per_block, items_per_block;
+    uint32_t largest_cell;        /* ratings in the largest cell                                            */
+    uint64_t bytes_resident;      /* booked after InitSideTask, caller buffers included                     */
+    uint64_t bytes_peak;          /* highest booking during InitSideTask                                    */
+} fr_sgd_info_t;
+
+/* Fills ops / profile for fr_task_register; *user_out is the task object (host).  Nothing touches the GPU yet. */
+int fr_sgd_make(const fr_sgd_desc* d, fr_task_ops* ops_out, void** user_out, fr_task_profile* prof_out);
+/* Frees the task object; FR_ERR_STATE while it is registered with a context (stop it first). */
+int fr_sgd_destroy(void* user);
+/* The two calls below need the layout: FR_ERR_STATE until InitSideTask has run. */
+int fr_sgd_info(void* user, fr_sgd_info_t* out);
+/* Ratings in the cells (a, (a + stratum) mod B), a = 0 .. B - 1; *n_out = B. */
+int fr_sgd_cell_sizes(void* user, uint32_t stratum, uint32_t* sizes_host, size_t cap, size_t* n_out);
+/*
+ * Runs one whole run (K iterations) outside any bubble on `stream`, at most `max_cells_per_launch` cells per
+ * kernel launch (0 = a whole stratum per launch), and waits for it.  Same kernel and cells as the harvested
+ * path.  The task must not be registered with a context.  ns_out (host, may be NULL) receives the GPU time.
+ */
+int fr_sgd_run_standalone(void* user, int32_t device_id, void* stream, uint32_t max_cells_per_launch, uint64_t* ns_out);
+
 /* ------------------------------------------------------------------ stage load and stage emulator */
 #define FR_LOAD_BUSYWAIT 0   /* one small kernel that spins on the GPU clock for fp_ns / bp_ns              */
 #define FR_LOAD_GPT      1   /* bf16 MFMA GEMM bursts shaped like `layers` transformer blocks               */

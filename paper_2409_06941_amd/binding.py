@@ -86,6 +86,19 @@ class fr_pagerank_info_t(C.Structure):
                 ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
 
 
+class fr_sgd_desc(C.Structure):
+    _fields_ = [("n_users", C.c_int64), ("n_items", C.c_int64), ("n_ratings", C.c_int64), ("row_ptr", C.c_void_p),
+                ("item", C.c_void_p), ("rating", C.c_void_p), ("P", C.c_void_p), ("Q", C.c_void_p),
+                ("factors", C.c_int32), ("blocks", C.c_int32), ("gamma", C.c_float), ("lam", C.c_float),
+                ("iterations", C.c_int32), ("max_runs", C.c_int32), ("mem_limit_bytes", C.c_uint64),
+                ("fs_per_rating", C.c_uint64), ("min_step_ns", C.c_uint64)]
+
+
+class fr_sgd_info_t(C.Structure):
+    _fields_ = [("blocks", C.c_uint32), ("users_per_block", C.c_uint32), ("items_per_block", C.c_uint32),
+                ("largest_cell", C.c_uint32), ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
+
+
 class fr_load_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("layers", C.c_int32), ("hidden", C.c_int32), ("ffn", C.c_int32),
                 ("tokens", C.c_int32), ("fp_ns", C.c_uint64), ("bp_ns", C.c_uint64), ("workspace", C.c_void_p),
@@ -137,6 +150,11 @@ SIGNATURES = {
     "fr_pagerank_tile_work": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_pagerank_tile_weights": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_pagerank_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
+    "fr_sgd_make": (C.c_int, [C.POINTER(fr_sgd_desc), C.POINTER(fr_task_ops), C.POINTER(C.c_void_p), C.POINTER(fr_task_profile)]),
+    "fr_sgd_destroy": (C.c_int, [C.c_void_p]),
+    "fr_sgd_info": (C.c_int, [C.c_void_p, C.POINTER(fr_sgd_info_t)]),
+    "fr_sgd_cell_sizes": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
+    "fr_sgd_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
     "fr_load_workspace_bytes": (C.c_int, [C.POINTER(fr_load_desc), C.POINTER(C.c_uint64)]),
     "fr_load_make": (C.c_int, [C.POINTER(fr_load_desc), C.c_void_p, C.POINTER(C.c_void_p)]),
     "fr_load_destroy": (C.c_int, [C.c_void_p]),
@@ -344,6 +362,48 @@ class PageRankTask:
         _check(lib().fr_pagerank_run_standalone(self.user, device_id, _stream(stream), max_tiles_per_launch,
                                                 ph if want_phase_ns else None), "fr_pagerank_run_standalone")
         return list(ph) if want_phase_ns else None
+
+
+class SgdTask:
+    """fr_sgd_make and friends.  Tensors (torch, on the GPU) are only read for their data_ptr."""
+
+    def __init__(self, n_users, n_items, n_ratings, row_ptr, item, rating, P, Q, factors, gamma, lam, iterations=1,
+                 blocks=0, max_runs=0, mem_limit_bytes=1 << 40, fs_per_rating=0, min_step_ns=0):
+        d = fr_sgd_desc()
+        d.n_users, d.n_items, d.n_ratings = n_users, n_items, n_ratings
+        d.row_ptr, d.item, d.rating, d.P, d.Q = _ptr(row_ptr), _ptr(item), _ptr(rating), _ptr(P), _ptr(Q)
+        d.factors, d.blocks, d.gamma, d.lam = factors, blocks, gamma, lam
+        d.iterations, d.max_runs, d.mem_limit_bytes = iterations, max_runs, mem_limit_bytes
+        d.fs_per_rating, d.min_step_ns = fs_per_rating, min_step_ns
+        self.desc = d
+        self._keep = (row_ptr, item, rating, P, Q)
+        self.ops = fr_task_ops()
+        self.user = C.c_void_p()
+        self.profile = fr_task_profile()
+        _check(lib().fr_sgd_make(C.byref(d), C.byref(self.ops), C.byref(self.user), C.byref(self.profile)), "fr_sgd_make")
+
+    def fr_sgd_destroy(self):
+        if self.user:
+            _check(lib().fr_sgd_destroy(self.user), "fr_sgd_destroy")
+            self.user = C.c_void_p()
+
+    def fr_sgd_info(self):
+        out = fr_sgd_info_t()
+        _check(lib().fr_sgd_info(self.user, C.byref(out)), "fr_sgd_info")
+        return out
+
+    def fr_sgd_cell_sizes(self, stratum):
+        n = self.fr_sgd_info().blocks
+        buf = (C.c_uint32 * n)()
+        got = C.c_size_t()
+        _check(lib().fr_sgd_cell_sizes(self.user, stratum, buf, n, C.byref(got)), "fr_sgd_cell_sizes")
+        return list(buf)
+
+    def fr_sgd_run_standalone(self, device_id=0, stream=None, max_cells_per_launch=0, want_ns=False):
+        ns = C.c_uint64()
+        _check(lib().fr_sgd_run_standalone(self.user, device_id, _stream(stream), max_cells_per_launch,
+                                           C.byref(ns) if want_ns else None), "fr_sgd_run_standalone")
+        return ns.value if want_ns else None
 
 
 class Load:

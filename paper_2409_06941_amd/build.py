@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfreeride.so")
-SOURCES = ["runtime.cpp", "stage.cpp", "pagerank.hip", "pagerank_prep.hip", "gemm.hip"]
+SOURCES = ["runtime.cpp", "stage.cpp", "pagerank.hip", "pagerank_prep.hip", "sgd.hip", "gemm.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

@@ -25,7 +25,7 @@ def test_every_declared_function_is_exported_and_bound():
     assert declared == set(fr.binding.SIGNATURES), declared ^ set(fr.binding.SIGNATURES)
 
 
-STRUCTS = ["fr_config", "fr_step", "fr_task_ops", "fr_task_profile", "fr_progress", "fr_event", "fr_pagerank_desc", "fr_pagerank_info_t",
+STRUCTS = ["fr_config", "fr_step", "fr_task_ops", "fr_task_profile", "fr_progress", "fr_event", "fr_pagerank_desc", "fr_pagerank_info_t", "fr_sgd_desc", "fr_sgd_info_t",
            "fr_load_desc", "fr_stage_desc", "fr_stage_op", "fr_epoch_result"]
 
 

@@ -1,0 +1,175 @@
+"""GPU parity of the Graph SGD side task (Section 6.1.4's second graph workload), through the C ABI:
+bit for bit against the oracle's fp32 mode (same steps, every rounding fixed), within a tolerance against its fp64
+mode, and the same bits however the cells are grouped into launches or harvested in bubbles."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2409_06941_amd as fr          # noqa: E402
+from oracle import sgd as osgd             # noqa: E402
+from workloads import ratings as wl        # noqa: E402
+
+# fp32 against fp64 after a few iterations: every update rounds a handful of times (2^-24 relative each) on factors
+# of order 1, a factor row is touched some tens of times per iteration, and the iteration is a contraction for
+# these step lengths; measured on the CPU between the oracle's two modes: below 1e-4.
+TOL64 = 1e-3
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    return (t.to(dtype) if dtype is not None else t).cuda()
+
+
+def _task(r, P, Q, F, gamma, lam, K, B, **kw):
+    rp, it, ra = _dev(r.row_ptr, torch.int32), _dev(r.item, torch.int32), _dev(r.rating, torch.float32)
+    if it.numel() == 0:
+        it, ra = torch.zeros(4, dtype=torch.int32, device="cuda"), torch.zeros(4, dtype=torch.float32, device="cuda")
+    return fr.SgdTask(r.n_users, r.n_items, r.n_ratings, rp, it, ra, P, Q, F, gamma, lam, iterations=K, blocks=B, **kw)
+
+
+def _run(r, P0, Q0, F, gamma, lam, K, B, max_cells=0):
+    P, Q = _dev(P0), _dev(Q0)
+    t = _task(r, P, Q, F, gamma, lam, K, B)
+    try:
+        t.fr_sgd_run_standalone(0, torch.cuda.current_stream(), max_cells)
+        info = t.fr_sgd_info()
+    finally:
+        t.fr_sgd_destroy()
+    return P.cpu().numpy(), Q.cpu().numpy(), info
+
+
+def _same_bits(a, b):
+    return np.array_equal(np.asarray(a).view(np.uint32), np.asarray(b).view(np.uint32))
+
+
+@pytest.mark.parametrize("scale,edges,F,B,seed", [(6, 700, 16, 1, 1), (8, 5000, 16, 3, 2), (9, 1 << 14, 32, 8, 3),
+                                                   (10, (1 << 16) + 77, 64, 16, 4), (12, 1 << 17, 64, 37, 5)])
+def test_factors_match_the_oracle(scale, edges, F, B, seed):
+    r = wl.rmat_ratings(scale, edges, seed=seed)
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed=seed)
+    gamma, lam, K = 0.02, 0.03, 3
+    print("case U=I=%d E=%d F=%d B=%d" % (r.n_users, r.n_ratings, F, B), flush=True)
+    P, Q, info = _run(r, P0, Q0, F, gamma, lam, K, B)
+    assert info.blocks == B
+    P32, Q32 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, K, B, ordered_fp32=True)
+    assert _same_bits(P, P32) and _same_bits(Q, Q32)
+    P64, Q64 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, K, B)
+    assert np.abs(P - P64).max() <= TOL64 and np.abs(Q - Q64).max() <= TOL64
+    assert osgd.rmse(r.row_ptr, r.item, r.rating, P, Q) < osgd.rmse(r.row_ptr, r.item, r.rating, P0, Q0)
+
+
+@pytest.mark.parametrize("max_cells", [1, 5, 64])
+def test_any_grouping_of_cells_into_launches_gives_identical_bits(max_cells):
+    r = wl.rmat_ratings(11, 1 << 16, seed=6)
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, 32, seed=6)
+    whole = _run(r, P0, Q0, 32, 0.02, 0.03, 2, 24)
+    parts = _run(r, P0, Q0, 32, 0.02, 0.03, 2, 24, max_cells)
+    assert _same_bits(whole[0], parts[0]) and _same_bits(whole[1], parts[1])
+
+
+def test_layout_facts_and_default_blocks():
+    r = wl.rmat_ratings(12, 1 << 18, seed=7)
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, 16, seed=7)
+    P, Q = _dev(P0), _dev(Q0)
+    t = _task(r, P, Q, 16, 0.01, 0.0, 1, 0)
+    t.fr_sgd_run_standalone(0, torch.cuda.current_stream())
+    info = t.fr_sgd_info()
+    B = info.blocks
+    assert 1 <= B <= 1024 and r.n_ratings // (B * B) >= 32 and r.n_ratings // (4 * B * B) < 32     # largest power of two that fits
+    assert info.users_per_block == -(-r.n_users // B) and info.items_per_block == -(-r.n_items // B)
+    users = np.repeat(np.arange(r.n_users), np.diff(r.row_ptr))
+    a, b = users // info.users_per_block, r.item // info.items_per_block
+    total, largest = 0, 0
+    for s in (0, 1, B - 1):
+        sizes = t.fr_sgd_cell_sizes(s)
+        want = np.bincount(a[(b - a) % B == s], minlength=B)
+        assert sizes == list(want)
+    for s in range(B):
+        sizes = t.fr_sgd_cell_sizes(s)
+        total += sum(sizes); largest = max(largest, max(sizes))
+    assert total == r.n_ratings and largest == info.largest_cell
+    assert info.bytes_resident >= 12 * r.n_ratings and info.bytes_peak >= info.bytes_resident
+    t.fr_sgd_destroy()
+
+
+def test_no_ratings_leaves_the_factors_alone():
+    r = wl.Ratings(5, 7, 0, np.zeros(6, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    P0, Q0 = wl.initial_factors(5, 7, 16, seed=1)
+    P, Q, _ = _run(r, P0, Q0, 16, 0.1, 0.1, 2, 2)
+    assert _same_bits(P, P0) and _same_bits(Q, Q0)
+
+
+def test_malformed_ratings_are_refused():
+    r = wl.rmat_ratings(6, 500, seed=8)
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, 16, seed=1)
+    with pytest.raises(fr.FreeRideError):
+        _task(r, _dev(P0), _dev(Q0), 8, 0.1, 0.1, 1, 1)                        # unsupported number of factors
+    u = int(np.argmax(np.diff(r.row_ptr) >= 2))
+    swapped = r.item.copy()
+    e = r.row_ptr[u]
+    swapped[e], swapped[e + 1] = swapped[e + 1], swapped[e]                     # a row whose items do not ascend
+    for bad_items in (swapped, np.where(np.arange(r.n_ratings) == 3, r.n_items, r.item).astype(np.int32)):
+        bad = wl.Ratings(r.n_users, r.n_items, r.n_ratings, r.row_ptr, bad_items, r.rating)
+        P, Q = _dev(P0), _dev(Q0)
+        t = _task(bad, P, Q, 16, 0.1, 0.1, 1, 2)
+        with pytest.raises(fr.FreeRideError) as ei:
+            t.fr_sgd_run_standalone(0, torch.cuda.current_stream())
+        assert ei.value.code == fr.FR_ERR_ARG
+        t.fr_sgd_destroy()
+        assert _same_bits(P.cpu().numpy(), P0)                                 # nothing ran
+
+
+def test_harvested_in_bubbles_gives_the_standalone_bits():
+    from workloads import configs
+    cfg = configs.by_name("cfg1")
+    r = wl.rmat_ratings(12, 1 << 17, seed=9)
+    F, gamma, lam, K, B, runs = 32, 0.02, 0.03, 2, 16, 2
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed=9)
+    # reference: `runs` standalone runs in a row (the factors carry over)
+    Pr, Qr = _dev(P0), _dev(Q0)
+    t_ref = _task(r, Pr, Qr, F, gamma, lam, K, B)
+    ns = [t_ref.fr_sgd_run_standalone(0, torch.cuda.current_stream(), want_ns=True) for _ in range(runs)]
+    t_ref.fr_sgd_destroy()
+    # cost model from the measured run: the cells of a stratum run side by side, so a step of any number of them takes
+    # about a stratum's time (the floor), and a whole stratum's cells add up to the same
+    stratum_ns = min(ns) / (K * B)
+    fs_per_rating = int(1.5 * stratum_ns * 1e6 / (r.n_ratings / B))
+    floor_ns = int(1.5 * stratum_ns) + 10_000
+    print("stratum %.1f us, %.2f us per rating of a cell" % (stratum_ns / 1e3, stratum_ns / 1e3 / (r.n_ratings / B / B)), flush=True)
+
+    P, Q = _dev(P0), _dev(Q0)
+    ctx = fr.Context(device_id=0, guard_ns=200_000, launch_cost_ns=20_000, max_chunk_ns=0, time_steps=1,
+                     mem_available_bytes=1 << 40)
+    task = _task(r, P, Q, F, gamma, lam, K, B, max_runs=runs, mem_limit_bytes=1 << 30, fs_per_rating=fs_per_rating,
+                 min_step_ns=floor_ns)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    import time
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 2_000_000_000)
+    t_end = time.time() + 30
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+        time.sleep(0.001)
+    ctx.fr_bubble_end()
+    assert ctx.fr_query_progress(tid).state == fr.FR_PAUSED
+    stream = torch.cuda.Stream()
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=cfg.busy_fp_ns, bp_ns=cfg.busy_bp_ns)
+    stage = fr.Stage(fr.FR_SCHED_1F1B, cfg.p, cfg.m, cfg.stage, cfg.busy_fp_ns, cfg.busy_bp_ns, load, stream)
+    overruns = 0
+    for ep in range(40):
+        print("epoch", ep, flush=True)
+        overruns += stage.fr_stage_run_epoch(ctx).overruns
+        if ctx.fr_query_progress(tid).runs_completed >= runs:
+            break
+    time.sleep(0.05)
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    ctx.fr_task_stop(tid)
+    got_P, got_Q = P.cpu().numpy(), Q.cpu().numpy()
+    task.fr_sgd_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    assert pr.runs_completed == runs and overruns == 0 and pr.deadline_misses == 0
+    chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
+    assert sum(e.work_units for e in chunks) == runs * K * r.n_ratings == pr.work_units_done
+    assert len(chunks) >= runs * K * B                         # a step never spans two strata
+    assert _same_bits(got_P, Pr.cpu().numpy()) and _same_bits(got_Q, Qr.cpu().numpy())
