@@ -28,45 +28,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=12)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg2")
-    ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
-    ap.add_argument("--margin", type=float, default=1.02, help="final model = measured in-bubble step cost x margin")
-    ap.add_argument("--guard-ns", type=int, default=100_000)
-    ap.add_argument("--time-steps", type=int, default=16,
-                    help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
-    ap.add_argument("--device-gate", type=int, default=0,
-                    help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py runs on one GPU only (--gpus 1).", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def stage_load(cfg, stage_stream):
+    """The stage's load and its declared FP/BP durations (medians of timed bursts)."""
     import torch
 
     import paper_2409_06941_amd as fr
-    from workloads import configs
-
-    cfg = configs.by_name(args.config)
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    t_setup = time.time()
-    g = cfg.build_graph()
-    V, E, K = g.n_vertices, g.n_edges, cfg.iterations
-    log("graph %s: V=%d E=%d built in %.1fs" % (cfg.name, V, E, time.time() - t_setup))
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    rp, col, od = dev(g.row_ptr), dev(g.col), dev(g.out_degree)
-    ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
-    stage_stream = torch.cuda.Stream()
-
-    # ---- stage load and its declared FP/BP durations (medians of timed bursts)
+    ws = None
     if cfg.load is not None:
         L = cfg.load
         need = fr.Load.fr_load_workspace_bytes(fr.FR_LOAD_GPT, L.layers, L.hidden, L.ffn, L.tokens)
@@ -92,6 +59,54 @@ def main():
         load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=cfg.busy_fp_ns, bp_ns=cfg.busy_bp_ns)
         fp_flops = bp_flops = 0
         f_ns, b_ns = cfg.busy_fp_ns, cfg.busy_bp_ns
+    return load, ws, f_ns, b_ns, fp_flops, bp_flops
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=12)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
+    ap.add_argument("--margin", type=float, default=1.02, help="final model = measured in-bubble step cost x margin")
+    ap.add_argument("--guard-ns", type=int, default=100_000)
+    ap.add_argument("--time-steps", type=int, default=16,
+                    help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
+    ap.add_argument("--device-gate", type=int, default=0,
+                    help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--side-task", default="pagerank", choices=("pagerank", "sgd"),
+                    help="sgd: the Graph SGD side task in the same stage's bubbles (a second line of its own, not the headline metric)")
+    ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py runs on one GPU only (--gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    if args.side_task == "sgd":
+        from bench_sgd import run as run_sgd
+        return run_sgd(args, stage_load, log)
+
+    import numpy as np
+    import torch
+
+    import paper_2409_06941_amd as fr
+    from workloads import configs
+
+    cfg = configs.by_name(args.config)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t_setup = time.time()
+    g = cfg.build_graph()
+    V, E, K = g.n_vertices, g.n_edges, cfg.iterations
+    log("graph %s: V=%d E=%d built in %.1fs" % (cfg.name, V, E, time.time() - t_setup))
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    rp, col, od = dev(g.row_ptr), dev(g.col), dev(g.out_degree)
+    ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+    stage_stream = torch.cuda.Stream()
+
+    load, ws, f_ns, b_ns, fp_flops, bp_flops = stage_load(cfg, stage_stream)
     log("stage load: f=%.3f ms b=%.3f ms" % (f_ns / 1e6, b_ns / 1e6))
 
     # ---- side-task profile: per-step costs from a few standalone iterations (the paper's side-task profiler)

@@ -1,0 +1,138 @@
+"""`bench.py --side-task sgd`: the Graph SGD side task harvested in the bubbles of the cfg2 stage (one JSON line).
+
+Not the headline metric (that is the PageRank line of bench.py); same method of measurement: inputs resident in HBM,
+the stage's FP/BP bursts are bf16 GEMMs, W warm-up epochs, K timed epochs bracketed by synchronisation, epochs without
+the side task before and after for the stage's slowdown.
+"""
+import json
+import statistics
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def run(args, stage_load, log):
+    import numpy as np
+    import torch
+
+    import paper_2409_06941_amd as fr
+    from workloads import configs
+    from workloads import ratings as wl
+
+    cfg = configs.by_name("cfg2")                    # the stage: 1F1B p=4 m=8 stage 2, GPT-shaped GEMM bursts
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    scale, edges, F, gamma, lam, seed = 20, 1 << 24, 64, 0.01, 0.02, 1
+    t0 = time.time()
+    r = wl.rmat_ratings(scale, edges, seed)
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed)
+    U, I, E = r.n_users, r.n_items, r.n_ratings
+    log("ratings: U=I=%d E=%d F=%d built in %.1fs" % (U, E, F, time.time() - t0))
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    rp, it, ra = dev(r.row_ptr), dev(r.item), dev(r.rating)
+    P, Q = dev(P0), dev(Q0)
+    stage_stream = torch.cuda.Stream()
+    load, ws, f_ns, b_ns, fp_flops, bp_flops = stage_load(cfg, stage_stream)
+    log("stage load: f=%.3f ms b=%.3f ms" % (f_ns / 1e6, b_ns / 1e6))
+
+    # ---- side-task profile: one standalone iteration, twice (the first also builds the layout)
+    probe_ctx = fr.Context(device_id=0)
+    probe = fr.SgdTask(U, I, E, rp, it, ra, P, Q, F, gamma, lam, iterations=1)
+    probe.fr_sgd_run_standalone(0, probe_ctx.fr_side_stream())
+    ns = min(probe.fr_sgd_run_standalone(0, probe_ctx.fr_side_stream(), want_ns=True) for _ in range(2))
+    info = probe.fr_sgd_info()
+    B = info.blocks
+    probe.fr_sgd_destroy(); probe_ctx.fr_destroy()
+    stratum_ns = ns / B
+    log("layout: %d x %d cells, largest %d ratings (mean %.1f); standalone iteration %.2f ms = %.1f us per stratum, %.2f us per rating of the largest cell" %
+        (B, B, info.largest_cell, E / B / B, ns / 1e6, stratum_ns / 1e3, stratum_ns / 1e3 / max(1, info.largest_cell)))
+    # the cells of a step run side by side: a step takes about a stratum's time whatever its number of cells (the
+    # floor), and the cells of a whole stratum add up to the same
+    derate = 1.3
+    model = dict(fs_per_rating=int(derate * stratum_ns * 1e6 / (E / B)), min_step_ns=int(derate * stratum_ns))
+    P.copy_(dev(P0)); Q.copy_(dev(Q0))
+
+    ctx = fr.Context(device_id=0, mem_available_bytes=(64 << 30) + 1, guard_ns=args.guard_ns, launch_cost_ns=5_000,
+                     max_chunk_ns=0, max_inflight=32, time_steps=max(1, args.time_steps), event_log_capacity=1 << 18)
+    task = fr.SgdTask(U, I, E, rp, it, ra, P, Q, F, gamma, lam, iterations=1, max_runs=0, mem_limit_bytes=64 << 30, **model)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
+    t_end = time.time() + 60
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+        time.sleep(0.001)
+    ctx.fr_bubble_end()
+    kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
+    stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
+
+    def epochs(n, with_task):
+        return [stage.fr_stage_run_epoch(ctx if with_task else None) for _ in range(n)]
+
+    epochs(max(1, args.warmup), True)
+    torch.cuda.synchronize()
+    base_a = epochs((args.steps + 1) // 2, False)
+    epochs(1, True)
+    ctx.fr_event_log_clear()
+    p0 = ctx.fr_query_progress(tid)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with_task = epochs(args.steps, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    base_b = epochs(args.steps // 2 if args.steps > 1 else 1, False)
+    time.sleep(0.05)
+    events = ctx.fr_event_log(1 << 18)
+    p1 = ctx.fr_query_progress(tid)
+    ctx.fr_task_stop(tid)
+
+    ratings_done = p1.work_units_done - p0.work_units_done
+    bubble_ns = sum(e.bubble_ns for e in with_task)
+    timed, group = [], []
+    for e in events:
+        if e.kind != fr.FR_EV_CHUNK:
+            continue
+        if group and group[-1].bubble != e.bubble:
+            group = []
+        group.append(e)
+        if e.measured_ns > 0:
+            timed += group
+            group = []
+    step_ns = sum(e.measured_ns for e in timed)
+    timed_ratings = sum(e.work_units for e in timed)
+    # algorithmic bytes of one rating: its key and value (12 B), its item's row read and written (8 F), and its user's
+    # row read and written once per run of ratings of that user inside a cell
+    users = np.repeat(np.arange(U), np.diff(r.row_ptr))
+    runs = len(np.unique(users.astype(np.int64) * B + r.item // info.items_per_block))
+    bytes_per_rating = 12.0 + 8.0 * F + 8.0 * F * runs / E
+    gbs = timed_ratings * bytes_per_rating / step_ns if step_ns else 0.0
+    e_with = statistics.mean(x.epoch_ns for x in with_task)
+    e_without = statistics.mean(x.epoch_ns for x in base_a + base_b)
+    out = {
+        "metric": "side-task SGD updates harvested in bubbles", "value": ratings_done / bubble_ns * 1e3 if bubble_ns else 0.0,
+        "unit": "Mupdates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": (t1 - t0) * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg2 stage (1f1b p=4 m=8 stage=2, bf16 GEMM bursts); Graph SGD on rmat 2^%d users x items, %d ratings, F=%d, %d x %d cells"
+                   % (scale, E, F, B, B), "f_ms": f_ns / 1e6, "b_ms": b_ns / 1e6},
+        "mupdates_in_kernel": timed_ratings / step_ns * 1e3 if step_ns else 0.0,
+        "bubble_time_used": sum(e.measured_ns for e in events if e.kind == fr.FR_EV_CHUNK) / bubble_ns if bubble_ns else 0.0,
+        "stage_slowdown_pct": 100.0 * (e_with - e_without) / e_without,
+        "overruns": sum(x.overruns for x in with_task), "deadline_misses": p1.deadline_misses - p0.deadline_misses,
+        "iterations_completed": p1.runs_completed - p0.runs_completed,
+        "standalone_iteration_ms": ns / 1e6, "largest_cell": info.largest_cell,
+        "roofline": {"kernel": "k_sgd<%d>" % F, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_rating": bytes_per_rating,
+                     "note": "latency-bound: one sequential chain of updates per cell, %d cells side by side" % B},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import sgd as osgd
+        small = wl.rmat_ratings(16, 1 << 20, seed)
+        Ps, Qs = wl.initial_factors(small.n_users, small.n_items, F, seed)
+        t0 = time.perf_counter()
+        osgd.sgd(small.row_ptr, small.item, small.rating, Ps, Qs, gamma, lam, 4, 64)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 4 * small.n_ratings / dt / 1e6, "unit": "Mupdates/s", "cores": 1, "kind": "oracle",
+                               "sample": "fp64 oracle, 4 iterations over rmat 2^16 x 2^16, %d ratings, F=%d, 64 x 64 cells" % (small.n_ratings, F)}
+    task.fr_sgd_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    print(json.dumps(out), flush=True)
+    return 0
