@@ -31,6 +31,10 @@
 namespace {
 
 constexpr int kSgdBlock = 256;
+#ifndef FR_SGD_AHEAD
+#define FR_SGD_AHEAD 2
+#endif
+constexpr int kAhead = FR_SGD_AHEAD;             // ratings whose rows are in flight ahead of the one being worked on (>= 2)
 constexpr int kIdBits = 27;                      // users and items below 2^27, at most 1024 blocks
 constexpr uint64_t kIdMask = (1ull << kIdBits) - 1;
 constexpr int kStratumShift = 2 * kIdBits;
@@ -57,9 +61,13 @@ __device__ __forceinline__ uint32_t item_of(uint64_t key) { return (uint32_t)(ke
 // The update, with every rounding fixed:
 //     t_l = p_l * q_l;  in rounds w = 1, 2, 4, .., F/2: t_l = t_l + t_(l xor w)   (all lanes end with the same sum)
 //     e = r - t;  ge = gamma * e;  p_l' = fma(ge, q_l, fma(-gl, p_l, p_l));  q_l' = fma(ge, p_l, fma(-gl, q_l, q_l))
-// The next rating, and the factor rows it needs that are not in registers already, are asked for before the
-// current update is computed.  A row asked for early is never one the current update writes: the next rating's row
-// is either the same user's / item's (then the registers are kept) or another one.
+// A cell is one chain of dependent updates, so what it costs per rating is the latency of fetching the rating's
+// rows.  The loop therefore looks two ratings ahead (and three for the keys): while rating x - 2 is being worked
+// on, the rows of rating x are requested, unless they are held in registers by then (same user / same item as
+// rating x - 1) or could still be written before they are used: q of rating x may be requested early only if its
+// item differs from those of ratings x - 2 and x - 1; if it is the item of rating x - 2, the request waits until
+// that rating's row has been stored (a wavefront's own store and later load of one address stay in order).  Users
+// ascend inside a cell, so a row of P asked for early is never written in between.
 // (The product p_l * q_l has to be kept from being folded into the first addition of the tree as a fused
 // multiply-add: the rounded-operation intrinsics are plain operators to the compiler, so the product passes
 // through an empty asm statement, which hides where it came from.)
@@ -68,6 +76,38 @@ __device__ __forceinline__ float rounded_product(float x, float y)
     float t = x * y;
     asm("" : "+v"(t));
     return t;
+}
+
+// The tree sum over a group of F lanes (F = 16, 32, 64; groups aligned in the wavefront): t_l + t_(l xor 1), then
+// xor 2, 4, ... as defined above.  A butterfly with ds_bpermute costs an LDS round trip per round, which is most of
+// what a rating costs a cell's chain, so the rounds inside a row of 16 lanes use DPP moves instead: quad
+// permutations for xor 1 and 2; for xor 4 and 8 the half-row and row mirrors, which pair every lane with a lane of
+// the other half - not lane l xor 4 itself, but by then all lanes of a quad (of a half-row) hold the same value, so
+// the sums are the same numbers.  Rows are joined through readlane: row sums R_0 .. R_3, (R_0 + R_1) and
+// (R_2 + R_3), then their sum - the same tree.  (readlane ignores the execution mask; a group only uses its own
+// rows, whose lanes are all active together.)
+template <int kCtrl>
+__device__ __forceinline__ float add_dpp(float t)
+{
+    const int moved = __builtin_amdgcn_mov_dpp(__float_as_int(t), kCtrl, 0xf, 0xf, false);
+    return __fadd_rn(t, __int_as_float(moved));
+}
+
+template <int F>
+__device__ __forceinline__ float group_sum(float t)
+{
+    t = add_dpp<0xB1>(t);        // quad_perm [1, 0, 3, 2]
+    t = add_dpp<0x4E>(t);        // quad_perm [2, 3, 0, 1]
+    t = add_dpp<0x141>(t);       // row_half_mirror
+    t = add_dpp<0x140>(t);       // row_mirror
+    if constexpr (F == 16) return t;
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t), 48));
+    const float lo = __fadd_rn(r0, r1), hi = __fadd_rn(r2, r3);
+    if constexpr (F == 32) return (threadIdx.x & 32) ? hi : lo;
+    return __fadd_rn(lo, hi);
 }
 
 template <int F>
@@ -79,33 +119,66 @@ __global__ __launch_bounds__(kSgdBlock) void k_sgd(SgdArgs A, GateArg G, uint32_
         uint32_t e = A.cell_ptr[cell0 + g];
         const uint32_t e1 = A.cell_ptr[cell0 + g + 1];
         if (e < e1) {
-            uint64_t key = A.keys[e];
-            float r = A.rating[e];
-            uint32_t u = user_of(key), i = item_of(key);
-            float p = A.P[(size_t)u * F + l], q = A.Q[(size_t)i * F + l];
-            for (;;) {
-                const bool more = e + 1 < e1;
-                uint64_t nkey = key;
-                float nr = r;
-                if (more) { nkey = A.keys[e + 1]; nr = A.rating[e + 1]; }
-                const uint32_t nu = user_of(nkey), ni = item_of(nkey);
-                float np = p, nq = q;
-                if (more && nu != u) np = A.P[(size_t)nu * F + l];
-                if (more && ni != i) nq = A.Q[(size_t)ni * F + l];
-                float t = rounded_product(p, q);
+            const float* __restrict__ rating = A.rating;
+            const uint64_t* __restrict__ keys = A.keys;
+            // Slot k holds rating e + k: slot 0 is being worked on, the rows of slots 1 .. kAhead have been asked
+            // for, slot kAhead + 1 holds a key only.  Every iteration issues the same loads and stores whether
+            // their values are needed or not (behind the cell's end: those of its last rating again), so that the
+            // compiler can count what is in flight and waits only for the oldest request, not for all of them.
+            uint32_t us[kAhead + 2], is[kAhead + 2];
+            float rs[kAhead + 2], ps[kAhead + 1], qs[kAhead + 1];
+            bool late[kAhead + 1] = {};
 #pragma unroll
-                for (int w = 1; w < F; w <<= 1) t = __fadd_rn(t, __shfl_xor(t, w, 64));
-                const float ge = __fmul_rn(A.gamma, __fsub_rn(r, t));
+            for (int k = 0; k < kAhead + 2; ++k) {
+                const uint32_t ek = e + k < e1 ? e + k : e1 - 1;
+                const uint64_t key = keys[ek];
+                us[k] = user_of(key); is[k] = item_of(key); rs[k] = rating[ek];
+            }
+#pragma unroll
+            for (int k = 0; k < kAhead; ++k) {
+                ps[k] = A.P[(size_t)us[k] * F + l];
+                qs[k] = A.Q[(size_t)is[k] * F + l];
+                bool clash = false;
+#pragma unroll
+                for (int j = 0; j + 1 < k; ++j) clash |= is[k] == is[j];
+                late[k] = k >= 2 && is[k] != is[k - 1] && clash;
+            }
+            for (;;) {
+                // the rows of slot kAhead.  q may be used as it arrives if no rating before it in flight writes it:
+                // not the one just before it (then the registers are handed on) and none of the others (then the
+                // row is asked for again once they have stored theirs: late)
+                ps[kAhead] = A.P[(size_t)us[kAhead] * F + l];
+                qs[kAhead] = A.Q[(size_t)is[kAhead] * F + l];
+                {
+                    bool clash = false;
+#pragma unroll
+                    for (int j = 0; j + 1 < kAhead; ++j) clash |= is[kAhead] == is[j];
+                    late[kAhead] = is[kAhead] != is[kAhead - 1] && clash;
+                }
+                const uint32_t en = e + kAhead + 2 < e1 ? e + kAhead + 2 : e1 - 1;
+                const uint64_t keyn = keys[en];
+                const float rn = rating[en];
+                const float p = ps[0], q = qs[0];
+                const float t = group_sum<F>(rounded_product(p, q));
+                const float ge = __fmul_rn(A.gamma, __fsub_rn(rs[0], t));
                 const float p2 = __fmaf_rn(ge, q, __fmaf_rn(-A.gl, p, p));
                 const float q2 = __fmaf_rn(ge, p, __fmaf_rn(-A.gl, q, q));
-                if (!more) {
-                    A.P[(size_t)u * F + l] = p2;
-                    A.Q[(size_t)i * F + l] = q2;
-                    break;
-                }
-                if (nu != u) { A.P[(size_t)u * F + l] = p2; p = np; } else p = p2;
-                if (ni != i) { A.Q[(size_t)i * F + l] = q2; q = nq; } else q = q2;
-                u = nu; i = ni; r = nr; key = nkey; ++e;
+                A.P[(size_t)us[0] * F + l] = p2;
+                A.Q[(size_t)is[0] * F + l] = q2;
+                if (e + 1 >= e1) break;
+                if (us[1] == us[0]) ps[1] = p2;          // the same user / item again: its row is in registers
+                if (is[1] == is[0]) qs[1] = q2;
+                // every rating before slot 1 has stored its row by now: a late row can be asked for
+                const float again = A.Q[(size_t)is[2] * F + l];
+                if (late[2]) qs[2] = again;
+#pragma unroll
+                for (int k = 0; k < kAhead; ++k) { ps[k] = ps[k + 1]; qs[k] = qs[k + 1]; }
+#pragma unroll
+                for (int k = 1; k < kAhead; ++k) late[k] = k == 1 ? false : late[k + 1];
+#pragma unroll
+                for (int k = 0; k < kAhead + 1; ++k) { us[k] = us[k + 1]; is[k] = is[k + 1]; rs[k] = rs[k + 1]; }
+                us[kAhead + 1] = user_of(keyn); is[kAhead + 1] = item_of(keyn); rs[kAhead + 1] = rn;
+                ++e;
             }
         }
     }
