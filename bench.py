@@ -76,6 +76,7 @@ def main():
     ap.add_argument("--device-gate", type=int, default=0,
                     help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sgd-margin", type=float, default=1.08, help="--side-task sgd: final model = measured in-bubble step cost x this")
     ap.add_argument("--side-task", default="pagerank", choices=("pagerank", "sgd"),
                     help="sgd: the Graph SGD side task in the same stage's bubbles (a second line of its own, not the headline metric)")
     ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")

@@ -48,22 +48,57 @@ def run(args, stage_load, log):
     log("layout: %d x %d cells, largest %d ratings (mean %.1f); standalone iteration %.2f ms = %.1f us per stratum, %.2f us per rating of the largest cell" %
         (B, B, info.largest_cell, E / B / B, ns / 1e6, stratum_ns / 1e3, stratum_ns / 1e3 / max(1, info.largest_cell)))
     # the cells of a step run side by side: a step takes about a stratum's time whatever its number of cells (the
-    # floor), and the cells of a whole stratum add up to the same
+    # floor), and the cells of a whole stratum add up to the same.  (The task's chain term - cost by the step's largest
+    # cell - is left off: measured stratum times follow the largest cell only loosely, 47 - 117 us for largest cells of
+    # 100 - 247 ratings, and a model that swings with it overran more bubbles than one that charges every stratum the mean.)
     derate = 1.3
     model = dict(fs_per_rating=int(derate * stratum_ns * 1e6 / (E / B)), min_step_ns=int(derate * stratum_ns))
+    log("critical path of an iteration: %d ratings (%.1f per stratum) -> %.3f us per rating of a chain" %
+        (info.chain_ratings, info.chain_ratings / B, ns / 1e3 / info.chain_ratings))
     P.copy_(dev(P0)); Q.copy_(dev(Q0))
 
-    ctx = fr.Context(device_id=0, mem_available_bytes=(64 << 30) + 1, guard_ns=args.guard_ns, launch_cost_ns=5_000,
-                     max_chunk_ns=0, max_inflight=32, time_steps=max(1, args.time_steps), event_log_capacity=1 << 18)
-    task = fr.SgdTask(U, I, E, rp, it, ra, P, Q, F, gamma, lam, iterations=1, max_runs=0, mem_limit_bytes=64 << 30, **model)
-    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
-    ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
-    t_end = time.time() + 60
-    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
-        time.sleep(0.001)
-    ctx.fr_bubble_end()
     kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
     stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
+
+    def start_task(launch_cost_ns, model):
+        # (guard: a timing group of 16 strata can run 20 % over the model - 150 us - where PageRank's sweeps stay within 5 %)
+        ctx = fr.Context(device_id=0, mem_available_bytes=(64 << 30) + 1, guard_ns=max(args.guard_ns, 250_000), launch_cost_ns=launch_cost_ns,
+                         max_chunk_ns=0, max_inflight=32, time_steps=max(1, args.time_steps), event_log_capacity=1 << 18)
+        task = fr.SgdTask(U, I, E, rp, it, ra, P, Q, F, gamma, lam, iterations=1, max_runs=0, mem_limit_bytes=64 << 30, **model)
+        tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+        ctx.fr_bubble_begin(fr.fr_now_ns(), 5_000_000_000)          # a long first bubble for InitSideTask
+        t_end = time.time() + 60
+        while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+            time.sleep(0.001)
+        ctx.fr_bubble_end()
+        return ctx, task, tid
+
+    # second profiling pass, in place: what the steps cost inside real bubbles (launch gaps included) against what the
+    # derated standalone model says; the final model is the measured cost plus a margin
+    ctx, task, tid = start_task(5_000, model)
+    for _ in range(3):
+        stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.02)
+    ctx.fr_event_log_clear()
+    stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.02)
+    ratios, group = [], []
+    for e in ctx.fr_event_log(1 << 18):
+        if e.kind != fr.FR_EV_CHUNK:
+            group = []
+            continue
+        if group and group[-1].bubble != e.bubble:
+            group = []
+        group.append(e)
+        if e.measured_ns > 0:
+            ratios.append(e.measured_ns / sum(x.modelled_ns for x in group))
+            group = []
+    ctx.fr_task_stop(tid); task.fr_sgd_destroy(); ctx.fr_destroy()
+    in_bubble = statistics.quantiles(ratios, n=4)[2] if len(ratios) >= 4 else 1.0      # upper quartile: strata differ
+    log("in-bubble step cost = model x %.3f (%d timing groups of %d steps, min %.3f max %.3f)" %
+        (in_bubble, len(ratios), max(1, args.time_steps), min(ratios, default=1.0), max(ratios, default=1.0)))
+    model = {k: int(v * in_bubble * args.sgd_margin) for k, v in model.items()}
+    ctx, task, tid = start_task(0, model)
 
     def epochs(n, with_task):
         return [stage.fr_stage_run_epoch(ctx if with_task else None) for _ in range(n)]

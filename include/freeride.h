@@ -375,8 +375,10 @@ int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint
  * As a side task: one run = `iterations` iterations = iterations * blocks segments (a segment is a stratum, a
  * tile is a cell); the factors carry over from run to run.  work_units = ratings visited.
  * Modelled cost of a cell = ceil(ratings * fs_per_rating / 10^6) ns, at least 1; of a step =
- * max(sum over its cells, min_step_ns): the cells of a step run side by side, so a step of few cells takes about
- * as long as its longest cell.
+ * max(sum over its cells, min_step_ns, ceil(ratings of its largest cell * fs_per_chain_rating / 10^6)): the cells of
+ * a step run side by side, each a chain of dependent updates, so a step takes as long as its largest cell, and
+ * strata differ in that by a factor of two and more.  A step is the largest run of cells whose sum fits; if the
+ * chain term then does not fit, nothing is planned.
  */
 typedef struct fr_sgd_desc {
     int64_t  n_users;             /* U >= 1, below 2^27 - 1024                                              */
@@ -397,12 +399,15 @@ typedef struct fr_sgd_desc {
     uint64_t mem_limit_bytes;     /* the task's memory limit; caller buffers above are booked against it    */
     uint64_t fs_per_rating;       /* cost model, femtoseconds (0 = library default)                         */
     uint64_t min_step_ns;         /* shortest step, ns (0 = none)                                           */
+    uint64_t fs_per_chain_rating; /* femtoseconds per rating of a step's largest cell (0 = term not used)   */
 } fr_sgd_desc;
 
 typedef struct fr_sgd_info_t {
     uint32_t blocks;              /* B in use                                                               */
     uint32_t users_per_block, items_per_block;
     uint32_t largest_cell;        /* ratings in the largest cell                                            */
+    uint64_t chain_ratings;       /* sum over the strata of their largest cell: the critical path of one
+                                     iteration, in ratings                                                  */
     uint64_t bytes_resident;      /* booked after InitSideTask, caller buffers included                     */
     uint64_t bytes_peak;          /* highest booking during InitSideTask                                    */
 } fr_sgd_info_t;

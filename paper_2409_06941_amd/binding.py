@@ -91,12 +91,13 @@ class fr_sgd_desc(C.Structure):
                 ("item", C.c_void_p), ("rating", C.c_void_p), ("P", C.c_void_p), ("Q", C.c_void_p),
                 ("factors", C.c_int32), ("blocks", C.c_int32), ("gamma", C.c_float), ("lam", C.c_float),
                 ("iterations", C.c_int32), ("max_runs", C.c_int32), ("mem_limit_bytes", C.c_uint64),
-                ("fs_per_rating", C.c_uint64), ("min_step_ns", C.c_uint64)]
+                ("fs_per_rating", C.c_uint64), ("min_step_ns", C.c_uint64), ("fs_per_chain_rating", C.c_uint64)]
 
 
 class fr_sgd_info_t(C.Structure):
     _fields_ = [("blocks", C.c_uint32), ("users_per_block", C.c_uint32), ("items_per_block", C.c_uint32),
-                ("largest_cell", C.c_uint32), ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
+                ("largest_cell", C.c_uint32), ("chain_ratings", C.c_uint64), ("bytes_resident", C.c_uint64),
+                ("bytes_peak", C.c_uint64)]
 
 
 class fr_load_desc(C.Structure):
@@ -368,13 +369,13 @@ class SgdTask:
     """fr_sgd_make and friends.  Tensors (torch, on the GPU) are only read for their data_ptr."""
 
     def __init__(self, n_users, n_items, n_ratings, row_ptr, item, rating, P, Q, factors, gamma, lam, iterations=1,
-                 blocks=0, max_runs=0, mem_limit_bytes=1 << 40, fs_per_rating=0, min_step_ns=0):
+                 blocks=0, max_runs=0, mem_limit_bytes=1 << 40, fs_per_rating=0, min_step_ns=0, fs_per_chain_rating=0):
         d = fr_sgd_desc()
         d.n_users, d.n_items, d.n_ratings = n_users, n_items, n_ratings
         d.row_ptr, d.item, d.rating, d.P, d.Q = _ptr(row_ptr), _ptr(item), _ptr(rating), _ptr(P), _ptr(Q)
         d.factors, d.blocks, d.gamma, d.lam = factors, blocks, gamma, lam
         d.iterations, d.max_runs, d.mem_limit_bytes = iterations, max_runs, mem_limit_bytes
-        d.fs_per_rating, d.min_step_ns = fs_per_rating, min_step_ns
+        d.fs_per_rating, d.min_step_ns, d.fs_per_chain_rating = fs_per_rating, min_step_ns, fs_per_chain_rating
         self.desc = d
         self._keep = (row_ptr, item, rating, P, Q)
         self.ops = fr_task_ops()

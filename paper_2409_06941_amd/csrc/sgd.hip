@@ -251,6 +251,7 @@ struct SgdTask {
     std::vector<uint32_t> cells;          // host copy of cell_ptr
     std::vector<uint64_t> prefix;         // cumulative modelled cost of the cells, in the order of cell_ptr
     uint32_t max_cell = 0;
+    uint64_t chain_ratings = 0;           // sum over the strata of their largest cell
     uint64_t footprint_after = 0, footprint_peak = 0;
     SgdArgs args{};
     bool inited = false, registered = false;
@@ -337,10 +338,14 @@ int sgd_init(void* user, fr_alloc* a, void* stream_v)
     if (p->cells[0] != 0 || p->cells[(size_t)B * B] != (uint32_t)E) return FR_ERR_ARG;
     p->prefix.assign((size_t)B * B + 1, 0);
     p->max_cell = 0;
+    p->chain_ratings = 0;
+    uint32_t stratum_max = 0;
     for (size_t c = 0; c < (size_t)B * B; ++c) {
         if (p->cells[c + 1] < p->cells[c]) return FR_ERR_ARG;
         const uint32_t len = p->cells[c + 1] - p->cells[c];
         p->max_cell = std::max(p->max_cell, len);
+        stratum_max = std::max(stratum_max, len);
+        if ((c + 1) % B == 0) { p->chain_ratings += stratum_max; stratum_max = 0; }
         p->prefix[c + 1] = p->prefix[c] + ceil_fs_to_ns((unsigned __int128)len * p->d.fs_per_rating);
     }
     SgdArgs& A = p->args;
@@ -373,9 +378,16 @@ int sgd_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* o
     int rc = fr_chunk_fit(pre, p->B, p->tile, budget_ns, launch_cost_ns, &n);
     if (rc != FR_OK) return rc;
     if (n == 0) return FR_OK;
-    out->tile1 = p->tile + n;
-    out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     const uint32_t c0 = (p->seg % p->B) * p->B;
+    uint64_t cost = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
+    if (p->d.fs_per_chain_rating) {
+        uint32_t longest = 0;
+        for (uint32_t t = p->tile; t < p->tile + n; ++t) longest = std::max(longest, p->cells[c0 + t + 1] - p->cells[c0 + t]);
+        cost = std::max(cost, ceil_fs_to_ns((unsigned __int128)longest * p->d.fs_per_chain_rating));
+        if (cost > budget_ns || launch_cost_ns > budget_ns - cost) return FR_OK;     // the chain does not fit
+    }
+    out->tile1 = p->tile + n;
+    out->modelled_ns = cost;
     out->work_units = p->cells[c0 + out->tile1] - p->cells[c0 + p->tile];
     out->completes_run = (p->seg + 1 == p->n_segments() && out->tile1 == p->B) ? 1 : 0;
     return FR_OK;
@@ -475,6 +487,7 @@ int fr_sgd_info(void* user, fr_sgd_info_t* out)
     out->users_per_block = p->ub;
     out->items_per_block = p->ib;
     out->largest_cell = p->max_cell;
+    out->chain_ratings = p->chain_ratings;
     out->bytes_resident = p->footprint_after;
     out->bytes_peak = p->footprint_peak;
     return FR_OK;

@@ -132,19 +132,23 @@ def test_harvested_in_bubbles_gives_the_standalone_bits():
     Pr, Qr = _dev(P0), _dev(Q0)
     t_ref = _task(r, Pr, Qr, F, gamma, lam, K, B)
     ns = [t_ref.fr_sgd_run_standalone(0, torch.cuda.current_stream(), want_ns=True) for _ in range(runs)]
+    info = t_ref.fr_sgd_info()
+    sizes = [t_ref.fr_sgd_cell_sizes(s) for s in range(B)]
+    assert info.chain_ratings == sum(max(row) for row in sizes)
     t_ref.fr_sgd_destroy()
     # cost model from the measured run: the cells of a stratum run side by side, so a step of any number of them takes
     # about a stratum's time (the floor), and a whole stratum's cells add up to the same
     stratum_ns = min(ns) / (K * B)
-    fs_per_rating = int(1.5 * stratum_ns * 1e6 / (r.n_ratings / B))
-    floor_ns = int(1.5 * stratum_ns) + 10_000
+    fs_per_rating = int(0.5 * stratum_ns * 1e6 / (r.n_ratings / B))
+    fs_chain = int(1.5 * min(ns) * 1e6 / info.chain_ratings)                 # a step takes as long as its largest cell
+    floor_ns = int(0.75 * stratum_ns) + 10_000
     print("stratum %.1f us, %.2f us per rating of a cell" % (stratum_ns / 1e3, stratum_ns / 1e3 / (r.n_ratings / B / B)), flush=True)
 
     P, Q = _dev(P0), _dev(Q0)
     ctx = fr.Context(device_id=0, guard_ns=200_000, launch_cost_ns=20_000, max_chunk_ns=0, time_steps=1,
                      mem_available_bytes=1 << 40)
     task = _task(r, P, Q, F, gamma, lam, K, B, max_runs=runs, mem_limit_bytes=1 << 30, fs_per_rating=fs_per_rating,
-                 min_step_ns=floor_ns)
+                 min_step_ns=floor_ns, fs_per_chain_rating=fs_chain)
     tid = ctx.fr_task_register(task.ops, task.user, task.profile)
     import time
     ctx.fr_bubble_begin(fr.fr_now_ns(), 2_000_000_000)
@@ -172,4 +176,9 @@ def test_harvested_in_bubbles_gives_the_standalone_bits():
     chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
     assert sum(e.work_units for e in chunks) == runs * K * r.n_ratings == pr.work_units_done
     assert len(chunks) >= runs * K * B                         # a step never spans two strata
+    ceil_ns = lambda fs: max(1, -(-fs // 10**6))
+    for e in chunks:                                           # the documented cost rule, on every step of the log
+        row = sizes[e.segment % B][e.tile0:e.tile1]
+        want = max(sum(ceil_ns(n * fs_per_rating) for n in row), floor_ns, ceil_ns(max(row) * fs_chain))
+        assert e.modelled_ns == want + 20_000 and e.work_units == sum(row)
     assert _same_bits(got_P, Pr.cpu().numpy()) and _same_bits(got_Q, Qr.cpu().numpy())
