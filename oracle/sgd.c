@@ -18,8 +18,11 @@
  *
  * Order of the updates (the paper is silent; a parallel machine needs one that does not
  * depend on timing).  Stratified SGD (Gemulla, Nijkamp, Haas, Sismanis 2011): users and
- * items are cut into B blocks of consecutive ids (ceil(U / B) users, ceil(I / B) items a
- * block); the ratings of user block a and item block b form cell (a, b).  One iteration
+ * items are cut into B blocks of consecutive ids holding about E / B ratings each - user
+ * block k begins at the first user with ceil(k E / B) or more ratings before it, item
+ * block k at the first item with that many ratings of smaller items, block 0 at id 0 (a
+ * block may be empty) - and the ratings of user block a and item block b form cell (a, b).
+ * One iteration
  * is B strata; stratum s holds the cells (a, (a + s) mod B), a = 0 .. B - 1, no two of
  * which share a user or an item.  Here the cells of a stratum are taken in order of a,
  * and inside a cell the ratings by user and then by item; since the cells of a stratum
@@ -40,7 +43,8 @@
  *
  * Pinned by tests: a hand-worked update, the gradient of the objective by finite
  * differences, exact low-rank ratings as a fixed point, the visiting order against a
- * brute-force enumeration, and fp32 against fp64.
+ * brute-force enumeration with block starts computed independently, and fp32 against
+ * fp64.
  */
 #include <math.h>
 #include <stdint.h>
@@ -51,17 +55,48 @@
    CSR must ascend. */
 typedef void (*visit_fn)(void* ctx, int64_t u, int64_t e);
 
+/* starts[k], k = 0 .. B: first id of block k; before[x] = ratings of the ids below x, x = 0 .. n. */
+static void block_starts(int64_t n, const int64_t* before, int64_t E, int32_t B, int64_t* starts)
+{
+    int64_t x = 0;
+    starts[0] = 0;
+    for (int32_t k = 1; k < B; ++k) {
+        const int64_t want = ((int64_t)k * E + B - 1) / B;
+        while (x < n && before[x] < want) ++x;
+        starts[k] = x;
+    }
+    starts[B] = n;
+}
+
+static int make_blocks(int64_t U, int64_t I, const int32_t* row_ptr, const int32_t* item, int32_t B, int64_t* ustart,
+                       int64_t* istart)
+{
+    const int64_t E = row_ptr[U];
+    int64_t* before = (int64_t*)calloc((size_t)((U > I ? U : I) + 2), sizeof(int64_t));
+    if (!before) return -3;
+    for (int64_t u = 0; u <= U; ++u) before[u] = row_ptr[u];
+    block_starts(U, before, E, B, ustart);
+    for (int64_t i = 0; i <= I; ++i) before[i] = 0;
+    for (int64_t e = 0; e < E; ++e) before[item[e] + 1]++;
+    for (int64_t i = 0; i < I; ++i) before[i + 1] += before[i];
+    block_starts(I, before, E, B, istart);
+    free(before);
+    return 0;
+}
+
 static int for_each_rating(int64_t U, int64_t I, const int32_t* row_ptr, const int32_t* item, int32_t B, visit_fn visit,
                            void* ctx)
 {
     if (U < 1 || I < 1 || B < 1) return -1;
-    const int64_t ub = (U + B - 1) / B, ib = (I + B - 1) / B;
+    int64_t* ustart = (int64_t*)malloc(sizeof(int64_t) * 2 * ((size_t)B + 1));
+    if (!ustart) return -3;
+    int64_t* istart = ustart + B + 1;
+    if (make_blocks(U, I, row_ptr, item, B, ustart, istart) != 0) { free(ustart); return -3; }
     for (int32_t s = 0; s < B; ++s) {
         for (int32_t a = 0; a < B; ++a) {
             const int32_t b = (int32_t)(((int64_t)a + s) % B);
-            const int64_t u0 = (int64_t)a * ub, u1 = (u0 + ub < U) ? u0 + ub : U;
-            const int64_t i0 = (int64_t)b * ib, i1 = (i0 + ib < I) ? i0 + ib : I;
-            for (int64_t u = u0; u < u1; ++u) {
+            const int64_t i0 = istart[b], i1 = istart[b + 1];
+            for (int64_t u = ustart[a]; u < ustart[a + 1]; ++u) {
                 int64_t lo = row_ptr[u], hi = row_ptr[u + 1];       /* first rating of the row with item >= i0 */
                 while (lo < hi) {
                     const int64_t mid = (lo + hi) / 2;
@@ -72,7 +107,16 @@ static int for_each_rating(int64_t U, int64_t I, const int32_t* row_ptr, const i
             }
         }
     }
+    free(ustart);
     return 0;
+}
+
+/* ---- the blocks alone (for the tests) ---- */
+int oracle_sgd_blocks(int64_t U, int64_t I, const int32_t* row_ptr, const int32_t* item, int32_t B, int64_t* ustart,
+                      int64_t* istart)
+{
+    if (U < 1 || I < 1 || B < 1) return -1;
+    return make_blocks(U, I, row_ptr, item, B, ustart, istart);
 }
 
 /* ---- the order alone (for the tests of the order) ---- */

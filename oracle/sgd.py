@@ -27,6 +27,9 @@ def _load():
         L = ctypes.CDLL(build())
         i32p, f32p, f64p = (ctypes.POINTER(t) for t in (ctypes.c_int32, ctypes.c_float, ctypes.c_double))
         L.oracle_sgd_order.argtypes = [ctypes.c_int64, ctypes.c_int64, i32p, i32p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)]
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        L.oracle_sgd_blocks.argtypes = [ctypes.c_int64, ctypes.c_int64, i32p, i32p, ctypes.c_int32, i64p, i64p]
+        L.oracle_sgd_blocks.restype = ctypes.c_int
         L.oracle_sgd_fp64.argtypes = [ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p, ctypes.c_int32, ctypes.c_double,
                                       ctypes.c_double, ctypes.c_int32, ctypes.c_int32, f64p, f64p]
         L.oracle_sgd_fp32_ordered.argtypes = [ctypes.c_int64, ctypes.c_int64, i32p, i32p, f32p, ctypes.c_int32,
@@ -61,6 +64,17 @@ def order(row_ptr, item, n_items: int, blocks: int):
     if rc != 0:
         raise RuntimeError("oracle_sgd_order failed: %d" % rc)
     return out
+
+
+def blocks(row_ptr, item, n_items: int, n_blocks: int):
+    """First ids of the user blocks and of the item blocks (n_blocks + 1 entries each)."""
+    row_ptr, item, _ = _csr(row_ptr, item, np.zeros(len(item), np.float32), n_items)
+    us, is_ = np.empty(n_blocks + 1, np.int64), np.empty(n_blocks + 1, np.int64)
+    rc = _load().oracle_sgd_blocks(row_ptr.shape[0] - 1, n_items, _ptr(row_ptr, ctypes.c_int32), _ptr(item, ctypes.c_int32),
+                                   n_blocks, _ptr(us, ctypes.c_int64), _ptr(is_, ctypes.c_int64))
+    if rc != 0:
+        raise RuntimeError("oracle_sgd_blocks failed: %d" % rc)
+    return us, is_
 
 
 def sgd(row_ptr, item, rating, P0, Q0, gamma: float, lam: float, iterations: int, blocks: int, ordered_fp32: bool = False):

@@ -57,15 +57,25 @@ def test_exact_low_rank_ratings_are_a_fixed_point_without_regularisation():
     assert np.abs(P - A).max() > 1e-3                                      # with lambda > 0 the factors shrink
 
 
+def _block_starts(rp, it, U, I, B):
+    """Block k begins at the first id with ceil(k E / B) ratings or more before it (numpy, independent of the C code)."""
+    E = int(rp[U])
+    want = [-(-k * E // B) for k in range(1, B)]
+    before_item = np.concatenate([[0], np.cumsum(np.bincount(it, minlength=I))])
+    us = [0] + [int(np.searchsorted(rp, w, side="left")) for w in want] + [U]
+    is_ = [0] + [int(np.searchsorted(before_item, w, side="left")) for w in want] + [I]
+    return us, is_
+
+
 def _brute_order(rp, it, U, I, B):
-    ub, ib = -(-U // B), -(-I // B)
+    us, is_ = _block_starts(rp, it, U, I, B)
     out = []
     for s in range(B):
         for a in range(B):
             b = (a + s) % B
-            for u in range(a * ub, min(U, (a + 1) * ub)):
+            for u in range(us[a], us[a + 1]):
                 for e in range(rp[u], rp[u + 1]):
-                    if b * ib <= it[e] < min(I, (b + 1) * ib):
+                    if is_[b] <= it[e] < is_[b + 1]:
                         out.append(e)
     return out
 
@@ -76,15 +86,31 @@ def test_order_is_the_stratified_one(B):
     got = osgd.order(r.row_ptr, r.item, r.n_items, B)
     assert sorted(got) == list(range(r.n_ratings))                         # every rating once per iteration
     assert list(got) == _brute_order(r.row_ptr, r.item, r.n_users, r.n_items, B)
+    us, is_ = _block_starts(r.row_ptr, r.item, r.n_users, r.n_items, B)
+    ous, ois = osgd.blocks(r.row_ptr, r.item, r.n_items, B)
+    assert list(ous) == us and list(ois) == is_
     # the cells of one stratum share neither a user block nor an item block
     users = np.repeat(np.arange(r.n_users), np.diff(r.row_ptr))
-    ub, ib = -(-r.n_users // B), -(-r.n_items // B)
-    a, b = users[got] // ub, r.item[got] // ib
+    a = np.searchsorted(np.array(us[1:B]), users[got], side="right")
+    b = np.searchsorted(np.array(is_[1:B]), r.item[got], side="right")
     s = (b - a) % B
     assert np.all(np.diff(s) >= 0)                                         # strata in order
     for k in range(B):
         cells = set(zip(a[s == k], b[s == k]))
         assert len({x for x, _ in cells}) == len(cells) == len({y for _, y in cells})
+
+
+def test_blocks_hold_about_the_same_number_of_ratings():
+    r = wl.rmat_ratings(10, 1 << 15, seed=5)
+    B = 16
+    us, is_ = osgd.blocks(r.row_ptr, r.item, r.n_items, B)
+    per_user_block = np.diff(r.row_ptr[us])
+    per_item_block = np.diff(np.concatenate([[0], np.cumsum(np.bincount(r.item, minlength=r.n_items))])[is_])
+    share = r.n_ratings / B
+    assert per_user_block.sum() == per_item_block.sum() == r.n_ratings
+    assert per_user_block.max() <= share + np.diff(r.row_ptr).max()        # a block overshoots by less than one row
+    assert per_item_block.max() <= share + np.bincount(r.item).max()
+    assert per_user_block.max() < 1.5 * share and per_item_block.max() < 1.5 * share   # on this graph: well balanced
 
 
 def test_with_one_block_the_order_is_plain_row_order_and_matches_a_python_loop():
