@@ -43,6 +43,7 @@ def run(args, stage_load, log):
     ns = min(probe.fr_sgd_run_standalone(0, probe_ctx.fr_side_stream(), want_ns=True) for _ in range(2))
     info = probe.fr_sgd_info()
     B = info.blocks
+    item_starts = probe.fr_sgd_block_starts(1)
     probe.fr_sgd_destroy(); probe_ctx.fr_destroy()
     stratum_ns = ns / B
     log("layout: %d x %d cells, largest %d ratings (mean %.1f); standalone iteration %.2f ms = %.1f us per stratum, %.2f us per rating of the largest cell" %
@@ -137,7 +138,7 @@ def run(args, stage_load, log):
     # algorithmic bytes of one rating: its key and value (12 B), its item's row read and written (8 F), and its user's
     # row read and written once per run of ratings of that user inside a cell
     users = np.repeat(np.arange(U), np.diff(r.row_ptr))
-    runs = len(np.unique(users.astype(np.int64) * B + r.item // info.items_per_block))
+    runs = len(np.unique(users.astype(np.int64) * B + np.searchsorted(np.array(item_starts[1:B]), r.item, side="right")))
     bytes_per_rating = 12.0 + 8.0 * F + 8.0 * F * runs / E
     gbs = timed_ratings * bytes_per_rating / step_ns if step_ns else 0.0
     e_with = statistics.mean(x.epoch_ns for x in with_task)

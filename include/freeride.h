@@ -365,8 +365,9 @@ int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint
  * Section 6.1.4 (one iteration = one pass over the graph, Section 6.2).  The paper names the method only; the
  * arithmetic is the textbook one (Koren, Bell, Volinsky 2009), for every rating r_ui, one after the other,
  *     e = r_ui - <p_u, q_i>,   p_u += gamma (e q_i - lambda p_u),   q_i += gamma (e p_u - lambda q_i),
- * and the order is stratified (Gemulla et al. 2011): users and items in `blocks` blocks of ceil(n / blocks)
- * consecutive ids; cell (a, b) = ratings of user block a and item block b; an iteration = `blocks` strata, stratum
+ * and the order is stratified (Gemulla et al. 2011): users and items in `blocks` blocks of consecutive ids holding
+ * about E / blocks ratings each (block k begins at the first id with ceil(k E / blocks) or more ratings before it;
+ * a block may be empty); cell (a, b) = ratings of user block a and item block b; an iteration = `blocks` strata, stratum
  * s = cells (a, (a + s) mod blocks), which share no factor row and run side by side; inside a cell by user, then
  * by item.  All roundings of an update are fixed: t_l = p_l * q_l; in rounds w = 1, 2, 4, .. t_l += t_(l xor w);
  * e = r - t; ge = gamma * e; gl = gamma * lambda; p_l' = fma(ge, q_l, fma(-gl, p_l, p_l)); q_l' likewise from the
@@ -404,7 +405,7 @@ typedef struct fr_sgd_desc {
 
 typedef struct fr_sgd_info_t {
     uint32_t blocks;              /* B in use                                                               */
-    uint32_t users_per_block, items_per_block;
+    uint32_t reserved[2];
     uint32_t largest_cell;        /* ratings in the largest cell                                            */
     uint64_t chain_ratings;       /* sum over the strata of their largest cell: the critical path of one
                                      iteration, in ratings                                                  */
@@ -418,6 +419,8 @@ int fr_sgd_make(const fr_sgd_desc* d, fr_task_ops* ops_out, void** user_out, fr_
 int fr_sgd_destroy(void* user);
 /* The two calls below need the layout: FR_ERR_STATE until InitSideTask has run. */
 int fr_sgd_info(void* user, fr_sgd_info_t* out);
+/* First ids of the user blocks (items = 0) or item blocks (items = 1): B + 1 entries; *n_out = B + 1. */
+int fr_sgd_block_starts(void* user, int32_t items, uint32_t* starts_host, size_t cap, size_t* n_out);
 /* Ratings in the cells (a, (a + stratum) mod B), a = 0 .. B - 1; *n_out = B. */
 int fr_sgd_cell_sizes(void* user, uint32_t stratum, uint32_t* sizes_host, size_t cap, size_t* n_out);
 /*

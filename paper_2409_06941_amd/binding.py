@@ -95,7 +95,7 @@ class fr_sgd_desc(C.Structure):
 
 
 class fr_sgd_info_t(C.Structure):
-    _fields_ = [("blocks", C.c_uint32), ("users_per_block", C.c_uint32), ("items_per_block", C.c_uint32),
+    _fields_ = [("blocks", C.c_uint32), ("reserved", C.c_uint32 * 2),
                 ("largest_cell", C.c_uint32), ("chain_ratings", C.c_uint64), ("bytes_resident", C.c_uint64),
                 ("bytes_peak", C.c_uint64)]
 
@@ -154,6 +154,7 @@ SIGNATURES = {
     "fr_sgd_make": (C.c_int, [C.POINTER(fr_sgd_desc), C.POINTER(fr_task_ops), C.POINTER(C.c_void_p), C.POINTER(fr_task_profile)]),
     "fr_sgd_destroy": (C.c_int, [C.c_void_p]),
     "fr_sgd_info": (C.c_int, [C.c_void_p, C.POINTER(fr_sgd_info_t)]),
+    "fr_sgd_block_starts": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_sgd_cell_sizes": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_sgd_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
     "fr_load_workspace_bytes": (C.c_int, [C.POINTER(fr_load_desc), C.POINTER(C.c_uint64)]),
@@ -392,6 +393,13 @@ class SgdTask:
         out = fr_sgd_info_t()
         _check(lib().fr_sgd_info(self.user, C.byref(out)), "fr_sgd_info")
         return out
+
+    def fr_sgd_block_starts(self, items):
+        n = self.fr_sgd_info().blocks + 1
+        buf = (C.c_uint32 * n)()
+        got = C.c_size_t()
+        _check(lib().fr_sgd_block_starts(self.user, 1 if items else 0, buf, n, C.byref(got)), "fr_sgd_block_starts")
+        return list(buf)
 
     def fr_sgd_cell_sizes(self, stratum):
         n = self.fr_sgd_info().blocks

@@ -5,7 +5,8 @@
 // rating r_ui, one after the other,
 //     e = r_ui - <p_u, q_i>,   p_u += gamma (e q_i - lambda p_u),   q_i += gamma (e p_u - lambda q_i)
 // and the order of the updates is a stratified one (Gemulla et al. 2011), which a GPU can follow without races and
-// without depending on timing: users and items are cut into B blocks of consecutive ids; the ratings of user block a
+// without depending on timing: users and items are cut into B blocks of consecutive ids holding about E / B ratings
+// each (block k begins at the first id with ceil(k E / B) or more ratings before it); the ratings of user block a
 // and item block b are cell (a, b); an iteration is B strata, stratum s = the cells (a, (a + s) mod B), which share
 // no user and no item and therefore run side by side; inside a cell the ratings are taken by user, then by item,
 // one after the other.  Every rounding of an update is fixed (see k_sgd), so the factors do not depend on how the
@@ -200,9 +201,52 @@ __global__ __launch_bounds__(256) void k_sgd_validate(int64_t U, int64_t I, int6
         if (item[e] < 0 || item[e] >= I) *bad = 1;
 }
 
+// The block of id x: the last k below B with starts[k] <= x (empty blocks share their start with the next one).
+__device__ __forceinline__ uint32_t block_of(const uint32_t* __restrict__ starts, uint32_t B, uint32_t x)
+{
+    uint32_t lo = 0, hi = B - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) / 2;
+        if (starts[mid] <= x) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void k_sgd_zero(uint32_t* p, uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void k_sgd_count_items(int64_t E, const int32_t* __restrict__ item, uint32_t* count)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < E) atomicAdd(&count[item[e]], 1u);
+}
+
+// starts[k], k = 0 .. B: block k begins at the first id x with before[x] >= ceil(k E / B); before[x] = ratings of the
+// ids below x (n + 1 entries, int32 or uint32: the values are below 2^31 either way).
+__global__ __launch_bounds__(256) void k_sgd_starts(uint32_t n, const uint32_t* __restrict__ before, int64_t E, uint32_t B,
+                                                    uint32_t* __restrict__ starts)
+{
+    const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k > B) return;
+    if (k == 0 || k == B) { starts[k] = k == 0 ? 0u : n; return; }
+    const uint64_t want = ((uint64_t)k * (uint64_t)E + B - 1) / B;
+    uint32_t lo = 0, hi = n;                    // first x with before[x] >= want (before[n] = E >= want)
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if ((uint64_t)before[mid] < want) lo = mid + 1;
+        else hi = mid;
+    }
+    starts[k] = lo;
+}
+
 // key of rating e; its user is found by bisection of row_ptr.  Also checks that items ascend inside a row.
 __global__ __launch_bounds__(256) void k_sgd_keys(int64_t U, int64_t E, const int32_t* __restrict__ row_ptr,
-                                                  const int32_t* __restrict__ item, uint32_t B, uint32_t ub, uint32_t ib,
+                                                  const int32_t* __restrict__ item, uint32_t B,
+                                                  const uint32_t* __restrict__ ustart, const uint32_t* __restrict__ istart,
                                                   uint64_t* __restrict__ keys, int32_t* bad)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -215,18 +259,18 @@ __global__ __launch_bounds__(256) void k_sgd_keys(int64_t U, int64_t E, const in
     }
     const uint32_t u = (uint32_t)lo, i = (uint32_t)item[e];
     if (e > row_ptr[u] && item[e - 1] >= item[e]) *bad = 1;
-    const uint32_t a = u / ub, b = i / ib;
+    const uint32_t a = block_of(ustart, B, u), b = block_of(istart, B, i);
     const uint32_t s = (b + B - a) % B;
     keys[e] = ((uint64_t)s << kStratumShift) | ((uint64_t)u << kIdBits) | i;
 }
 
-__global__ __launch_bounds__(256) void k_sgd_cells(int64_t E, uint32_t B, uint32_t ub, const uint64_t* __restrict__ keys,
-                                                   uint32_t* __restrict__ cell_ptr)
+__global__ __launch_bounds__(256) void k_sgd_cells(int64_t E, uint32_t B, const uint32_t* __restrict__ ustart,
+                                                   const uint64_t* __restrict__ keys, uint32_t* __restrict__ cell_ptr)
 {
     const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c > B * B) return;
     const uint64_t s = c / B, a = c % B;
-    const uint64_t want = c == B * B ? ~0ull : (s << kStratumShift) | ((a * ub) << kIdBits);
+    const uint64_t want = c == B * B ? ~0ull : (s << kStratumShift) | ((uint64_t)ustart[a] << kIdBits);
     int64_t lo = 0, hi = E;                     // first rating with key >= want
     while (lo < hi) {
         const int64_t mid = (lo + hi) / 2;
@@ -244,7 +288,9 @@ uint64_t ceil_fs_to_ns(unsigned __int128 fs)
 
 struct SgdTask {
     fr_sgd_desc d{};
-    uint32_t B = 0, ub = 0, ib = 0;
+    uint32_t B = 0;
+    uint32_t *ustart = nullptr, *istart = nullptr;      // device, B + 1 entries each
+    std::vector<uint32_t> ustart_host, istart_host;
     uint64_t* keys = nullptr;
     float* rating = nullptr;
     uint32_t* cell_ptr = nullptr;
@@ -290,8 +336,6 @@ int sgd_init(void* user, fr_alloc* a, void* stream_v)
     const uint64_t caller = 4ull * (uint64_t)(U + 1) + 8ull * (uint64_t)E + 4ull * (uint64_t)F * (uint64_t)(U + I);
     if (fr_alloc_charge(a, caller) != FR_OK) return FR_ERR_OOM;
     const uint32_t B = p->B;
-    p->ub = (uint32_t)((U + B - 1) / B);
-    p->ib = (uint32_t)((I + B - 1) / B);
 
     int32_t* bad = static_cast<int32_t*>(fr_alloc_device(a, sizeof(int32_t)));
     SGD_NEED(bad);
@@ -303,6 +347,31 @@ int sgd_init(void* user, fr_alloc* a, void* stream_v)
     SGD_HIP(hipStreamSynchronize(stream));
     if (bad_host) return FR_ERR_ARG;          // (indices are only trusted from here on)
 
+    // ---- blocks of about E / B ratings
+    p->ustart = static_cast<uint32_t*>(fr_alloc_device(a, ((uint64_t)B + 1) * 4));
+    p->istart = static_cast<uint32_t*>(fr_alloc_device(a, ((uint64_t)B + 1) * 4));
+    SGD_NEED(p->ustart); SGD_NEED(p->istart);
+    {
+        uint32_t* count = static_cast<uint32_t*>(fr_alloc_device(a, ((uint64_t)I + 1) * 4));
+        uint32_t* before = static_cast<uint32_t*>(fr_alloc_device(a, ((uint64_t)I + 1) * 4));
+        SGD_NEED(count); SGD_NEED(before);
+        hipLaunchKernelGGL(k_sgd_zero, dim3((unsigned)((I + 1 + 255) / 256)), dim3(256), 0, stream, count, (uint64_t)I + 1);
+        if (E > 0) hipLaunchKernelGGL(k_sgd_count_items, dim3((unsigned)((E + 255) / 256)), dim3(256), 0, stream, E, p->d.item, count);
+        size_t bytes = 0;
+        SGD_HIP(rocprim::exclusive_scan(nullptr, bytes, count, before, 0u, (size_t)I + 1, rocprim::plus<uint32_t>(), stream));
+        void* tmp = fr_alloc_device(a, bytes ? bytes : 1);
+        SGD_NEED(tmp);
+        SGD_HIP(rocprim::exclusive_scan(tmp, bytes, count, before, 0u, (size_t)I + 1, rocprim::plus<uint32_t>(), stream));
+        hipLaunchKernelGGL(k_sgd_starts, dim3((B + 1 + 255) / 256), dim3(256), 0, stream, (uint32_t)I, before, E, B, p->istart);
+        hipLaunchKernelGGL(k_sgd_starts, dim3((B + 1 + 255) / 256), dim3(256), 0, stream, (uint32_t)U,
+                           reinterpret_cast<const uint32_t*>(p->d.row_ptr), E, B, p->ustart);
+        p->ustart_host.assign((size_t)B + 1, 0); p->istart_host.assign((size_t)B + 1, 0);
+        SGD_HIP(hipMemcpyAsync(p->ustart_host.data(), p->ustart, ((size_t)B + 1) * 4, hipMemcpyDeviceToHost, stream));
+        SGD_HIP(hipMemcpyAsync(p->istart_host.data(), p->istart, ((size_t)B + 1) * 4, hipMemcpyDeviceToHost, stream));
+        SGD_HIP(hipStreamSynchronize(stream));
+        (void)fr_alloc_free(a, tmp); (void)fr_alloc_free(a, before); (void)fr_alloc_free(a, count);
+    }
+
     const uint64_t n = (uint64_t)(E ? E : 1);
     uint64_t* keys_a = static_cast<uint64_t*>(fr_alloc_device(a, n * 8));
     uint64_t* keys_b = static_cast<uint64_t*>(fr_alloc_device(a, n * 8));
@@ -312,7 +381,7 @@ int sgd_init(void* user, fr_alloc* a, void* stream_v)
     SGD_NEED(p->cell_ptr);
     if (E > 0) {
         hipLaunchKernelGGL(k_sgd_keys, dim3((unsigned)((E + 255) / 256)), dim3(256), 0, stream, U, E, p->d.row_ptr, p->d.item, B,
-                           p->ub, p->ib, keys_a, bad);
+                           p->ustart, p->istart, keys_a, bad);
         SGD_HIP(hipMemcpyAsync(&bad_host, bad, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
         SGD_HIP(hipStreamSynchronize(stream));
         if (bad_host) return FR_ERR_ARG;      // items of a row not ascending / not distinct
@@ -331,7 +400,7 @@ int sgd_init(void* user, fr_alloc* a, void* stream_v)
     (void)fr_alloc_free(a, bad);
     p->keys = keys_b;
     p->rating = val_b;
-    hipLaunchKernelGGL(k_sgd_cells, dim3((B * B + 1 + 255) / 256), dim3(256), 0, stream, E, B, p->ub, p->keys, p->cell_ptr);
+    hipLaunchKernelGGL(k_sgd_cells, dim3((B * B + 1 + 255) / 256), dim3(256), 0, stream, E, B, p->ustart, p->keys, p->cell_ptr);
     p->cells.assign((size_t)B * B + 1, 0);
     SGD_HIP(hipMemcpyAsync(p->cells.data(), p->cell_ptr, p->cells.size() * 4, hipMemcpyDeviceToHost, stream));
     SGD_HIP(hipStreamSynchronize(stream));
@@ -484,12 +553,21 @@ int fr_sgd_info(void* user, fr_sgd_info_t* out)
     if (p->prefix.empty()) return FR_ERR_STATE;          // known once InitSideTask has run
     std::memset(out, 0, sizeof(*out));
     out->blocks = p->B;
-    out->users_per_block = p->ub;
-    out->items_per_block = p->ib;
     out->largest_cell = p->max_cell;
     out->chain_ratings = p->chain_ratings;
     out->bytes_resident = p->footprint_after;
     out->bytes_peak = p->footprint_peak;
+    return FR_OK;
+}
+
+int fr_sgd_block_starts(void* user, int32_t items, uint32_t* starts_host, size_t cap, size_t* n_out)
+{
+    SgdTask* p = static_cast<SgdTask*>(user);
+    if (!p || !n_out || (!starts_host && cap)) return FR_ERR_ARG;
+    if (p->prefix.empty()) return FR_ERR_STATE;
+    const std::vector<uint32_t>& v = items ? p->istart_host : p->ustart_host;
+    for (size_t k = 0; k < std::min(v.size(), cap); ++k) starts_host[k] = v[k];
+    *n_out = v.size();
     return FR_OK;
 }
 

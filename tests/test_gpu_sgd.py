@@ -79,9 +79,12 @@ def test_layout_facts_and_default_blocks():
     info = t.fr_sgd_info()
     B = info.blocks
     assert 1 <= B <= 1024 and r.n_ratings // (B * B) >= 32 and r.n_ratings // (4 * B * B) < 32     # largest power of two that fits
-    assert info.users_per_block == -(-r.n_users // B) and info.items_per_block == -(-r.n_items // B)
+    us, is_ = t.fr_sgd_block_starts(0), t.fr_sgd_block_starts(1)
+    ous, ois = osgd.blocks(r.row_ptr, r.item, r.n_items, B)
+    assert us == list(ous) and is_ == list(ois)
     users = np.repeat(np.arange(r.n_users), np.diff(r.row_ptr))
-    a, b = users // info.users_per_block, r.item // info.items_per_block
+    a = np.searchsorted(np.array(us[1:B]), users, side="right")
+    b = np.searchsorted(np.array(is_[1:B]), r.item, side="right")
     total, largest = 0, 0
     for s in (0, 1, B - 1):
         sizes = t.fr_sgd_cell_sizes(s)
@@ -91,6 +94,7 @@ def test_layout_facts_and_default_blocks():
         sizes = t.fr_sgd_cell_sizes(s)
         total += sum(sizes); largest = max(largest, max(sizes))
     assert total == r.n_ratings and largest == info.largest_cell
+    assert largest < 4 * r.n_ratings / (B * B)                      # blocks of equal numbers of ratings keep the cells close
     assert info.bytes_resident >= 12 * r.n_ratings and info.bytes_peak >= info.bytes_resident
     t.fr_sgd_destroy()
 
