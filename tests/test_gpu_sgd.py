@@ -186,3 +186,19 @@ def test_harvested_in_bubbles_gives_the_standalone_bits():
         want = max(sum(ceil_ns(n * fs_per_rating) for n in row), floor_ns, ceil_ns(max(row) * fs_chain))
         assert e.modelled_ns == want + 20_000 and e.work_units == sum(row)
     assert _same_bits(got_P, Pr.cpu().numpy()) and _same_bits(got_Q, Qr.cpu().numpy())
+
+
+@pytest.mark.timeout(600)
+def test_full_size_of_the_benchmark_gives_the_oracles_bits():
+    # the workload of `bench.py --side-task sgd` (2^20 x 2^20, 16.1 M ratings, 64 factors, blocks chosen by the library),
+    # one iteration, every factor compared bit for bit with the oracle's fp32 mode (about half a minute of CPU)
+    r = wl.rmat_ratings(20, 1 << 24, seed=1)
+    F, gamma, lam = 64, 0.01, 0.02
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed=1)
+    print("case U=I=%d E=%d F=%d" % (r.n_users, r.n_ratings, F), flush=True)
+    P, Q, info = _run(r, P0, Q0, F, gamma, lam, 1, 0)
+    assert info.blocks == 512
+    print("gpu done, oracle running", flush=True)
+    P32, Q32 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, 1, info.blocks, ordered_fp32=True)
+    assert _same_bits(P, P32) and _same_bits(Q, Q32)
+    assert not _same_bits(P, P0)
