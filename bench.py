@@ -75,6 +75,8 @@ def main():
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--device-gate", type=int, default=0,
                     help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
+    ap.add_argument("--adapt-costs", type=int, default=0,
+                    help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sgd-margin", type=float, default=1.08, help="--side-task sgd: final model = measured in-bubble step cost x this")
     ap.add_argument("--side-task", default="pagerank", choices=("pagerank", "sgd"),
@@ -164,11 +166,11 @@ def main():
     seg_kind = lambda g: (fr.FR_PR_SEG_VERTEX if g == 0 else fr.FR_PR_SEG_FINISH if g == n_segs - 1
                           else fr.FR_PR_SEG_SCATTER + ((g - 1) & 1))
 
-    def start_task(launch_cost_ns, model, time_steps):
+    def start_task(launch_cost_ns, model, time_steps, adapt=0):
         ctx = fr.Context(device_id=0, cu_count=cfg.cu_count if cfg.cu_count < 256 else 0,
                          mem_available_bytes=mem_cap + 1, guard_ns=args.guard_ns, launch_cost_ns=launch_cost_ns,
                          max_chunk_ns=0, max_inflight=32, time_steps=time_steps, event_log_capacity=1 << 18,
-                         device_gate=args.device_gate)
+                         device_gate=args.device_gate, adapt_costs=adapt)
         task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
                                mem_limit_bytes=mem_cap, **model)
         tid = ctx.fr_task_register(task.ops, task.user, task.profile)
@@ -225,7 +227,7 @@ def main():
     if ratios:
         log("  group ratios min %.3f quartiles %.3f %.3f %.3f max %.3f" % ((min(ratios),) + tuple(statistics.quantiles(ratios, n=4)) + (max(ratios),)))
     one_tile_ns = [x * in_bubble for x in one_tile_standalone]
-    ctx, task, tid = start_task(0, rates(*insitu, args.margin), ts)     # the measured group times already hold the launch gaps
+    ctx, task, tid = start_task(0, rates(*insitu, args.margin), ts, args.adapt_costs)     # the measured group times already hold the launch gaps
     def epochs(n, with_task):
         out = []
         for _ in range(n):
