@@ -202,3 +202,54 @@ def test_full_size_of_the_benchmark_gives_the_oracles_bits():
     P32, Q32 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, 1, info.blocks, ordered_fp32=True)
     assert _same_bits(P, P32) and _same_bits(Q, Q32)
     assert not _same_bits(P, P0)
+
+
+def test_pagerank_and_sgd_queued_on_one_worker_run_one_after_the_other():
+    # Algorithms 1 and 2 with two different side tasks: both are accepted, the first one submitted runs until it reports
+    # that it has finished, then the second takes the bubbles; each ends with the bits of its standalone run.
+    import time
+    from oracle.pagerank import pagerank
+    from workloads import configs, graphs
+    cfg = configs.by_name("cfg1")
+    g = graphs.rmat_csr(13, 1 << 17, seed=3)
+    r = wl.rmat_ratings(11, 1 << 16, seed=10)
+    F, gamma, lam, K_sgd, B, K_pr = 16, 0.02, 0.03, 2, 8, 10
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed=10)
+    Pr, Qr, _ = _run(r, P0, Q0, F, gamma, lam, K_sgd, B)                        # SGD reference bits
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    P, Q = _dev(P0), _dev(Q0)
+    ctx = fr.Context(device_id=0, guard_ns=200_000, launch_cost_ns=20_000, max_chunk_ns=0, time_steps=1, mem_available_bytes=1 << 40)
+    pr_task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=K_pr, max_runs=1, mem_limit_bytes=1 << 30,
+                              fs_per_edge=400_000, fs_per_message=400_000, fs_per_vertex=300_000, finish_tile_ns=15000)
+    sgd_task = _task(r, P, Q, F, gamma, lam, K_sgd, B, max_runs=1, mem_limit_bytes=1 << 30, fs_per_rating=100_000_000, min_step_ns=200_000)
+    t_pr = ctx.fr_task_register(pr_task.ops, pr_task.user, pr_task.profile)
+    t_sgd = ctx.fr_task_register(sgd_task.ops, sgd_task.user, sgd_task.profile)
+    assert ctx.fr_query_progress(t_pr).state == fr.FR_CREATED and ctx.fr_query_progress(t_sgd).state == fr.FR_SUBMITTED
+    stream = torch.cuda.Stream()
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=cfg.busy_fp_ns, bp_ns=cfg.busy_bp_ns)
+    stage = fr.Stage(fr.FR_SCHED_1F1B, cfg.p, cfg.m, cfg.stage, cfg.busy_fp_ns, cfg.busy_bp_ns, load, stream)
+    order = []
+    for ep in range(30):
+        print("epoch", ep, flush=True)
+        stage.fr_stage_run_epoch(ctx)
+        a, b = ctx.fr_query_progress(t_pr), ctx.fr_query_progress(t_sgd)
+        if a.runs_completed and "pagerank" not in order:
+            order.append("pagerank")
+            assert b.runs_completed == 0                                       # the second task has not finished before the first
+        if b.runs_completed:
+            order.append("sgd")
+            break
+    time.sleep(0.05)
+    a, b = ctx.fr_query_progress(t_pr), ctx.fr_query_progress(t_sgd)
+    if b.state != fr.FR_STOPPED:
+        ctx.fr_task_stop(t_sgd)
+    if a.state != fr.FR_STOPPED:
+        ctx.fr_task_stop(t_pr)
+    got_ranks, got_P, got_Q = ranks.cpu().numpy(), P.cpu().numpy(), Q.cpu().numpy()
+    pr_task.fr_pagerank_destroy(); sgd_task.fr_sgd_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    assert order == ["pagerank", "sgd"] and a.runs_completed == 1 and b.runs_completed == 1
+    assert a.state == fr.FR_STOPPED and a.last_error == fr.FR_OK                # finished and gave way to the next in the queue
+    assert a.overruns == 0 and b.overruns == 0
+    assert np.abs(got_ranks.astype(np.float64) - pagerank(g.row_ptr, g.col, g.out_degree, 0.85, K_pr)).max() <= 1e-5
+    assert _same_bits(got_P, Pr) and _same_bits(got_Q, Qr)
