@@ -253,3 +253,55 @@ def test_pagerank_and_sgd_queued_on_one_worker_run_one_after_the_other():
     assert a.overruns == 0 and b.overruns == 0
     assert np.abs(got_ranks.astype(np.float64) - pagerank(g.row_ptr, g.col, g.out_degree, 0.85, K_pr)).max() <= 1e-5
     assert _same_bits(got_P, Pr) and _same_bits(got_Q, Qr)
+
+
+def test_device_gate_refuses_late_sgd_steps_and_the_factors_keep_their_bits():
+    # The model claims a quarter of what the strata take, so the host keeps enqueueing steps that cannot end inside the
+    # bubble; with the device gate the late ones do nothing and the task is rewound to the first of them.  SGD updates
+    # its factors in place, so a step that ran twice, or half, would show in the bits.
+    import time
+    r = wl.rmat_ratings(12, 1 << 17, seed=11)
+    F, gamma, lam, K, B = 32, 0.02, 0.03, 2, 16
+    P0, Q0 = wl.initial_factors(r.n_users, r.n_items, F, seed=11)
+    Pr, Qr = _dev(P0), _dev(Q0)
+    t_ref = _task(r, Pr, Qr, F, gamma, lam, K, B)
+    t_ref.fr_sgd_run_standalone(0, torch.cuda.current_stream())
+    ns = t_ref.fr_sgd_run_standalone(0, torch.cuda.current_stream(), want_ns=True)
+    t_ref.fr_sgd_destroy()
+    Pr, Qr, _ = _run(r, P0, Q0, F, gamma, lam, K, B)                            # one run from the start: the reference bits
+    stratum_ns = ns / (K * B)
+    low = 0.25
+    P, Q = _dev(P0), _dev(Q0)
+    ctx = fr.Context(device_id=0, guard_ns=20_000, launch_cost_ns=5_000, max_chunk_ns=0, time_steps=4, device_gate=1,
+                     mem_available_bytes=1 << 40)
+    task = _task(r, P, Q, F, gamma, lam, K, B, max_runs=1, mem_limit_bytes=1 << 30,
+                 fs_per_rating=int(low * stratum_ns * 1e6 / (r.n_ratings / B)), min_step_ns=int(low * stratum_ns))
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    ctx.fr_bubble_begin(fr.fr_now_ns(), 2_000_000_000)
+    t_end = time.time() + 30
+    while ctx.fr_query_progress(tid).state == fr.FR_CREATED and time.time() < t_end:
+        time.sleep(0.001)
+    ctx.fr_bubble_end()
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 1_000_000, 2_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+    for ep in range(40):
+        print("epoch", ep, flush=True)
+        stage.fr_stage_run_epoch(ctx)
+        time.sleep(0.01)
+        if ctx.fr_query_progress(tid).runs_completed >= 1:
+            break
+    time.sleep(0.05)
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    if pr.state != fr.FR_STOPPED:
+        ctx.fr_task_stop(tid)
+    got_P, got_Q = P.cpu().numpy(), Q.cpu().numpy()
+    task.fr_sgd_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
+    refused = [e for e in log if e.kind == fr.FR_EV_REFUSED]
+    print("steps", pr.steps, "refused", pr.steps_refused, "runs", pr.runs_completed, flush=True)
+    assert pr.runs_completed == 1 and pr.steps_refused > 0 and len(refused) == pr.steps_refused
+    assert pr.work_units_done == sum(e.work_units for e in chunks) - sum(e.work_units for e in refused) == K * r.n_ratings
+    assert _same_bits(got_P, Pr) and _same_bits(got_Q, Qr)
