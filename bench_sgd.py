@@ -6,7 +6,6 @@ the side task before and after for the stage's slowdown.
 """
 import json
 import statistics
-import sys
 import time
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
