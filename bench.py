@@ -75,7 +75,7 @@ def main():
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--device-gate", type=int, default=0,
                     help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
-    ap.add_argument("--adapt-costs", type=int, default=0,
+    ap.add_argument("--adapt-costs", type=int, default=1,
                     help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sgd-margin", type=float, default=1.08, help="--side-task sgd: final model = measured in-bubble step cost x this")
