@@ -294,6 +294,19 @@ def main():
     busy_with = statistics.mean(r.busy_ns for r in with_task)
     busy_without = statistics.mean(r.busy_ns for r in base)
 
+    # context for the roofline: what a plain device-to-device copy of 1 GiB moves on this GPU (read + write)
+    cp_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(10):
+        cp_dst.copy_(cp_src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2.0 * cp_src.numel() * 4 / (ev0.elapsed_time(ev1) * 1e6)
+    del cp_src, cp_dst
+
     out = {
         "metric": "side-task GTEPS harvested in bubbles",
         "value": edges / bubble_ns if bubble_ns else 0.0,
@@ -333,6 +346,8 @@ def main():
                      "traffic": CFG2_TRAFFIC_BYTES if cfg.name == "cfg2" else None,
                      "traffic_gbs": (CFG2_TRAFFIC_BYTES * iters_done / pull_ns) if (cfg.name == "cfg2" and pull_ns) else None,
                      "traffic_frac_of_peak": (CFG2_TRAFFIC_BYTES * iters_done / pull_ns / HBM_PEAK_GBS) if (cfg.name == "cfg2" and pull_ns) else None,
+                     "device_copy_gbs": copy_gbs,
+                     "traffic_frac_of_device_copy": (CFG2_TRAFFIC_BYTES * iters_done / pull_ns / copy_gbs) if (cfg.name == "cfg2" and pull_ns) else None,
                      "iterations": iters_done,
                      "avg_iteration_us": (pull_ns / iters_done / 1e3) if iters_done else None,
                      "timing": "HIP events on the side stream around groups of %d steps, all inside the timed epochs" % max(1, args.time_steps),
