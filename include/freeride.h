@@ -85,11 +85,14 @@ typedef struct fr_config {
                                       steps of a bubble (the last group of a bubble may be shorter); the group's time
                                       is reported on its last step's record.  1 times every step, at the price of
                                       about 3 us of GPU idle time between steps; 0 = no timing.                 */
-    uint32_t adapt_costs;          /* nonzero: the profiler keeps running (Section 4.3): every measured step updates a
-                                      cost scale for its cost class (measured / modelled, taken at once when it
-                                      rises, up to a doubling, and eased by 1/8 per step when it falls) and steps are planned against the
-                                      scaled costs.  The plan then depends on measurements and no longer matches a
-                                      plan computed ahead of time.  Needs time_steps.                          */
+    uint32_t adapt_costs;          /* nonzero: the profiler keeps running (Section 4.3): the timing groups of a bubble
+                                      are summed and, before the next bubble is planned, update a cost scale for
+                                      each of their cost classes (measured / modelled, taken at once when it
+                                      rises, up to a doubling, and eased by 1/8 when it falls); a single group that
+                                      took over 1.25 times its scaled cost updates the scales at once instead.
+                                      Steps are planned against the scaled costs.  The plan then depends on
+                                      measurements and no longer matches a plan computed ahead of time.  Needs
+                                      time_steps.                                                              */
     uint32_t device_gate;          /* nonzero: every step also checks the GPU clock when its kernel starts and does
                                       nothing if it could not end guard_ns before the bubble's declared end
                                       (freeride_device.h); refused steps are taken back (fr_task_ops.rewind) and

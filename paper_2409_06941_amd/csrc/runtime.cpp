@@ -45,6 +45,16 @@ struct PendingTiming {
     hipEvent_t end;
     uint32_t class_mask;     // for cost adaptation: the cost classes in the group and the task's own (unscaled)
     uint64_t task_modelled_ns;   // modelled cost of its steps
+    uint64_t bubble;         // index of the bubble the group ran in
+};
+
+// Cost adaptation gathers the timing groups of a bubble and updates the scales once from the bubble's totals: single
+// groups scatter by several percent (the first after a burst of the main workload runs slowest), and a scale that
+// follows every group ends up charging every step for the slowest one.
+struct BubbleTotals {
+    uint64_t bubble = ~0ull;
+    uint64_t modelled_ns = 0, measured_ns = 0;
+    uint32_t class_mask = 0;
 };
 
 constexpr uint32_t kScaleOne = 1000000, kScaleMin = 250000, kScaleMax = 16000000;
@@ -107,6 +117,7 @@ struct fr_ctx {
     std::deque<PendingTiming> pending;
     hipEvent_t chain_tail = nullptr;        // end event of the newest step of the bubble being served
     uint32_t cost_scale[8] = {kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne, kScaleOne};
+    BubbleTotals totals;     // of the bubble whose timing groups are being resolved
 
     // device gate
     fr_gate* gate = nullptr;                // device memory, NULL when the gate is off
@@ -165,6 +176,17 @@ hipEvent_t event_get(fr_ctx* c)
     return e;
 }
 
+// The scales take in what the finished bubble showed (ctx->mu held).
+void apply_totals(fr_ctx* c)
+{
+    BubbleTotals& b = c->totals;
+    if (b.modelled_ns)
+        for (int k = 0; k < 8; ++k)
+            if ((b.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], b.modelled_ns, b.measured_ns);
+    b.modelled_ns = b.measured_ns = 0;
+    b.class_mask = 0;
+}
+
 // Resolve finished step timings (ctx->mu held).  wait = true blocks until every pending step has finished.
 void resolve_timings(fr_ctx* c, bool wait)
 {
@@ -177,9 +199,23 @@ void resolve_timings(fr_ctx* c, bool wait)
             const uint64_t ns = (uint64_t)((double)ms * 1.0e6 + 0.5);
             if (fr_event* ev = log_at(c, p.log_seq)) ev->measured_ns = ns;
             if (c->task) c->task->prog.ns_measured += ns;
-            if (c->cfg.adapt_costs)
+            if (c->cfg.adapt_costs) {
+                if (p.bubble != c->totals.bubble) { apply_totals(c); c->totals.bubble = p.bubble; }
+                // a group that took over 1.25 times its scaled cost is no scatter: the model is wrong, and the steps
+                // still to be planned for this bubble should know
+                bool far_off = false;
                 for (int k = 0; k < 8; ++k)
-                    if ((p.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], p.task_modelled_ns, ns);
+                    if ((p.class_mask >> k) & 1u)
+                        far_off |= (unsigned __int128)ns * kScaleOne * 4 > (unsigned __int128)p.task_modelled_ns * c->cost_scale[k] * 5;
+                if (far_off) {
+                    for (int k = 0; k < 8; ++k)
+                        if ((p.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], p.task_modelled_ns, ns);
+                } else {
+                    c->totals.modelled_ns += p.task_modelled_ns;
+                    c->totals.measured_ns += ns;
+                    c->totals.class_mask |= p.class_mask;
+                }
+            }
         }
         // Steps resolve in order, so nothing older still needs this begin event.  The end event lives on if a
         // later step uses (or may still come to use) it as its begin; that step releases it.
@@ -319,6 +355,11 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     const bool timed = c->cfg.time_steps && !c->host_only;
     const bool adapt = timed && c->cfg.adapt_costs;
     const bool gated = c->gate && t->ops.rewind;
+    if (adapt) {                                             // what the bubble before showed goes into this one's plan
+        std::lock_guard<std::mutex> lk(c->mu);
+        resolve_timings(c, false);
+        if (c->totals.bubble != index) apply_totals(c);
+    }
     if (gated) {
         gate_settle(c, t);                                   // the previous bubble's verdicts, if still unread
         if (t->state != FR_RUNNING) return;                  // a failing rewind stopped the task
@@ -341,7 +382,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         { std::lock_guard<std::mutex> lk(c->mu); ev_end = event_get(c); }
         if (ev_end && group_begin && hipEventRecord(ev_end, c->side) == hipSuccess) {
             std::lock_guard<std::mutex> lk(c->mu);
-            c->pending.push_back(PendingTiming{group_last_seq, group_begin, ev_end, group_mask, group_modelled});
+            c->pending.push_back(PendingTiming{group_last_seq, group_begin, ev_end, group_mask, group_modelled, index});
             c->chain_tail = ev_end;
         }
         group_n = 0; group_mask = 0; group_modelled = 0; group_begin = nullptr;
@@ -882,6 +923,7 @@ int fr_cost_scales(fr_ctx* c, uint32_t* out)
     if (!c || !out) return FR_ERR_ARG;
     std::lock_guard<std::mutex> lk(c->mu);
     if (!c->host_only) resolve_timings(c, false);
+    if (c->pending.empty()) apply_totals(c);
     for (int i = 0; i < 8; ++i) out[i] = c->cost_scale[i];
     return FR_OK;
 }
