@@ -70,7 +70,8 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
     ap.add_argument("--margin", type=float, default=1.02, help="final model = measured in-bubble step cost x margin")
-    ap.add_argument("--guard-ns", type=int, default=100_000)
+    ap.add_argument("--guard-ns", type=int, default=150_000,
+                    help="time kept free at the end of every bubble (covers the slow first sweeps after a burst)")
     ap.add_argument("--time-steps", type=int, default=16,
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--device-gate", type=int, default=0,
