@@ -263,6 +263,56 @@ def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheape
     assert late[0] > 0 and late[1] == 0, late
 
 
+def test_running_profiler_changes_the_scales_between_bubbles_and_inside_one_only_after_a_step_that_is_far_off():
+    # The model claims the standalone sweep times; every step is timed on its own.  The scales move when a bubble's
+    # steps have been summed, before the next bubble is planned, and inside a bubble only after a step that took over
+    # 1.25 times its scaled cost: in a bubble without such a step the logged cost of a whole gather sweep (scaled
+    # cost + launch cost) is one number, and over the bubbles it takes several values.
+    import time
+    g = graphs.rmat_csr(21, 1 << 25, seed=9)
+    V, E, K = g.n_vertices, g.n_edges, 20
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+    probe = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K)
+    probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
+    info = probe.fr_pagerank_info()
+    gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
+    probe.fr_pagerank_destroy()
+    model = _scaled_model(1.0, ph, K, gw, sw, info)
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 1_000_000, 2_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    launch_ns = 5_000
+    ctx = fr.Context(device_id=0, guard_ns=100_000, launch_cost_ns=launch_ns, time_steps=1, adapt_costs=1, event_log_capacity=1 << 16)
+    task = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K, max_runs=0, **model)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+    for _ in range(6):
+        stage.fr_stage_run_epoch(ctx)
+    time.sleep(0.05)
+    scales = ctx.fr_cost_scales()
+    events = ctx.fr_event_log(1 << 16)
+    ctx.fr_task_stop(tid)
+    task.fr_pagerank_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+    sweeps, far_off = {}, set()      # bubble -> logged costs of its whole gather sweeps; bubbles with a step far off
+    for e in events:
+        if e.kind != fr.FR_EV_CHUNK:
+            continue
+        if e.measured_ns * 4 > (e.modelled_ns - launch_ns) * 5 * 0.97:       # (a little wider than the runtime's test)
+            far_off.add(e.bubble)
+        if e.tile0 == 0 and e.tile1 == info.gather_tiles and e.segment >= 2 and e.segment % 2 == 0:
+            sweeps.setdefault(e.bubble, []).append(e.modelled_ns)
+    quiet = [b for b in sweeps if b not in far_off and len(sweeps[b]) >= 2]
+    print("scales", scales[:4], "bubbles with gather sweeps", len(sweeps), "without a step far off", len(quiet),
+          "costs of a gather sweep", sorted({v[0] for v in sweeps.values()})[:6], flush=True)
+    assert len(quiet) >= 4, (len(sweeps), len(far_off))
+    assert all(len(set(sweeps[b])) == 1 for b in quiet), {b: sorted(set(sweeps[b])) for b in quiet if len(set(sweeps[b])) > 1}
+    assert len({sweeps[b][0] for b in sweeps}) >= 3
+    assert scales[1] != 1_000_000 and scales[2] != 1_000_000
+
+
 def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back():
     # The model claims 25 % of the real step times, so the host keeps enqueueing steps that cannot end inside the
     # bubble.  With the device gate each step asks the GPU clock when its kernel starts: the late ones do nothing,
