@@ -89,8 +89,9 @@ typedef struct fr_config {
                                       are summed and, before the next bubble is planned, update a cost scale for
                                       each of their cost classes (measured / modelled, taken at once when it
                                       rises, up to a doubling, and eased by 1/8 when it falls); a single group that
-                                      took over 1.25 times its scaled cost updates the scales at once instead.
-                                      Steps are planned against the scaled costs.  The plan then depends on
+                                      took over 1.25 times its scaled cost also updates the scales at once, for the
+                                      rest of its bubble (the update from the bubble's sums then starts from the
+                                      scales before it).  Steps are planned against the scaled costs.  The plan then depends on
                                       measurements and no longer matches a plan computed ahead of time.  Needs
                                       time_steps.                                                              */
     uint32_t device_gate;          /* nonzero: every step also checks the GPU clock when its kernel starts and does

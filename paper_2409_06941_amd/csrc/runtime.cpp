@@ -53,8 +53,9 @@ struct PendingTiming {
 // follows every group ends up charging every step for the slowest one.
 struct BubbleTotals {
     uint64_t bubble = ~0ull;
-    uint64_t modelled_ns = 0, measured_ns = 0;
-    uint32_t class_mask = 0;
+    uint64_t modelled_ns[8] = {}, measured_ns[8] = {};       // per cost class: of the groups that hold steps of it
+    bool surged = false;         // a group far over its cost has raised the scales for the rest of this bubble ...
+    uint32_t before_surge[8];    // ... from these values, which the bubble's totals then update
 };
 
 constexpr uint32_t kScaleOne = 1000000, kScaleMin = 250000, kScaleMax = 16000000;
@@ -180,11 +181,14 @@ hipEvent_t event_get(fr_ctx* c)
 void apply_totals(fr_ctx* c)
 {
     BubbleTotals& b = c->totals;
-    if (b.modelled_ns)
-        for (int k = 0; k < 8; ++k)
-            if ((b.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], b.modelled_ns, b.measured_ns);
-    b.modelled_ns = b.measured_ns = 0;
-    b.class_mask = 0;
+    if (b.surged) {
+        for (int k = 0; k < 8; ++k) c->cost_scale[k] = b.before_surge[k];
+        b.surged = false;
+    }
+    for (int k = 0; k < 8; ++k) {
+        if (b.modelled_ns[k]) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], b.modelled_ns[k], b.measured_ns[k]);
+        b.modelled_ns[k] = b.measured_ns[k] = 0;
+    }
 }
 
 // Resolve finished step timings (ctx->mu held).  wait = true blocks until every pending step has finished.
@@ -201,20 +205,23 @@ void resolve_timings(fr_ctx* c, bool wait)
             if (c->task) c->task->prog.ns_measured += ns;
             if (c->cfg.adapt_costs) {
                 if (p.bubble != c->totals.bubble) { apply_totals(c); c->totals.bubble = p.bubble; }
-                // a group that took over 1.25 times its scaled cost is no scatter: the model is wrong, and the steps
-                // still to be planned for this bubble should know
+                // a group that took over 1.25 times its scaled cost is no scatter: the steps still to be planned for
+                // this bubble are charged more at once.  What stays after the bubble is what its totals say, this
+                // group included: a model that is wrong shows there too, a hiccup does not weigh much
                 bool far_off = false;
                 for (int k = 0; k < 8; ++k)
                     if ((p.class_mask >> k) & 1u)
                         far_off |= (unsigned __int128)ns * kScaleOne * 4 > (unsigned __int128)p.task_modelled_ns * c->cost_scale[k] * 5;
                 if (far_off) {
+                    if (!c->totals.surged) {
+                        for (int k = 0; k < 8; ++k) c->totals.before_surge[k] = c->cost_scale[k];
+                        c->totals.surged = true;
+                    }
                     for (int k = 0; k < 8; ++k)
                         if ((p.class_mask >> k) & 1u) c->cost_scale[k] = fr_cost_scale_next(c->cost_scale[k], p.task_modelled_ns, ns);
-                } else {
-                    c->totals.modelled_ns += p.task_modelled_ns;
-                    c->totals.measured_ns += ns;
-                    c->totals.class_mask |= p.class_mask;
                 }
+                for (int k = 0; k < 8; ++k)
+                    if ((p.class_mask >> k) & 1u) { c->totals.modelled_ns[k] += p.task_modelled_ns; c->totals.measured_ns[k] += ns; }
             }
         }
         // Steps resolve in order, so nothing older still needs this begin event.  The end event lives on if a
