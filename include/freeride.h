@@ -252,8 +252,8 @@ int fr_chunk_fit(const uint64_t* prefix, uint32_t n_tiles, uint32_t tile0, uint6
                  uint64_t launch_cost_ns, uint32_t* n_fit);
 
 /*
- * Cost adaptation (fr_config.adapt_costs).  Scales are parts per million of the task's own modelled cost,
- * 1000000 at the start, kept within [250000, 16000000].
+ * Cost adaptation (fr_config.adapt_costs).  Scales are parts per million of the current task's own modelled cost,
+ * 1000000 when a task becomes the worker's current one, kept within [250000, 16000000].
  * fr_cost_scale_next: the update rule as a pure function: with r = measured_ns / modelled_ns (in ppm, clamped to
  *   the range above; the old scale if modelled_ns is 0) the new scale is min(r, 2 * scale_ppm) if
  *   r >= scale_ppm, else scale_ppm - (scale_ppm - r) / 8.

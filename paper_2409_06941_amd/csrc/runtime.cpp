@@ -258,6 +258,8 @@ void promote_locked(fr_ctx* c)
         if (rc != FR_OK) { t->state = FR_STOPPED; t->last_error = rc; continue; }
         t->state = FR_CREATED;
         c->task = t;
+        for (int k = 0; k < 8; ++k) c->cost_scale[k] = kScaleOne;     // what the task before taught says nothing about this one
+        c->totals = BubbleTotals{};
     }
 }
 
