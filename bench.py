@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--device-gate", type=int, default=0,
                     help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
     ap.add_argument("--adapt-costs", type=int, default=1,
-                    help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs; PageRank only: Graph SGD is harvested 2 % better with its frozen model, 0 overruns either way)")
+                    help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs; PageRank only: Graph SGD is harvested 2 percent better with its frozen model, 0 overruns either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sgd-margin", type=float, default=1.08, help="--side-task sgd: final model = measured in-bubble step cost x this")
     ap.add_argument("--side-task", default="pagerank", choices=("pagerank", "sgd"),
