@@ -181,6 +181,7 @@ __device__ __forceinline__ float fill_merged(const DevArgs& A, RangeInfo info, u
 // this thread's share of the dangling mass among the rows finished here.  The tile is walked range by range (a
 // handful at most), so that each loop has one kind of row and its loads can be issued back to back.
 // `first_info`: what range_info holds for the range of u0.
+constexpr int kFillRound = 16;
 template <int kThreads>
 __device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint32_t n, float base, float* slice, RangeInfo first_info)
 {
@@ -191,15 +192,32 @@ __device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint3
         const uint32_t i1 = range_end < n ? range_end : n;
         const RangeInfo info = i0 == 0 ? first_info : A.range_info[q];
         const uint32_t cls = info.cls_tiles & 3u;
-        if (cls == kRangeDirect) {                                   // finished by its gather tile
-#pragma unroll 4
-            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) slice[i] = A.contrib[u0 + i] * kMsgScale;
-        } else if (cls == kRangeEmpty) {
-#pragma unroll 4
-            for (uint32_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
-                const float inv = A.inv_out[u0 + i];
-                slice[i] = base * inv * kMsgScale;
-                dangling += (inv == 0.0f ? base : 0.0f);
+        if (cls == kRangeDirect || cls == kRangeEmpty) {
+            // one value per row: contrib, finished by the range's gather tile, or 1/outdeg of a row without in-edges.
+            // All loads of a round are issued before the first is used: a round is kFillRound rows per thread, and a
+            // range's share of the slice is no more than that at 1024 threads, so the slice costs one memory latency.
+            const float* __restrict__ from = cls == kRangeDirect ? A.contrib : A.inv_out;
+            for (uint32_t ib = i0 + threadIdx.x; ib < i1; ib += kFillRound * kThreads) {
+                float v[kFillRound];
+#pragma unroll
+                for (int k = 0; k < kFillRound; ++k) {
+                    const uint32_t i = ib + k * kThreads;
+                    v[k] = i < i1 ? from[u0 + i] : 1.0f;
+                }
+                if (cls == kRangeDirect) {
+#pragma unroll
+                    for (int k = 0; k < kFillRound; ++k) {
+                        const uint32_t i = ib + k * kThreads;
+                        if (i < i1) slice[i] = v[k] * kMsgScale;
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < kFillRound; ++k) {
+                        const uint32_t i = ib + k * kThreads;
+                        if (i < i1) slice[i] = base * v[k] * kMsgScale;
+                        dangling += (v[k] == 0.0f ? base : 0.0f);
+                    }
+                }
             }
         } else {
             // few rows (sources with many messages; their rows are the ones with many partial sums): several lanes a row
@@ -363,8 +381,19 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
         const uint32_t n = T.u1 - T.u0 < kSrcPerPart ? T.u1 - T.u0 : kSrcPerPart;
         if (first) {
             const float r0 = 1.0f / (float)A.V;
-#pragma unroll 4
-            for (uint32_t i = threadIdx.x; i < n; i += kScatterBlock) slice[i] = r0 * A.inv_out[u0 + i] * kMsgScale;
+            for (uint32_t ib = threadIdx.x; ib < n; ib += kFillRound * kScatterBlock) {
+                float v[kFillRound];
+#pragma unroll
+                for (int k = 0; k < kFillRound; ++k) {
+                    const uint32_t i = ib + k * kScatterBlock;
+                    v[k] = i < n ? A.inv_out[u0 + i] : 0.0f;
+                }
+#pragma unroll
+                for (int k = 0; k < kFillRound; ++k) {
+                    const uint32_t i = ib + k * kScatterBlock;
+                    if (i < n) slice[i] = r0 * v[k] * kMsgScale;
+                }
+            }
         } else {
             const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice, first_info), red);
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
@@ -729,36 +758,39 @@ void build_cost_tables(PrTask* p)
     for (uint32_t t = 0; t < nf; ++t) h[t + 1] = h[t] + std::max<uint64_t>(1, p->d.finish_tile_ns);
 }
 
-int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0})
+// `with`: the kernel arguments to use instead of the task's own (the run that works in the static scratch array).
+int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0},
+              const DevArgs* with = nullptr)
 {
+    const DevArgs& args = with ? *with : p->args;
     const int kind = p->kind_of(g);
     if (tile1 <= tile0 || tile1 > p->tiles_of(kind)) return FR_ERR_ARG;
     const uint32_t n = tile1 - tile0;
     const uint32_t K = (uint32_t)p->d.iterations;
     if (kind == FR_PR_SEG_VERTEX) {
-        hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, p->args, G, tile0, K == 0 ? 1 : 0);
+        hipLaunchKernelGGL(k_vertex0, dim3(n), dim3(kBlock), 0, stream, args, G, tile0, K == 0 ? 1 : 0);
     } else if (kind == FR_PR_SEG_FINISH) {
         // after G_{K-1}: the dangling partials of r_{K-1} sit in set (K-1) & 1
-        hipLaunchKernelGGL(k_finish, dim3(n), dim3(kBlock), 0, stream, p->args, G, tile0, (int)((K - 1) & 1u));
+        hipLaunchKernelGGL(k_finish, dim3(n), dim3(kBlock), 0, stream, args, G, tile0, (int)((K - 1) & 1u));
     } else {
         const uint32_t k = (g - 1) / 2;
         if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes rows of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
             const bool packed = p->L.n_scatter != p->L.n_spieces;
             if (p->L.src_per_part == kSrcLarge)
-                hipLaunchKernelGGL((k_scatter<kSrcLarge, true>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+                hipLaunchKernelGGL((k_scatter<kSrcLarge, true>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
             else if (packed)
-                hipLaunchKernelGGL((k_scatter<kSrcSmall, true>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+                hipLaunchKernelGGL((k_scatter<kSrcSmall, true>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
             else
-                hipLaunchKernelGGL((k_scatter<kSrcSmall, false>), dim3(n), dim3(kScatterBlock), 0, stream, p->args, G, tile0, parity, first);
+                hipLaunchKernelGGL((k_scatter<kSrcSmall, false>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
         } else {
             const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
             if (p->L.rows_per_part == kRowsLarge)
-                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass,
-                                   p->args.starts, p->args.mbase);
+                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, args, G, tile0, parity, final_pass,
+                                   args.starts, args.mbase);
             else
-                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, p->args, G, tile0, parity, final_pass,
-                                   p->args.starts, p->args.mbase);
+                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, args, G, tile0, parity, final_pass,
+                                   args.starts, args.mbase);
         }
     }
     hipError_t e = hipGetLastError();
