@@ -362,6 +362,19 @@ int fr_pagerank_tile_weights(void* user, int32_t seg_kind, uint64_t* weights_hos
  */
 int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream, uint32_t max_tiles_per_launch,
                                uint64_t* phase_ns_out);
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): the same run as fr_pagerank_run_standalone with the same kernels and tiles, hence the same bits in
+ * ranks_out, but the run's working memory (messages, contributions, dangling partials, partial sums) lies in a
+ * 64 MiB array inside the library's device code, of which every GPU holds its own copy until the process ends.  Makes no
+ * hipMalloc / hipFree and creates no events; it does wait for the stream.  The task's layout must have been built
+ * before by fr_pagerank_run_standalone on the same device (FR_ERR_STATE otherwise; this call builds nothing), and the
+ * task must not be registered with a context.  FR_ERR_ARG if the working memory of this graph does not fit the array
+ * (it needs about 4 bytes per message and per vertex plus 65536 per partial-sum row, each part rounded up to 256), or if device_id is not in 0 .. 63.
+ * All calls on one GPU share the array, which keeps the last call's contents (every part is written before it is
+ * read, so nothing needs clearing): calls that overlap in time on one GPU race; run them one after the other.
+ */
+int fr_pagerank_run_standalone_noalloc(void* user, int32_t device_id, void* stream, uint32_t max_tiles_per_launch);
 
 /* ------------------------------------------------------------------ Graph SGD side task */
 /*

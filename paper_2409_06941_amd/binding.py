@@ -156,6 +156,7 @@ SIGNATURES = {
     "fr_sgd_info": (C.c_int, [C.c_void_p, C.POINTER(fr_sgd_info_t)]),
     "fr_sgd_block_starts": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
     "fr_sgd_cell_sizes": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.c_size_t, C.POINTER(C.c_size_t)]),
+    "fr_pagerank_run_standalone_noalloc": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32]),
     "fr_sgd_run_standalone": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64)]),
     "fr_load_workspace_bytes": (C.c_int, [C.POINTER(fr_load_desc), C.POINTER(C.c_uint64)]),
     "fr_load_make": (C.c_int, [C.POINTER(fr_load_desc), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -364,6 +365,10 @@ class PageRankTask:
         _check(lib().fr_pagerank_run_standalone(self.user, device_id, _stream(stream), max_tiles_per_launch,
                                                 ph if want_phase_ns else None), "fr_pagerank_run_standalone")
         return list(ph) if want_phase_ns else None
+
+    def fr_pagerank_run_standalone_noalloc(self, device_id=0, stream=None, max_tiles_per_launch=0):
+        _check(lib().fr_pagerank_run_standalone_noalloc(self.user, device_id, _stream(stream), max_tiles_per_launch),
+               "fr_pagerank_run_standalone_noalloc")
 
 
 class SgdTask:

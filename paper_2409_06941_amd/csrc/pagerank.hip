@@ -24,6 +24,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "freeride_device.h"
@@ -926,6 +927,18 @@ int pr_stop(void* user)
     return FR_OK;
 }
 
+// ---- working memory of fr_pagerank_run_standalone_noalloc: messages, contributions, dangling partials and partial
+// sums of one run live in this array instead of in memory taken from an allocator.  Every GPU the library is loaded
+// on holds its own copy at its own address; host code never uses the array's name as an address, only the pointer
+// hipGetSymbolAddress gave for the device at hand.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+size_t round256(size_t n) { return (n + 255) / 256 * 256; }
+
 }  // namespace
 
 extern "C" {
@@ -1085,6 +1098,46 @@ int fr_pagerank_run_standalone(void* user, int32_t device_id, void* stream_v, ui
         (void)hipEventDestroy(ev[0]);
         (void)hipEventDestroy(ev[1]);
     }
+    if (rc != FR_OK) return rc;
+    if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
+    return FR_OK;
+}
+
+int fr_pagerank_run_standalone_noalloc(void* user, int32_t device_id, void* stream_v, uint32_t max_tiles)
+{
+    PrTask* p = static_cast<PrTask*>(user);
+    if (!p || device_id < 0 || device_id >= kMaxDevices) return FR_ERR_ARG;
+    if (p->registered || !p->inited) return FR_ERR_STATE;        // the layout must exist already: nothing is built here
+    hipStream_t stream = (hipStream_t)stream_v;
+    FR_HIP_TRY(hipSetDevice(device_id), p->hip_error);
+    unsigned char* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        if (!g_scratch_ptr[device_id]) {
+            void* sym = nullptr;
+            FR_HIP_TRY(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)), p->hip_error);
+            g_scratch_ptr[device_id] = static_cast<unsigned char*>(sym);
+        }
+        base = g_scratch_ptr[device_id];
+    }
+    const PrLayout& L = p->L;
+    const size_t b_msg = round256((size_t)std::max<uint64_t>(L.M, 1) * 4), b_contrib = round256((size_t)L.V * 4),
+                 b_dpart = round256((size_t)2 * p->n_dpart * 4),
+                 b_partials = round256((size_t)std::max<uint64_t>((uint64_t)L.n_partials * L.rows_per_part, 1) * 4);
+    if (b_msg + b_contrib + b_dpart + b_partials > kStaticScratchBytes) return FR_ERR_ARG;   // too large for the array
+    DevArgs A = p->args;
+    A.msg = reinterpret_cast<float*>(base);
+    A.contrib = reinterpret_cast<float*>(base + b_msg);
+    A.dpart = reinterpret_cast<float*>(base + b_msg + b_contrib);
+    A.partials = reinterpret_cast<float*>(base + b_msg + b_contrib + b_dpart);
+    int rc = FR_OK;
+    for (uint32_t g = 0; g < p->n_segments() && rc == FR_OK; ++g) {
+        const uint32_t nt = p->tiles_of(p->kind_of(g));
+        const uint32_t step = max_tiles ? max_tiles : nt;
+        for (uint32_t t0 = 0; t0 < nt && rc == FR_OK; t0 += step)
+            rc = pr_launch(p, g, t0, std::min(nt, t0 + step), stream, GateArg{nullptr, 0, 0}, &A);
+    }
+    hipError_t e = hipStreamSynchronize(stream);
     if (rc != FR_OK) return rc;
     if (e != hipSuccess) { p->hip_error = (int)e; return FR_ERR_HIP; }
     return FR_OK;
