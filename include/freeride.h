@@ -268,7 +268,9 @@ int fr_cost_scales(fr_ctx* ctx, uint32_t* scales_ppm_out);
  * Jacobi iterations (the paper's graph-analytics side task, Section 6.1.4; one iteration = one pass over the
  * graph, Section 6.2).  InitSideTask rebuilds the CSR into a partition-centric layout on the GPU (vertices
  * renumbered by in-degree, rows cut into ranges); work is cut into tiles fixed at that point and results do not
- * depend on how tiles are grouped into launches.
+ * depend on how tiles are grouped into launches.  A launch has at most as many workgroups as the stream's compute
+ * units run side by side; if it holds more tiles, its workgroups hand them out among themselves.  The layout is cut
+ * for the compute units of the stream InitSideTask runs on, and the last bit of a rank may differ between layouts.
  * A run is the segment sequence  V0, S_0, G_0, S_1, G_1, ..., S_{K-1}, G_{K-1}, F  where
  *   V0  (vertex pass)  r_0 = 1/V: per-tile partial sums of dangling r_0;
  *   S_k (scatter)      one message contrib_k[u] = r_k[u] / outdeg[u] per (range, source u) pair; for k > 0 it first
@@ -328,8 +330,8 @@ typedef struct fr_pagerank_desc {
 typedef struct fr_pagerank_info_t {
     uint64_t messages;            /* distinct (range, source) pairs                                         */
     uint32_t ranges;              /* row ranges, ceil(V / rows_per_partition)                               */
-    uint32_t scatter_tiles;       /* source intervals of about equal numbers of messages                    */
-    uint32_t gather_tiles;        /* one heavy piece (a run of edges of one range) or several light ones    */
+    uint32_t scatter_tiles;       /* one source interval (a piece), or several light ones on small graphs   */
+    uint32_t gather_tiles;        /* one piece (a run of edges of one range), or several light ones on small graphs */
     uint32_t merged_ranges;       /* ranges cut into several gather pieces                                  */
     uint32_t nonempty_ranges;     /* ranges with in-edges (they come first: rows are ordered by in-degree)  */
     uint32_t rows_per_partition;  /* destination rows per range                                             */

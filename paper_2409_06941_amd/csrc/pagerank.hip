@@ -32,19 +32,10 @@
 
 namespace {
 
-#ifndef FR_GATHER_BLOCK
-#define FR_GATHER_BLOCK 1024
-#endif
-#ifndef FR_AHEAD
-#define FR_AHEAD 4
-#endif
-#ifndef FR_SCATTER_BLOCK
-#define FR_SCATTER_BLOCK 1024
-#endif
 constexpr int kBlock = 512;                     // threads per workgroup of the first vertex pass
-constexpr int kGatherBlock = FR_GATHER_BLOCK;   // threads per workgroup of the gather sweep
+constexpr int kGatherBlock = 1024;              // threads per workgroup of the gather sweep
 constexpr int kGatherWaves = kGatherBlock / 64;
-constexpr int kScatterBlock = FR_SCATTER_BLOCK; // threads per workgroup of the scatter sweep
+constexpr int kScatterBlock = 1024;             // threads per workgroup of the scatter sweep
 constexpr int kScatterWaves = kScatterBlock / 64;
 // row sums are kept as 64-bit fixed point with scale 2^62: contrib sums are <= 1, so they fit
 constexpr float kFixInv = 1.0f / 4611686018427387904.0f;
@@ -115,6 +106,7 @@ struct DevArgs {
     float* dpart;                 // [2][n_dpart]
     float* partials;              // [n_partials][rows_per_part]
     float* ranks_out;
+    uint32_t* sched;              // [2] tiles handed out beyond a launch's first round; workgroups that have left
 };
 
 // What a step's kernels need to ask the device gate (Section 4.5's check, made by the GPU when the kernel starts).
@@ -182,8 +174,7 @@ __device__ __forceinline__ float fill_merged(const DevArgs& A, RangeInfo info, u
 // this thread's share of the dangling mass among the rows finished here.  The tile is walked range by range (a
 // handful at most), so that each loop has one kind of row and its loads can be issued back to back.
 // `first_info`: what range_info holds for the range of u0.
-constexpr int kFillRound = 16;
-template <int kThreads>
+template <int kThreads, int kFillRound>
 __device__ __forceinline__ float fill_slice(const DevArgs& A, uint32_t u0, uint32_t n, float base, float* slice, RangeInfo first_info)
 {
     float dangling = 0.0f;
@@ -271,8 +262,39 @@ __device__ __forceinline__ uint32_t xcd_runs(uint32_t b, uint32_t n)
     return ((b / kXcds / kTileRun) * kXcds + b % kXcds) * kTileRun + (b / kXcds) % kTileRun;
 }
 
+// ---- hand-out of a launch's tiles ----
+// A launch covers the tiles tile0 .. tile0 + n - 1 of one segment with g <= n workgroups.  Workgroup b starts on
+// the b-th of them (the first g dealt by first_round).  If n > g, it asks towards the end of every tile for the next
+// tile nobody has taken: tile g + (value of a counter that every asker bumps); the answer is looked at once the
+// tile in hand is done, so most of the atomic's round trip is covered (asked at the start of a tile, the answer
+// stood in the way of the tile's first loads, which the hardware hands back in order: with all workgroups of
+// a launch asking at once that was 10 to 20 us).  The last workgroup to leave puts the two words back to zero for
+// the next launch (launches of one task run one after the other on one stream).  Which workgroup takes which tile has
+// no bearing on what the tile computes.  Thread 0 only.
+__device__ __forceinline__ uint32_t ask_next_tile(uint32_t* sched, uint32_t n_tiles)
+{
+    (void)n_tiles;
+    return gridDim.x + atomicAdd(&sched[0], 1u);
+}
+
+__device__ __forceinline__ void leave_launch(uint32_t* sched, uint32_t n_tiles)
+{
+    // (this thread's own asks have returned: their values were used)
+    (void)n_tiles;
+    if (atomicAdd(&sched[1], 1u) == gridDim.x - 1) {
+        __hip_atomic_store(&sched[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&sched[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// The two words start at zero (and every launch leaves them so).
+__global__ void k_clear_sched(uint32_t* sched)
+{
+    if (threadIdx.x < 2) sched[threadIdx.x] = 0u;
+}
+
 // ---- S_k ----
-// One workgroup per scatter tile: contrib of its sources sits in LDS, and for every range j the messages of bin
+// One workgroup per scatter tile at a time: contrib of its sources sits in LDS, and for every range j the messages of bin
 // (tile, j) - a contiguous run [x, y) of message numbers - are written.  The unit of work is a GROUP of eight
 // consecutive message numbers, aligned to eight: one 16-byte load brings the eight sources, eight LDS reads their
 // contrib, two 16-byte stores write the messages (groups cut by the ends of a bin store element by element).
@@ -352,21 +374,20 @@ __device__ __forceinline__ void emit_group(const GroupRef& ref, const uint2* des
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
 // kPacked: some tile has more than one piece (kept apart: the loop over pieces costs the small size registers it
 // does not have).
-template <uint32_t kSrcPerPart, bool kPacked>
+// kDynamic: the launch has more tiles than workgroups (else a workgroup's one tile is all it does, and the code of
+// the hand-out, which costs registers too, is left out).
+template <uint32_t kSrcPerPart, bool kPacked, bool kDynamic>
 __global__ __launch_bounds__(kScatterBlock) __attribute__((amdgpu_waves_per_eu(kSrcPerPart == kSrcSmall ? 8 : 4, kSrcPerPart == kSrcSmall ? 8 : 4)))
-void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
+void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity, int first)
 {
     __shared__ __align__(16) float slice[kSrcPerPart];
     __shared__ uint2 desc[kDescBatch];
     __shared__ uint32_t gpre[kScatterBlock + 1];          // groups before each bin of the batch; [kScatterBlock] = all
     __shared__ uint32_t wave_tot[kScatterWaves + 1];
     __shared__ float red[kScatterWaves];
+    __shared__ uint32_t next_local;
     static_assert(kDescBatch <= kScatterBlock, "one bin per thread");
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t tile = tile0 + xcd_runs(blockIdx.x, gridDim.x);
-    const uint4* rec = reinterpret_cast<const uint4*>(A.scatter_tiles + tile);
-    const uint4 span = rec[0];                                   // the tile's pieces [x, y), worked on one after the other;
-    const uint4 span_info = rec[1];                              // z, w: the sources of the first; then their range
     const uint32_t Qe = A.Qe;
     float base = 0.0f;
     if (!first) {
@@ -374,6 +395,10 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
         base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     }
     const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
+    // rows a thread reads per round while the slice is filled (the small size has 64 registers per lane)
+    constexpr int kFillRound = kSrcPerPart == kSrcSmall ? 4 : 16;
+    uint32_t asked = 0;                  // thread 0: the answer to its question for the next tile
+    bool last_piece = false;
     auto do_piece = [&](uint32_t t, ScatterPiece T, RangeInfo first_info) {
         // the first batch of bin descriptors is asked for now and used after the slice is filled
         uint2 d_first = make_uint2(0, 0);
@@ -396,9 +421,11 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
                 }
             }
         } else {
-            const float total = block_sum(fill_slice<kScatterBlock>(A, u0, n, base, slice, first_info), red);
+            const float total = block_sum(fill_slice<kScatterBlock, kFillRound>(A, u0, n, base, slice, first_info), red);
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
         }
+        if constexpr (kDynamic)
+            if (last_piece && threadIdx.x == 0) asked = ask_next_tile(A.sched, n_tiles);    // covered by the messages below
         for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
             const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
             __syncthreads();                                     // slice filled / previous batch consumed
@@ -412,7 +439,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
             }
             block_exclusive_scan(groups, gpre, wave_tot);
             const uint32_t total = gpre[kScatterBlock];
-            constexpr int kAhead = FR_AHEAD;                     // groups a thread has in flight
+            constexpr int kAhead = 4;                            // groups a thread has in flight
             for (uint32_t k0 = threadIdx.x; k0 < total; k0 += kAhead * kScatterBlock) {
                 GroupRef ref[kAhead];
                 uint4 raw[kAhead];
@@ -429,19 +456,35 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, int parity, int first)
             }
         }
     };
-    if constexpr (!kPacked) {
-        do_piece(span.x, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
-    } else {
-        for (uint32_t t = span.x; t < span.y; ++t) {
-            __syncthreads();                                     // the piece before is done with slice and desc
-            if (t == span.x) {
-                do_piece(t, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
-            } else {
-                const ScatterPiece T = A.scatter_pieces[t];
-                do_piece(t, T, first ? RangeInfo{kRangeEmpty, 0} : A.range_info[T.u0 >> A.rows_shift]);
+    uint32_t local = xcd_runs(blockIdx.x, gridDim.x);
+    do {
+        const uint4* rec = reinterpret_cast<const uint4*>(A.scatter_tiles + tile0 + local);
+        const uint4 span = rec[0];                               // x, y: the tile's pieces, worked on one after the other;
+        const uint4 span_info = rec[1];                          // z, w: the sources of the first; then their range
+        if constexpr (!kPacked) {
+            last_piece = true;
+            do_piece(span.x, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
+            __syncthreads();                                     // the piece is done with slice and desc
+        } else {
+            for (uint32_t t = span.x; t < span.y; ++t) {
+                last_piece = t + 1 == span.y;
+                if (t == span.x) {
+                    do_piece(t, ScatterPiece{span.z, span.w}, RangeInfo{span_info.x, span_info.y});
+                } else {
+                    const ScatterPiece T = A.scatter_pieces[t];
+                    do_piece(t, T, first ? RangeInfo{kRangeEmpty, 0} : A.range_info[T.u0 >> A.rows_shift]);
+                }
+                __syncthreads();                                 // the piece is done with slice and desc
             }
         }
-    }
+        if constexpr (kDynamic) {
+            if (threadIdx.x == 0) next_local = asked;
+            __syncthreads();
+            local = next_local;
+        }
+    } while (kDynamic && local < n_tiles);
+    if constexpr (kDynamic)
+        if (threadIdx.x == 0) leave_launch(A.sched, n_tiles);
     fr_gate_done(G.gate);
 }
 
@@ -483,9 +526,9 @@ __device__ __forceinline__ uint32_t id_of(const uint4& raw, int j)
 // nothing, a third or fourth buffer of messages in flight made it 6 to 9 % slower, and so did start records that
 // come through a vector load (one dword a lane, handed to the scalar side with readlane) instead of scalar loads.
 // (two workgroups of the small size share a CU: 8 wavefronts per SIMD, hence at most 64 registers per lane)
-template <uint32_t kRowsPerPart>
+template <uint32_t kRowsPerPart, bool kDynamic>
 __global__ __launch_bounds__(kGatherBlock) __attribute__((amdgpu_waves_per_eu(kRowsPerPart == kRowsSmall ? 8 : 4, kRowsPerPart == kRowsSmall ? 8 : 4)))
-void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, const uint64_t* __restrict__ starts,
+void k_gather(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity, int final_pass, const uint64_t* __restrict__ starts,
               const uint32_t* __restrict__ mbase)
 {
     constexpr uint32_t kAccSlots = kRowsPerPart;
@@ -493,22 +536,24 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
     static_assert(65535u * (8 / kIdScale) + 8 <= (kAccSlots + 1) * 8, "any id addresses a slot of acc");
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[kGatherWaves];
+    __shared__ uint32_t next_local;
     if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
-    const uint32_t tile = tile0 + blockIdx.x;
-    const uint4* rec = reinterpret_cast<const uint4*>(A.gather_tiles + tile);
-    const uint4 span = rec[0];                                   // x, y: the tile's pieces, worked on one after the other;
-    const uint4 span_more = rec[1];                              // then a copy of the first (saves a dependent load)
     const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
-    if (tile == 0 && !final_pass)                                // slots no piece and no scatter tile writes
+    if (tile0 == 0 && blockIdx.x == 0 && !final_pass)            // slots no piece and no scatter tile writes
         for (uint32_t i = A.n_pieces + A.n_spieces + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
+    uint32_t local = blockIdx.x;
+    do {
+    const uint4* rec = reinterpret_cast<const uint4*>(A.gather_tiles + tile0 + local);
+    const uint4 span = rec[0];                                   // x, y: the tile's pieces, worked on one after the other;
+    const uint4 span_more = rec[1];                              // then a copy of the first (saves a dependent load)
+    uint32_t asked = 0;
     for (uint32_t t = span.x; t < span.y; ++t) {
     const GatherPiece T = t == span.x ? GatherPiece{span.z, span.w, span_more.x, span_more.y} : A.gather_pieces[t];
     const uint32_t q = T.range;
     const int64_t left = A.V - (int64_t)q * kRowsPerPart;
     const uint32_t nrows = (uint32_t)(left < (int64_t)kRowsPerPart ? left : (int64_t)kRowsPerPart);
-    __syncthreads();                                             // the piece before is done with acc
     for (uint32_t i = threadIdx.x; i < kAccSlots + 1; i += kGatherBlock) acc[i] = 0ull;
     __syncthreads();
 
@@ -624,14 +669,15 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
         stage_c(Y);
     }
     __syncthreads();
+    if constexpr (kDynamic)
+        if (t + 1 == span.y && threadIdx.x == 0) asked = ask_next_tile(A.sched, n_tiles);   // covered by the row pass below
 
     if (T.partial != kNoPartial) {
         // merged range: the sums go out as one row of partial sums; the next scatter sweep (or F) finishes the rows
         float* out = A.partials + (size_t)T.partial * kRowsPerPart;
         for (uint32_t i = threadIdx.x; i < kRowsPerPart; i += kGatherBlock) out[i] = (float)acc[i] * kFixInv;
         if (threadIdx.x == 0 && !final_pass) dnext[t] = 0.0f;
-        continue;
-    }
+    } else {
     // direct range: fused vertex pass for its rows
     const int64_t v0 = (int64_t)q * kRowsPerPart;
     float dangling = 0.0f;
@@ -660,7 +706,17 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, int parity, int final_pass, 
         const float total = block_sum(dangling, red);
         if (threadIdx.x == 0) dnext[t] = total;
     }
+    }
+    __syncthreads();                                             // the piece is done with acc
     }       // pieces
+    if constexpr (kDynamic) {
+        if (threadIdx.x == 0) next_local = asked;
+        __syncthreads();
+        local = next_local;
+    }
+    } while (kDynamic && local < n_tiles);       // tiles
+    if constexpr (kDynamic)
+        if (threadIdx.x == 0) leave_launch(A.sched, n_tiles);
     fr_gate_done(G.gate);
 }
 
@@ -704,6 +760,7 @@ struct PrTask {
     std::vector<uint64_t> prefix[4];      // cumulative modelled tile costs per segment kind (after init)
     uint64_t footprint_after = 0, footprint_peak = 0;
     float *msg = nullptr, *contrib = nullptr, *dpart = nullptr, *partials = nullptr;
+    uint32_t* sched = nullptr;
     uint32_t n_dpart = 0;
     DevArgs args{};
     bool inited = false;
@@ -777,21 +834,25 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
         const uint32_t k = (g - 1) / 2;
         if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes rows of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
-            const bool packed = p->L.n_scatter != p->L.n_spieces;
-            if (p->L.src_per_part == kSrcLarge)
-                hipLaunchKernelGGL((k_scatter<kSrcLarge, true>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
-            else if (packed)
-                hipLaunchKernelGGL((k_scatter<kSrcSmall, true>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
-            else
-                hipLaunchKernelGGL((k_scatter<kSrcSmall, false>), dim3(n), dim3(kScatterBlock), 0, stream, args, G, tile0, parity, first);
+            const uint32_t grid = std::min(n, p->L.scatter_slots);
+            const bool packed = p->L.n_scatter != p->L.n_spieces, dynamic = n > grid;
+            auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(kScatterBlock), 0, stream, args, G, tile0, n, parity, first); };
+            if (p->L.src_per_part == kSrcLarge) {
+                if (packed) { if (dynamic) go(k_scatter<kSrcLarge, true, true>); else go(k_scatter<kSrcLarge, true, false>); }
+                else { if (dynamic) go(k_scatter<kSrcLarge, false, true>); else go(k_scatter<kSrcLarge, false, false>); }
+            } else {
+                if (packed) { if (dynamic) go(k_scatter<kSrcSmall, true, true>); else go(k_scatter<kSrcSmall, true, false>); }
+                else { if (dynamic) go(k_scatter<kSrcSmall, false, true>); else go(k_scatter<kSrcSmall, false, false>); }
+            }
         } else {
             const int parity = (int)(k & 1u), final_pass = (k + 1 == K) ? 1 : 0;
-            if (p->L.rows_per_part == kRowsLarge)
-                hipLaunchKernelGGL(k_gather<kRowsLarge>, dim3(n), dim3(kGatherBlock), 0, stream, args, G, tile0, parity, final_pass,
-                                   args.starts, args.mbase);
-            else
-                hipLaunchKernelGGL(k_gather<kRowsSmall>, dim3(n), dim3(kGatherBlock), 0, stream, args, G, tile0, parity, final_pass,
-                                   args.starts, args.mbase);
+            const uint32_t grid = std::min(n, p->L.gather_slots);
+            const bool dynamic = n > grid;
+            auto go = [&](auto kernel) {
+                hipLaunchKernelGGL(kernel, dim3(grid), dim3(kGatherBlock), 0, stream, args, G, tile0, n, parity, final_pass, args.starts, args.mbase);
+            };
+            if (p->L.rows_per_part == kRowsLarge) { if (dynamic) go(k_gather<kRowsLarge, true>); else go(k_gather<kRowsLarge, false>); }
+            else { if (dynamic) go(k_gather<kRowsSmall, true>); else go(k_gather<kRowsSmall, false>); }
         }
     }
     hipError_t e = hipGetLastError();
@@ -839,8 +900,10 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     // dangling partials: one slot per range (V0), or one per gather piece followed by one per scatter piece
     p->n_dpart = std::max(L.Q, L.n_pieces + L.n_spieces);
     if (!take(a, &p->msg, L.M) || !take(a, &p->contrib, (uint64_t)V) || !take(a, &p->dpart, 2ull * p->n_dpart) ||
-        !take(a, &p->partials, (uint64_t)L.n_partials * L.rows_per_part))
+        !take(a, &p->partials, (uint64_t)L.n_partials * L.rows_per_part) || !take(a, &p->sched, 2))
         return a->hip_error ? FR_ERR_HIP : FR_ERR_OOM;
+    hipLaunchKernelGGL(k_clear_sched, dim3(1), dim3(64), 0, stream, p->sched);
+    if (hipStreamSynchronize(stream) != hipSuccess) return FR_ERR_HIP;
     DevArgs& A = p->args;
     A.V = V; A.E = E; A.M = (uint32_t)L.M; A.Q = L.Q; A.Qe = L.Qe;
     A.n_gather = L.n_gather; A.n_pieces = L.n_pieces; A.n_scatter = L.n_scatter; A.n_spieces = L.n_spieces;
@@ -853,6 +916,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     A.gather_pieces = L.gather_pieces; A.gather_tiles = L.gather_tiles;
     A.scatter_pieces = L.scatter_pieces; A.scatter_tiles = L.scatter_tiles; A.finish_ranges = L.finish_ranges;
     A.msg = p->msg; A.contrib = p->contrib; A.dpart = p->dpart; A.partials = p->partials; A.ranks_out = p->d.ranks_out;
+    A.sched = p->sched;
     build_cost_tables(p);
     p->footprint_after = fr_alloc_used(a);
     p->footprint_peak = fr_alloc_peak(a);
@@ -1124,12 +1188,15 @@ int fr_pagerank_run_standalone_noalloc(void* user, int32_t device_id, void* stre
     const size_t b_msg = round256((size_t)std::max<uint64_t>(L.M, 1) * 4), b_contrib = round256((size_t)L.V * 4),
                  b_dpart = round256((size_t)2 * p->n_dpart * 4),
                  b_partials = round256((size_t)std::max<uint64_t>((uint64_t)L.n_partials * L.rows_per_part, 1) * 4);
-    if (b_msg + b_contrib + b_dpart + b_partials > kStaticScratchBytes) return FR_ERR_ARG;   // too large for the array
+    constexpr size_t b_sched = 256;
+    if (b_msg + b_contrib + b_dpart + b_partials + b_sched > kStaticScratchBytes) return FR_ERR_ARG;   // too large for the array
     DevArgs A = p->args;
     A.msg = reinterpret_cast<float*>(base);
     A.contrib = reinterpret_cast<float*>(base + b_msg);
     A.dpart = reinterpret_cast<float*>(base + b_msg + b_contrib);
     A.partials = reinterpret_cast<float*>(base + b_msg + b_contrib + b_dpart);
+    A.sched = reinterpret_cast<uint32_t*>(base + b_msg + b_contrib + b_dpart + b_partials);
+    hipLaunchKernelGGL(k_clear_sched, dim3(1), dim3(64), 0, stream, A.sched);     // the hand-out words must start at zero
     int rc = FR_OK;
     for (uint32_t g = 0; g < p->n_segments() && rc == FR_OK; ++g) {
         const uint32_t nt = p->tiles_of(p->kind_of(g));

@@ -15,10 +15,6 @@
 
 #include "pr_layout.h"
 
-#ifndef FR_SMALL_SLOTS
-#define FR_SMALL_SLOTS 2
-#endif
-
 namespace {
 
 constexpr int kBlk = 256;
@@ -441,16 +437,22 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     {
         // A piece costs its weight plus a fixed part (kTileFixedWeight: the chain of dependent loads at its start and
         // the row pass at its end).  Ranges are cut into pieces of at most `body` weight; pieces are then grouped, in
-        // order, into tiles of at most body + kTileFixedWeight.  `body` is the smallest (to 2 %) that gives no more
-        // tiles than workgroups run side by side.
-        const uint64_t slots = (uint64_t)cus * (rows_per_part == kRowsSmall ? FR_SMALL_SLOTS : 1);
+        // order, into tiles of at most body + kTileFixedWeight.  A launch has no more workgroups than run side by
+        // side (`slots`), each of which takes the next tile when it is done with one.  Where a slot's share of the
+        // sweep is long against what a tile costs to start and to end (kGatherFineShare), heavy ranges are cut for
+        // two pieces per slot and every piece is a tile of its own, so that the many light tiles at the end fill
+        // the gaps the heavy ones leave; below that there are no more tiles than slots, light pieces share tiles, and
+        // `body` is the smallest (to 2 %) that achieves it.
+        const uint64_t slots = (uint64_t)cus * (rows_per_part == kRowsSmall ? 2 : 1);
         std::vector<uint64_t> w(Qe);
         uint64_t total = 0;
         for (uint32_t j = 0; j < Qe; ++j) { w[j] = weight_at(eoff_host[j + 1]) - weight_at(eoff_host[j]); total += w[j]; }
+        const uint64_t share = (total + slots - 1) / slots;
+        const uint64_t fine = share >= kGatherFineShare ? 2 : 1;
         std::vector<GatherPiece> pieces;
         std::vector<uint64_t> piece_w;
         std::vector<uint2> tiles;
-        uint64_t body = std::max<uint64_t>(kMinTileEdges * kGatherEdgeWeight, (total + slots - 1) / slots);
+        uint64_t body = std::max<uint64_t>(kMinTileEdges * kGatherEdgeWeight, (total + slots * fine - 1) / (slots * fine));
         for (int round = 0; round < 400; ++round, body += body / 50 + 1) {
             pieces.clear(); piece_w.clear(); tiles.clear();
             L->ri.assign(Q, RangeInfo{kRangeEmpty, 0});
@@ -487,14 +489,14 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             uint64_t in_tile = 0;
             uint32_t first = 0;
             for (uint32_t i = 0; i < pieces.size(); ++i) {
-                if (i > first && in_tile + piece_w[i] > body + kTileFixedWeight) {
+                if (i > first && (fine > 1 || in_tile + piece_w[i] > body + kTileFixedWeight)) {
                     tiles.push_back(make_uint2(first, i));
                     first = i; in_tile = 0;
                 }
                 in_tile += piece_w[i];
             }
             tiles.push_back(make_uint2(first, (uint32_t)pieces.size()));
-            if (tiles.size() <= slots) break;
+            if (fine > 1 || tiles.size() <= slots) break;
         }
         for (uint32_t j = Qe; j < Q; ++j) L->fin.push_back(j);
         L->gp = pieces;
@@ -507,6 +509,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             L->gt_edges.push_back(esum);
         }
     }
+    L->gather_slots = cus * (rows_per_part == kRowsSmall ? 2u : 1u);
+    L->scatter_slots = cus * (src_per_part == kSrcSmall ? 2u : 1u);
     L->n_pieces = (uint32_t)L->gp.size();
     L->n_gather = (uint32_t)L->gt.size();
     L->n_finish = (uint32_t)L->fin.size();
@@ -516,8 +520,11 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     // finish it (its contrib or 1/outdeg, and the partial sums of a row of a merged range); the pieces of the sources
     // with few messages are as wide as allowed and light whatever the target.  A tile is a run of consecutive pieces
     // whose costs (weight + kScatterFixedWeight a piece, for the chain of dependent loads at its start) add up to at
-    // most target + kScatterFixedWeight.  The target is the smallest one (to 2 %) that leaves no more tiles than
-    // workgroups run side by side.
+    // most target + kScatterFixedWeight.  A launch has no more workgroups than run side by side (`slots`), each of
+    // which takes the next tile when it is done with one; with `fine` tiles per slot the light tiles at the end fill
+    // the gaps the heavy ones leave, which pays where a slot's share of the sweep is long: from kScatterFineShare on
+    // the pieces are cut for two per slot and each is a tile of its own.  Below that the target is the smallest one
+    // (to 2 %) that leaves no more tiles than slots.
     std::vector<uint32_t> ubound;
     std::vector<uint2> stiles;
     {
@@ -566,9 +573,15 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         };
         const uint64_t slots = (uint64_t)cus * (src_per_part == kSrcSmall ? 2 : 1);
         const uint64_t all = weight_before((uint64_t)V), least = kMinTileMessages * kScatterMessageWeight;
-        const uint64_t start = std::max<uint64_t>(least, (all + slots - 1) / slots);
+        const uint64_t share = (all + slots - 1) / slots;
+        const uint64_t fine = share >= kScatterFineShare ? 2 : 1;
+        const uint64_t start = std::max<uint64_t>(least, (all + slots * fine - 1) / (slots * fine));
         bool done = false;
-        if (src_per_part == kSrcSmall) {
+        if (fine > 1) {
+            cut(start);
+            pack(0);
+            done = true;
+        } else if (src_per_part == kSrcSmall) {
             // the small kernel is faster without the loop over pieces: a tile per piece, if a target up to one
             // compute unit's share of the weight leaves few enough pieces
             const uint64_t most = std::max<uint64_t>(least, (all + cus - 1) / cus);

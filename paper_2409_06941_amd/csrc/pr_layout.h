@@ -21,22 +21,23 @@
 //     sums do not depend on the order the hardware performs them in.
 //
 // Ordering by degree makes the ranges very unequal (the first range of that graph holds 42 % of the edges), so
-// the unit of work is not the range but a TILE of about equal work:
-//   * the gather sweep works in PIECES, runs of consecutive edges of one range (hence a source interval of it).
-//     A gather tile is one heavy piece, or several light pieces in a row that one workgroup takes one after the
-//     other: all tiles cost about the same, and there are no more of them than workgroups run side by side
-//     (a second round of workgroups only starts where a whole first-round workgroup has ended, which was
-//     measured to leave a quarter of the sweep's time half idle).  A range that needs several pieces is a MERGED
-//     range: each of its pieces stores its row sums as one row of fp32 partial sums (plain stores, no global
-//     atomics: 2.5 million 64-bit atomics from 150 workgroups were measured at 22 us on an otherwise idle chip),
-//     and the rows are finished - partial sums added in a fixed tree order, then r and contrib - at the start
-//     of the next scatter sweep.  This also spreads rows with very many in-edges over many
-//     workgroups; no other treatment of such rows is needed.  A range with one piece is DIRECT: its piece
-//     finishes its rows itself;
-//   * the scatter sweep works in pieces too: intervals of at most src_per_part consecutive sources with about
-//     equal numbers of messages (narrow for the sources that point into many ranges), heavy ones a tile each, light
-//     ones several to a tile; every source belongs to exactly one piece, so the finishing of merged rows is done
-//     once per row;
+// the unit of work is not the range but a TILE:
+//   * a gather tile is a PIECE, a run of consecutive edges of one range (hence a source interval of it).  A range
+//     heavier than a workgroup's share of the sweep is cut into several pieces and is a MERGED range: each of its
+//     pieces stores its row sums as one row of fp32 partial sums (plain stores, no global atomics: 2.5 million
+//     64-bit atomics from 150 workgroups were measured at 22 us on an otherwise idle chip), and the rows are
+//     finished - partial sums added in a fixed tree order, then r and contrib - at the start of the next scatter
+//     sweep.  This also spreads rows with very many in-edges over many workgroups; no other treatment of such rows
+//     is needed.  A range with one piece is DIRECT: its piece finishes its rows itself;
+//   * a scatter tile is a piece too: an interval of at most src_per_part consecutive sources, cut by weight
+//     (messages + values read; narrow for the sources that point into many ranges); every source belongs to exactly
+//     one piece, so the finishing of merged rows is done once per row;
+//   * a launch has at most as many workgroups as run side by side; each starts on the tile of its own number and,
+//     when done, takes the next tile nobody has taken yet (one atomic counter per task, reset by the last
+//     workgroup to leave).  Tiles are in order of falling weight, so the light ones at the end fill the gaps the
+//     heavy ones leave.  (With one fixed tile list per workgroup, cut by modelled weights, the sweeps of a graph of
+//     2^26 vertices ran 14 % and 28 % over the mean time of their workgroups.)  What a tile computes does not depend
+//     on which workgroup takes it;
 //   * ranges behind the last row with an in-edge are EMPTY and have no gather piece: their rows' rank is the
 //     iteration's base value, which the scatter sweep puts into its slice without reading a sum.
 #pragma once
@@ -56,23 +57,19 @@ constexpr int kKeyLocalBits = 15;            // sort key = range << 46 | source 
 constexpr uint32_t kLocalMask = (1u << kKeyLocalBits) - 1;
 static_assert(kRowsLarge <= (1u << kKeyLocalBits) && kSrcLarge <= 65536, "id fields");
 constexpr int kKeySrcBits = 31;
-constexpr uint32_t kDefaultCus = 256;        // a sweep is cut into as many tiles as workgroups run side by side ...
+constexpr uint32_t kDefaultCus = 256;        // heavy ranges and source intervals are cut for this many workgroups side by side ...
 constexpr uint64_t kMinTileEdges = 32768;    // ... but no smaller than this (in weight: times kGatherEdgeWeight)
 constexpr uint64_t kMinTileMessages = 16384;
 // weight of a gather tile = kGatherEdgeWeight * edges + kGatherMessageWeight * messages + kGatherRepeatWeight *
-// repeated edges; its cost in the cutter adds kTileFixedWeight
-#ifndef FR_W_EDGE
-#define FR_W_EDGE 2
-#define FR_W_MSG 0
-#define FR_W_REP 6
-#define FR_W_FIX 147456
-#endif
-// weight of a scatter piece = messages + values read for its sources (measured: a row of partial sums costs a tile
-// about as much as a message, with one or with two workgroups per compute unit); its cost in the packer adds
-// kScatterFixedWeight
+// repeated edges + kTileFixedWeight
+constexpr uint64_t kGatherEdgeWeight = 2, kGatherMessageWeight = 0, kGatherRepeatWeight = 6, kTileFixedWeight = 147456;
+// weight of a scatter tile = messages + values read for its sources (measured: a row of partial sums costs a tile
+// about as much as a message, with one or with two workgroups per compute unit) + kScatterFixedWeight
 constexpr uint64_t kScatterMessageWeight = 1, kScatterRowWeight = 1, kScatterFixedWeight = 8192;
-constexpr uint64_t kGatherEdgeWeight = FR_W_EDGE, kGatherMessageWeight = FR_W_MSG, kGatherRepeatWeight = FR_W_REP,
-                   kTileFixedWeight = FR_W_FIX;
+// a slot's share of a sweep's weight from which on the sweep is cut fine: heavy parts for two pieces per slot, every
+// piece a tile (measured: 2^24 vertices / 2^28 edges gains 15 % in the gather sweep and nothing in the scatter sweep,
+// 2^26 / 2^30 gains 20 % and 24 %, 2^22 / 2^26 loses in both; three, four or six pieces per slot are no better than two)
+constexpr uint64_t kGatherFineShare = 2000000, kScatterFineShare = 1000000;
 
 // An id is stored as the byte offset of its row's 8-byte accumulator, or half of it where that needs 17 bits.
 constexpr uint32_t id_scale_for(uint32_t rows_per_part) { return rows_per_part <= 8192 ? 8u : 4u; }
@@ -84,11 +81,11 @@ struct GatherPiece { uint32_t range, e0, e1, partial; };   // edges [e0, e1) of 
                                                            // sums the piece writes (kNoPartial: direct range)
 struct ScatterPiece { uint32_t u0, u1; };                  // sources [u0, u1)
 struct RangeInfo { uint32_t cls_tiles, partial0; };        // class | gather tiles << 2; first row of partial sums
-// pieces [p0, p1) of a scatter tile; the sources [u0, u1) of piece p0 and the range of u0 come along, so that the
-// workgroup's first loads of vertex data depend on one load only
+// a scatter tile: its piece p0 (p1 = p0 + 1), the piece's sources [u0, u1) and what range_info holds for the range of
+// u0, so that the workgroup's first loads of vertex data depend on one load only
 struct alignas(32) ScatterTile { uint32_t p0, p1, u0, u1; RangeInfo first; uint32_t pad[2]; };
 static_assert(sizeof(ScatterTile) == 32, "read as two 16-byte words");
-// pieces [p0, p1) of a gather tile, with a copy of piece p0 for the same reason
+// a gather tile: its piece p0 (p1 = p0 + 1) and a copy of it, for the same reason
 struct alignas(32) GatherTile { uint32_t p0, p1; GatherPiece first; uint32_t pad[2]; };
 static_assert(sizeof(GatherTile) == 32, "read as two 16-byte words");
 
@@ -100,7 +97,8 @@ struct PrLayout {
     uint32_t Qe = 0;                 // ranges with at least one in-edge (they come first)
     uint32_t n_pieces = 0;           // gather pieces: runs of edges of one range
     uint32_t n_spieces = 0;          // scatter pieces: intervals of sources
-    uint32_t n_gather = 0, n_scatter = 0;   // tiles (a tile is one heavy piece or several light ones in a row)
+    uint32_t n_gather = 0, n_scatter = 0;   // tiles (= pieces)
+    uint32_t gather_slots = 0, scatter_slots = 0;   // workgroups of a sweep that run side by side
     uint32_t n_merged = 0;           // ranges cut into several gather pieces
     uint32_t n_partials = 0;         // gather pieces of merged ranges = rows of partial sums
     uint32_t n_finish = 0;           // merged + empty ranges (the tiles of the pass after the last iteration)
@@ -127,7 +125,7 @@ struct PrLayout {
     // host copies for the cost model
     std::vector<GatherPiece> gp;
     std::vector<GatherTile> gt;
-    std::vector<uint64_t> gt_weight;     // weight of each gather tile (its pieces' weights, kTileFixedWeight a piece included)
+    std::vector<uint64_t> gt_weight;     // weight of each gather tile (kTileFixedWeight included)
     std::vector<uint64_t> gt_edges;      // edges of each gather tile
     std::vector<ScatterPiece> sp;
     std::vector<ScatterTile> st;
@@ -141,7 +139,7 @@ struct PrLayout {
 // rows_per_part / src_per_part: 0 = chosen from V, else one of the two sizes above (FR_ERR_ARG otherwise).
 // Temporary memory is taken from and returned to `a`.  Returns FR_OK, FR_ERR_OOM, FR_ERR_HIP or FR_ERR_ARG
 // (malformed CSR).  `hip_error` receives the failing HIP code, if any.
-// cus: compute units the sweeps will have (tiles are made for that many workgroups side by side).
+// cus: compute units the sweeps will have (heavy ranges and source intervals are cut for that many workgroups).
 int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, const int32_t* col,
                     const int32_t* out_degree, uint32_t rows_per_part, uint32_t src_per_part, uint32_t cus, fr_alloc* a,
                     hipStream_t stream, int* hip_error);

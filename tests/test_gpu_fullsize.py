@@ -48,11 +48,15 @@ def test_full_size_harvested_run_matches_oracle_and_standalone_bits(name):
     ref = torch.zeros(V, dtype=torch.float32, device="cuda")
     ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
 
+    # (on a stream with the configuration's CU mask: the layout is cut for the compute units of the stream it is built
+    # on, and a range cut into several pieces adds its partial sums in fp32, so bits are only the same per CU count)
     print("standalone run, 37 tiles per launch", flush=True)
+    probe = fr.Context(device_id=0, cu_count=cu_count)
     t = fr.PageRankTask(V, E, rp, col, od, ref, damping=cfg.damping, iterations=K, mem_limit_bytes=mem_cap)
-    t.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), 37)
+    t.fr_pagerank_run_standalone(0, probe.fr_side_stream(), 37)
     info = t.fr_pagerank_info()
     t.fr_pagerank_destroy()
+    probe.fr_destroy()
     assert info.bytes_resident <= info.bytes_peak <= mem_cap            # set-up scratch included
 
     print("harvested run beside the GEMM stage load", flush=True)
