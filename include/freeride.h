@@ -339,6 +339,9 @@ typedef struct fr_pagerank_info_t {
     uint32_t partial_rows;        /* gather pieces of merged ranges (rows of fp32 partial sums)             */
     uint64_t bytes_resident;      /* booked against the limit after init (caller buffers included)          */
     uint64_t bytes_peak;          /* highest amount booked during init (set-up scratch included)            */
+    uint32_t scatter_slots;       /* workgroups of a scatter launch / of a gather launch that run side by side on  */
+    uint32_t gather_slots;        /* the stream's compute units: a step of more tiles runs in rounds, and plan_step
+                                     cuts a step that does not reach its segment's end to whole rounds             */
 } fr_pagerank_info_t;
 
 /* Builds the task object and fills in the callbacks and profile to register with.  No device work yet. */
@@ -515,6 +518,19 @@ int fr_stage_ops(fr_stage* s, fr_stage_op* buf, size_t cap, size_t* n_out, uint6
    (may be NULL: nothing is reported, the stage just waits) with fr_bubble_begin, waited out on the host
    clock, and closed with fr_bubble_end. */
 int fr_stage_run_epoch(fr_stage* s, fr_ctx* ctx, fr_epoch_result* out);
+/*
+ * For measuring the stage's slowdown (Section 6.1.5: I = (T_with - T_no) / T_no).  A GPU whose bubbles are idle
+ * may run its next burst at other clocks than one whose bubbles are harvested, which an A/B of "with side task"
+ * against "idle bubbles" cannot tell from interference.  With a filler set, epochs run with ctx == NULL fill every
+ * bubble longer than guard_ns with a kernel of `workgroups` workgroups of 256 threads on `stream` that does
+ * register-only arithmetic for the bubble's length minus guard_ns (no memory traffic; it ends by the GPU clock, or
+ * by a trip cap), and wait for it at the bubble's end: a baseline that differs from a harvested epoch by the side
+ * task's memory traffic only.  workgroups = 0 switches the filler off.  Epochs with a ctx are not affected.
+ */
+int fr_stage_set_filler(fr_stage* s, void* stream, uint32_t workgroups, uint64_t guard_ns);
+/* Host-clock durations (enqueue to completion) of the latest epoch's operations, in the order of fr_stage_ops;
+   *n_out = their number. */
+int fr_stage_op_times(fr_stage* s, uint64_t* ns_host, size_t cap, size_t* n_out);
 
 #ifdef __cplusplus
 }

@@ -27,6 +27,12 @@ bubble lengths and the cost table -- no clock is read.
 The floor is the profiled duration of the segment's shortest step (Section 4.3 profiles the per-step duration):
 tiles of one step run side by side on the GPU, so a step of a few tiles is not shorter than a step of one.
 
+Rounds (optional, per segment): a task may say that at most `slots` tiles of a segment run side by side and that a
+step of more tiles runs in rounds, its modelled cost - the sum - being what whole rounds take.  Section 4.5 lets a
+step run only if the time left is enough for it, so a step must not take longer than modelled: a chunk of more
+than `slots` tiles that does not reach the segment's end is cut down to a whole number of rounds,
+n -> (n // slots) * slots (a round and a few tiles would take two rounds' time).  slots = 0: no such rule.
+
 When the last segment of a run completes the task starts over (run index + 1) unless `max_runs` is reached,
 after which it harvests nothing more.
 """
@@ -47,9 +53,10 @@ class Record:
 
 def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard: int, launch_cost: int,
          max_chunk: int, max_runs: Optional[int] = None, start_created: bool = True,
-         floors: Optional[Sequence[int]] = None) -> List[Record]:
+         floors: Optional[Sequence[int]] = None, slots: Optional[Sequence[int]] = None) -> List[Record]:
     """Plan over the given bubbles.  segments[g][t] is the modelled cost of tile t of segment g (ints >= 0);
-    floors[g] (default 0) is the least modelled cost of any step of segment g.
+    floors[g] (default 0) is the least modelled cost of any step of segment g; slots[g] (default 0 = no rule) is the
+    number of tiles of segment g that run side by side (see "Rounds" above).
 
     start_created: the task begins in CREATED, so the first bubble is consumed by initialisation.
     """
@@ -57,6 +64,10 @@ def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard
         floors = [0] * len(segments)
     if len(floors) != len(segments) or any(f < 0 for f in floors):
         raise ValueError("one non-negative floor per segment")
+    if slots is None:
+        slots = [0] * len(segments)
+    if len(slots) != len(segments) or any(x < 0 for x in slots):
+        raise ValueError("one non-negative slot count per segment")
     if launch_cost < 0 or guard < 0 or max_chunk <= 0:
         raise ValueError("bad planner constants")
     if any(len(seg) == 0 for seg in segments) or len(segments) == 0:
@@ -81,6 +92,9 @@ def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard
             while tile + n < len(costs) and launch_cost + max(tiles_cost + costs[tile + n], floors[seg]) <= budget:
                 tiles_cost += costs[tile + n]
                 n += 1
+            if slots[seg] and n > slots[seg] and tile + n < len(costs):
+                n = n // slots[seg] * slots[seg]
+                tiles_cost = sum(costs[tile:tile + n])
             total = launch_cost + max(tiles_cost, floors[seg])
             if n == 0:
                 out.append(Record("IDLE", i, run, seg, tile, tile, max(remaining, 0)))

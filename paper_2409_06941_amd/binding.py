@@ -83,7 +83,8 @@ class fr_pagerank_info_t(C.Structure):
     _fields_ = [("messages", C.c_uint64), ("ranges", C.c_uint32), ("scatter_tiles", C.c_uint32),
                 ("gather_tiles", C.c_uint32), ("merged_ranges", C.c_uint32), ("nonempty_ranges", C.c_uint32),
                 ("rows_per_partition", C.c_uint32), ("sources_per_partition", C.c_uint32), ("partial_rows", C.c_uint32),
-                ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64)]
+                ("bytes_resident", C.c_uint64), ("bytes_peak", C.c_uint64), ("scatter_slots", C.c_uint32),
+                ("gather_slots", C.c_uint32)]
 
 
 class fr_sgd_desc(C.Structure):
@@ -169,6 +170,8 @@ SIGNATURES = {
     "fr_stage_destroy": (C.c_int, [C.c_void_p]),
     "fr_stage_ops": (C.c_int, [C.c_void_p, C.POINTER(fr_stage_op), C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "fr_stage_run_epoch": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(fr_epoch_result)]),
+    "fr_stage_set_filler": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64]),
+    "fr_stage_op_times": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.c_size_t, C.POINTER(C.c_size_t)]),
 }
 
 _lib = None
@@ -486,6 +489,16 @@ class Stage:
         _check(lib().fr_stage_run_epoch(self.handle, ctx.handle if ctx is not None else None, C.byref(out)),
                "fr_stage_run_epoch")
         return out
+
+    def fr_stage_set_filler(self, stream=None, workgroups=0, guard_ns=0):
+        _check(lib().fr_stage_set_filler(self.handle, _stream(stream), workgroups, guard_ns), "fr_stage_set_filler")
+
+    def fr_stage_op_times(self):
+        n = C.c_size_t()
+        _check(lib().fr_stage_op_times(self.handle, None, 0, C.byref(n)), "fr_stage_op_times")
+        buf = (C.c_uint64 * max(1, n.value))()
+        _check(lib().fr_stage_op_times(self.handle, buf, n.value, C.byref(n)), "fr_stage_op_times")
+        return list(buf)[:n.value]
 
     def fr_stage_destroy(self):
         if self.handle:

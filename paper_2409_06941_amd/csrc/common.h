@@ -26,6 +26,7 @@ void fr_alloc_release(fr_alloc* a);   // frees every block handed out
 
 // Stage-load kernels (gemm.hip).
 int fr_busywait_launch(uint64_t ns, int wall_clock_khz, hipStream_t stream);
+int fr_alufill_launch(uint64_t ns, int wall_clock_khz, uint32_t workgroups, hipStream_t stream);
 
 #define FR_HIP_TRY(expr, errslot)                      \
     do {                                               \

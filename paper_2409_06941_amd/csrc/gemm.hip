@@ -139,6 +139,22 @@ __global__ void k_busywait(uint64_t ticks, uint64_t max_trips)
     }
 }
 
+// Keeps compute units busy with register-only arithmetic (no memory traffic) until the GPU's constant-rate clock has
+// advanced by `ticks`: what fills the bubbles of the baseline that differs from a harvested epoch only by the side
+// task's memory traffic.  The trip cap ends the kernel even if the clock did not advance; the result is stored only
+// if it is NaN (it never is), so the loop cannot be optimised away.
+__global__ __launch_bounds__(256) void k_alu_fill(uint64_t ticks, uint64_t max_trips, float* sink)
+{
+    const uint64_t t0 = wall_clock64();
+    float a = (float)threadIdx.x * 1.0e-3f, b = 0.999f, c = 1.0e-4f;
+    for (uint64_t i = 0; i < max_trips; ++i) {
+        if (wall_clock64() - t0 >= ticks) break;
+#pragma unroll
+        for (int k = 0; k < 64; ++k) a = fmaf(a, b, c);
+    }
+    if (a != a && sink) *sink = a;
+}
+
 struct GemmShape { int M, N, K; size_t a_off, b_off, c_off; };   // offsets in bf16 elements into the workspace
 
 }  // namespace
@@ -212,6 +228,14 @@ int fr_busywait_launch(uint64_t ns, int wall_clock_khz, hipStream_t stream)
     const uint64_t ticks = (uint64_t)((unsigned __int128)ns * (uint64_t)wall_clock_khz / 1000000ull);
     const uint64_t max_trips = ns / 20 + 4096;        // one trip takes well over 20 ns
     hipLaunchKernelGGL(k_busywait, dim3(1), dim3(64), 0, stream, ticks, max_trips);
+    return hipGetLastError() == hipSuccess ? FR_OK : FR_ERR_HIP;
+}
+
+int fr_alufill_launch(uint64_t ns, int wall_clock_khz, uint32_t workgroups, hipStream_t stream)
+{
+    const uint64_t ticks = (uint64_t)((unsigned __int128)ns * (uint64_t)wall_clock_khz / 1000000ull);
+    const uint64_t max_trips = ns / 50 + 4096;        // one trip (64 dependent fused multiply-adds) takes well over 50 ns
+    hipLaunchKernelGGL(k_alu_fill, dim3(workgroups ? workgroups : 1), dim3(256), 0, stream, ticks, max_trips, (float*)nullptr);
     return hipGetLastError() == hipSuccess ? FR_OK : FR_ERR_HIP;
 }
 

@@ -947,6 +947,12 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     int rc = fr_chunk_fit(pre.data(), p->tiles_of(kind), p->tile, budget_ns, launch_cost_ns, &n);
     if (rc != FR_OK) return rc;
     if (n == 0) return FR_OK;
+    // A launch of more tiles than workgroups runs in rounds, each workgroup taking a next tile when it is done with
+    // one; the summed tile costs are what whole rounds take.  A step that does not reach the segment's end is
+    // therefore cut to whole rounds (the tiles are in order of falling weight, so the light ones that close the
+    // segment's last round smoothly are at its end): a round and a few tiles would take two rounds' time.
+    const uint32_t slots = kind == FR_PR_SEG_SCATTER ? p->L.scatter_slots : kind == FR_PR_SEG_GATHER ? p->L.gather_slots : 0;
+    if (slots && n > slots && p->tile + n < p->tiles_of(kind)) n = n / slots * slots;
     out->tile1 = p->tile + n;
     out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     if (kind == FR_PR_SEG_GATHER) {
@@ -1063,6 +1069,8 @@ int fr_pagerank_info(void* user, fr_pagerank_info_t* out)
     out->sources_per_partition = p->L.src_per_part;
     out->bytes_resident = p->footprint_after;
     out->bytes_peak = p->footprint_peak;
+    out->scatter_slots = p->L.scatter_slots;
+    out->gather_slots = p->L.gather_slots;
     return FR_OK;
 }
 

@@ -97,6 +97,11 @@ struct fr_stage {
     bool own_stream = false;
     std::vector<fr_stage_op> ops;
     uint64_t epoch_ns = 0, tail_ns = 0;
+    std::vector<uint64_t> op_ns;            // measured burst times of the latest epoch, one per operation
+    hipStream_t filler_stream = nullptr;    // fr_stage_set_filler
+    uint32_t filler_workgroups = 0;
+    uint64_t filler_guard_ns = 0;
+    int wall_clock_khz = 100000;
 };
 
 extern "C" {
@@ -162,18 +167,47 @@ int fr_stage_ops(fr_stage* s, fr_stage_op* buf, size_t cap, size_t* n_out, uint6
     return FR_OK;
 }
 
+int fr_stage_set_filler(fr_stage* s, void* stream, uint32_t workgroups, uint64_t guard_ns)
+{
+    if (!s) return FR_ERR_ARG;
+    if (workgroups > 65536) return FR_ERR_ARG;
+    int device = 0, khz = 0;
+    if (workgroups && (hipGetDevice(&device) != hipSuccess ||
+                       hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, device) != hipSuccess || khz <= 0))
+        return FR_ERR_HIP;
+    if (workgroups) s->wall_clock_khz = khz;
+    s->filler_stream = (hipStream_t)stream;
+    s->filler_workgroups = workgroups;
+    s->filler_guard_ns = guard_ns;
+    return FR_OK;
+}
+
+int fr_stage_op_times(fr_stage* s, uint64_t* ns_host, size_t cap, size_t* n_out)
+{
+    if (!s || !n_out || (!ns_host && cap)) return FR_ERR_ARG;
+    const size_t n = std::min(cap, s->op_ns.size());
+    for (size_t i = 0; i < n; ++i) ns_host[i] = s->op_ns[i];
+    *n_out = s->op_ns.size();
+    return FR_OK;
+}
+
 int fr_stage_run_epoch(fr_stage* s, fr_ctx* ctx, fr_epoch_result* out)
 {
     if (!s || !out || !s->load) return FR_ERR_ARG;
     fr_epoch_result r{};
     int hip_err = 0;
+    s->op_ns.clear();
     auto bubble = [&](uint64_t len) -> int {
         const uint64_t tb = clock_ns();
         if (ctx) {
             int rc = fr_bubble_begin(ctx, tb, len);
             if (rc != FR_OK) return rc;
+        } else if (s->filler_workgroups && len > s->filler_guard_ns) {
+            int rc = fr_alufill_launch(len - s->filler_guard_ns, s->wall_clock_khz, s->filler_workgroups, s->filler_stream);
+            if (rc != FR_OK) return rc;
         }
         wait_until(tb + len);          // the other stages' work, as a timed wait
+        if (!ctx && s->filler_workgroups && len > s->filler_guard_ns) FR_HIP_TRY(hipStreamSynchronize(s->filler_stream), hip_err);
         if (ctx) {
             int rc = fr_bubble_end(ctx);
             if (rc == FR_ERR_OVERRUN) r.overruns++;
@@ -193,7 +227,9 @@ int fr_stage_run_epoch(fr_stage* s, fr_ctx* ctx, fr_epoch_result* out)
         int rc = op.kind == 0 ? fr_load_fp(s->load, (void*)s->stream) : fr_load_bp(s->load, (void*)s->stream);
         if (rc != FR_OK) return rc;
         FR_HIP_TRY(hipStreamSynchronize(s->stream), hip_err);
-        r.busy_ns += clock_ns() - a;
+        const uint64_t took = clock_ns() - a;
+        r.busy_ns += took;
+        s->op_ns.push_back(took);
         r.n_ops++;
     }
     if (s->tail_ns) {

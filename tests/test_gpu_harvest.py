@@ -142,6 +142,67 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     assert all(r.epoch_ns >= T for r in results)
 
 
+def test_harvest_in_rounds_matches_plan_and_oracle():
+    # On a stream of 8 CUs a launch has 16 workgroups, and this uniform graph of 16.8 M edges is cut into hundreds of
+    # tiles per sweep, which the workgroups hand out among themselves.  Steps that end inside a sweep are cut to
+    # whole rounds of 16 tiles: the runtime's log is the plan of the oracle's planner with that rule, record for
+    # record, and the ranks are the standalone run's bits and the fp64 oracle's values.
+    K = 3
+    g = graphs.fixed_outdeg_csr(1 << 20, 16, seed=34)
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    ref = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    guard, launch, max_chunk = 300_000, 10_000, 10**12
+    floors = (20_000, 150_000, 150_000, 20_000)
+    ctx = fr.Context(device_id=0, cu_count=8, guard_ns=guard, launch_cost_ns=launch, max_chunk_ns=max_chunk, time_steps=1,
+                     mem_available_bytes=1 << 40)
+    t_ref = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ref, iterations=K)
+    t_ref.fr_pagerank_run_standalone(0, ctx.fr_side_stream())         # same CU mask, hence the same layout
+    t_ref.fr_pagerank_destroy()
+    # a cost model well above what the sweeps take on 8 CUs (about 1.6 ms each), so that nothing overruns
+    task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=K, max_runs=1, mem_limit_bytes=1 << 32,
+                           fs_per_edge=400_000, fs_per_message=400_000, fs_per_vertex=100_000, finish_tile_ns=5_000,
+                           min_step_ns=floors)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 3_000_000, 6_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+    results = []
+    for ep in range(6):
+        print("epoch", ep, flush=True)
+        results.append(stage.fr_stage_run_epoch(ctx))
+        if ctx.fr_query_progress(tid).runs_completed >= 1:
+            break
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    segs = _segments(task, K)
+    info = task.fr_pagerank_info()
+    ctx.fr_task_stop(tid)
+    got, want_bits = ranks.cpu().numpy(), ref.cpu().numpy()
+    task.fr_pagerank_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+
+    assert info.scatter_slots == 16 and info.gather_slots == 16       # two workgroups per CU at these sizes
+    assert len(segs[1]) >= 4 * info.scatter_slots and len(segs[2]) >= 4 * info.gather_slots
+    assert pr.runs_completed == 1 and pr.overruns == 0 and pr.deadline_misses == 0
+    windows, _ = schedule.bubbles("1f1b", 4, 8, f_ns, b_ns, 2)
+    lengths = [2_000_000_000] + [e - a for a, e in windows] * len(results)
+    slots = [0] + [info.scatter_slots, info.gather_slots] * K + [0]
+    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=1, floors=_floors(floors, K), slots=slots)
+    got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
+    want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
+    assert got_log == want_log[:len(got_log)] and len(got_log) >= len([r for r in want if r.kind == "CHUNK"])
+    cut = [r for r in want if r.kind == "CHUNK" and slots[r.segment] and r.tile1 - r.tile0 > slots[r.segment] and r.tile1 < len(segs[r.segment])]
+    assert cut and all((r.tile1 - r.tile0) % slots[r.segment] == 0 for r in cut)      # the rule was at work
+    assert sum(e.work_units for e in log if e.kind == fr.FR_EV_CHUNK) == K * g.n_edges
+    assert np.array_equal(got.view(np.uint32), want_bits.view(np.uint32))
+    oracle = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, K)
+    assert np.abs(got.astype(np.float64) - oracle).max() <= 1e-5
+    big = oracle > 1.0 / g.n_vertices
+    assert (np.abs(got[big] - oracle[big]) / oracle[big]).max() <= 1e-4
+
+
 def test_pagerank_task_is_stopped_alone_when_it_exceeds_its_memory_limit():
     g = graphs.rmat_csr(12, 1 << 15, seed=2)
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)

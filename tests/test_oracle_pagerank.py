@@ -154,3 +154,32 @@ def test_zero_iterations_and_edgeless_graph():
     g = graphs.csr_from_edges(5, np.zeros(0, np.int32), np.zeros(0, np.int32))
     assert np.allclose(pagerank(g.row_ptr, g.col, g.out_degree, D, 0), 0.2)
     assert np.allclose(pagerank(g.row_ptr, g.col, g.out_degree, D, 9), 0.2, atol=1e-15)   # all mass dangling
+
+
+# ---- the fp32, thread-parallel sibling that bench.py times as the CPU baseline (oracle/pagerank_f32.c)
+
+def test_fp32_baseline_ring_and_stars_follow_the_closed_forms():
+    from oracle.pagerank import pagerank_f32
+    g = graphs.ring_csr(64)
+    r = pagerank_f32(g.row_ptr, g.col, g.out_degree, D, 30)
+    assert np.allclose(r, 1.0 / 64, rtol=1e-6, atol=0)
+    n, V = 7, 8
+    for kind, ratio, c_star in (("both", -D, ((1 - D) / V + D) / (1 + D)),
+                                ("in", -D * n / V, ((1 - D) / V + D) / (1 + D * n / V)),
+                                ("out", -D / V, 1.0 / (V + D))):
+        g = graphs.star_csr(n, kind)
+        for k in (1, 2, 5, 30):
+            r = pagerank_f32(g.row_ptr, g.col, g.out_degree, D, k)
+            assert r[0] == pytest.approx(_geometric(c_star, ratio, 1.0 / V, k), abs=2e-6), (kind, k)
+            assert abs(float(r.astype(np.float64).sum()) - 1.0) < 1e-5
+
+
+@pytest.mark.parametrize("threads", [1, 3, 0])
+def test_fp32_baseline_agrees_with_the_fp64_oracle_and_ignores_the_thread_count(threads):
+    from oracle.pagerank import pagerank_f32
+    g = graphs.rmat_csr(12, 1 << 16, seed=5)
+    want = pagerank(g.row_ptr, g.col, g.out_degree, D, 20)
+    got = pagerank_f32(g.row_ptr, g.col, g.out_degree, D, 20, n_threads=threads)
+    assert np.abs(got.astype(np.float64) - want).max() <= 1e-6
+    one = pagerank_f32(g.row_ptr, g.col, g.out_degree, D, 20, n_threads=1)
+    assert np.array_equal(got.view(np.uint32), one.view(np.uint32))

@@ -146,3 +146,40 @@ def test_floor_invariants_on_random_inputs(seed):
         else:
             assert r.kind == "IDLE" and step(r.tile0, r.tile0 + 1) > min(rem, max_chunk)
             assert r.modelled_ns == max(rem, 0)
+
+
+def test_whole_rounds_rule_hand_worked():
+    # one segment of ten tiles of cost 10, three tiles side by side (slots 3), launch 0, no floor.
+    # bubble 0: 75 left: seven tiles fit (70), more than a round and short of the segment's end -> six (two whole
+    #           rounds, 60); 15 left: one tile (a step of up to `slots` tiles is not cut), 5 left: idle
+    # bubble 1: 100 left: the last three tiles reach the segment's end (30); next run: seven fit (70) -> six (60);
+    #           10 left: one tile; idle with nothing left
+    # without the rule the first step would be the seven tiles
+    segs = [[10] * 10]
+    recs = plan([75, 100], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, slots=[3])
+    assert recs == [
+        Record("CHUNK", 0, 0, 0, 0, 6, 60), Record("CHUNK", 0, 0, 0, 6, 7, 10), Record("IDLE", 0, 0, 0, 7, 7, 5),
+        Record("CHUNK", 1, 0, 0, 7, 10, 30), Record("CHUNK", 1, 1, 0, 0, 6, 60), Record("CHUNK", 1, 1, 0, 6, 7, 10),
+        Record("IDLE", 1, 1, 0, 7, 7, 0),
+    ]
+    free = plan([75], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False)
+    assert free[0] == Record("CHUNK", 0, 0, 0, 0, 7, 70)
+    # a chunk that reaches the end of its segment is never cut, whatever its length
+    recs = plan([1000], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, slots=[3], max_runs=1)
+    assert recs == [Record("CHUNK", 0, 0, 0, 0, 10, 100)]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_whole_rounds_rule_invariants(seed):
+    rng = random.Random(100 + seed)
+    segments = [[rng.randint(1, 20) for _ in range(rng.randint(1, 40))] for _ in range(rng.randint(1, 4))]
+    slots = [rng.choice([0, 2, 5]) for _ in segments]
+    bl = [rng.randint(0, 300) for _ in range(30)]
+    recs = plan(bl, segments, guard=3, launch_cost=2, max_chunk=10**9, slots=slots)
+    for r in recs:
+        if r.kind != "CHUNK":
+            continue
+        n, s = r.tile1 - r.tile0, slots[r.segment]
+        assert r.modelled_ns == 2 + sum(segments[r.segment][r.tile0:r.tile1])
+        if s and n > s and r.tile1 < len(segments[r.segment]):
+            assert n % s == 0
