@@ -59,8 +59,10 @@ extern "C" {
 #define FR_EV_IDLE  3   /* the next step did not fit: rest of the bubble left idle ("insufficient time")    */
 #define FR_EV_MISS  4   /* the step fitted the modelled budget but not the real clock; it was not launched  */
 #define FR_EV_OVERRUN 5 /* fr_bubble_end found side work of the bubble still going on (written by that call) */
-#define FR_EV_REFUSED 6 /* device gate: this step, enqueued in the bubble, found too little time left when its kernel
-                           started and did nothing; the task was rewound to it (one record per refused step)       */
+#define FR_EV_REFUSED 6 /* device gate: the tiles [tile0, tile1) of a step enqueued in the bubble were not done - the
+                           whole step (too little time left when its kernel started, or a step behind such a one),
+                           or the tail of a step that stopped between tiles, whose CHUNK record then ends at tile0;
+                           the task was rewound to the first of them (one record per step)                          */
 
 typedef struct fr_ctx fr_ctx;
 typedef struct fr_alloc fr_alloc;
@@ -95,9 +97,11 @@ typedef struct fr_config {
                                       measurements and no longer matches a plan computed ahead of time.  Needs
                                       time_steps.                                                              */
     uint32_t device_gate;          /* nonzero: every step also checks the GPU clock when its kernel starts and does
-                                      nothing if it could not end guard_ns before the bubble's declared end
-                                      (freeride_device.h); refused steps are taken back (fr_task_ops.rewind) and
-                                      logged as FR_EV_REFUSED.  Only for tasks that provide rewind.             */
+                                      nothing if it could not end guard_ns before the bubble's declared end; a kernel
+                                      that hands its tiles out checks again before every further tile and stops
+                                      between tiles (freeride_device.h); what was not done is taken back
+                                      (fr_task_ops.rewind) and logged as FR_EV_REFUSED.  Only for tasks that provide
+                                      rewind.                                                                     */
     uint32_t reserved2;
     uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
                                       callback or InitSideTask -- is still going on this long after the end of the
@@ -131,7 +135,9 @@ typedef struct fr_step {
     uint32_t gate_slot;
     void*    gate;          /* device pointer to the context's fr_gate                                      */
     uint32_t gate_need_ticks;   /* the step's modelled duration in GPU wall-clock ticks                     */
-    uint32_t reserved;
+    uint32_t gate_tile;     /* plan_step: modelled duration, ns, of the step's heaviest tile run alone if the step's
+                               kernel can stop between tiles (0 if it cannot: the step is all or nothing); the runtime
+                               turns it into GPU wall-clock ticks, scaled like the step's cost, before run_step      */
 } fr_step;
 
 /*
@@ -143,8 +149,11 @@ typedef struct fr_step {
  *            Sets modelled_ns = 0 when not even the smallest step fits.
  * run_step : RunNextStep(): enqueue exactly the planned step on `stream` and advance the cursor.
  * stop     : -> STOPPED, release everything taken in init (the accounting allocator frees what it handed out).
- * rewind   : optional (may be NULL).  The step `first_undone`, run_step of which has returned, and every step after
- *            it did nothing on the GPU (refused by the device gate): the task's cursor goes back to its start.
+ * rewind   : optional (may be NULL).  Of the step `first_undone`, run_step of which has returned, only the first
+ *            `tiles_done` tiles were done on the GPU (0: the device gate refused the step; more: its kernel
+ *            stopped between tiles when the bubble's time ran out), and every step after it did nothing: the task's
+ *            cursor goes back to the first tile not done, and *work_units_done_out receives the work units of
+ *            the tiles that were.
  * Each returns FR_OK or an FR_ERR_* code; a failure stops the task.
  */
 typedef struct fr_task_ops {
@@ -153,7 +162,7 @@ typedef struct fr_task_ops {
     int (*plan_step)(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* out);
     int (*run_step)(void* user, void* stream, const fr_step* planned);
     int (*stop)(void* user);
-    int (*rewind)(void* user, const fr_step* first_undone);
+    int (*rewind)(void* user, const fr_step* first_undone, uint32_t tiles_done, uint64_t* work_units_done_out);
 } fr_task_ops;
 
 /* The side-task profile (Section 4.3): memory need and shortest step. */
@@ -221,8 +230,9 @@ typedef struct fr_progress {
     uint64_t deadline_misses;
     uint64_t mem_used_bytes;
     uint64_t killed;                /* 1 if the framework-enforced limit stopped the task                  */
-    uint64_t steps_refused;         /* steps the device gate refused; they leave steps / work_units_done /
-                                       runs_completed again once the bubble's GPU work has drained        */
+    uint64_t steps_refused;         /* steps the device gate refused or cut short; what they did not do leaves
+                                       steps / work_units_done / runs_completed again once the bubble's GPU
+                                       work has drained                                                    */
 } fr_progress;
 int fr_query_progress(fr_ctx* ctx, fr_task_id id, fr_progress* out);
 

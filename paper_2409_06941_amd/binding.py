@@ -35,7 +35,7 @@ class fr_step(C.Structure):
     _fields_ = [("modelled_ns", C.c_uint64), ("work_units", C.c_uint64), ("run", C.c_uint32), ("segment", C.c_uint32),
                 ("tile0", C.c_uint32), ("tile1", C.c_uint32), ("finished", C.c_int32), ("completes_run", C.c_int32),
                 ("cost_class", C.c_uint32), ("gate_slot", C.c_uint32), ("gate", C.c_void_p), ("gate_need_ticks", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("gate_tile", C.c_uint32)]
 
 
 CREATE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p)
@@ -43,7 +43,7 @@ INIT_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p, C.c_void_p)
 PLAN_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(fr_step))
 RUN_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p, C.POINTER(fr_step))
 STOP_FN = C.CFUNCTYPE(C.c_int, C.c_void_p)
-REWIND_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(fr_step))
+REWIND_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(fr_step), C.c_uint32, C.POINTER(C.c_uint64))
 
 
 class fr_task_ops(C.Structure):

@@ -112,7 +112,8 @@ struct DevArgs {
 // What a step's kernels need to ask the device gate (Section 4.5's check, made by the GPU when the kernel starts).
 struct GateArg {
     fr_gate* gate;                // NULL: no gate
-    uint32_t slot, need_ticks;
+    uint32_t slot, need_ticks;    // need_ticks: the whole step's modelled duration
+    uint32_t tile_ticks;          // the modelled duration of the step's heaviest tile run alone
 };
 
 // Sum of a merged row's partial sums p_0 .. p_{nt-1}.  The order is fixed: sixteen leaves, leaf g = p_g + p_{g+16} +
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(kBlock) void k_vertex0(DevArgs A, GateArg G, uint32
         if (q == 0)
             for (uint32_t i = A.Q + threadIdx.x; i < A.n_dpart; i += kBlock) A.dpart[i] = 0.0f;
     }
-    fr_gate_done(G.gate);
+    fr_gate_done(G.gate, G.slot);
 }
 
 // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), and every XCD has an L2 of its
@@ -271,16 +272,44 @@ __device__ __forceinline__ uint32_t xcd_runs(uint32_t b, uint32_t n)
 // a launch asking at once that was 10 to 20 us).  The last workgroup to leave puts the two words back to zero for
 // the next launch (launches of one task run one after the other on one stream).  Which workgroup takes which tile has
 // no bearing on what the tile computes.  Thread 0 only.
-__device__ __forceinline__ uint32_t ask_next_tile(uint32_t* sched, uint32_t n_tiles)
+constexpr uint32_t kHandOutStopped = 1u << 30;      // set in the counter: every later asker is sent home
+constexpr uint32_t kAskLater = 0xffffffffu;
+
+__device__ __forceinline__ uint32_t ask_next_tile(uint32_t* sched)
 {
-    (void)n_tiles;
-    return gridDim.x + atomicAdd(&sched[0], 1u);
+    return gridDim.x + atomicAdd(&sched[0], 1u);        // (at or beyond the launch's tile count: nothing left)
 }
 
-__device__ __forceinline__ void leave_launch(uint32_t* sched, uint32_t n_tiles)
+// With the device gate: the time left in the bubble is no longer enough for another tile.  The hand-out stops - the
+// tiles taken so far, which form the head of the launch's tile list, are finished by their workgroups - and the
+// first workgroup to find this out records how many tiles that is.  Returns a tile number beyond the launch.
+__device__ __forceinline__ uint32_t stop_hand_out(uint32_t* sched, const GateArg& G, uint32_t n_tiles)
+{
+    const uint32_t before = atomicOr(&sched[0], kHandOutStopped);
+    if (!(before & kHandOutStopped)) {
+        const uint32_t taken = gridDim.x + before < n_tiles ? gridDim.x + before : n_tiles;
+        if (taken < n_tiles) fr_gate_stop_short(G.gate, G.slot, taken);
+    }
+    return n_tiles;
+}
+
+// The question for the next tile, put late in a tile (ahead_ticks: what of the tile is still to come): asked only
+// if the gate leaves time for the rest of this tile and another one, else put off to the tile's end.
+__device__ __forceinline__ uint32_t ask_if_time(uint32_t* sched, const GateArg& G)
+{
+    return fr_gate_may_take(G.gate, G.tile_ticks, G.tile_ticks) ? ask_next_tile(sched) : kAskLater;
+}
+
+// At a tile's end: the answer, asking now if that was put off and stopping the hand-out if time has run out.
+__device__ __forceinline__ uint32_t settle_next_tile(uint32_t asked, uint32_t* sched, const GateArg& G, uint32_t n_tiles)
+{
+    if (asked != kAskLater) return asked;
+    return fr_gate_may_take(G.gate, 0u, G.tile_ticks) ? ask_next_tile(sched) : stop_hand_out(sched, G, n_tiles);
+}
+
+__device__ __forceinline__ void leave_launch(uint32_t* sched)
 {
     // (this thread's own asks have returned: their values were used)
-    (void)n_tiles;
     if (atomicAdd(&sched[1], 1u) == gridDim.x - 1) {
         __hip_atomic_store(&sched[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&sched[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -387,7 +416,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
     __shared__ float red[kScatterWaves];
     __shared__ uint32_t next_local;
     static_assert(kDescBatch <= kScatterBlock, "one bin per thread");
-    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
+    if (!fr_gate_admit(G.gate, G.slot, kDynamic ? G.tile_ticks : G.need_ticks)) return;
     const uint32_t Qe = A.Qe;
     float base = 0.0f;
     if (!first) {
@@ -425,7 +454,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
         }
         if constexpr (kDynamic)
-            if (last_piece && threadIdx.x == 0) asked = ask_next_tile(A.sched, n_tiles);    // covered by the messages below
+            if (last_piece && threadIdx.x == 0) asked = ask_if_time(A.sched, G);    // covered by the messages below
         for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
             const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
             __syncthreads();                                     // slice filled / previous batch consumed
@@ -478,14 +507,14 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
             }
         }
         if constexpr (kDynamic) {
-            if (threadIdx.x == 0) next_local = asked;
+            if (threadIdx.x == 0) next_local = settle_next_tile(asked, A.sched, G, n_tiles);
             __syncthreads();
             local = next_local;
         }
     } while (kDynamic && local < n_tiles);
     if constexpr (kDynamic)
-        if (threadIdx.x == 0) leave_launch(A.sched, n_tiles);
-    fr_gate_done(G.gate);
+        if (threadIdx.x == 0) leave_launch(A.sched);
+    fr_gate_done(G.gate, G.slot);
 }
 
 // ---- G_k ----
@@ -537,7 +566,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity
     __shared__ unsigned long long acc[kAccSlots + 1];            // + the sink slot
     __shared__ float red[kGatherWaves];
     __shared__ uint32_t next_local;
-    if (!fr_gate_admit(G.gate, G.slot, G.need_ticks)) return;
+    if (!fr_gate_admit(G.gate, G.slot, kDynamic ? G.tile_ticks : G.need_ticks)) return;
     const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
@@ -670,7 +699,7 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity
     }
     __syncthreads();
     if constexpr (kDynamic)
-        if (t + 1 == span.y && threadIdx.x == 0) asked = ask_next_tile(A.sched, n_tiles);   // covered by the row pass below
+        if (t + 1 == span.y && threadIdx.x == 0) asked = ask_if_time(A.sched, G);   // covered by the row pass below
 
     if (T.partial != kNoPartial) {
         // merged range: the sums go out as one row of partial sums; the next scatter sweep (or F) finishes the rows
@@ -710,14 +739,14 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity
     __syncthreads();                                             // the piece is done with acc
     }       // pieces
     if constexpr (kDynamic) {
-        if (threadIdx.x == 0) next_local = asked;
+        if (threadIdx.x == 0) next_local = settle_next_tile(asked, A.sched, G, n_tiles);
         __syncthreads();
         local = next_local;
     }
     } while (kDynamic && local < n_tiles);       // tiles
     if constexpr (kDynamic)
-        if (threadIdx.x == 0) leave_launch(A.sched, n_tiles);
-    fr_gate_done(G.gate);
+        if (threadIdx.x == 0) leave_launch(A.sched);
+    fr_gate_done(G.gate, G.slot);
 }
 
 // ---- F ----
@@ -743,7 +772,7 @@ __global__ __launch_bounds__(kBlock) void k_finish(DevArgs A, GateArg G, uint32_
             A.ranks_out[A.perm[v]] = merged ? fmaf(A.damping, merged_sum<1>(A, info, i, 0), base) : base;
         }
     }
-    fr_gate_done(G.gate);
+    fr_gate_done(G.gate, G.slot);
 }
 
 uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
@@ -817,7 +846,7 @@ void build_cost_tables(PrTask* p)
 }
 
 // `with`: the kernel arguments to use instead of the task's own (the run that works in the static scratch array).
-int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0},
+int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t stream, GateArg G = GateArg{nullptr, 0, 0, 0},
               const DevArgs* with = nullptr)
 {
     const DevArgs& args = with ? *with : p->args;
@@ -955,6 +984,13 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     if (slots && n > slots && p->tile + n < p->tiles_of(kind)) n = n / slots * slots;
     out->tile1 = p->tile + n;
     out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
+    if (slots && n > slots) {
+        // the step's kernel hands its tiles out and can stop between them: what its heaviest tile - the first, they
+        // are in order of falling weight - takes alone, i.e. the slot's whole time for it (a tile's cost is its
+        // share of a round of `slots` tiles side by side)
+        const uint64_t alone = std::max<uint64_t>(floor_ns, (pre[p->tile + 1] - pre[p->tile]) * slots);
+        out->gate_tile = (uint32_t)std::min<uint64_t>(alone, 4000000000ull);
+    }
     if (kind == FR_PR_SEG_GATHER) {
         uint64_t edges = 0;
         for (uint32_t t = p->tile; t < p->tile + n && t < p->L.n_gather; ++t) edges += p->L.gt_edges[t];
@@ -969,7 +1005,7 @@ int pr_run(void* user, void* stream, const fr_step* st)
     PrTask* p = static_cast<PrTask*>(user);
     if (!p->inited || st->run != p->run || st->segment != p->seg || st->tile0 != p->tile) return FR_ERR_STATE;
     int rc = pr_launch(p, p->seg, st->tile0, st->tile1, (hipStream_t)stream,
-                       GateArg{static_cast<fr_gate*>(st->gate), st->gate_slot, st->gate_need_ticks});
+                       GateArg{static_cast<fr_gate*>(st->gate), st->gate_slot, st->gate_need_ticks, st->gate_tile});
     if (rc != FR_OK) return rc;
     p->tile = st->tile1;
     if (p->tile == p->tiles_of(p->kind_of(p->seg))) {
@@ -979,13 +1015,24 @@ int pr_run(void* user, void* stream, const fr_step* st)
     return FR_OK;
 }
 
-// The device gate refused `first` and every step after it: they did nothing, so the cursor goes back to its start.
-int pr_rewind(void* user, const fr_step* first)
+// The device gate cut `first` off after `tiles_done` of its tiles, and every step after it did nothing: the cursor goes
+// back to the first tile not done.  (A tile done twice computes the same values again: tiles only read what earlier
+// segments wrote.)
+int pr_rewind(void* user, const fr_step* first, uint32_t tiles_done, uint64_t* work_done)
 {
     PrTask* p = static_cast<PrTask*>(user);
-    if (!p->inited || !first || first->segment >= p->n_segments() || first->tile0 >= p->tiles_of(p->kind_of(first->segment)))
-        return FR_ERR_ARG;
-    p->run = first->run; p->seg = first->segment; p->tile = first->tile0;
+    if (!p->inited || !first || !work_done || first->segment >= p->n_segments()) return FR_ERR_ARG;
+    const int kind = p->kind_of(first->segment);
+    if (first->tile0 >= p->tiles_of(kind) || first->tile1 > p->tiles_of(kind) || tiles_done > first->tile1 - first->tile0) return FR_ERR_ARG;
+    p->run = first->run; p->seg = first->segment; p->tile = first->tile0 + tiles_done;
+    uint64_t edges = 0;
+    if (kind == FR_PR_SEG_GATHER)
+        for (uint32_t t = first->tile0; t < first->tile0 + tiles_done && t < p->L.n_gather; ++t) edges += p->L.gt_edges[t];
+    *work_done = edges;
+    if (p->tile == p->tiles_of(kind)) {            // (a step is only cut off before its last tile; kept for safety)
+        p->tile = 0;
+        if (++p->seg == p->n_segments()) { p->seg = 0; p->run++; }
+    }
     return FR_OK;
 }
 
@@ -1210,7 +1257,7 @@ int fr_pagerank_run_standalone_noalloc(void* user, int32_t device_id, void* stre
         const uint32_t nt = p->tiles_of(p->kind_of(g));
         const uint32_t step = max_tiles ? max_tiles : nt;
         for (uint32_t t0 = 0; t0 < nt && rc == FR_OK; t0 += step)
-            rc = pr_launch(p, g, t0, std::min(nt, t0 + step), stream, GateArg{nullptr, 0, 0}, &A);
+            rc = pr_launch(p, g, t0, std::min(nt, t0 + step), stream, GateArg{nullptr, 0, 0, 0}, &A);
     }
     hipError_t e = hipStreamSynchronize(stream);
     if (rc != FR_OK) return rc;

@@ -24,8 +24,9 @@ __global__ void k_gate_open(fr_gate* g, unsigned long long deadline_ticks)
 {
     g->deadline_ticks = deadline_ticks;
     g->opened_ticks = wall_clock64();
-    g->closed = 0u;
-    g->first_refused = 0xffffffffu;
+    g->end_ticks[0] = g->end_ticks[1] = 0ull;
+    g->state = FR_GATE_OPEN;
+    g->tiles_done = 0u;
 }
 
 __global__ void k_gate_clock(fr_gate* g) { g->deadline_ticks = wall_clock64(); }
@@ -46,6 +47,7 @@ struct PendingTiming {
     uint32_t class_mask;     // for cost adaptation: the cost classes in the group and the task's own (unscaled)
     uint64_t task_modelled_ns;   // modelled cost of its steps
     uint64_t bubble;         // index of the bubble the group ran in
+    void* owner;             // the task whose steps these are (it may no longer be the current one when they resolve)
 };
 
 // Cost adaptation gathers the timing groups of a bubble and updates the scales once from the bubble's totals: single
@@ -99,8 +101,10 @@ struct fr_ctx {
     uint64_t enforce_callback = 0;          //   the late callback's start time (identifies it)
     uint64_t enforce_deadline = 0;
     bool bubble_open = false;               // stage thread only
-    uint64_t cur_begin = 0, cur_len = 0;
-    uint32_t cur_index = 0;                 // 0-based bubble index
+    // (written by the stage thread before bubble_seq is bumped; the worker reads them, checks that bubble_seq has not
+    // moved meanwhile and reads again if it has: a bubble may open while the worker is still closing the one before)
+    std::atomic<uint64_t> cur_begin{0}, cur_len{0};
+    std::atomic<uint32_t> cur_index{0};     // 0-based bubble index
     uint64_t bubbles_total = 0;
 
     Task* task = nullptr;                   // the worker's current task (Algorithm 2)
@@ -126,6 +130,7 @@ struct fr_ctx {
     int64_t gpu_minus_host_ns = 0;          // wall_clock64() / ticks_per_ns - CLOCK_MONOTONIC
     std::vector<fr_step> gate_steps;        // steps enqueued since the gate was last opened, by slot (worker only)
     std::vector<uint32_t> gate_bubble;      //   and the bubble each belongs to
+    std::vector<uint64_t> gate_seq;         //   and the sequence number of its CHUNK record
     std::atomic<bool> gate_pending{false};  // their verdicts have not been read back yet
 
     // Overrun detection: the worker records this event behind the last work it enqueued for a bubble;
@@ -202,7 +207,8 @@ void resolve_timings(fr_ctx* c, bool wait)
         if (q == hipSuccess && hipEventElapsedTime(&ms, p.begin, p.end) == hipSuccess) {
             const uint64_t ns = (uint64_t)((double)ms * 1.0e6 + 0.5);
             if (fr_event* ev = log_at(c, p.log_seq)) ev->measured_ns = ns;
-            if (c->task) c->task->prog.ns_measured += ns;
+            for (Task* t : c->tasks)
+                if (t == p.owner) t->prog.ns_measured += ns;
             if (c->cfg.adapt_costs) {
                 if (p.bubble != c->totals.bubble) { apply_totals(c); c->totals.bubble = p.bubble; }
                 // a group that took over 1.25 times its scaled cost is no scatter: the steps still to be planned for
@@ -240,7 +246,7 @@ void stop_task_locked(fr_ctx* c, Task* t, int error)
     if (!c->host_only && c->side) (void)hipStreamSynchronize(c->side);
     resolve_timings(c, true);
     if (t->ops.stop) t->ops.stop(t->user);
-    if (t == c->task) { c->gate_steps.clear(); c->gate_bubble.clear(); c->gate_pending = false; }
+    if (t == c->task) { c->gate_steps.clear(); c->gate_bubble.clear(); c->gate_seq.clear(); c->gate_pending = false; }
     t->prog.mem_used_bytes = t->alloc.used;
     fr_alloc_release(&t->alloc);
     t->state = FR_STOPPED;
@@ -285,34 +291,47 @@ bool killed_if_asked(fr_ctx* c, Task* t)
     return true;
 }
 
-// Reads back which steps the device gate refused and takes them back: the task's cursor is rewound to the first
-// of them, the counters forget them and one FR_EV_REFUSED record is written for each.  Waits for the side stream
-// (its work belongs to a bubble that is over).  Worker thread, work_mu held, ctx->mu not held.
+// Reads back where the device gate cut the bubble's steps off and takes back what was not done: the task's cursor
+// is rewound to the first tile not done, the counters forget it and one FR_EV_REFUSED record is written for each
+// step concerned (a step that stopped between tiles keeps its CHUNK record, shortened to the tiles it did).  Waits
+// for the side stream (its work belongs to a bubble that is over).  Worker thread, work_mu held, ctx->mu not held.
 void gate_settle(fr_ctx* c, Task* t)
 {
     if (!c->gate_pending.exchange(false)) return;
-    uint32_t first = 0xffffffffu;
-    if (hipStreamSynchronize(c->side) != hipSuccess ||
-        hipMemcpy(&first, &c->gate->first_refused, sizeof(first), hipMemcpyDeviceToHost) != hipSuccess)
-        first = 0xffffffffu;
+    fr_gate g{};
+    g.state = FR_GATE_OPEN;
+    if (hipStreamSynchronize(c->side) != hipSuccess || hipMemcpy(&g, c->gate, sizeof(g), hipMemcpyDeviceToHost) != hipSuccess)
+        g.state = FR_GATE_OPEN;
+    const size_t first = g.state == FR_GATE_OPEN ? c->gate_steps.size() : (size_t)(g.state >> 1);
     if (first < c->gate_steps.size() && t && t->state != FR_STOPPED && t->ops.rewind) {
-        const int rc = t->ops.rewind(t->user, &c->gate_steps[first]);
+        const fr_step& cut = c->gate_steps[first];
+        uint32_t done = (g.state & 1u) ? g.tiles_done : 0u;
+        if (done > cut.tile1 - cut.tile0) done = cut.tile1 - cut.tile0;       // (cannot happen)
+        uint64_t work_done = 0;
+        const int rc = t->ops.rewind(t->user, &cut, done, &work_done);
         std::lock_guard<std::mutex> lk(c->mu);
         for (size_t i = first; i < c->gate_steps.size(); ++i) {
             const fr_step& st = c->gate_steps[i];
+            const bool partly = i == first && done > 0;
             fr_event ev{};
             ev.kind = FR_EV_REFUSED; ev.bubble = c->gate_bubble[i]; ev.run = st.run; ev.segment = st.segment;
-            ev.tile0 = st.tile0; ev.tile1 = st.tile1; ev.work_units = st.work_units; ev.t_host_ns = now_ns();
+            ev.tile0 = st.tile0 + (partly ? done : 0u); ev.tile1 = st.tile1;
+            ev.work_units = st.work_units - (partly ? work_done : 0); ev.t_host_ns = now_ns();
             log_push(c, ev);
-            t->prog.steps--;
             t->prog.steps_refused++;
-            t->prog.work_units_done -= st.work_units;
+            t->prog.work_units_done -= ev.work_units;
+            if (partly) {
+                if (fr_event* chunk = log_at(c, c->gate_seq[i])) { chunk->tile1 = ev.tile0; chunk->work_units = work_done; }
+            } else {
+                t->prog.steps--;
+            }
             if (st.completes_run) t->prog.runs_completed--;
         }
         if (rc != FR_OK) { stop_task_locked(c, t, rc); promote_locked(c); }
     }
     c->gate_steps.clear();
     c->gate_bubble.clear();
+    c->gate_seq.clear();
 }
 
 // One bubble, on the worker thread, work_mu held.
@@ -326,7 +345,11 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         t->prog.bubbles_seen++;
         t->prog.ns_bubble_declared += len;
     }
-    auto stop_now = [&]() { return c->end_requested.load(std::memory_order_acquire) || c->abort_steps.load() || c->quit.load(); };
+    // (a newer bubble_seq: this bubble was closed without the worker's acknowledgement and the next one is open)
+    auto stop_now = [&]() {
+        return c->end_requested.load(std::memory_order_acquire) || c->abort_steps.load() || c->quit.load() ||
+               c->bubble_seq.load(std::memory_order_acquire) != seq;
+    };
     if (killed_if_asked(c, t)) return;
 
     if (t->state == FR_CREATED) {
@@ -391,7 +414,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         { std::lock_guard<std::mutex> lk(c->mu); ev_end = event_get(c); }
         if (ev_end && group_begin && hipEventRecord(ev_end, c->side) == hipSuccess) {
             std::lock_guard<std::mutex> lk(c->mu);
-            c->pending.push_back(PendingTiming{group_last_seq, group_begin, ev_end, group_mask, group_modelled, index});
+            c->pending.push_back(PendingTiming{group_last_seq, group_begin, ev_end, group_mask, group_modelled, index, t});
             c->chain_tail = ev_end;
         }
         group_n = 0; group_mask = 0; group_modelled = 0; group_begin = nullptr;
@@ -482,6 +505,9 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             st.gate_slot = (uint32_t)c->gate_steps.size();
             const double need = (double)scaled * c->ticks_per_ns;
             st.gate_need_ticks = need < 4.0e9 ? (uint32_t)need : 4000000000u;
+            // the heaviest tile's time alone, scaled like the step's cost
+            const double tile = st.modelled_ns ? (double)st.gate_tile * ((double)scaled / (double)st.modelled_ns) * c->ticks_per_ns : 0.0;
+            st.gate_tile = tile < 4.0e9 ? (uint32_t)tile : 4000000000u;
         }
         c->in_callback.store(now_ns(), std::memory_order_release);
         rc = t->ops.run_step(t->user, (void*)c->side, &st);
@@ -499,7 +525,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
             if (st.completes_run) t->prog.runs_completed++;
             if (!used) { used = true; t->prog.bubbles_used++; }
         }
-        if (gated) { c->gate_steps.push_back(st); c->gate_bubble.push_back(index); }
+        if (gated) { c->gate_steps.push_back(st); c->gate_bubble.push_back(index); c->gate_seq.push_back(group_last_seq); }
         if (timed) {
             group_n++; group_mask |= 1u << (st.cost_class & 7); group_modelled += st.modelled_ns;
             if (group_n >= group_size) close_group();
@@ -508,7 +534,6 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
         if (c->kill_current.load(std::memory_order_acquire)) break;
         remaining -= (int64_t)cost;
     }
-    (void)seq;
     if (timed && group_n) close_group();
     if (gated) c->gate_pending.store(!c->gate_steps.empty());
     if (used && !c->host_only && c->tail_event) c->tail_armed = hipEventRecord(c->tail_event, c->side) == hipSuccess;
@@ -558,14 +583,23 @@ void worker_main(fr_ctx* c)
         }
         idle_spins = 0;
         seen = seq;
-        const uint64_t t_begin = c->cur_begin, len = c->cur_len;
-        const uint32_t index = c->cur_index;
+        uint64_t t_begin, len, served = seq;
+        uint32_t index;
+        for (;;) {
+            t_begin = c->cur_begin.load(std::memory_order_relaxed);
+            len = c->cur_len.load(std::memory_order_relaxed);
+            index = c->cur_index.load(std::memory_order_relaxed);
+            const uint64_t again = c->bubble_seq.load(std::memory_order_acquire);
+            if (again == served) break;
+            served = again;
+        }
+        seen = served;
         c->tail_armed = false;
         {
             std::lock_guard<std::mutex> wl(c->work_mu);
-            serve_bubble(c, seq, t_begin, len, index);
+            serve_bubble(c, served, t_begin, len, index);
         }
-        c->ack_seq.store(seq, std::memory_order_release);
+        c->ack_seq.store(served, std::memory_order_release);
     }
 }
 
@@ -574,7 +608,7 @@ void note_overrun(fr_ctx* c)
 {
     if (c->task) c->task->prog.overruns++;
     fr_event ev{};
-    ev.kind = FR_EV_OVERRUN; ev.bubble = c->cur_index; ev.t_host_ns = now_ns();
+    ev.kind = FR_EV_OVERRUN; ev.bubble = c->cur_index.load(std::memory_order_relaxed); ev.t_host_ns = now_ns();
     log_push(c, ev);
 }
 
@@ -822,9 +856,9 @@ int fr_bubble_begin(fr_ctx* c, uint64_t t_begin_ns, uint64_t duration_ns)
     if (c->bubble_open) return FR_ERR_STATE;
     enforce_check(c);
     c->bubble_open = true;
-    c->cur_begin = t_begin_ns;
-    c->cur_len = duration_ns;
-    c->cur_index = (uint32_t)c->bubbles_total++;
+    c->cur_begin.store(t_begin_ns, std::memory_order_relaxed);
+    c->cur_len.store(duration_ns, std::memory_order_relaxed);
+    c->cur_index.store((uint32_t)c->bubbles_total++, std::memory_order_relaxed);
     c->end_requested.store(false, std::memory_order_release);
     c->bubble_seq.fetch_add(1, std::memory_order_release);
     return FR_OK;
@@ -844,7 +878,7 @@ int fr_bubble_end(fr_ctx* c)
         const bool init_late = c->in_init.load(std::memory_order_acquire);
         const uint64_t cb = c->in_callback.load(std::memory_order_acquire);
         const uint64_t now = now_ns();
-        if (init_late || (cb && now > cb + kCallbackPatienceNs && now > c->cur_begin + c->cur_len)) {
+        if (init_late || (cb && now > cb + kCallbackPatienceNs && now > c->cur_begin.load(std::memory_order_relaxed) + c->cur_len.load(std::memory_order_relaxed))) {
             c->bubble_open = false;
             if (c->cfg.grace_ns && !c->enforce_armed) {
                 c->enforce_armed = true; c->enforce_gpu = false;

@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kSgdBlock) void k_sgd(SgdArgs A, GateArg G, uint32_
             }
         }
     }
-    fr_gate_done(G.gate);
+    fr_gate_done(G.gate, G.slot);
 }
 
 // ---- set-up kernels ----
@@ -477,11 +477,14 @@ int sgd_run(void* user, void* stream, const fr_step* st)
     return FR_OK;
 }
 
-int sgd_rewind(void* user, const fr_step* first)
+// (this task's steps are all or nothing - plan_step leaves gate_tile at 0 and the kernel never stops between cells,
+// whose updates are made in place and must not be made twice - so tiles_done is always 0)
+int sgd_rewind(void* user, const fr_step* first, uint32_t tiles_done, uint64_t* work_done)
 {
     SgdTask* p = static_cast<SgdTask*>(user);
-    if (!p->inited || !first || first->segment >= p->n_segments() || first->tile0 >= p->B) return FR_ERR_ARG;
+    if (!p->inited || !first || !work_done || tiles_done != 0 || first->segment >= p->n_segments() || first->tile0 >= p->B) return FR_ERR_ARG;
     p->run = first->run; p->seg = first->segment; p->tile = first->tile0;
+    *work_done = 0;
     return FR_OK;
 }
 

@@ -316,6 +316,7 @@ def test_running_profiler_repairs_a_cost_model_that_claims_steps_are_much_cheape
         print("adapt", adapt, "overruns in epochs 2-4:", late[adapt], "scales", scales[:4], "runs", pr.runs_completed, flush=True)
         assert pr.runs_completed >= 1
         assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+        _oracle_check(got, g, K)
         if adapt:
             assert all(s >= 2_500_000 for s in scales[1:3]), scales      # scatter and gather: about 1 / 0.2, or above
         else:
@@ -374,10 +375,38 @@ def test_running_profiler_changes_the_scales_between_bubbles_and_inside_one_only
     assert scales[1] != 1_000_000 and scales[2] != 1_000_000
 
 
+def _gate_accounts(log, pr):
+    """What the device gate took back is consistent: every FR_EV_REFUSED record is a whole step of the log, or the tail
+    of a step whose CHUNK record was shortened to the tiles it did; the progress counters hold what was done."""
+    chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
+    refused = [e for e in log if e.kind == fr.FR_EV_REFUSED]
+    whole = {(e.bubble, e.run, e.segment, e.tile0, e.tile1) for e in chunks}
+    heads = {(e.bubble, e.run, e.segment, e.tile1) for e in chunks}
+    n_whole = n_tail = 0
+    for r in refused:
+        if (r.bubble, r.run, r.segment, r.tile0, r.tile1) in whole:
+            n_whole += 1
+        else:
+            assert (r.bubble, r.run, r.segment, r.tile0) in heads, "a refused tail follows the tiles its step did"
+            n_tail += 1
+    assert len(refused) == pr.steps_refused and len(chunks) == pr.steps + n_whole
+    whole_refused_work = sum(r.work_units for r in refused if (r.bubble, r.run, r.segment, r.tile0, r.tile1) in whole)
+    assert pr.work_units_done == sum(e.work_units for e in chunks) - whole_refused_work
+    return n_whole, n_tail
+
+
+def _oracle_check(got, g, K):
+    oracle = pagerank(g.row_ptr, g.col, g.out_degree, 0.85, K)
+    assert np.abs(got.astype(np.float64) - oracle).max() <= 1e-5
+    big = oracle > 1.0 / g.n_vertices
+    assert (np.abs(got[big] - oracle[big]) / oracle[big]).max() <= 1e-4
+
+
 def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back():
     # The model claims 25 % of the real step times, so the host keeps enqueueing steps that cannot end inside the
     # bubble.  With the device gate each step asks the GPU clock when its kernel starts: the late ones do nothing,
-    # are logged, and the task is rewound to the first of them.  The ranks keep the standalone run's bits.
+    # are logged, and the task is rewound to the first of them.  The ranks keep the standalone run's bits and are the
+    # fp64 oracle's values.
     g = graphs.rmat_csr(21, 1 << 25, seed=9)
     V, E, K = g.n_vertices, g.n_edges, 20
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
@@ -388,6 +417,7 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
     info = probe.fr_pagerank_info()
     gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
     probe.fr_pagerank_destroy()
+    _oracle_check(ref.cpu().numpy(), g, K)
     low = 0.25
     model = _scaled_model(low, ph, K, gw, sw, info)
     stream = torch.cuda.Stream()
@@ -409,13 +439,10 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
         ctx.fr_task_stop(tid)
         got = ranks.cpu().numpy()
         task.fr_pagerank_destroy(); stage.fr_stage_destroy(); ctx.fr_destroy()
-        chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
-        refused = [e for e in log if e.kind == fr.FR_EV_REFUSED]
         print("gate", gate, "overruns", late[gate], "steps", pr.steps, "refused", pr.steps_refused, "runs", pr.runs_completed, flush=True)
         assert pr.runs_completed >= 1
         assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
-        assert len(refused) == pr.steps_refused and len(chunks) == pr.steps + pr.steps_refused
-        assert pr.work_units_done == sum(e.work_units for e in chunks) - sum(e.work_units for e in refused)
+        _gate_accounts(log, pr)
         # the work that counts covers the completed runs (and the run in progress, which may have all its gather
         # sweeps behind it and only the finishing pass to go), refused steps excluded
         assert K * E * pr.runs_completed <= pr.work_units_done <= K * E * (pr.runs_completed + 1)
@@ -425,6 +452,121 @@ def test_device_gate_refuses_steps_that_would_start_too_late_and_takes_them_back
             assert pr.steps_refused == 0
     load.fr_load_destroy()
     assert late[0] > 0 and late[1] <= late[0], late
+
+
+def test_device_gate_stops_a_step_between_tiles_and_the_rest_is_taken_up_in_the_next_bubble():
+    # On a stream of 8 CUs the sweeps of this graph are hundreds of tiles that the 16 workgroups of a launch hand out
+    # among themselves.  The model claims 40 % of the real step times, so steps are still running when their bubble's
+    # time is up.  With the device gate the workgroups look at the GPU clock before they take another tile: the step
+    # stops after a whole number of its tiles, its record is shortened to those, the rest is logged as refused and
+    # done in the next bubble - no step runs past its bubble any more, and the ranks are the standalone run's bits
+    # and the fp64 oracle's values.
+    K = 4
+    g = graphs.fixed_outdeg_csr(1 << 20, 16, seed=34)
+    V, E = g.n_vertices, g.n_edges
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ref = torch.zeros(V, dtype=torch.float32, device="cuda")
+    side = fr.Context(device_id=0, cu_count=8)
+    probe = fr.PageRankTask(V, E, rp, col, od, ref, iterations=K)
+    probe.fr_pagerank_run_standalone(0, side.fr_side_stream())
+    ph = probe.fr_pagerank_run_standalone(0, side.fr_side_stream(), want_phase_ns=True)
+    one = probe.fr_pagerank_run_standalone(0, side.fr_side_stream(), 1, want_phase_ns=True)      # a tile per launch
+    info = probe.fr_pagerank_info()
+    gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
+    probe.fr_pagerank_destroy(); side.fr_destroy()
+    _oracle_check(ref.cpu().numpy(), g, K)
+    tile_ns = max(one[1] / (K * info.scatter_tiles), one[2] / (K * info.gather_tiles))       # a tile run alone, real time
+    low = 0.4
+    model = _scaled_model(low, ph, K, gw, sw, info)
+    stream = torch.cuda.Stream()
+    f_ns, b_ns = 2_000_000, 4_000_000
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=f_ns, bp_ns=b_ns)
+    late, tails = {}, {}
+    for gate in (0, 1):
+        ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+        # the guard covers what the clock checks cannot know: they use the model's tile time, 40 % of the real one, and
+        # the tiles of a round run side by side, two workgroups to a compute unit, slower than one alone
+        ctx = fr.Context(device_id=0, cu_count=8, guard_ns=int(3 * tile_ns) + 50_000, launch_cost_ns=5_000, time_steps=4, device_gate=gate)
+        task = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K, max_runs=0, **model)
+        tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+        assert _init_bubble(ctx, tid) == fr.FR_OK
+        stage = fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 2, f_ns, b_ns, load, stream)
+        late[gate] = 0
+        for ep in range(8):
+            print("gate", gate, "epoch", ep, flush=True)
+            late[gate] += stage.fr_stage_run_epoch(ctx).overruns
+        import time
+        time.sleep(0.05)
+        pr = ctx.fr_query_progress(tid)
+        log = ctx.fr_event_log()
+        ctx.fr_task_stop(tid)
+        got = ranks.cpu().numpy()
+        task.fr_pagerank_destroy(); stage.fr_stage_destroy(); ctx.fr_destroy()
+        n_whole, tails[gate] = _gate_accounts(log, pr)
+        print("gate", gate, "overruns", late[gate], "steps", pr.steps, "refused whole", n_whole, "cut short", tails[gate], "runs", pr.runs_completed, flush=True)
+        assert pr.runs_completed >= 1
+        assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+        assert K * E * pr.runs_completed <= pr.work_units_done <= K * E * (pr.runs_completed + 1)
+    load.fr_load_destroy()
+    assert late[0] > 0 and tails[0] == 0
+    assert tails[1] > 0 and late[1] == 0, (late, tails)
+
+
+def test_bubbles_that_end_before_their_declared_end_pause_the_task_and_nothing_is_lost():
+    # The paper's online setting: the training system reports a bubble with its expected duration, and the bubble
+    # may be over earlier (the next operation's inputs arrived).  Here every bubble is closed after 55 % of its
+    # declared length.  The worker stops planning at once; what it had enqueued finishes or is counted as an
+    # overrun of the early end, never of the declared one; the task resumes in the next bubble, and a run completed
+    # over many such bubbles has the standalone run's bits and the fp64 oracle's values.
+    import time
+    g = graphs.rmat_csr(18, 1 << 22, seed=15)
+    V, E, K = g.n_vertices, g.n_edges, 12
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ref = torch.zeros(V, dtype=torch.float32, device="cuda")
+    probe = fr.PageRankTask(V, E, rp, col, od, ref, iterations=K)
+    probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    ph = probe.fr_pagerank_run_standalone(0, torch.cuda.current_stream(), want_phase_ns=True)
+    info = probe.fr_pagerank_info()
+    gw, sw = (sum(probe.fr_pagerank_tile_weights(k)) for k in (fr.FR_PR_SEG_GATHER, fr.FR_PR_SEG_SCATTER))
+    probe.fr_pagerank_destroy()
+    model = _scaled_model(1.5, ph, K, gw, sw, info)
+    ranks = torch.zeros(V, dtype=torch.float32, device="cuda")
+    ctx = fr.Context(device_id=0, guard_ns=50_000, launch_cost_ns=5_000, max_chunk_ns=200_000, max_inflight=2, time_steps=1)
+    task = fr.PageRankTask(V, E, rp, col, od, ranks, iterations=K, max_runs=1, **model)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    declared, early_ends, late_at_early_end = 2_000_000, 0, 0
+    for i in range(400):
+        t0 = fr.fr_now_ns()
+        ctx.fr_bubble_begin(t0, declared)
+        while fr.fr_now_ns() - t0 < 0.55 * declared:
+            pass
+        rc = ctx.fr_bubble_end()                          # 0.9 ms before the declared end
+        assert rc in (fr.FR_OK, fr.FR_ERR_OVERRUN)
+        early_ends += 1
+        late_at_early_end += rc == fr.FR_ERR_OVERRUN
+        while fr.fr_now_ns() - t0 < declared:             # the stage's next operation
+            pass
+        if ctx.fr_query_progress(tid).runs_completed >= 1:
+            break
+    time.sleep(0.02)
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    ctx.fr_task_stop(tid)
+    got = ranks.cpu().numpy()
+    task.fr_pagerank_destroy(); ctx.fr_destroy()
+    print("bubbles", early_ends, "steps", pr.steps, "still running at the early end", late_at_early_end, flush=True)
+    assert pr.runs_completed == 1 and pr.bubbles_seen == early_ends + 1
+    # a step is at most 0.2 ms of modelled (1.5 x real) time and at most two are in flight: whatever was enqueued when
+    # the bubble was closed early is done well before the declared end, 0.9 ms later
+    chunks = [e for e in log if e.kind == fr.FR_EV_CHUNK]
+    ends = {}
+    for e in chunks:
+        ends[e.bubble] = max(ends.get(e.bubble, 0), e.t_host_ns + e.measured_ns)
+    assert pr.overruns == late_at_early_end
+    assert sum(e.work_units for e in chunks) == K * E == pr.work_units_done
+    assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+    _oracle_check(got, g, K)
 
 
 def test_steps_are_timed_in_groups_of_time_steps():

@@ -305,3 +305,8 @@ def test_device_gate_refuses_late_sgd_steps_and_the_factors_keep_their_bits():
     assert pr.runs_completed == 1 and pr.steps_refused > 0 and len(refused) == pr.steps_refused
     assert pr.work_units_done == sum(e.work_units for e in chunks) - sum(e.work_units for e in refused) == K * r.n_ratings
     assert _same_bits(got_P, Pr) and _same_bits(got_Q, Qr)
+    # and against the oracle itself, not only against another GPU run: the bits of its fp32 mode, the values of its fp64 mode
+    P32, Q32 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, K, B, ordered_fp32=True)
+    assert _same_bits(got_P, P32) and _same_bits(got_Q, Q32)
+    P64, Q64 = osgd.sgd(r.row_ptr, r.item, r.rating, P0, Q0, gamma, lam, K, B)
+    assert np.abs(got_P - P64).max() <= TOL64 and np.abs(got_Q - Q64).max() <= TOL64
