@@ -184,7 +184,15 @@ def run_config(name, steps, warmup, args, headline):
     # ---- runtime, task, stage
     mem_cap = cfg.mem_cap_bytes if cfg.mem_cap_bytes else (64 << 30)
     kind = fr.FR_SCHED_1F1B if cfg.schedule == "1f1b" else fr.FR_SCHED_GPIPE
-    stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream)
+    chunks = 0
+    if args.interleave > 1:
+        # the same stage under interleaved 1F1B with that many model chunks: an operation is one chunk's share of
+        # the burst, the bubbles add up to 1 / chunks of the plain schedule's, in more and shorter windows
+        if cfg.schedule != "1f1b" or cfg.m % cfg.p or (cfg.load and cfg.load.layers % args.interleave):
+            raise SystemExit("bench.py: --interleave needs a 1F1B configuration with m a multiple of p and layers a multiple of the chunks")
+        kind, chunks = fr.FR_SCHED_INTERLEAVED, args.interleave
+        f_ns, b_ns = f_ns // chunks, b_ns // chunks
+    stage = fr.Stage(kind, cfg.p, cfg.m, cfg.stage, f_ns, b_ns, load, stage_stream, chunks=chunks)
     _, ideal_epoch_ns, _ = stage.fr_stage_ops()
     n_segs = 2 * K + 2
     seg_kind = lambda g: (fr.FR_PR_SEG_VERTEX if g == 0 else fr.FR_PR_SEG_FINISH if g == n_segs - 1
@@ -380,6 +388,7 @@ def run_config(name, steps, warmup, args, headline):
                    % (cfg.name, cfg.schedule, cfg.p, cfg.m, cfg.stage, cfg.graph, cfg.scale, E, K, cfg.seed),
                    "stage_load": ("bf16 GEMM bursts: %d GPT layers h=%d ffn=%d tokens=%d" %
                                   (cfg.load.layers, cfg.load.hidden, cfg.load.ffn, cfg.load.tokens)) if cfg.load else "busy-wait",
+                   "schedule": ("interleaved 1F1B, %d chunks" % chunks) if chunks else cfg.schedule,
                    "f_ms": f_ns / 1e6, "b_ms": b_ns / 1e6, "cu_count": cfg.cu_count,
                    "mem_cap_bytes": cfg.mem_cap_bytes, "guard_us": guard_ns / 1e3},
         "gteps_in_kernel": edges / chunk_ns if chunk_ns else 0.0,
@@ -493,6 +502,8 @@ def main():
     ap.add_argument("--sgd-margin", type=float, default=1.08, help="--side-task sgd: final model = measured in-bubble step cost x this")
     ap.add_argument("--side-task", default="pagerank", choices=("pagerank", "sgd"),
                     help="sgd: the Graph SGD side task in the bubbles of cfg2's stage (a second line of its own, not the headline metric)")
+    ap.add_argument("--interleave", type=int, default=0,
+                    help="run the configuration's stage under interleaved 1F1B with this many model chunks (1F1B configurations): shorter bubbles, a second bubble workload")
     ap.add_argument("--profile-standalone", action="store_true",
                     help="stop after the standalone profile of the side task (for rocprofv3 counter runs: every sweep dispatch is a whole sweep)")
     ap.add_argument("--dump-events", default=None, help="write the timed epochs' event log (one JSON object per line) here")

@@ -483,6 +483,10 @@ int fr_load_destroy(fr_load* l);
    down), BP = the 8 matching data- and weight-gradient GEMMs per layer. */
 int fr_load_fp(fr_load* l, void* stream);
 int fr_load_bp(fr_load* l, void* stream);
+/* Part `part` of `parts` of a burst (kind 0 = FP, 1 = BP): the GEMMs of the layers [part * layers / parts,
+   (part + 1) * layers / parts) (parts must divide layers), or a busy-wait of 1 / parts of the burst's time: what
+   one model chunk of an interleaved schedule runs.  parts = 1 is the whole burst. */
+int fr_load_part(fr_load* l, void* stream, int32_t kind, int32_t part, int32_t parts);
 /* Floating-point operations of one FP / BP burst (2 M N K per GEMM); 0 for busy-wait loads. */
 int fr_load_flops(fr_load* l, uint64_t* fp_flops_out, uint64_t* bp_flops_out);
 
@@ -495,18 +499,28 @@ int fr_gemm_bf16(const void* A, const void* B, void* C, int32_t M, int32_t N, in
 
 #define FR_SCHED_1F1B  0
 #define FR_SCHED_GPIPE 1
+#define FR_SCHED_INTERLEAVED 2   /* interleaved 1F1B (Narayanan et al. 2021), one of the bubble-reducing schedules
+                                    Sections 1 and 2.2.2 name: the stage holds `chunks` model chunks, an operation is
+                                    one chunk's FP or BP; the bubbles add up to 1 / chunks of the plain schedule's,
+                                    in more and shorter windows.  m must be a multiple of p.                         */
 typedef struct fr_stage fr_stage;
 typedef struct fr_stage_desc {
     int32_t  schedule;      /* FR_SCHED_*                                                                   */
     int32_t  p, m, stage;   /* pipeline depth, micro-batches per epoch, emulated stage (0-based)            */
-    uint64_t f_ns, b_ns;    /* declared FP / BP durations of every stage: fix the waits that stand for the
-                               other stages and the declared bubble lengths                                 */
+    uint64_t f_ns, b_ns;    /* declared FP / BP durations of one operation on every stage (FR_SCHED_INTERLEAVED: of
+                               one chunk): fix the waits that stand for the other stages and the declared
+                               bubble lengths                                                               */
+    int32_t  chunks;        /* FR_SCHED_INTERLEAVED: model chunks per stage, 1 .. 64, a divisor of the load's
+                               layers; otherwise 0 or 1                                                     */
+    int32_t  reserved;
 } fr_stage_desc;
 typedef struct fr_stage_op {
     int32_t  kind;          /* 0 = FP, 1 = BP                                                               */
     int32_t  microbatch;
     uint64_t start_ns, end_ns;      /* in the ideal schedule, from the epoch start                          */
     uint64_t bubble_before_ns;      /* idle time in front of this operation (0 = none)                      */
+    int32_t  chunk;                 /* model chunk (FR_SCHED_INTERLEAVED), else 0                           */
+    int32_t  reserved;
 } fr_stage_op;
 typedef struct fr_epoch_result {
     uint64_t epoch_ns;          /* wall time of the epoch on this stage                                      */

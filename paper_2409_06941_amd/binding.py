@@ -11,7 +11,7 @@ FR_SUBMITTED, FR_CREATED, FR_PAUSED, FR_RUNNING, FR_STOPPED = range(5)
 FR_EV_INIT, FR_EV_CHUNK, FR_EV_IDLE, FR_EV_MISS, FR_EV_OVERRUN, FR_EV_REFUSED = 1, 2, 3, 4, 5, 6
 FR_PR_SEG_VERTEX, FR_PR_SEG_SCATTER, FR_PR_SEG_GATHER, FR_PR_SEG_FINISH = 0, 1, 2, 3
 FR_LOAD_BUSYWAIT, FR_LOAD_GPT = 0, 1
-FR_SCHED_1F1B, FR_SCHED_GPIPE = 0, 1
+FR_SCHED_1F1B, FR_SCHED_GPIPE, FR_SCHED_INTERLEAVED = 0, 1, 2
 
 _ERR_NAMES = {0: "FR_OK", -1: "FR_ERR_ARG", -2: "FR_ERR_STATE", -3: "FR_ERR_NOMEM", -4: "FR_ERR_OOM",
               -5: "FR_ERR_OVERRUN", -6: "FR_ERR_HIP"}
@@ -109,12 +109,12 @@ class fr_load_desc(C.Structure):
 
 class fr_stage_desc(C.Structure):
     _fields_ = [("schedule", C.c_int32), ("p", C.c_int32), ("m", C.c_int32), ("stage", C.c_int32),
-                ("f_ns", C.c_uint64), ("b_ns", C.c_uint64)]
+                ("f_ns", C.c_uint64), ("b_ns", C.c_uint64), ("chunks", C.c_int32), ("reserved", C.c_int32)]
 
 
 class fr_stage_op(C.Structure):
     _fields_ = [("kind", C.c_int32), ("microbatch", C.c_int32), ("start_ns", C.c_uint64), ("end_ns", C.c_uint64),
-                ("bubble_before_ns", C.c_uint64)]
+                ("bubble_before_ns", C.c_uint64), ("chunk", C.c_int32), ("reserved", C.c_int32)]
 
 
 class fr_epoch_result(C.Structure):
@@ -164,6 +164,7 @@ SIGNATURES = {
     "fr_load_destroy": (C.c_int, [C.c_void_p]),
     "fr_load_fp": (C.c_int, [C.c_void_p, C.c_void_p]),
     "fr_load_bp": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "fr_load_part": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "fr_load_flops": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
     "fr_gemm_bf16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]),
     "fr_stage_make": (C.c_int, [C.POINTER(fr_stage_desc), C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -450,6 +451,9 @@ class Load:
     def fr_load_bp(self, stream=None):
         return _check(lib().fr_load_bp(self.handle, _stream(stream)), "fr_load_bp")
 
+    def fr_load_part(self, stream=None, kind=0, part=0, parts=1):
+        return _check(lib().fr_load_part(self.handle, _stream(stream), kind, part, parts), "fr_load_part")
+
     def fr_load_flops(self):
         a, b = C.c_uint64(), C.c_uint64()
         _check(lib().fr_load_flops(self.handle, C.byref(a), C.byref(b)), "fr_load_flops")
@@ -468,9 +472,9 @@ def fr_gemm_bf16(A, B, Cmat, M, N, K, stream=None):
 class Stage:
     """fr_stage: one emulated pipeline stage."""
 
-    def __init__(self, schedule, p, m, stage, f_ns, b_ns, load=None, stream=None):
+    def __init__(self, schedule, p, m, stage, f_ns, b_ns, load=None, stream=None, chunks=0):
         d = fr_stage_desc()
-        d.schedule, d.p, d.m, d.stage, d.f_ns, d.b_ns = schedule, p, m, stage, f_ns, b_ns
+        d.schedule, d.p, d.m, d.stage, d.f_ns, d.b_ns, d.chunks = schedule, p, m, stage, f_ns, b_ns, chunks
         self._keep = (load, stream)
         self.handle = C.c_void_p()
         _check(lib().fr_stage_make(C.byref(d), load.handle if load is not None else None, _stream(stream),

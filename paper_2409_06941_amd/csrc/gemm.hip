@@ -210,11 +210,17 @@ int gemm_launch(const void* A, const void* B, void* C, int M, int N, int K, hipS
     return hipGetLastError() == hipSuccess ? FR_OK : FR_ERR_HIP;
 }
 
-int burst(fr_load* l, const std::vector<GemmShape>& list, uint64_t ns, hipStream_t stream)
+// Part `part` of `parts` of a burst: the GEMMs of the layers [part * layers / parts, (part + 1) * layers / parts)
+// (the list holds the layers one after the other, the same number of GEMMs each), or that share of a busy-wait.
+int burst(fr_load* l, const std::vector<GemmShape>& list, uint64_t ns, hipStream_t stream, int part = 0, int parts = 1)
 {
-    if (l->d.kind == FR_LOAD_BUSYWAIT) return fr_busywait_launch(ns, l->wall_clock_khz, stream);
+    if (parts < 1 || part < 0 || part >= parts) return FR_ERR_ARG;
+    if (l->d.kind == FR_LOAD_BUSYWAIT) return fr_busywait_launch(ns / (uint64_t)parts, l->wall_clock_khz, stream);
+    if (l->d.layers % parts != 0) return FR_ERR_ARG;
+    const size_t per_layer = list.size() / (size_t)l->d.layers, layers = (size_t)l->d.layers / (size_t)parts;
     uint16_t* ws = static_cast<uint16_t*>(l->d.workspace);
-    for (const GemmShape& g : list) {
+    for (size_t i = (size_t)part * layers * per_layer; i < ((size_t)part + 1) * layers * per_layer; ++i) {
+        const GemmShape& g = list[i];
         int rc = gemm_launch(ws + g.a_off, ws + g.b_off, ws + g.c_off, g.M, g.N, g.K, stream);
         if (rc != FR_OK) return rc;
     }
@@ -311,6 +317,13 @@ int fr_load_bp(fr_load* l, void* stream)
 {
     if (!l) return FR_ERR_ARG;
     return burst(l, l->bp, l->d.bp_ns, (hipStream_t)stream);
+}
+
+int fr_load_part(fr_load* l, void* stream, int32_t kind, int32_t part, int32_t parts)
+{
+    if (!l || (kind != 0 && kind != 1)) return FR_ERR_ARG;
+    return kind == 0 ? burst(l, l->fp, l->d.fp_ns, (hipStream_t)stream, part, parts)
+                     : burst(l, l->bp, l->d.bp_ns, (hipStream_t)stream, part, parts);
 }
 
 int fr_load_flops(fr_load* l, uint64_t* fp, uint64_t* bp)

@@ -21,48 +21,70 @@
 
 namespace {
 
-struct OpRef { int kind; int mb; };   // kind 0 = FP, 1 = BP
+struct OpRef { int kind; int mb; int chunk; };   // kind 0 = FP, 1 = BP; chunk: model chunk (interleaved schedule)
 
 // Serial order of stage s.  GPipe: all forwards then all backwards.  1F1B: min(p - 1 - s, m) warm-up forwards,
-// then one forward / one backward alternately, then the backwards that are left.
-std::vector<OpRef> order_of(int schedule, int p, int m, int s)
+// then one forward / one backward alternately, then the backwards that are left.  Interleaved 1F1B (Narayanan et
+// al. 2021, one of the bubble-reducing schedules the paper's Sections 1 and 2.2.2 refer to): the stage holds v model
+// chunks, chunk c being virtual stage c p + s; with n = m v operations of each kind, min(n, 2 (p - 1 - s) + (v - 1) p)
+// warm-up forwards, then pairs, then the backwards that are left; the k-th forward is chunk (k mod p v) div p of
+// micro-batch (k div p v) p + k mod p, the k-th backward the same micro-batch of chunk v - 1 - (k mod p v) div p.
+std::vector<OpRef> order_of(int schedule, int p, int m, int v, int s)
 {
     std::vector<OpRef> o;
-    o.reserve(2 * (size_t)m);
+    o.reserve(2 * (size_t)m * (size_t)v);
     if (schedule == FR_SCHED_GPIPE) {
-        for (int j = 0; j < m; ++j) o.push_back({0, j});
-        for (int j = 0; j < m; ++j) o.push_back({1, j});
+        for (int j = 0; j < m; ++j) o.push_back({0, j, 0});
+        for (int j = 0; j < m; ++j) o.push_back({1, j, 0});
+        return o;
+    }
+    if (schedule == FR_SCHED_INTERLEAVED) {
+        const int n = m * v, pv = p * v;
+        auto fwd = [&](int k) { return OpRef{0, (k / pv) * p + k % p, (k % pv) / p}; };
+        auto bwd = [&](int k) { return OpRef{1, (k / pv) * p + k % p, v - 1 - (k % pv) / p}; };
+        const int warm = std::min(n, 2 * (p - 1 - s) + (v - 1) * p);
+        int f = 0, b = 0;
+        for (; f < warm; ++f) o.push_back(fwd(f));
+        while (b < n) {
+            if (f < n) o.push_back(fwd(f++));
+            o.push_back(bwd(b++));
+        }
         return o;
     }
     const int warm = std::min(p - 1 - s, m);
     int f = 0, b = 0;
-    for (; f < warm; ++f) o.push_back({0, f});
+    for (; f < warm; ++f) o.push_back({0, f, 0});
     while (b < m) {
-        if (f < m) o.push_back({0, f++});
-        o.push_back({1, b++});
+        if (f < m) o.push_back({0, f++, 0});
+        o.push_back({1, b++, 0});
     }
     return o;
 }
 
+// The dependency graph runs over virtual stages vs = chunk * p + stage (vs = stage when there is one chunk): FP of
+// vs needs FP of vs - 1, BP of vs needs BP of vs + 1, and on the last virtual stage the BP needs its own FP.
 struct IdealSchedule {
-    int p, m;
+    int p, m, v;
     uint64_t f, b;
     std::vector<std::vector<OpRef>> order;          // [stage][slot]
-    std::vector<std::vector<int>> slot_of[2];       // [kind][stage][mb] -> slot
+    std::vector<std::vector<int>> slot_of[2];       // [kind][stage][chunk * m + mb] -> slot
     std::vector<std::vector<int64_t>> finish;       // [stage][slot], -1 = not yet known
+
+    int64_t finish_vs(int kind, int vs, int mb) { return finish_of(vs % p, slot_of[kind][vs % p][(vs / p) * m + mb]); }
 
     int64_t finish_of(int s, int slot)
     {
         int64_t& memo = finish[s][slot];
         if (memo >= 0) return memo;
         const OpRef op = order[s][slot];
+        const int vs = op.chunk * p + s;
         int64_t ready = slot > 0 ? finish_of(s, slot - 1) : 0;
         if (op.kind == 0) {
-            if (s > 0) ready = std::max(ready, finish_of(s - 1, slot_of[0][s - 1][op.mb]));
-        } else if (s == p - 1) {
-            ready = std::max(ready, finish_of(s, slot_of[0][s][op.mb]));
+            if (vs > 0) ready = std::max(ready, finish_vs(0, vs - 1, op.mb));
+        } else if (vs == v * p - 1) {
+            ready = std::max(ready, finish_vs(0, vs, op.mb));
         } else {
-            ready = std::max(ready, finish_of(s + 1, slot_of[1][s + 1][op.mb]));
+            ready = std::max(ready, finish_vs(1, vs + 1, op.mb));
         }
         memo = ready + (int64_t)(op.kind == 0 ? f : b);
         return memo;
@@ -109,9 +131,12 @@ extern "C" {
 int fr_stage_make(const fr_stage_desc* d, fr_load* load, void* stage_stream, fr_stage** out)
 {
     if (!d || !out) return FR_ERR_ARG;
-    if (d->schedule != FR_SCHED_1F1B && d->schedule != FR_SCHED_GPIPE) return FR_ERR_ARG;
+    if (d->schedule != FR_SCHED_1F1B && d->schedule != FR_SCHED_GPIPE && d->schedule != FR_SCHED_INTERLEAVED) return FR_ERR_ARG;
     if (d->p < 1 || d->m < 1 || d->stage < 0 || d->stage >= d->p || d->f_ns == 0 || d->b_ns == 0) return FR_ERR_ARG;
     if (d->p > 1024 || d->m > 4096) return FR_ERR_ARG;   // keeps the recursion shallow
+    const int v = d->schedule == FR_SCHED_INTERLEAVED ? d->chunks : 1;
+    if (v < 1 || v > 64 || (d->schedule == FR_SCHED_INTERLEAVED && d->m % d->p != 0)) return FR_ERR_ARG;
+    if (d->schedule != FR_SCHED_INTERLEAVED && d->chunks > 1) return FR_ERR_ARG;
     fr_stage* s = new (std::nothrow) fr_stage();
     if (!s) return FR_ERR_ARG;
     s->d = *d;
@@ -119,15 +144,18 @@ int fr_stage_make(const fr_stage_desc* d, fr_load* load, void* stage_stream, fr_
     s->stream = (hipStream_t)stage_stream;
 
     IdealSchedule is;
-    is.p = d->p; is.m = d->m; is.f = d->f_ns; is.b = d->b_ns;
+    is.p = d->p; is.m = d->m; is.v = v; is.f = d->f_ns; is.b = d->b_ns;
     is.order.resize(d->p);
-    is.slot_of[0].assign(d->p, std::vector<int>(d->m, -1));
-    is.slot_of[1].assign(d->p, std::vector<int>(d->m, -1));
+    is.slot_of[0].assign(d->p, std::vector<int>((size_t)d->m * v, -1));
+    is.slot_of[1].assign(d->p, std::vector<int>((size_t)d->m * v, -1));
     is.finish.resize(d->p);
     for (int st = 0; st < d->p; ++st) {
-        is.order[st] = order_of(d->schedule, d->p, d->m, st);
+        is.order[st] = order_of(d->schedule, d->p, d->m, v, st);
         is.finish[st].assign(is.order[st].size(), -1);
-        for (size_t k = 0; k < is.order[st].size(); ++k) is.slot_of[is.order[st][k].kind][st][is.order[st][k].mb] = (int)k;
+        for (size_t k = 0; k < is.order[st].size(); ++k) {
+            const OpRef& op = is.order[st][k];
+            is.slot_of[op.kind][st][(size_t)op.chunk * d->m + op.mb] = (int)k;
+        }
     }
     int64_t epoch = 0;
     for (int st = 0; st < d->p; ++st) epoch = std::max(epoch, is.finish_of(st, (int)is.order[st].size() - 1));
@@ -137,7 +165,7 @@ int fr_stage_make(const fr_stage_desc* d, fr_load* load, void* stage_stream, fr_
         const int64_t end = is.finish_of(d->stage, (int)k);
         const int64_t start = end - (int64_t)(mine[k].kind == 0 ? d->f_ns : d->b_ns);
         fr_stage_op op{};
-        op.kind = mine[k].kind; op.microbatch = mine[k].mb;
+        op.kind = mine[k].kind; op.microbatch = mine[k].mb; op.chunk = mine[k].chunk;
         op.start_ns = (uint64_t)start; op.end_ns = (uint64_t)end;
         op.bubble_before_ns = (uint64_t)(start - prev_end);
         s->ops.push_back(op);
@@ -224,7 +252,8 @@ int fr_stage_run_epoch(fr_stage* s, fr_ctx* ctx, fr_epoch_result* out)
             if (rc != FR_OK) return rc;
         }
         const uint64_t a = clock_ns();
-        int rc = op.kind == 0 ? fr_load_fp(s->load, (void*)s->stream) : fr_load_bp(s->load, (void*)s->stream);
+        const int parts = s->d.schedule == FR_SCHED_INTERLEAVED ? s->d.chunks : 1;
+        int rc = fr_load_part(s->load, (void*)s->stream, op.kind, op.chunk, parts);
         if (rc != FR_OK) return rc;
         FR_HIP_TRY(hipStreamSynchronize(s->stream), hip_err);
         const uint64_t took = clock_ns() - a;

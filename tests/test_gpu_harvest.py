@@ -203,6 +203,56 @@ def test_harvest_in_rounds_matches_plan_and_oracle():
     assert (np.abs(got[big] - oracle[big]) / oracle[big]).max() <= 1e-4
 
 
+def test_harvest_in_the_bubbles_of_an_interleaved_schedule_matches_plan_and_oracle():
+    # Interleaved 1F1B with two model chunks per stage (bubble-reducing prior work, Sections 1 and 2.2.2): the same
+    # stage idles half as long, in more and shorter windows.  The side task still lands in them exactly as the
+    # oracle's planner says, and ends with the standalone run's bits and the oracle's values.
+    cfg = configs.by_name("cfg1")
+    g = cfg.build_graph()
+    K = 10
+    rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)
+    ranks = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    ref = torch.zeros(g.n_vertices, dtype=torch.float32, device="cuda")
+    t_ref = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ref, iterations=K)
+    t_ref.fr_pagerank_run_standalone(0, torch.cuda.current_stream())
+    t_ref.fr_pagerank_destroy()
+    guard, launch, max_chunk = 200_000, 25_000, 400_000
+    floors = (9_000, 60_000, 80_000, 20_000)
+    ctx = fr.Context(device_id=0, guard_ns=guard, launch_cost_ns=launch, max_chunk_ns=max_chunk, time_steps=1)
+    task = fr.PageRankTask(g.n_vertices, g.n_edges, rp, col, od, ranks, iterations=K, max_runs=2,
+                           fs_per_edge=260_000, fs_per_message=400_000, fs_per_vertex=300_000, finish_tile_ns=15000,
+                           min_step_ns=floors)
+    tid = ctx.fr_task_register(task.ops, task.user, task.profile)
+    assert _init_bubble(ctx, tid) == fr.FR_OK
+    p, m, v, s, f_ns, b_ns = 4, 8, 2, 2, 1_000_000, 2_000_000          # per chunk: half of cfg1's 2 ms / 4 ms
+    stream = torch.cuda.Stream()
+    load = fr.Load(fr.FR_LOAD_BUSYWAIT, fp_ns=v * f_ns, bp_ns=v * b_ns)     # a chunk's operation is 1 / v of the burst
+    stage = fr.Stage(fr.FR_SCHED_INTERLEAVED, p, m, s, f_ns, b_ns, load, stream, chunks=v)
+    n_epochs = 4
+    results = [stage.fr_stage_run_epoch(ctx) for _ in range(n_epochs)]
+    pr = ctx.fr_query_progress(tid)
+    log = ctx.fr_event_log()
+    segs = _segments(task, K)
+    ctx.fr_task_stop(tid)
+    got = ranks.cpu().numpy()
+    task.fr_pagerank_destroy(); stage.fr_stage_destroy(); load.fr_load_destroy(); ctx.fr_destroy()
+
+    windows, T = schedule.bubbles_interleaved(p, m, v, f_ns, b_ns, s)
+    plain, T_plain = schedule.bubbles("1f1b", p, m, v * f_ns, v * b_ns, s)
+    assert sum(e - a for a, e in windows) * v == sum(e - a for a, e in plain) and len(windows) > len(plain)
+    assert [r.n_bubbles for r in results] == [len(windows)] * n_epochs
+    assert [r.bubble_ns for r in results] == [sum(e - a for a, e in windows)] * n_epochs
+    assert pr.overruns == 0 and pr.deadline_misses == 0
+    lengths = [2_000_000_000] + [e - a for a, e in windows] * n_epochs
+    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=2, floors=_floors(floors, K))
+    got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
+    want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
+    assert got_log == want_log
+    assert pr.runs_completed == 2
+    assert np.array_equal(got.view(np.uint32), ref.cpu().numpy().view(np.uint32))
+    _oracle_check(got, g, K)
+
+
 def test_pagerank_task_is_stopped_alone_when_it_exceeds_its_memory_limit():
     g = graphs.rmat_csr(12, 1 << 15, seed=2)
     rp, col, od = _dev(g.row_ptr, torch.int32), _dev(g.col, torch.int32), _dev(g.out_degree, torch.int32)

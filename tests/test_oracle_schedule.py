@@ -115,3 +115,59 @@ def test_paper_measured_bubble_rates_sit_just_below_the_ideal_schedule():
         # 6B row: the paper notes the rate drops slightly with model size; allow 3 points there
         tol = 3.0 if row["model"] == "6B" else 1.5
         assert 0 <= ideal - row["bubble_rate_percent"] <= tol, row
+
+
+# ---- interleaved 1F1B (bubble-reducing prior work the paper names in Sections 1 and 2.2.2)
+
+@pytest.mark.parametrize("p,m,v", [(2, 2, 2), (4, 4, 2), (4, 8, 2), (4, 12, 3), (8, 16, 2), (8, 16, 4), (3, 9, 5)])
+@pytest.mark.parametrize("f,b", [(2, 4), (3, 3), (5, 7)])
+def test_interleaved_closed_forms(p, m, v, f, b):
+    # with f, b the per-chunk durations: every device idles (p - 1)(f + b) in an epoch of m v (f + b) + (p - 1)(f + b),
+    # i.e. 1 / v of the plain schedule's bubble time for the same model (whose FP takes v f); fraction
+    # (p - 1) / (m v + p - 1)
+    from oracle.schedule import simulate_interleaved
+    timed, T = simulate_interleaved(p, m, v, f, b)
+    assert T == (m * v + p - 1) * (f + b)
+    for s in range(p):
+        busy = sum(o.end - o.start for o in timed[s])
+        assert busy == m * v * (f + b)
+        assert T - busy == (p - 1) * (f + b)
+        # every (kind, micro-batch, chunk) exactly once, serially, and no operation before what it depends on
+        assert sorted((o.kind, o.mb, o.chunk) for o in timed[s]) == sorted((k, j, c) for k in "FB" for j in range(m) for c in range(v))
+        assert all(a.end <= b_.start for a, b_ in zip(timed[s], timed[s][1:]))
+    end = {(o.kind, o.chunk * p + s, o.mb): o.end for s in range(p) for o in timed[s]}
+    for s in range(p):
+        for o in timed[s]:
+            vs = o.chunk * p + s
+            if o.kind == "F" and vs > 0:
+                assert o.start >= end[("F", vs - 1, o.mb)]
+            if o.kind == "B":
+                assert o.start >= (end[("F", vs, o.mb)] if vs == v * p - 1 else end[("B", vs + 1, o.mb)])
+
+
+def test_interleaved_hand_worked_windows():
+    # p = 2, m = 2, v = 2, f = b = 1: virtual stages 0 (device 0, chunk 0), 1 (device 1, chunk 0), 2 (device 0, chunk 1),
+    # 3 (device 1, chunk 1).  Device 0 runs four warm-up forwards 0-1, 1-2, 2-3, 3-4, then waits for the first backward
+    # of virtual stage 3 (4-5): backwards 5-6, 7-8, 8-9, 9-10 -> idle [4, 5) and [6, 7).  Device 1: forwards 1-2, 2-3,
+    # 3-4, backward 4-5, forward 5-6, backwards 6-7, 7-8, 8-9 -> idle [0, 1) and [9, 10).  Epoch 10 = (4 + 1) * 2.
+    from oracle.schedule import bubbles_interleaved
+    assert bubbles_interleaved(2, 2, 2, 1, 1, 0) == ([(4, 5), (6, 7)], 10)
+    assert bubbles_interleaved(2, 2, 2, 1, 1, 1) == ([(0, 1), (9, 10)], 10)
+
+
+def test_interleaving_cuts_the_bubble_time_of_the_same_model_by_v():
+    # the same model on the same devices: plain 1F1B with FP = 8, BP = 16 against two chunks of FP = 4, BP = 8
+    from oracle.schedule import simulate_interleaved
+    plain, T1 = simulate("1f1b", 4, 8, 8, 16)
+    inter, T2 = simulate_interleaved(4, 8, 2, 4, 8)
+    idle1 = T1 - sum(o.end - o.start for o in plain[2])
+    idle2 = T2 - sum(o.end - o.start for o in inter[2])
+    assert idle1 == 72 and idle2 == 36 and T1 - T2 == 36
+    w2, _ = bubbles_interleaved_windows(4, 8, 2, 4, 8, 2)
+    w1, _ = bubbles("1f1b", 4, 8, 8, 16, 2)
+    assert len(w2) >= len(w1) and max(e - a for a, e in w2) <= max(e - a for a, e in w1)
+
+
+def bubbles_interleaved_windows(p, m, v, f, b, s):
+    from oracle.schedule import bubbles_interleaved
+    return bubbles_interleaved(p, m, v, f, b, s)

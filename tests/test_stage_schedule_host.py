@@ -35,3 +35,34 @@ def test_bad_stage_arguments_are_rejected():
         with pytest.raises(fr.FreeRideError) as e:
             fr.Stage(*args)
         assert e.value.code == fr.FR_ERR_ARG
+
+
+@pytest.mark.parametrize("p,m,v", [(2, 2, 2), (4, 8, 2), (4, 8, 1), (4, 12, 3), (8, 16, 4), (3, 6, 2)])
+@pytest.mark.parametrize("f,b", [(1_000_000, 2_000_000), (7, 11)])
+def test_interleaved_ops_and_bubbles_match_oracle(p, m, v, f, b):
+    timed, T = schedule.simulate_interleaved(p, m, v, f, b)
+    for s in range(p):
+        st = fr.Stage(fr.FR_SCHED_INTERLEAVED, p, m, s, f, b, chunks=v)
+        ops, epoch, tail = st.fr_stage_ops()
+        st.fr_stage_destroy()
+        assert epoch == T
+        assert [("F" if o.kind == 0 else "B", o.microbatch, o.chunk, o.start_ns, o.end_ns) for o in ops] == \
+            [(o.kind, o.mb, o.chunk, o.start, o.end) for o in timed[s]]
+        windows, _ = schedule.bubbles_interleaved(p, m, v, f, b, s)
+        got, t = [], 0
+        for o in ops:
+            if o.bubble_before_ns:
+                got.append((o.start_ns - o.bubble_before_ns, o.start_ns))
+            t = o.end_ns
+        if tail:
+            got.append((t, t + tail))
+        assert got == windows
+
+
+def test_interleaved_needs_whole_groups_of_micro_batches_and_chunks():
+    for kw in [dict(p=4, m=6, chunks=2), dict(p=4, m=8, chunks=0), dict(p=4, m=8, chunks=65)]:
+        with pytest.raises(fr.FreeRideError) as e:
+            fr.Stage(fr.FR_SCHED_INTERLEAVED, kw["p"], kw["m"], 0, 5, 5, chunks=kw["chunks"])
+        assert e.value.code == fr.FR_ERR_ARG
+    with pytest.raises(fr.FreeRideError):
+        fr.Stage(fr.FR_SCHED_1F1B, 4, 8, 0, 5, 5, chunks=2)
