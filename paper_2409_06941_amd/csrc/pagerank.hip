@@ -87,6 +87,8 @@ struct DevArgs {
     int64_t V, E;
     uint32_t M, Q, Qe, n_gather, n_pieces, n_scatter, n_spieces, n_finish, n_dpart;
     uint32_t rows_per_part, rows_shift;           // rows per range and its log2
+    uint32_t void_slot;                           // scatter piece whose slot of dangling partials takes the void pieces' mass (kNoVoid: none)
+    float n_void_dangling;                        // rows of void pieces in ranges without in-edges: each holds the base value
     float damping;
     const uint16_t* ids16;
     const uint16_t* src16;
@@ -525,6 +527,8 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
     };
     uint32_t local = xcd_runs(blockIdx.x, gridDim.x);
     do {
+        if (tile0 + local == 0 && !first && A.void_slot != kNoVoid && threadIdx.x == 0)       // (once per sweep)
+            A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + A.void_slot] = base * A.n_void_dangling;
         const uint4* rec = reinterpret_cast<const uint4*>(A.scatter_tiles + tile0 + local);
         const uint4 span = rec[0];                               // x, y: the tile's pieces, worked on one after the other;
         const uint4 span_info = rec[1];                          // z, w: the sources of the first; then their range
@@ -608,8 +612,8 @@ void k_gather(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parity
     const float D = dangling_total(A.dpart + (size_t)parity * A.n_dpart, A.n_dpart);
     const float base = (1.0f - A.damping) / (float)A.V + A.damping * D / (float)A.V;
     float* dnext = A.dpart + (size_t)(parity ^ 1) * A.n_dpart;
-    if (tile0 == 0 && blockIdx.x == 0 && !final_pass)            // slots no piece and no scatter tile writes
-        for (uint32_t i = A.n_pieces + A.n_spieces + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;
+    if (tile0 == 0 && blockIdx.x == 0 && !final_pass)            // slots no gather piece writes: the scatter tiles of the next sweep
+        for (uint32_t i = A.n_pieces + threadIdx.x; i < A.n_dpart; i += kGatherBlock) dnext[i] = 0.0f;     // fill theirs in, void pieces have none
     uint32_t local = blockIdx.x;
     do {
     const uint4* rec = reinterpret_cast<const uint4*>(A.gather_tiles + tile0 + local);
@@ -902,7 +906,7 @@ int pr_launch(PrTask* p, uint32_t g, uint32_t tile0, uint32_t tile1, hipStream_t
         if (kind == FR_PR_SEG_SCATTER) {    // S_k finishes rows of r_k with D_{k-1}: set (k-1) & 1
             const int parity = (int)((k + 1) & 1u), first = k == 0 ? 1 : 0;
             const uint32_t grid = std::min(n, p->L.scatter_slots);
-            const bool packed = p->L.n_scatter != p->L.n_spieces, dynamic = n > grid;
+            const bool packed = p->L.scatter_packed, dynamic = n > grid;
             auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(grid), dim3(kScatterBlock), 0, stream, args, G, tile0, n, parity, first); };
             if (p->L.src_per_part == kSrcLarge) {
                 if (packed) { if (dynamic) go(k_scatter<kSrcLarge, true, true>); else go(k_scatter<kSrcLarge, true, false>); }
@@ -978,6 +982,7 @@ int pr_init(void* user, fr_alloc* a, void* stream_v)
     A.n_dpart = p->n_dpart; A.damping = p->d.damping;
     A.rows_per_part = L.rows_per_part;
     A.rows_shift = L.rows_per_part == kRowsLarge ? 14 : 13;
+    A.void_slot = L.void_slot; A.n_void_dangling = (float)L.n_void_dangling;
     A.ids16 = L.ids16; A.src16 = L.src16; A.mbase = L.mbase; A.starts = L.starts; A.bins = L.bins;
     A.inv_out = L.inv_out; A.perm = L.perm; A.range_info = L.range_info;
     A.gather_pieces = L.gather_pieces; A.gather_tiles = L.gather_tiles;

@@ -54,23 +54,46 @@ __global__ __launch_bounds__(kBlk) void k_validate(int64_t V, int64_t E, const i
     if (err) *bad = 1;
 }
 
-// Sort key of a vertex: larger in-degree first, ties by the caller's id.
-__global__ __launch_bounds__(kBlk) void k_vertex_keys(int64_t V, const int32_t* __restrict__ row_ptr, uint64_t* __restrict__ keys)
+// Vertex order: larger in-degree first, ties by the caller's id - except among the vertices without in-edges, which
+// are ordered by falling out-degree first.  Those vertices have no row sums to gather, so their order is free as far
+// as the gather sweep goes, and for the scatter sweep it lines up the ones without out-edges, which send no message,
+// in one run at the very end that no scatter piece has to load.  (Breaking all ties by out-degree gives a few more
+// such runs and made the gather sweep 2 to 6 % slower on R-MAT graphs: rows of like out-degree are like in whom
+// they are pointed to by, and the ids of a wavefront's 64 edges then fall on fewer accumulators.)
+// Two sorts of 64-bit keys: by (out-degree falling, id), then by (in-degree falling, id or, without in-edges, the
+// rank in the first order).
+__global__ __launch_bounds__(kBlk) void k_vertex_keys_out(int64_t V, const int32_t* __restrict__ outdeg, uint64_t* __restrict__ keys)
 {
     const int64_t v = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (v >= V) return;
+    const uint32_t d = (uint32_t)(outdeg[v] < 0 ? 0 : outdeg[v]);
+    keys[v] = ((uint64_t)(0x7fffffffu - d) << 32) | (uint64_t)(uint32_t)v;
+}
+
+__global__ __launch_bounds__(kBlk) void k_vertex_keys_in(int64_t V, const int32_t* __restrict__ row_ptr, const uint64_t* __restrict__ by_out,
+                                                         uint64_t* __restrict__ keys)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlk + threadIdx.x;
+    if (i >= V) return;
+    uint32_t v = (uint32_t)(by_out[i] & 0xffffffffu);
+    if ((int64_t)v >= V) v = 0;                        // cannot happen: the keys hold 0 .. V-1
     const uint32_t indeg = (uint32_t)(row_ptr[v + 1] - row_ptr[v]);
-    keys[v] = ((uint64_t)(0x7fffffffu - indeg) << 32) | (uint64_t)(uint32_t)v;
+    keys[i] = ((uint64_t)(0x7fffffffu - indeg) << 32) | (uint64_t)(indeg ? v : (uint32_t)i);
 }
 
 // perm[new] = old, inv[old] = new, inv_out[new] = 1/outdeg (0 for dangling vertices)
-__global__ __launch_bounds__(kBlk) void k_perm(int64_t V, const uint64_t* __restrict__ sorted, const int32_t* __restrict__ outdeg,
-                                               int32_t* __restrict__ perm, int32_t* __restrict__ inv, float* __restrict__ inv_out)
+__global__ __launch_bounds__(kBlk) void k_perm(int64_t V, const uint64_t* __restrict__ sorted, const uint64_t* __restrict__ by_out,
+                                               const int32_t* __restrict__ outdeg, int32_t* __restrict__ perm, int32_t* __restrict__ inv,
+                                               float* __restrict__ inv_out)
 {
     const int64_t n = (int64_t)blockIdx.x * kBlk + threadIdx.x;
     if (n >= V) return;
-    uint32_t old = (uint32_t)(sorted[n] & 0xffffffffu);
-    if ((int64_t)old >= V) old = 0;                    // cannot happen: the keys hold 0 .. V-1
+    uint32_t old = (uint32_t)(sorted[n] & 0xffffffffu);          // the id, or for a vertex without in-edges its rank by out-degree
+    if ((int64_t)old >= V) old = 0;                    // cannot happen
+    if ((sorted[n] >> 32) == 0x7fffffffull) {
+        old = (uint32_t)(by_out[old] & 0xffffffffu);
+        if ((int64_t)old >= V) old = 0;                // cannot happen
+    }
     perm[n] = (int32_t)old;
     inv[old] = (int32_t)n;
     const int32_t d = outdeg[old];
@@ -311,24 +334,32 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     PREP_HIP(hipStreamSynchronize(stream));
     if (bad_host) return FR_ERR_ARG;
 
-    // ---- vertices in order of falling in-degree
+    // ---- vertices in order of falling in-degree; those without in-edges by falling out-degree
     if (!keep(a, &L->perm, (uint64_t)V) || !keep(a, &L->inv_out, (uint64_t)V)) PREP_NEED((void*)nullptr);
     int32_t* inv = tmp.take<int32_t>((uint64_t)V);
     PREP_NEED(inv);
     {
+        uint64_t* by_out = tmp.take<uint64_t>((uint64_t)V);
         uint64_t* vk_a = tmp.take<uint64_t>((uint64_t)V);
         uint64_t* vk_b = tmp.take<uint64_t>((uint64_t)V);
-        PREP_NEED(vk_a); PREP_NEED(vk_b);
-        hipLaunchKernelGGL(k_vertex_keys, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, vk_a);
-        rocprim::double_buffer<uint64_t> db(vk_a, vk_b);
+        PREP_NEED(by_out); PREP_NEED(vk_a); PREP_NEED(vk_b);
         size_t bytes = 0;
-        PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, db, (size_t)V, 0u, 64u, stream));
+        {
+            rocprim::double_buffer<uint64_t> probe(vk_a, vk_b);
+            PREP_HIP(rocprim::radix_sort_keys(nullptr, bytes, probe, (size_t)V, 0u, 64u, stream));
+        }
         void* t = tmp.take<uint8_t>(bytes);
         PREP_NEED(t);
-        PREP_HIP(rocprim::radix_sort_keys(t, bytes, db, (size_t)V, 0u, 64u, stream));
-        hipLaunchKernelGGL(k_perm, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, db.current(), out_degree, L->perm, inv, L->inv_out);
+        hipLaunchKernelGGL(k_vertex_keys_out, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, out_degree, vk_a);
+        rocprim::double_buffer<uint64_t> first(vk_a, vk_b);
+        PREP_HIP(rocprim::radix_sort_keys(t, bytes, first, (size_t)V, 0u, 64u, stream));
+        PREP_HIP(hipMemcpyAsync(by_out, first.current(), (size_t)V * 8, hipMemcpyDeviceToDevice, stream));
+        hipLaunchKernelGGL(k_vertex_keys_in, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, row_ptr, by_out, vk_a);
+        rocprim::double_buffer<uint64_t> second(vk_a, vk_b);
+        PREP_HIP(rocprim::radix_sort_keys(t, bytes, second, (size_t)V, 0u, 64u, stream));
+        hipLaunchKernelGGL(k_perm, dim3(blocks_for((uint64_t)V)), dim3(kBlk), 0, stream, V, second.current(), by_out, out_degree, L->perm, inv, L->inv_out);
         PREP_HIP(hipStreamSynchronize(stream));
-        tmp.drop(t); tmp.drop(vk_a); tmp.drop(vk_b);
+        tmp.drop(t); tmp.drop(vk_a); tmp.drop(vk_b); tmp.drop(by_out);
     }
 
     // ---- sort the edges by (range, source, local row); set-up scratch is returned as soon as it is done with
@@ -526,6 +557,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
     // the pieces are cut for two per slot and each is a tile of its own.  Below that the target is the smallest one
     // (to 2 %) that leaves no more tiles than slots.
     std::vector<uint32_t> ubound;
+    std::vector<uint8_t> piece_void;
     std::vector<uint2> stiles;
     {
         std::vector<uint64_t> per_row(Q), rows_before((size_t)Q + 1, 0);
@@ -534,16 +566,47 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             const uint64_t lo = (uint64_t)j * rows_per_part, hi = std::min<uint64_t>((uint64_t)V, lo + rows_per_part);
             rows_before[j + 1] = rows_before[j] + (hi - lo) * per_row[j];
         }
+        // Runs of kVoidMin or more consecutive sources that send no message (vertices without out-edges: the order by
+        // in-degree, then out-degree, lines them up at the end of every class of equal in-degree) become VOID pieces,
+        // which no tile holds: nothing of them is loaded.  Not in merged ranges, whose rows the scatter sweep
+        // finishes.  Their dangling mass is not lost: in a range with in-edges the gather tile counts it, and in a
+        // range without, every such row holds the base value, so the sweep adds base x their number in one go.
+        std::vector<std::pair<uint64_t, uint64_t>> voids;
+        std::vector<uint64_t> void_rows_before_void;        // rows in the void runs before each of them
+        {
+            uint64_t first_voidable = std::min<uint64_t>((uint64_t)V, src_per_part);      // (the first piece always exists)
+            for (uint32_t j = 0; j < Q; ++j)
+                if ((L->ri[j].cls_tiles & 3u) == kRangeMerged) first_voidable = std::max(first_voidable, std::min<uint64_t>((uint64_t)V, ((uint64_t)j + 1) * rows_per_part));
+            uint64_t run_start = first_voidable, rows = 0;
+            for (uint64_t u = first_voidable; u <= (uint64_t)V; ++u) {
+                if (u < (uint64_t)V && cum[u + 1] == cum[u]) continue;
+                if (u - run_start >= kVoidMin) { voids.push_back({run_start, u}); void_rows_before_void.push_back(rows); rows += u - run_start; }
+                run_start = u + 1;
+            }
+            void_rows_before_void.push_back(rows);
+        }
+        auto void_rows_before = [&](uint64_t u) -> uint64_t {        // rows of void runs among the sources before u
+            const size_t k = (size_t)(std::upper_bound(voids.begin(), voids.end(), std::pair<uint64_t, uint64_t>(u, ~(uint64_t)0)) - voids.begin());   // runs starting at or before u
+            if (k == 0) return 0;
+            return void_rows_before_void[k - 1] + std::min(u, voids[k - 1].second) - voids[k - 1].first;
+        };
         auto weight_before = [&](uint64_t u) -> uint64_t {
             const uint64_t j = std::min<uint64_t>(u / rows_per_part, Q);
             const uint64_t rows = rows_before[j] + (j < Q ? (u - j * rows_per_part) * per_row[j] : 0);
-            return kScatterMessageWeight * (uint64_t)cum[u] + kScatterRowWeight * rows;
+            return kScatterMessageWeight * (uint64_t)cum[u] + kScatterRowWeight * (rows - void_rows_before(u));
         };
         auto cut = [&](uint64_t target) {
-            ubound.clear();
+            ubound.clear(); piece_void.clear();
             uint64_t u = 0;
+            size_t vi = 0;
             while (u < (uint64_t)V) {
-                const uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
+                if (vi < voids.size() && u == voids[vi].first) {
+                    ubound.push_back((uint32_t)u); piece_void.push_back(1);
+                    u = voids[vi++].second;
+                    continue;
+                }
+                uint64_t limit = std::min<uint64_t>((uint64_t)V, u + src_per_part);
+                if (vi < voids.size()) limit = std::min(limit, voids[vi].first);
                 const uint64_t want = weight_before(u) + target;
                 uint64_t lo = u + 1, hi = limit;             // the first end in (u, limit] that reaches `want`, else limit
                 while (lo < hi) {
@@ -551,25 +614,33 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
                     if (weight_before(mid) >= want) hi = mid;
                     else lo = mid + 1;
                 }
-                ubound.push_back((uint32_t)u);
+                ubound.push_back((uint32_t)u); piece_void.push_back(0);
                 u = lo;
             }
             ubound.push_back((uint32_t)V);
         };
-        auto pack = [&](uint64_t limit) {                    // (limit 0: a tile per piece)
+        auto live_pieces = [&]() { size_t n = 0; for (uint8_t v : piece_void) n += v ? 0 : 1; return n; };
+        auto pack = [&](uint64_t limit) {                    // (limit 0: a tile per piece); void pieces are in no tile
             stiles.clear();
             const uint32_t n = (uint32_t)ubound.size() - 1;
             uint64_t in_tile = 0;
             uint32_t first = 0;
+            bool open = false;
             for (uint32_t i = 0; i < n; ++i) {
-                const uint64_t c = weight_before(ubound[i + 1]) - weight_before(ubound[i]) + kScatterFixedWeight;
-                if (i > first && in_tile + c > limit) {
-                    stiles.push_back(make_uint2(first, i));
-                    first = i; in_tile = 0;
+                if (piece_void[i]) {
+                    if (open) stiles.push_back(make_uint2(first, i));
+                    open = false;
+                    continue;
                 }
+                const uint64_t c = weight_before(ubound[i + 1]) - weight_before(ubound[i]) + kScatterFixedWeight;
+                if (open && in_tile + c > limit) {
+                    stiles.push_back(make_uint2(first, i));
+                    open = false;
+                }
+                if (!open) { first = i; in_tile = 0; open = true; }
                 in_tile += c;
             }
-            stiles.push_back(make_uint2(first, n));
+            if (open) stiles.push_back(make_uint2(first, n));
         };
         const uint64_t slots = (uint64_t)cus * (src_per_part == kSrcSmall ? 2 : 1);
         const uint64_t all = weight_before((uint64_t)V), least = kMinTileMessages * kScatterMessageWeight;
@@ -587,7 +658,7 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             const uint64_t most = std::max<uint64_t>(least, (all + cus - 1) / cus);
             for (uint64_t target = start;; target = std::min(most, target + target / 50 + 1)) {
                 cut(target);
-                if (ubound.size() - 1 <= slots) { pack(0); done = true; break; }
+                if (live_pieces() <= slots) { pack(0); done = true; break; }
                 if (target >= most) break;
             }
         }
@@ -599,6 +670,18 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
             }
     }
     L->n_spieces = (uint32_t)ubound.size() - 1;
+    // the void pieces' rows in ranges without in-edges (all dangling: no message means no out-edge), and the slot of
+    // the dangling partials that takes base x their number
+    L->void_slot = kNoVoid; L->n_void_dangling = 0;
+    {
+        const uint64_t first_empty_row = std::min<uint64_t>((uint64_t)V, (uint64_t)Qe * rows_per_part);
+        for (uint32_t i = 0; i < L->n_spieces; ++i) {
+            if (!piece_void[i]) continue;
+            if (L->void_slot == kNoVoid) L->void_slot = i;
+            const uint64_t u0 = std::max<uint64_t>(ubound[i], first_empty_row), u1 = ubound[i + 1];
+            if (u1 > u0) L->n_void_dangling += u1 - u0;
+        }
+    }
     uint32_t* ubound_dev = tmp.take<uint32_t>(ubound.size());
     PREP_NEED(ubound_dev);
     PREP_HIP(hipMemcpyAsync(ubound_dev, ubound.data(), ubound.size() * 4, hipMemcpyHostToDevice, stream));
@@ -630,6 +713,8 @@ int pr_build_layout(PrLayout* L, int64_t V, int64_t E, const int32_t* row_ptr, c
         }
     }
     L->n_scatter = (uint32_t)L->st.size();
+    L->scatter_packed = false;
+    for (const ScatterTile& t : L->st) L->scatter_packed = L->scatter_packed || t.p1 - t.p0 > 1;
 
     if (!keep(a, &L->bins, (uint64_t)L->n_spieces * Qe) || !keep(a, &L->range_info, (uint64_t)Q) ||
         !keep(a, &L->gather_pieces, (uint64_t)L->n_pieces) || !keep(a, &L->gather_tiles, (uint64_t)L->n_gather) || !keep(a, &L->scatter_pieces, (uint64_t)L->n_spieces) || !keep(a, &L->scatter_tiles, (uint64_t)L->n_scatter) ||

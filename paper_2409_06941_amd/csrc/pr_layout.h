@@ -5,7 +5,8 @@
 // two streaming sweeps whose random accesses all land in LDS (the two-phase partition-centric idea of Beamer et
 // al., "propagation blocking", 2017, and Lakhotia et al., "PCPM", 2018, rebuilt around CDNA's 160 KB LDS):
 //
-//   * vertices are renumbered by in-degree, largest first (ties by old id); everything below is in new ids, and
+//   * vertices are renumbered by in-degree, largest first (ties by old id; without in-edges: by out-degree, largest
+//     first); everything below is in new ids, and
 //     perm[] leads back to the caller's ids when the final ranks are written.  With this order the rows that
 //     receive most edges sit together, so that many edges of one source fall into one row range and share one
 //     message: on an R-MAT graph of 2^22 vertices and 2^26 edges the messages drop from 0.50 to 0.20 per edge;
@@ -31,7 +32,10 @@
 //     is needed.  A range with one piece is DIRECT: its piece finishes its rows itself;
 //   * a scatter tile is a piece too: an interval of at most src_per_part consecutive sources, cut by weight
 //     (messages + values read; narrow for the sources that point into many ranges); every source belongs to exactly
-//     one piece, so the finishing of merged rows is done once per row;
+//     one piece, so the finishing of merged rows is done once per row.  The vertices without in-edges are ordered
+//     by out-degree, so those of them without out-edges either, which send no message, form one run at the end; such
+//     a run (any long run of sources without messages outside the merged ranges) is a VOID piece that belongs to no
+//     tile;
 //   * a launch has at most as many workgroups as run side by side; each starts on the tile of its own number and,
 //     when done, takes the next tile nobody has taken yet (one atomic counter per task, reset by the last
 //     workgroup to leave).  Tiles are in order of falling weight, so the light ones at the end fill the gaps the
@@ -77,6 +81,8 @@ constexpr uint32_t id_scale_for(uint32_t rows_per_part) { return rows_per_part <
 enum : uint32_t { kRangeDirect = 0, kRangeMerged = 1, kRangeEmpty = 2 };
 
 constexpr uint32_t kNoPartial = 0xffffffffu;
+constexpr uint32_t kNoVoid = 0xffffffffu;
+constexpr uint64_t kVoidMin = 4096;           // sources in a run without messages from which on the run is a void piece
 struct GatherPiece { uint32_t range, e0, e1, partial; };   // edges [e0, e1) of the sorted edge array; row of partial
                                                            // sums the piece writes (kNoPartial: direct range)
 struct ScatterPiece { uint32_t u0, u1; };                  // sources [u0, u1)
@@ -102,6 +108,9 @@ struct PrLayout {
     uint32_t n_merged = 0;           // ranges cut into several gather pieces
     uint32_t n_partials = 0;         // gather pieces of merged ranges = rows of partial sums
     uint32_t n_finish = 0;           // merged + empty ranges (the tiles of the pass after the last iteration)
+    bool scatter_packed = false;     // some scatter tile holds more than one piece
+    uint32_t void_slot = kNoVoid;    // first void scatter piece (kNoVoid: none)
+    uint64_t n_void_dangling = 0;    // rows of void pieces in ranges without in-edges
     uint32_t n_chunks = 0;           // ceil(E / kIdChunk)
 
     // device arrays (allocated through the task's accounting allocator)

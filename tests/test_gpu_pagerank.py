@@ -205,10 +205,12 @@ def test_memory_limit_refuses_the_task():
 
 
 def _host_layout(g, rows_per_range):
-    """Vertices renumbered by in-degree (largest first, ties by id); sorted (range, source, row) keys of the edges."""
+    """Vertices renumbered by in-degree (largest first, ties by id; the vertices without in-edges by out-degree, largest
+    first, then by id); sorted (range, source, row) keys of the edges."""
     V = g.n_vertices
     indeg = np.diff(g.row_ptr)
-    order = np.argsort(-indeg, kind="stable")
+    tie = np.where(indeg == 0, -g.out_degree.astype(np.int64), 0)
+    order = np.lexsort((np.arange(V), tie, -indeg.astype(np.int64)))
     new_id = np.empty(V, dtype=np.int64)
     new_id[order] = np.arange(V)
     row = new_id[np.repeat(np.arange(V), indeg)]
