@@ -142,6 +142,16 @@ def run_config(name, steps, warmup, args, headline):
         c = cal.fr_pagerank_tile_costs(kind)
         tile_cost_spread.append(max(c) * len(c) / max(1, sum(c)))      # heaviest tile / mean tile
     cal.fr_pagerank_destroy()
+    if args.profile_standalone:
+        # for counter and trace runs: every k_scatter / k_gather dispatch up to here is a whole sweep of the iteration
+        print(json.dumps({"config": cfg.name, "standalone_us": {"k_scatter": ph[1] / cal_iters / 1e3, "k_gather": ph[2] / cal_iters / 1e3},
+                          "whole_sweeps_per_kernel": 2 * cal_iters, "kernel_sources_sha256": kernel_sources_sha256(),
+                          "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0,
+                          "layout": {"messages": info.messages, "messages_per_edge": info.messages / max(1, E),
+                                     "partial_rows": info.partial_rows, "nonempty_ranges": info.nonempty_ranges,
+                                     "gather_tiles": info.gather_tiles, "scatter_tiles": info.scatter_tiles}}))
+        side_probe.fr_destroy()
+        sys.exit(0)
     # shortest steps: one iteration launched one tile at a time; a launch of a few tiles takes about as long as
     # one tile alone, which the additive tile costs cannot express (min_step_ns of the task's cost model)
     one = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=1)
@@ -151,16 +161,6 @@ def run_config(name, steps, warmup, args, headline):
     # (mean over the tiles, scaled to the heaviest tile by the default cost model's spread)
     one_tile_ns = [ph1[k] / max(1, n_tiles_kind[k]) * tile_cost_spread[k] for k in range(4)]
     side_probe.fr_destroy()
-    if args.profile_standalone:
-        # for counter and trace runs: every k_scatter / k_gather dispatch up to here but those of the one-tile-per-launch
-        # pass (grids of one workgroup) is a whole sweep of the iteration
-        print(json.dumps({"config": cfg.name, "standalone_us": {"k_scatter": ph[1] / cal_iters / 1e3, "k_gather": ph[2] / cal_iters / 1e3},
-                          "whole_sweeps_per_kernel": 2 * cal_iters, "kernel_sources_sha256": kernel_sources_sha256(),
-                          "algorithmic_bytes_per_iteration": 4.0 * E + 24.0 * V + 4.0,
-                          "layout": {"messages": info.messages, "messages_per_edge": info.messages / max(1, E),
-                                     "partial_rows": info.partial_rows, "nonempty_ranges": info.nonempty_ranges,
-                                     "gather_tiles": info.gather_tiles, "scatter_tiles": info.scatter_tiles}}))
-        sys.exit(0)
     M = max(1, info.messages)
     v_ns, s_ns, g_ns, h_ns = ph[0], ph[1] / cal_iters, ph[2] / cal_iters, ph[3]      # V0 and H run once per run
 
