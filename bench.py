@@ -340,8 +340,14 @@ def run_config(name, steps, warmup, args, headline):
         if e.measured_ns > 0:
             timed += group
             group = []
-    per_kind_n = [sum(1 for e in timed if seg_kind(e.segment) == k) for k in range(4)]
-    timed_edges = sum(e.work_units for e in timed)
+    # (with the device gate a step that was refused as a whole keeps its CHUNK record next to a REFUSED record of the
+    # same tiles: it did no work, and what time its kernel took stays in its group)
+    key = lambda e: (e.bubble, e.run, e.segment, e.tile0, e.tile1)
+    refused_whole = {key(e) for e in events if e.kind == fr.FR_EV_REFUSED}
+    timed = [e for e in timed if key(e) not in refused_whole or e.measured_ns > 0]
+    worked = lambda e: key(e) not in refused_whole
+    per_kind_n = [sum(1 for e in timed if worked(e) and seg_kind(e.segment) == k) for k in range(4)]
+    timed_edges = sum(e.work_units for e in timed if worked(e))
     # One iteration = one scatter + one gather sweep and moves 4E + 24V + 4 algorithmic bytes (col entries, row starts, one
     # compulsory read of every contribution, the rank write, and the vertex pass); iterations done = edges / E.
     iters_done = timed_edges / E
@@ -493,8 +499,10 @@ def main():
                     help="least time kept free at the end of every bubble (covers the slow first sweeps after a burst)")
     ap.add_argument("--time-steps", type=int, default=16,
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
-    ap.add_argument("--device-gate", type=int, default=0,
-                    help="1: every step also checks the GPU clock when its kernel starts and does nothing if it would end late")
+    ap.add_argument("--device-gate", type=int, default=1,
+                    help="1 (default): the steps also check the GPU clock, when their kernel starts and before a workgroup takes another "
+                         "tile, and stop where the bubble's time is up; what was not done is taken up in the next bubble.  "
+                         "0: the host's plan alone (a little more bubble time used, and now and then a step that ends late)")
     ap.add_argument("--adapt-costs", type=int, default=1,
                     help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs; PageRank only: Graph SGD is harvested 2 percent better with its frozen model, 0 overruns either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the fp32 CPU loops (the fp64 oracle still runs, as the parity check)")
@@ -528,7 +536,8 @@ def main():
     if args.per_config and args.config == "cfg5":
         out["per_config"] = {}
         keep = ("value", "unit", "steps", "ms_per_step", "config", "gteps_in_kernel", "bubble_time_used", "stage_slowdown_pct",
-                "stage_slowdown_vs_busy_bubbles_pct", "overruns", "deadline_misses", "runs_completed", "standalone_iteration_us",
+                "stage_slowdown_vs_busy_bubbles_pct", "overruns", "deadline_misses", "device_gate", "steps_refused", "runs_completed",
+                "standalone_iteration_us", "bubble_breakdown",
                 "roofline", "layout", "parity", "cpu_baseline")
         for name in ("cfg2", "cfg3", "cfg4"):
             r = run_config(name, 4, 1, args, headline=False)

@@ -75,8 +75,8 @@ typedef struct fr_config {
                                       heap; meant for tasks that enqueue no GPU work (runtime tests).        */
     uint32_t cu_count;             /* side stream may use this many compute units (first cu_count mask bits,
                                       which the driver deals round-robin over the XCDs); 0 = use cu_mask.    */
-    uint32_t cu_mask[8];           /* 256-bit CU mask for the side stream when cu_count == 0; all-zero = no
-                                      mask (an ordinary stream on every CU).                                 */
+    uint32_t cu_mask[8];           /* 256-bit CU mask for the side stream when cu_count == 0; all-zero, or a bit
+                                      for every CU of the device = no mask (an ordinary stream on every CU). */
     uint64_t mem_available_bytes;  /* free device memory in this stage's bubbles (Section 2.2.1)             */
     uint64_t guard_ns;             /* modelled work must end this long before the declared bubble end        */
     uint64_t launch_cost_ns;       /* modelled fixed cost added to every step                                */

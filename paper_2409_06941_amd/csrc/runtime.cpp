@@ -751,6 +751,13 @@ int fr_create(const fr_config* cfg, fr_ctx** out)
         } else if (cfg->cu_count == 0) {
             for (int i = 0; i < 8; ++i) { mask[i] = cfg->cu_mask[i]; masked |= mask[i] != 0; }
         }
+        if (masked) {
+            // a mask that leaves out no compute unit asks for what a plain stream is
+            int cus = 0, set = 0;
+            for (uint32_t w : mask) set += __builtin_popcount(w);
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device_id) == hipSuccess && cus > 0 && set >= cus)
+                masked = false;
+        }
         // Both stream kinds keep the default priority.
         if (masked) e = hipExtStreamCreateWithCUMask(&c->side, 8, mask);
         else e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
