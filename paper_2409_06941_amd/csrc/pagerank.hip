@@ -466,7 +466,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
     const uint4* src8 = reinterpret_cast<const uint4*>(A.src16);
     // rows a thread reads per round while the slice is filled (the small size has 64 registers per lane)
     constexpr int kFillRound = kSrcPerPart == kSrcSmall ? 4 : 16;
-    uint32_t asked = 0;                  // thread 0: the answer to its question for the next tile
+    uint32_t asked = kAskLater;          // thread 0: the answer to its question for the next tile
     bool last_piece = false;
     auto do_piece = [&](uint32_t t, ScatterPiece T, RangeInfo first_info) {
         // the first batch of bin descriptors is asked for now and used after the slice is filled
@@ -493,8 +493,6 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
             const float total = block_sum(fill_slice<kScatterBlock, kFillRound, kSrcPerPart == kSrcLarge>(A, u0, n, base, slice, first_info), red);
             if (threadIdx.x == 0) A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + t] = total;
         }
-        if constexpr (kDynamic)
-            if (last_piece && threadIdx.x == 0) asked = ask_if_time(A.sched, G);    // covered by the messages below
         for (uint32_t qb = 0; qb < Qe; qb += kDescBatch) {
             const uint32_t nb = Qe - qb < kDescBatch ? Qe - qb : kDescBatch;
             __syncthreads();                                     // slice filled / previous batch consumed
@@ -510,6 +508,11 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
             const uint32_t total = gpre[kScatterBlock];
             constexpr int kAhead = 4;                            // groups a thread has in flight
             for (uint32_t k0 = threadIdx.x; k0 < total; k0 += kAhead * kScatterBlock) {
+                // the question for the next tile goes out with the tile's last groups: put earlier, a workgroup on a
+                // heavy tile would book its next tile hundreds of microseconds before it is free to start it
+                if constexpr (kDynamic)
+                    if (threadIdx.x == 0 && last_piece && qb + kDescBatch >= Qe && k0 + kAhead * kScatterBlock >= total)
+                        asked = ask_if_time(A.sched, G);
                 GroupRef ref[kAhead];
                 uint4 raw[kAhead];
 #pragma unroll
@@ -529,6 +532,7 @@ void k_scatter(DevArgs A, GateArg G, uint32_t tile0, uint32_t n_tiles, int parit
     do {
         if (tile0 + local == 0 && !first && A.void_slot != kNoVoid && threadIdx.x == 0)       // (once per sweep)
             A.dpart[(size_t)(parity ^ 1) * A.n_dpart + A.n_pieces + A.void_slot] = base * A.n_void_dangling;
+        asked = kAskLater;
         const uint4* rec = reinterpret_cast<const uint4*>(A.scatter_tiles + tile0 + local);
         const uint4 span = rec[0];                               // x, y: the tile's pieces, worked on one after the other;
         const uint4 span_info = rec[1];                          // z, w: the sources of the first; then their range

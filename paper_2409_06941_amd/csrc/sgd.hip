@@ -32,10 +32,7 @@
 namespace {
 
 constexpr int kSgdBlock = 256;
-#ifndef FR_SGD_AHEAD
-#define FR_SGD_AHEAD 2
-#endif
-constexpr int kAhead = FR_SGD_AHEAD;             // ratings whose rows are in flight ahead of the one being worked on (>= 2)
+constexpr int kAhead = 2;                        // ratings whose rows are in flight ahead of the one being worked on (>= 2)
 constexpr int kIdBits = 27;                      // users and items below 2^27, at most 1024 blocks
 constexpr uint64_t kIdMask = (1ull << kIdBits) - 1;
 constexpr int kStratumShift = 2 * kIdBits;
