@@ -488,7 +488,7 @@ def run_config(name, steps, warmup, args, headline):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="timed epochs with the side task; 0 = 6 for cfg5 (2.5 s epochs), 12 otherwise")
+    ap.add_argument("--steps", type=int, default=0, help="timed epochs with the side task; 0 = 8 for cfg5 (2.5 s epochs), 12 otherwise")
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="cfg5")
     ap.add_argument("--per-config", type=int, default=1,
@@ -529,7 +529,7 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    steps = args.steps if args.steps else (6 if args.config == "cfg5" else 12)
+    steps = args.steps if args.steps else (8 if args.config == "cfg5" else 12)
     out = run_config(args.config, steps, args.warmup, args, headline=True)
     out["paper_context"] = {"bubble_rate_pct": 42.4, "cost_savings_pct": 7.8, "overhead_pct": 1.1,
                             "pagerank_iterations_per_s": 333.9, "hardware": "4x RTX 6000 Ada (paper, Section 6)"}
