@@ -289,7 +289,11 @@ def run_config(name, steps, warmup, args, headline):
         epochs(1, "A")                           # includes nothing of the task's initialisation: that had its own bubble
     torch.cuda.synchronize()
     half = [steps - steps // 2, steps // 2]
+    # (the arms without the side task get a quarter of the timed epochs per block, but no more than what keeps the
+    # whole default run within a few minutes when the epochs are seconds long)
     nb = max(1, steps // 4)
+    if ideal_epoch_ns >= 500_000_000:
+        nb = min(nb, 2)
     with_task, idle, busy, events = [], [], [], []
     p_edges = 0
     prog0 = ctx.fr_query_progress(tid)
