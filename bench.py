@@ -205,7 +205,7 @@ def run_config(name, steps, warmup, args, headline):
         ctx = fr.Context(device_id=0, cu_count=cu_count,
                          mem_available_bytes=mem_cap + 1, guard_ns=guard_ns, launch_cost_ns=launch_cost_ns,
                          max_chunk_ns=0, max_inflight=32, time_steps=time_steps, event_log_capacity=1 << 18,
-                         device_gate=args.device_gate, adapt_costs=adapt)
+                         device_gate=args.device_gate, gate_guard_ns=args.gate_guard_ns, adapt_costs=adapt)
         task = fr.PageRankTask(V, E, rp, col, od, ranks, damping=cfg.damping, iterations=K, max_runs=0,
                                mem_limit_bytes=mem_cap, **model)
         tid = ctx.fr_task_register(task.ops, task.user, task.profile)
@@ -507,6 +507,8 @@ def main():
                     help="1 (default): the steps also check the GPU clock, when their kernel starts and before a workgroup takes another "
                          "tile, and stop where the bubble's time is up; what was not done is taken up in the next bubble.  "
                          "0: the host's plan alone (a little more bubble time used, and now and then a step that ends late)")
+    ap.add_argument("--gate-guard-ns", type=int, default=50_000,
+                    help="the device gate's own guard (its clock is the GPU's: it needs no allowance for the host model's drift over a bubble); 0 = --guard-ns")
     ap.add_argument("--adapt-costs", type=int, default=1,
                     help="1: the runtime's running profiler also scales the step costs by what the timed groups show (in the timed epochs; PageRank only: Graph SGD is harvested 2 percent better with its frozen model, 0 overruns either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the fp32 CPU loops (the fp64 oracle still runs, as the parity check)")

@@ -97,12 +97,15 @@ typedef struct fr_config {
                                       measurements and no longer matches a plan computed ahead of time.  Needs
                                       time_steps.                                                              */
     uint32_t device_gate;          /* nonzero: every step also checks the GPU clock when its kernel starts and does
-                                      nothing if it could not end guard_ns before the bubble's declared end; a kernel
+                                      nothing if it could not end gate_guard_ns before the bubble's declared end; a kernel
                                       that hands its tiles out checks again before every further tile and stops
                                       between tiles (freeride_device.h); what was not done is taken back
                                       (fr_task_ops.rewind) and logged as FR_EV_REFUSED.  Only for tasks that provide
                                       rewind.                                                                     */
-    uint32_t reserved2;
+    uint32_t gate_guard_ns;        /* the device gate's own guard: its deadline is the declared end minus this.  The
+                                      host's guard_ns also has to cover steps that run slower than their model all
+                                      bubble long; the gate reads the GPU's clock, so what is left for it to allow for
+                                      is the error of one step's or tile's model and of the clock offset.  0 = guard_ns */
     uint64_t grace_ns;             /* framework-enforced limit (Section 4.5): a task whose work -- GPU steps, a step
                                       callback or InitSideTask -- is still going on this long after the end of the
                                       bubble it belongs to is stopped (FR_STOPPED, last_error FR_ERR_OVERRUN, memory
@@ -135,7 +138,7 @@ typedef struct fr_step {
     uint32_t gate_slot;
     void*    gate;          /* device pointer to the context's fr_gate                                      */
     uint32_t gate_need_ticks;   /* the step's modelled duration in GPU wall-clock ticks                     */
-    uint32_t gate_tile;     /* plan_step: modelled duration, ns, of the step's heaviest tile run alone if the step's
+    uint32_t gate_tile;     /* plan_step: modelled time, ns, a workgroup takes for the step's heaviest tile if the step's
                                kernel can stop between tiles (0 if it cannot: the step is all or nothing); the runtime
                                turns it into GPU wall-clock ticks, scaled like the step's cost, before run_step      */
 } fr_step;

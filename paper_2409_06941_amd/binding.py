@@ -27,7 +27,7 @@ class fr_config(C.Structure):
     _fields_ = [("device_id", C.c_int32), ("cu_count", C.c_uint32), ("cu_mask", C.c_uint32 * 8),
                 ("mem_available_bytes", C.c_uint64), ("guard_ns", C.c_uint64), ("launch_cost_ns", C.c_uint64),
                 ("max_chunk_ns", C.c_uint64), ("max_inflight", C.c_uint32), ("event_log_capacity", C.c_uint32),
-                ("time_steps", C.c_uint32), ("adapt_costs", C.c_uint32), ("device_gate", C.c_uint32), ("reserved2", C.c_uint32),
+                ("time_steps", C.c_uint32), ("adapt_costs", C.c_uint32), ("device_gate", C.c_uint32), ("gate_guard_ns", C.c_uint32),
                 ("grace_ns", C.c_uint64)]
 
 
@@ -241,7 +241,7 @@ class Context:
 
     def __init__(self, device_id=0, cu_count=0, cu_mask=None, mem_available_bytes=1 << 62, guard_ns=0,
                  launch_cost_ns=0, max_chunk_ns=0, max_inflight=0, event_log_capacity=0, time_steps=0, grace_ns=0,
-                 adapt_costs=0, device_gate=0):
+                 adapt_costs=0, device_gate=0, gate_guard_ns=0):
         cfg = fr_config()
         cfg.device_id = device_id
         cfg.cu_count = cu_count
@@ -251,6 +251,7 @@ class Context:
         cfg.guard_ns, cfg.launch_cost_ns, cfg.max_chunk_ns = guard_ns, launch_cost_ns, max_chunk_ns
         cfg.max_inflight, cfg.event_log_capacity, cfg.time_steps = max_inflight, event_log_capacity, time_steps
         cfg.grace_ns, cfg.adapt_costs, cfg.device_gate = grace_ns, adapt_costs, device_gate
+        cfg.gate_guard_ns = gate_guard_ns
         self.handle = C.c_void_p()
         _check(lib().fr_create(C.byref(cfg), C.byref(self.handle)), "fr_create")
         self._keep = []

@@ -1033,10 +1033,11 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
     if (slots && n > slots) {
         // the step's kernel hands its tiles out and can stop between them: what its heaviest tile - the first, they
-        // are in order of falling weight - takes alone, i.e. the slot's whole time for it (a tile's cost is its
-        // share of a round of `slots` tiles side by side)
-        const uint64_t alone = std::max<uint64_t>(floor_ns, (pre[p->tile + 1] - pre[p->tile]) * slots);
-        out->gate_tile = (uint32_t)std::min<uint64_t>(alone, 4000000000ull);
+        // are in order of falling weight - takes a workgroup, i.e. the slot's whole time for it (a tile's cost is its
+        // share of a round of `slots` tiles side by side) and a quarter more.  (Not the floor of the segment, which is
+        // the heaviest tile of the whole sweep run alone: the steps near a bubble's end are made of the light tiles.)
+        const uint64_t heaviest = std::max<uint64_t>(10000, (pre[p->tile + 1] - pre[p->tile]) * slots * 5 / 4);
+        out->gate_tile = (uint32_t)std::min<uint64_t>(heaviest, 4000000000ull);
     }
     if (kind == FR_PR_SEG_GATHER) {
         uint64_t edges = 0;

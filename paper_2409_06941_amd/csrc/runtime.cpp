@@ -395,7 +395,8 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     if (gated) {
         gate_settle(c, t);                                   // the previous bubble's verdicts, if still unread
         if (t->state != FR_RUNNING) return;                  // a failing rewind stopped the task
-        const int64_t end_gpu_ns = (int64_t)(t_begin + len) - (int64_t)guard + c->gpu_minus_host_ns;
+        const uint64_t gate_guard = c->cfg.gate_guard_ns ? c->cfg.gate_guard_ns : guard;
+        const int64_t end_gpu_ns = (int64_t)(t_begin + len) - (int64_t)gate_guard + c->gpu_minus_host_ns;
         const unsigned long long deadline = end_gpu_ns > 0 ? (unsigned long long)((double)end_gpu_ns * c->ticks_per_ns) : 0ull;
         hipLaunchKernelGGL(k_gate_open, dim3(1), dim3(1), 0, c->side, c->gate, deadline);
     }
