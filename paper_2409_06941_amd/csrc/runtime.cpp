@@ -128,6 +128,8 @@ struct fr_ctx {
     fr_gate* gate = nullptr;                // device memory, NULL when the gate is off
     double ticks_per_ns = 0.0;              // GPU wall clock
     int64_t gpu_minus_host_ns = 0;          // wall_clock64() / ticks_per_ns - CLOCK_MONOTONIC
+    uint64_t clock_window_ns = 0;           // width of the window that reading came from
+    uint64_t clock_read_ns = 0;             // host time of that reading
     std::vector<fr_step> gate_steps;        // steps enqueued since the gate was last opened, by slot (worker only)
     std::vector<uint32_t> gate_bubble;      //   and the bubble each belongs to
     std::vector<uint64_t> gate_seq;         //   and the sequence number of its CHUNK record
@@ -334,6 +336,8 @@ void gate_settle(fr_ctx* c, Task* t)
     c->gate_seq.clear();
 }
 
+void gate_refresh_clock(fr_ctx* c);
+
 // One bubble, on the worker thread, work_mu held.
 void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint32_t index)
 {
@@ -395,6 +399,7 @@ void serve_bubble(fr_ctx* c, uint64_t seq, uint64_t t_begin, uint64_t len, uint3
     if (gated) {
         gate_settle(c, t);                                   // the previous bubble's verdicts, if still unread
         if (t->state != FR_RUNNING) return;                  // a failing rewind stopped the task
+        gate_refresh_clock(c);
         const uint64_t gate_guard = c->cfg.gate_guard_ns ? c->cfg.gate_guard_ns : guard;
         const int64_t end_gpu_ns = (int64_t)(t_begin + len) - (int64_t)gate_guard + c->gpu_minus_host_ns;
         const unsigned long long deadline = end_gpu_ns > 0 ? (unsigned long long)((double)end_gpu_ns * c->ticks_per_ns) : 0ull;
@@ -616,6 +621,32 @@ void note_overrun(fr_ctx* c)
 // Allocates the gate and measures how the GPU's wall clock relates to the host's: a one-thread kernel stores
 // wall_clock64(), the host notes its own clock before the launch and after the wait; the tightest of a few
 // such windows gives the offset (good to a few microseconds, which guard_ns must cover).
+// `rounds` windows on an idle side stream, the first `skip` of them not counted; the tightest one is taken if it is
+// no wider than `at_most`.
+int gate_read_clock(fr_ctx* c, int rounds, int skip, uint64_t at_most)
+{
+    uint64_t best_window = ~0ull;
+    int64_t best_offset = 0;
+    for (int i = 0; i < rounds; ++i) {
+        const uint64_t t0 = now_ns();
+        hipLaunchKernelGGL(k_gate_clock, dim3(1), dim3(1), 0, c->side, c->gate);
+        if (hipStreamSynchronize(c->side) != hipSuccess) return FR_ERR_HIP;
+        const uint64_t t1 = now_ns();
+        unsigned long long ticks = 0;
+        if (hipMemcpy(&ticks, &c->gate->deadline_ticks, sizeof(ticks), hipMemcpyDeviceToHost) != hipSuccess) return FR_ERR_HIP;
+        if (i >= skip && t1 - t0 < best_window) {
+            best_window = t1 - t0;
+            best_offset = (int64_t)((double)ticks / c->ticks_per_ns) - (int64_t)(t0 + (t1 - t0) / 2);
+        }
+    }
+    if (best_window <= at_most) {
+        c->gpu_minus_host_ns = best_offset;
+        c->clock_window_ns = best_window;
+        c->clock_read_ns = now_ns();
+    }
+    return FR_OK;
+}
+
 int gate_setup(fr_ctx* c)
 {
     int khz = 0;
@@ -623,20 +654,19 @@ int gate_setup(fr_ctx* c)
     c->ticks_per_ns = (double)khz * 1.0e-6;
     if (hipMalloc(reinterpret_cast<void**>(&c->gate), sizeof(fr_gate)) != hipSuccess) { c->gate = nullptr; return FR_ERR_HIP; }
     if (hipMemset(c->gate, 0, sizeof(fr_gate)) != hipSuccess) return FR_ERR_HIP;
-    uint64_t best_window = ~0ull;
-    for (int i = 0; i < 12; ++i) {
-        const uint64_t t0 = now_ns();
-        hipLaunchKernelGGL(k_gate_clock, dim3(1), dim3(1), 0, c->side, c->gate);
-        if (hipStreamSynchronize(c->side) != hipSuccess) return FR_ERR_HIP;
-        const uint64_t t1 = now_ns();
-        unsigned long long ticks = 0;
-        if (hipMemcpy(&ticks, &c->gate->deadline_ticks, sizeof(ticks), hipMemcpyDeviceToHost) != hipSuccess) return FR_ERR_HIP;
-        if (i >= 2 && t1 - t0 < best_window) {                  // the first launches pay one-time costs
-            best_window = t1 - t0;
-            c->gpu_minus_host_ns = (int64_t)((double)ticks / c->ticks_per_ns) - (int64_t)(t0 + (t1 - t0) / 2);
-        }
-    }
-    return FR_OK;
+    return gate_read_clock(c, 12, 2, ~0ull);                    // (the first launches pay one-time costs)
+}
+
+// The two clocks drift apart (some tens of microseconds a second were seen), so the reading is renewed now and then,
+// at the start of a bubble, when the side stream is idle anyway: three windows, about 50 us, four times a second at
+// most; a reading from a window much wider than the first one's (something held the stream up) is not taken.
+constexpr uint64_t kClockRereadNs = 250000000;
+void gate_refresh_clock(fr_ctx* c)
+{
+    if (now_ns() - c->clock_read_ns < kClockRereadNs) return;
+    const uint64_t before = c->clock_read_ns;
+    (void)gate_read_clock(c, 3, 0, 2 * c->clock_window_ns + 2000);
+    if (c->clock_read_ns == before) c->clock_read_ns = now_ns() - kClockRereadNs / 2;      // not taken: try again sooner
 }
 
 // How long fr_bubble_end waits for a step callback that is still running after the bubble's end.
