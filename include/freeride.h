@@ -330,7 +330,12 @@ typedef struct fr_pagerank_desc {
     uint64_t finish_tile_ns;
     /* Shortest step per segment kind (indexed by FR_PR_SEG_*), ns; 0 = none.  A launch of a few tiles takes about
        as long as one tile alone (the tiles run side by side), so the modelled cost of a step is
-       max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.                   */
+       max(sum of its tile costs, min_step_ns[kind]), and a step is only planned if that fits.  A sweep's tiles run
+       `slots` at a time (fr_pagerank_info_t): a step of more tiles than that which does not reach the segment's end
+       is a whole number of rounds, and a step of n <= slots tiles, which fills only part of the slots, is modelled as
+       max(min_step_ns[kind], sum of its tile costs + min_step_ns[kind] * (full - n) / full), full = min(slots,
+       tiles of the sweep) - between one tile alone (the floor) and a full round (the sum) the time was measured to
+       grow linearly with n - with n taken down until that fits.                                                  */
     uint64_t min_step_ns[4];
     /* Partition sizes of the layout: destination rows per range (8192 or 16384) and the most source vertices of a
        scatter tile (16384 or 32768); 0 = chosen by the library (16384 rows from 2^22 vertices on, 32768 sources

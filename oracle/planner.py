@@ -31,7 +31,11 @@ Rounds (optional, per segment): a task may say that at most `slots` tiles of a s
 step of more tiles runs in rounds, its modelled cost - the sum - being what whole rounds take.  Section 4.5 lets a
 step run only if the time left is enough for it, so a step must not take longer than modelled: a chunk of more
 than `slots` tiles that does not reach the segment's end is cut down to a whole number of rounds,
-n -> (n // slots) * slots (a round and a few tiles would take two rounds' time).  slots = 0: no such rule.
+n -> (n // slots) * slots (a round and a few tiles would take two rounds' time).  A step of up to one round runs its
+tiles side by side on part of the slots: one tile alone takes the floor, a full round the sum of its tile costs, and
+in between the time grows with the number of tiles, so such a step is modelled as
+    max(floor, sum of its n tile costs + floor * (full - n) // full),   full = min(slots, tiles of the segment)
+and n is taken down until that fits.  slots = 0: neither rule.
 
 When the last segment of a run completes the task starts over (run index + 1) unless `max_runs` is reached,
 after which it harvests nothing more.
@@ -96,6 +100,16 @@ def plan(bubble_lengths: Sequence[int], segments: Sequence[Sequence[int]], guard
                 n = n // slots[seg] * slots[seg]
                 tiles_cost = sum(costs[tile:tile + n])
             total = launch_cost + max(tiles_cost, floors[seg])
+            if slots[seg] and 0 < n <= slots[seg]:
+                full = min(slots[seg], len(costs))          # a segment of fewer tiles than slots is full with all of them
+
+                def part(k):
+                    return max(floors[seg], sum(costs[tile:tile + k]) + floors[seg] * (full - k) // full)
+                while n > 0 and launch_cost + part(n) > budget:
+                    n -= 1
+                if n > 0:
+                    tiles_cost = sum(costs[tile:tile + n])
+                    total = launch_cost + part(n)
             if n == 0:
                 out.append(Record("IDLE", i, run, seg, tile, tile, max(remaining, 0)))
                 break

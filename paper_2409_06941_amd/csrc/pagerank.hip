@@ -1029,8 +1029,23 @@ int pr_plan(void* user, uint64_t budget_ns, uint64_t launch_cost_ns, fr_step* ou
     // segment's last round smoothly are at its end): a round and a few tiles would take two rounds' time.
     const uint32_t slots = kind == FR_PR_SEG_SCATTER ? p->L.scatter_slots : kind == FR_PR_SEG_GATHER ? p->L.gather_slots : 0;
     if (slots && n > slots && p->tile + n < p->tiles_of(kind)) n = n / slots * slots;
+    uint64_t cost = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
+    if (slots && n <= slots) {
+        // A step of up to a round: its tiles run side by side on part of the slots.  One tile alone takes the floor,
+        // a full round the sum of its tiles' costs (each a share of a round), and in between the time was measured
+        // to grow linearly with the number of tiles: the sum plus the floor's share of the slots left empty.
+        // (a sweep of fewer tiles than slots is full with all of them)
+        const uint32_t full = std::min(slots, p->tiles_of(kind));
+        auto part = [&](uint32_t k) {
+            return std::max(floor_ns, pre[p->tile + k] - pre[p->tile] + floor_ns * (full - k) / full);
+        };
+        const uint64_t room = budget_ns - launch_cost_ns;            // (launch_cost_ns <= budget_ns - floor_ns, above)
+        while (n > 0 && part(n) > room) --n;
+        if (n == 0) return FR_OK;
+        cost = part(n);
+    }
     out->tile1 = p->tile + n;
-    out->modelled_ns = std::max(pre[p->tile + n] - pre[p->tile], floor_ns);
+    out->modelled_ns = cost;
     if (slots && n > slots) {
         // the step's kernel hands its tiles out and can stop between them: what its heaviest tile - the first, they
         // are in order of falling weight - takes a workgroup, i.e. the slot's whole time for it (a tile's cost is its

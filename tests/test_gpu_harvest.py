@@ -108,6 +108,7 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     pr = ctx.fr_query_progress(tid)
     log = ctx.fr_event_log()
     segs = _segments(task, cfg.iterations)          # the cost tables exist once InitSideTask has run
+    info = task.fr_pagerank_info()
     _check_cost_rule(task, 260_000, 400_000, 300_000, 15000)
     ctx.fr_task_stop(tid)
     got = ranks.cpu().numpy()
@@ -123,9 +124,10 @@ def test_config1_harvest_matches_plan_and_oracle_bits():
     assert pr.overruns == 0 and pr.deadline_misses == 0 and sum(r.overruns for r in results) == 0
     assert pr.bubbles_seen == len(lengths)
 
-    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=3, floors=_floors(floors, cfg.iterations))
-    # (the two rules of the step cost, floor and sum, are pinned on the planner by the CPU tests; here the log
-    # must follow whatever the plan says)
+    slots = [0] + [info.scatter_slots, info.gather_slots] * cfg.iterations + [0]
+    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=3, floors=_floors(floors, cfg.iterations), slots=slots)
+    # (the rules of the step cost - floor, sum, steps of up to a round - are pinned on the planner by the CPU tests;
+    # here the log must follow whatever the plan says)
     got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
     want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
     assert got_log == want_log
@@ -232,6 +234,7 @@ def test_harvest_in_the_bubbles_of_an_interleaved_schedule_matches_plan_and_orac
     results = [stage.fr_stage_run_epoch(ctx) for _ in range(n_epochs)]
     pr = ctx.fr_query_progress(tid)
     log = ctx.fr_event_log()
+    info = task.fr_pagerank_info()
     segs = _segments(task, K)
     ctx.fr_task_stop(tid)
     got = ranks.cpu().numpy()
@@ -244,7 +247,8 @@ def test_harvest_in_the_bubbles_of_an_interleaved_schedule_matches_plan_and_orac
     assert [r.bubble_ns for r in results] == [sum(e - a for a, e in windows)] * n_epochs
     assert pr.overruns == 0 and pr.deadline_misses == 0
     lengths = [2_000_000_000] + [e - a for a, e in windows] * n_epochs
-    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=2, floors=_floors(floors, K))
+    slots = [0] + [info.scatter_slots, info.gather_slots] * K + [0]
+    want = planner.plan(lengths, segs, guard, launch, max_chunk, max_runs=2, floors=_floors(floors, K), slots=slots)
     got_log = [(NAMES[e.kind], e.bubble, e.run, e.segment, e.tile0, e.tile1, e.modelled_ns) for e in log]
     want_log = [(r.kind, r.bubble, r.run, r.segment, r.tile0, r.tile1, r.modelled_ns) for r in want]
     assert got_log == want_log

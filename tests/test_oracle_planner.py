@@ -183,3 +183,56 @@ def test_whole_rounds_rule_invariants(seed):
         assert r.modelled_ns == 2 + sum(segments[r.segment][r.tile0:r.tile1])
         if s and n > s and r.tile1 < len(segments[r.segment]):
             assert n % s == 0
+
+
+def test_steps_of_up_to_a_round_hand_worked():
+    # One segment of eight tiles of cost 10, four side by side (slots 4), floor 20, launch 0.  A step of n <= 4 tiles is
+    # modelled as max(20, 10 n + 20 (4 - n) // 4): 1 -> 25, 2 -> 30, 3 -> 35, 4 -> 40 (a tile alone: its cost and three
+    # quarters of the floor; a full round: the sum).
+    # bubble 0, 35 left: three tiles fit by the sum (30), and 35 <= 35: three tiles, 35; nothing left: idle
+    # bubble 1, 34 left: three fit by the sum but cost 35: two tiles, 30; 4 left: idle
+    # bubble 2, 19 left: less than the floor: idle
+    # bubble 3, 200 left: tiles 5 .. 7, three tiles: 35; the next run's eight tiles fit and reach the segment's end
+    #           (more than a round: the sum, 80); 85 left: eight tiles again, 80; 5 left: idle
+    segs = [[10] * 8]
+    recs = plan([35, 34, 19, 200], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, floors=[20], slots=[4])
+    assert recs == [
+        Record("CHUNK", 0, 0, 0, 0, 3, 35), Record("IDLE", 0, 0, 0, 3, 3, 0),
+        Record("CHUNK", 1, 0, 0, 3, 5, 30), Record("IDLE", 1, 0, 0, 5, 5, 4),
+        Record("IDLE", 2, 0, 0, 5, 5, 19),
+        Record("CHUNK", 3, 0, 0, 5, 8, 35), Record("CHUNK", 3, 1, 0, 0, 8, 80), Record("CHUNK", 3, 2, 0, 0, 8, 80),
+        Record("IDLE", 3, 3, 0, 0, 0, 5),
+    ]
+    # no floor: the rule adds nothing; no slots: the old rule, max(sum, floor)
+    assert plan([35], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, slots=[4])[0] == Record("CHUNK", 0, 0, 0, 0, 3, 30)
+    assert plan([35], segs, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, floors=[20])[0] == Record("CHUNK", 0, 0, 0, 0, 3, 30)
+    # a segment of fewer tiles than slots is full with all of them: three tiles of cost 10, slots 8, floor 20:
+    # 1 -> 10 + 20 * 2 // 3 = 23, 2 -> 20 + 20 * 1 // 3 = 26, 3 -> 30
+    short = [[10] * 3]
+    assert plan([25], short, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, floors=[20], slots=[8])[0] == Record("CHUNK", 0, 0, 0, 0, 1, 23)
+    assert plan([29], short, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, floors=[20], slots=[8])[0] == Record("CHUNK", 0, 0, 0, 0, 2, 26)
+    assert plan([30], short, guard=0, launch_cost=0, max_chunk=10**9, start_created=False, floors=[20], slots=[8])[0] == Record("CHUNK", 0, 0, 0, 0, 3, 30)
+    # launch cost counts: 33 left, launch 5: three tiles would be 5 + 35, two are 5 + 30 = 35 > 33, one is 5 + 25 = 30
+    assert plan([33], segs, guard=0, launch_cost=5, max_chunk=10**9, start_created=False, floors=[20], slots=[4])[0] == Record("CHUNK", 0, 0, 0, 0, 1, 30)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_steps_of_up_to_a_round_invariants(seed):
+    rng = random.Random(300 + seed)
+    segments = [[rng.randint(1, 20) for _ in range(rng.randint(1, 40))] for _ in range(rng.randint(1, 4))]
+    slots = [rng.choice([0, 3, 6]) for _ in segments]
+    floors = [rng.choice([0, 7, 25]) for _ in segments]
+    bl = [rng.randint(0, 300) for _ in range(40)]
+    recs = plan(bl, segments, guard=3, launch_cost=2, max_chunk=10**9, floors=floors, slots=slots)
+    remaining = {}
+    for r in recs:
+        if r.kind == "INIT":
+            continue
+        rem = remaining.get(r.bubble, bl[r.bubble] - 3)
+        if r.kind == "CHUNK":
+            n, s, fl = r.tile1 - r.tile0, slots[r.segment], floors[r.segment]
+            total = sum(segments[r.segment][r.tile0:r.tile1])
+            full = min(s, len(segments[r.segment]))
+            want = max(fl, total + fl * (full - n) // full) if s and n <= s else max(total, fl)
+            assert r.modelled_ns == 2 + want <= rem
+            remaining[r.bubble] = rem - r.modelled_ns
