@@ -167,6 +167,8 @@ def test_tiles_follow_the_cu_mask_of_the_stream(cu_count):
     if cu_count == 16:
         assert info.gather_tiles <= 32 and info.scatter_tiles <= 32
         assert pieces > info.gather_tiles                                      # pieces share tiles
+        assert info.merged_ranges > 0                                          # rows whose sums are joined from partial sums: the
+                                                                               # chunkings agree bit for bit on a masked stream too
         assert -(-g.n_vertices // 16384) > info.scatter_tiles
     else:
         assert info.gather_tiles > 16 and info.scatter_tiles > 16             # more tiles than workgroups: handed out
