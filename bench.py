@@ -199,7 +199,8 @@ def run_config(name, steps, warmup, args, headline):
                           else fr.FR_PR_SEG_SCATTER + ((g - 1) & 1))
     # the guard also has to cover what a step of a round or less may take beyond its model (its tiles run side by
     # side at a rate the additive costs do not describe): a quarter of the heaviest tile's time alone
-    guard_ns = max(args.guard_ns, int(0.25 * max(one_tile_ns[1], one_tile_ns[2])))
+    guard_ns = max(args.guard_ns if args.guard_ns else (60_000 if args.device_gate else 150_000),
+                   int(0.25 * max(one_tile_ns[1], one_tile_ns[2])))
 
     def start_task(launch_cost_ns, model, time_steps, adapt=0):
         ctx = fr.Context(device_id=0, cu_count=cu_count,
@@ -400,7 +401,8 @@ def run_config(name, steps, warmup, args, headline):
                                   (cfg.load.layers, cfg.load.hidden, cfg.load.ffn, cfg.load.tokens)) if cfg.load else "busy-wait",
                    "schedule": ("interleaved 1F1B, %d chunks" % chunks) if chunks else cfg.schedule,
                    "f_ms": f_ns / 1e6, "b_ms": b_ns / 1e6, "cu_count": cfg.cu_count,
-                   "mem_cap_bytes": cfg.mem_cap_bytes, "guard_us": guard_ns / 1e3},
+                   "mem_cap_bytes": cfg.mem_cap_bytes, "guard_us": guard_ns / 1e3,
+                   "gate_guard_us": (args.gate_guard_ns if args.gate_guard_ns else guard_ns) / 1e3 if args.device_gate else None},
         "gteps_in_kernel": edges / chunk_ns if chunk_ns else 0.0,
         "gteps_wall": edges / (wall_s * 1e9) if wall_s else 0.0,
         "bubble_fraction_of_epoch": bubble_ns / sum(r.epoch_ns for r, _ in with_task),
@@ -499,8 +501,9 @@ def main():
                     help="1: with the default configuration, also run cfg2, cfg3 and cfg4 (4 timed epochs each) and report them under per_config")
     ap.add_argument("--derate", type=float, default=1.25, help="first model = measured standalone cost x derate")
     ap.add_argument("--margin", type=float, default=1.02, help="final model = measured in-bubble step cost x margin")
-    ap.add_argument("--guard-ns", type=int, default=150_000,
-                    help="least time kept free at the end of every bubble (covers the slow first sweeps after a burst)")
+    ap.add_argument("--guard-ns", type=int, default=0,
+                    help="least time the host's plan keeps free at the end of every bubble; 0 = 60 us with the device gate (which "
+                         "stops by the GPU's clock what the plan got wrong), 150 us without (covers the slow first sweeps after a burst)")
     ap.add_argument("--time-steps", type=int, default=16,
                     help="steps per HIP-event timing group in the measured epochs (an event between two kernels idles the GPU ~3 us)")
     ap.add_argument("--device-gate", type=int, default=1,
